@@ -1,0 +1,241 @@
+"""ctypes front end of the fp64 CPU oracle (oracle/skim_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and
+by the cpu_baseline leg of bench.py.  The product package never imports it.
+The oracle and the HIP library share no code; this module only marshals numpy
+arrays into the C functions and compiles the C file with gcc when needed.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "skim_oracle.c")
+_LIB = os.path.join(_HERE, "libskim_oracle.so")
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, no fast-math, no FP contraction, OpenMP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        cmd = ["gcc", "-O2", "-std=c11", "-fno-fast-math", "-ffp-contract=off", "-fopenmp", "-fPIC",
+               "-shared", "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.oracle_f32_to_f16.restype = C.c_uint16
+        _lib.oracle_f32_to_f16.argtypes = [C.c_float]
+        _lib.oracle_f16_to_f32.restype = C.c_float
+        _lib.oracle_f16_to_f32.argtypes = [C.c_uint16]
+        _lib.oracle_pack.restype = C.c_int64
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def _p(a, ct=C.c_void_p):
+    return None if a is None else a.ctypes.data_as(ct)
+
+
+def _f32(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with status {rc}")
+
+
+def scale_row(w, s, alpha):
+    w, s, alpha = _f32(w), _f32(s), _f32(alpha)
+    m = w.shape[0]
+    wt = np.empty(m, np.float32)
+    st = np.empty(m, np.float32)
+    lib().oracle_scale_row(_p(w), _p(s), _p(alpha), C.c_int64(m), _p(wt), _p(st))
+    return wt, st
+
+
+def quantile_init(w, s, K):
+    w, s = _f32(w), _f32(s)
+    m = w.shape[0]
+    c0 = np.empty(K, np.float64)
+    ranks = np.empty(K, np.int64)
+    _check(lib().oracle_quantile_init(_p(w), _p(s), C.c_int64(m), C.c_int(K), _p(c0), _p(ranks)),
+           "quantile_init")
+    return c0, ranks
+
+
+def cluster_row(w, s, K, T=30, count_near=False):
+    """One row.  Returns dict(labels, centroids, upper, err, J, near)."""
+    w, s = _f32(w), _f32(s)
+    m = w.shape[0]
+    labels = np.empty(m, np.uint8)
+    cent = np.empty(K, np.float64)
+    upper = np.empty(K, np.float64)
+    err = C.c_double(0)
+    J = np.empty(T, np.float64)
+    near = np.zeros(2, np.int64)
+    _check(lib().oracle_cluster_row(_p(w), _p(s), C.c_int64(m), C.c_int(K), C.c_int(T), _p(labels),
+                                    _p(cent), _p(upper), C.byref(err), _p(J),
+                                    _p(near) if count_near else None), "cluster_row")
+    return dict(labels=labels, centroids=cent, upper=upper, err=err.value, J=J, near=near)
+
+
+def error_table(W, S, alpha=None, bmin=1, bmax=4, T=30, count_near=False):
+    """Returns dict(E n x nb, centroids_all n x sum 2^b, upper_all, near[2])."""
+    W, S, alpha = _f32(W), _f32(S), _f32(alpha)
+    n, m = W.shape
+    nb = bmax - bmin + 1
+    stride = sum(1 << b for b in range(bmin, bmax + 1))
+    E = np.empty((n, nb), np.float64)
+    ca = np.empty((n, stride), np.float64)
+    ua = np.empty((n, stride), np.float64)
+    near = np.zeros(2, np.int64)
+    _check(lib().oracle_error_table(_p(W), _p(S), _p(alpha), C.c_int64(n), C.c_int64(m),
+                                    C.c_int64(m), C.c_int(bmin), C.c_int(bmax), C.c_int(T), _p(E),
+                                    _p(ca), _p(ua), _p(near) if count_near else None),
+           "error_table")
+    return dict(E=E, centroids_all=ca, upper_all=ua, near=near)
+
+
+def cluster_rows(W, S, bits, alpha=None, T=30, count_near=False, want_labels=True):
+    W, S, alpha = _f32(W), _f32(S), _f32(alpha)
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    n, m = W.shape
+    labels = np.empty((n, m), np.uint8) if want_labels else None
+    cent = np.empty((n, 16), np.float64)
+    upper = np.empty((n, 16), np.float64)
+    err = np.empty(n, np.float64)
+    near_rows = np.zeros(n, np.int64) if count_near else None
+    _check(lib().oracle_cluster_rows(_p(W), _p(S), _p(alpha), C.c_int64(n), C.c_int64(m),
+                                     C.c_int64(m), _p(bits), C.c_int(T), _p(labels), _p(cent),
+                                     _p(upper), _p(err), _p(near_rows)), "cluster_rows")
+    return dict(labels=labels, centroids=cent, upper=upper, err=err, near_rows=near_rows)
+
+
+def greedy(E, avg_bits, bmin=1, bmax=4, cost=None, count_near=False):
+    E = np.ascontiguousarray(E, dtype=np.float64)
+    n = E.shape[0]
+    assert E.shape[1] == bmax - bmin + 1
+    cost_a = None if cost is None else np.ascontiguousarray(cost, dtype=np.int64)
+    bits = np.empty(n, np.uint8)
+    spent = C.c_int64(0)
+    budget = C.c_int64(0)
+    near = np.zeros(1, np.int64)
+    rc = lib().oracle_greedy(_p(E), _p(cost_a), C.c_int64(n), C.c_int(bmin), C.c_int(bmax),
+                             C.c_double(avg_bits), _p(bits), C.byref(spent), C.byref(budget),
+                             _p(near) if count_near else None)
+    if rc == -3:
+        raise ValueError("budget outside [n*bmin, n*bmax]")
+    _check(rc, "greedy")
+    return dict(bits=bits, spent=spent.value, budget=budget.value, near=int(near[0]))
+
+
+def words_per_row(m, b):
+    return (m * b + 31) // 32
+
+
+def pack(W, bits, labels, centroids, alpha=None, want_dW=False):
+    W, alpha = _f32(W), _f32(alpha)
+    n, m = W.shape
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    labels = np.ascontiguousarray(labels, dtype=np.uint8)
+    centroids = np.ascontiguousarray(centroids, dtype=np.float64)
+    assert centroids.shape == (n, 16) and labels.shape == (n, m)
+    nwords = int(sum(words_per_row(m, int(b)) for b in bits))
+    ncb = int(sum(1 << int(b) for b in bits))
+    codes = np.zeros(nwords, np.uint32)
+    gwo = np.zeros(6, np.int64)
+    perm = np.empty(n, np.int32)
+    cbs = np.zeros(ncb, np.uint16)
+    dW = np.empty((n, m), np.float32) if want_dW else None
+    rc = lib().oracle_pack(_p(W), _p(alpha), C.c_int64(n), C.c_int64(m), C.c_int64(m), _p(bits),
+                           _p(labels), _p(centroids), _p(codes), _p(gwo), _p(perm), _p(cbs), _p(dW))
+    if rc < 0:
+        raise RuntimeError(f"oracle pack failed with status {rc}")
+    assert rc == nwords
+    return dict(codes=codes, group_word_offset=gwo, row_perm=perm, codebooks=cbs, dW=dW)
+
+
+def f32_to_f16(x):
+    x = np.ascontiguousarray(x, dtype=np.float32).ravel()
+    f = lib().oracle_f32_to_f16
+    return np.array([f(float(v)) for v in x], dtype=np.uint16)
+
+
+def f16_to_f32(h):
+    h = np.ascontiguousarray(h, dtype=np.uint16).ravel()
+    f = lib().oracle_f16_to_f32
+    return np.array([f(int(v)) for v in h], dtype=np.float32)
+
+
+def centroids_from_labels(W, S, labels, alpha=None):
+    W, S, alpha = _f32(W), _f32(S), _f32(alpha)
+    n, m = W.shape
+    labels = np.ascontiguousarray(labels, dtype=np.uint8)
+    c = np.empty((n, 16), np.float64)
+    D = np.empty((n, 16), np.float64)
+    _check(lib().oracle_centroids_from_labels(_p(W), _p(S), _p(alpha), C.c_int64(n), C.c_int64(m),
+                                              C.c_int64(m), _p(labels), _p(c), _p(D)),
+           "centroids_from_labels")
+    return c, D
+
+
+def layer_loss(W, H, labels, c, alpha=None, want_P=False):
+    W, alpha, H = _f32(W), _f32(alpha), _f32(H)
+    n, m = W.shape
+    labels = np.ascontiguousarray(labels, dtype=np.uint8)
+    c = np.ascontiguousarray(c, dtype=np.float64)
+    loss = C.c_double(0)
+    row_loss = np.empty(n, np.float64)
+    P = np.empty((n, m), np.float64) if want_P else None
+    _check(lib().oracle_layer_loss(_p(W), _p(alpha), _p(H), C.c_int64(n), C.c_int64(m),
+                                   C.c_int64(m), _p(labels), _p(c), C.byref(loss), _p(row_loss),
+                                   _p(P)), "layer_loss")
+    return dict(loss=loss.value, row_loss=row_loss, P=P)
+
+
+def scale_grad(W, S, H, labels, alpha=None):
+    W, S, alpha, H = _f32(W), _f32(S), _f32(alpha), _f32(H)
+    n, m = W.shape
+    labels = np.ascontiguousarray(labels, dtype=np.uint8)
+    loss = C.c_double(0)
+    grad = np.empty(m, np.float64)
+    c = np.empty((n, 16), np.float64)
+    _check(lib().oracle_scale_grad(_p(W), _p(S), _p(alpha), _p(H), C.c_int64(n), C.c_int64(m),
+                                   C.c_int64(m), _p(labels), C.byref(loss), _p(grad), _p(c)),
+           "scale_grad")
+    return dict(loss=loss.value, grad=grad, centroids=c)
+
+
+ADAM_DEFAULTS = dict(lr0=0.01, beta1=0.9, beta2=0.999, eps=1e-8, decay=0.5, decay_every=40)
+
+
+def adam_step(alpha, m1, m2, grad, t, **opts):
+    """Updates copies of (alpha, m1, m2); returns them."""
+    o = dict(ADAM_DEFAULTS)
+    o.update(opts)
+    alpha = np.array(alpha, dtype=np.float32, copy=True)
+    m1 = np.array(m1, dtype=np.float32, copy=True)
+    m2 = np.array(m2, dtype=np.float32, copy=True)
+    grad = np.ascontiguousarray(grad, dtype=np.float64)
+    _check(lib().oracle_adam_step(_p(alpha), _p(m1), _p(m2), _p(grad), C.c_int64(alpha.shape[0]),
+                                  C.c_int64(t), C.c_double(o["lr0"]), C.c_double(o["beta1"]),
+                                  C.c_double(o["beta2"]), C.c_double(o["eps"]),
+                                  C.c_double(o["decay"]), C.c_int64(o["decay_every"])), "adam_step")
+    return alpha, m1, m2
