@@ -1,0 +1,186 @@
+/*
+ * skim.h -- C ABI of the MI355X (gfx950) implementation of the data-parallel
+ * hot path of SKIM (arXiv 2412.04180): per-output-channel sensitivity-weighted
+ * 1-D K-means at every candidate bit width, the channel x bit error table,
+ * greedy mixed-precision bit allocation, packing, and the scaling-vector step
+ * with its layer-wise loss.
+ *
+ * General rules
+ *   - Plain C types only.  "dev" = pointer to device (HBM) memory of the
+ *     context's GPU, "host" = pointer to host memory.
+ *   - The caller owns every buffer.  The library allocates no device memory:
+ *     scratch comes from the workspace the caller registers.  It keeps no
+ *     pointer after a call returns, except the registered workspace.
+ *   - Device calls enqueue work on the context's HIP stream and return without
+ *     synchronising; results (including scalars) land in device memory.
+ *     skim_greedy_allocate is synchronous host code.
+ *   - Matrices are row-major; a row is one output channel.  ld is the row
+ *     stride in elements (ld >= m).
+ *   - Every call returns SKIM_OK or a negative skim_status; after an error the
+ *     outputs are unspecified and skim_last_error() describes the cause.
+ *     There is no CPU fallback: without a usable GPU, skim_create fails.
+ *   - Inputs must be finite, S >= 0, alpha > 0.  Violations are not detected.
+ *   - Calls on one context must not overlap in time (they share the workspace).
+ *
+ * Labels and cluster order.  Cluster k of a row (k = 0 .. 2^b - 1) is the k-th
+ * starting centroid, taken at ascending weighted quantiles of the row; a
+ * label is that cluster index.  Centroid values are almost always ascending in
+ * k but the library does not rely on it.
+ */
+#ifndef SKIM_H
+#define SKIM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct skim_ctx skim_ctx;
+
+typedef enum {
+    SKIM_OK = 0,
+    SKIM_ERR_ARG = -1,       /* null pointer, bit range, iteration count ...          */
+    SKIM_ERR_SHAPE = -2,     /* n, m, ld outside what the kernels support               */
+    SKIM_ERR_BUDGET = -3,    /* average bits outside [bmin, bmax]                       */
+    SKIM_ERR_WORKSPACE = -4, /* workspace missing or too small                          */
+    SKIM_ERR_HIP = -5,       /* a HIP runtime call failed                               */
+    SKIM_ERR_NONFINITE = -6  /* reserved                                                */
+} skim_status;
+
+/* Adam with step decay for the scaling vector (Sec. 5.1 "Settings": Adam,
+ * lr 0.01 halved every 40 steps).  beta1/beta2/eps are the optimiser's
+ * published defaults 0.9 / 0.999 / 1e-8; moments are bias-corrected. */
+typedef struct {
+    float lr0, beta1, beta2, eps, decay;
+    int32_t decay_every;
+} skim_adam_opts;
+
+#define SKIM_MAX_BITS 4
+#define SKIM_MAX_K 16
+/* Longest row the clustering kernel accepts (row and sensitivities are staged
+ * in the 160 KB LDS of one compute unit). */
+#define SKIM_MAX_M 16384
+
+/* ---- context ------------------------------------------------------------ */
+
+/* Create a context on GPU `device` that enqueues on `hip_stream` (a
+ * hipStream_t passed as void*, NULL = the default stream).  Fails with
+ * SKIM_ERR_HIP when the device is not a usable gfx950 GPU. */
+skim_status skim_create(skim_ctx **out, int device, void *hip_stream);
+skim_status skim_destroy(skim_ctx *ctx);
+/* Text of the last error on this context (ctx-owned, valid until the next
+ * call); ctx == NULL returns the text of the last skim_create failure. */
+const char *skim_last_error(const skim_ctx *ctx);
+
+/* Scratch needed by any call on an n x m matrix (bytes), and its registration.
+ * dev pointer, 256-byte aligned, must stay valid while calls use it. */
+size_t skim_workspace_bytes(int64_t n, int64_t m);
+skim_status skim_set_workspace(skim_ctx *ctx, void *dev_ptr, size_t bytes);
+
+/* ---- clustering --------------------------------------------------------- */
+
+/* Error pre-recording (Alg. 3 lines 2-10): for every row i and every bit
+ * width b in [bmin, bmax] run the weighted K-means
+ *     Kmeans(W_i * alpha^-1, weights = S_i * alpha^2, n_centroids = 2^b)
+ * (Alg. 3 line 5; objective: the S-diag form of Sec. 3.3) from the
+ * weighted-quantile start for `iters` Lloyd iterations and record
+ *     E[i][b - bmin] = sum_j s~_ij (w~_ij - c_{a_ij})^2 .
+ * W, S: dev, n x m float32, stride ld.  alpha: dev, m float32, or NULL (= 1).
+ * E: dev, n x (bmax-bmin+1) float64.
+ * centroids_all: dev float64, n x (2^bmin + ... + 2^bmax), per row the blocks
+ *   for b = bmin..bmax back to back; may be NULL.
+ * upper_all: dev float32, same layout: largest member w~ of each cluster,
+ *   -inf for an empty cluster (the thresholds skim_pack rebuilds labels from);
+ *   may be NULL.
+ * 1 <= bmin <= bmax <= 4, 16 <= 2^bmax <= m <= SKIM_MAX_M, iters >= 1. */
+skim_status skim_error_table(skim_ctx *ctx, const float *W, const float *S, const float *alpha,
+                             int64_t n, int64_t m, int64_t ld, int bmin, int bmax, int iters,
+                             double *E, double *centroids_all, float *upper_all);
+
+/* K-means at one bit width per row (Alg. 3 lines 12-15; the re-clustering of
+ * W * alpha^-1 in Alg. 2).  bits: dev uint8[n], each in 1..4.
+ * labels: dev uint8 n x m (dense, stride m), may be NULL.
+ * centroids: dev float64 n x 16 (first 2^bits[i] used, rest 0).
+ * upper: dev float32 n x 16 (rest -inf), may be NULL.  err: dev float64[n]. */
+skim_status skim_cluster_rows(skim_ctx *ctx, const float *W, const float *S, const float *alpha,
+                              int64_t n, int64_t m, int64_t ld, const uint8_t *bits, int iters,
+                              uint8_t *labels, double *centroids, float *upper, double *err);
+
+/* Pick, for every row, the block of its allocated bit width out of the
+ * per-bit outputs of skim_error_table (clustering is deterministic, so the
+ * K-means of Alg. 3 lines 12-15 need not be run again).  All pointers dev.
+ * centroids: n x 16 float64, upper: n x 16 float32 (layout of
+ * skim_cluster_rows), err: float64[n], may be NULL. */
+skim_status skim_select_allocated(skim_ctx *ctx, int64_t n, int bmin, int bmax, const uint8_t *bits,
+                                  const double *E, const double *centroids_all,
+                                  const float *upper_all, double *centroids, float *upper,
+                                  double *err);
+
+/* ---- allocation --------------------------------------------------------- */
+
+/* Greedy bit allocation (Alg. 1), host memory only.  E: host float64
+ * n x (bmax-bmin+1).  Every row starts at bmin; the row with the largest error
+ * reduction per unit cost, E[i][b_i] - E[i][b_i+1] over row_cost[i], gets one
+ * more bit while it fits the budget floor(avg_bits * sum(cost) + 1e-9); equal
+ * reductions go to the lowest row index.  row_cost: host int64[n] (weights per
+ * row, for tables joining matrices of different width) or NULL = unit cost,
+ * the algorithm as printed.  bits_out: host uint8[n].  spent_out, budget_out
+ * (may be NULL): bits spent / available, in cost units. */
+skim_status skim_greedy_allocate(const double *E, const int64_t *row_cost, int64_t n, int bmin,
+                                 int bmax, double avg_bits, uint8_t *bits_out, int64_t *spent_out,
+                                 int64_t *budget_out);
+
+/* ---- packing ------------------------------------------------------------ */
+
+/* Number of 32-bit words / binary16 codebook entries skim_pack writes for the
+ * given host bits[n] (each 1..4). */
+int64_t skim_packed_words(const uint8_t *bits_host, int64_t n, int64_t m);
+int64_t skim_codebook_entries(const uint8_t *bits_host, int64_t n);
+
+/* Pack (Sec. 4.2 last paragraph, App. D.2: rows of equal bit width are
+ * gathered and processed together; Sec. 5.4: centroids in lower precision).
+ * Layout: rows ordered by (bits ascending, row index ascending), row_perm[p] =
+ * original row; a b-bit row takes ceil(m*b/32) uint32 words, the label of
+ * column j at bit j*b of the row's little-endian bit stream, padding bits 0;
+ * group_word_offset[b] (b=1..4) = first word of the b-bit group, [5] = total,
+ * [0] = 0.  codebooks: same row order, 2^b binary16 per row,
+ * f16(f32(centroid)) both round-to-nearest-even.  dW (optional, n x m float32,
+ * stride m, original row order) = fl32(w - alpha * f32(codebook value)).
+ * Labels are rebuilt from the thresholds: the cluster with the smallest upper
+ * bound >= w~.  All pointers dev; group_word_offset is dev int64[6]. */
+skim_status skim_pack(skim_ctx *ctx, const float *W, const float *alpha, int64_t n, int64_t m,
+                      int64_t ld, const uint8_t *bits, const double *centroids, const float *upper,
+                      uint32_t *codes, int64_t *group_word_offset, int32_t *row_perm,
+                      uint16_t *codebooks_fp16, float *dW);
+
+/* ---- scaling vector ----------------------------------------------------- */
+
+/* Layer-wise (L-full) loss of Alg. 2 with fixed labels:
+ *   c   = calc_centroids(W * alpha^-1, L)      (weighted means, weights S alpha^2)
+ *   dW  = W - replace(c, L) * alpha
+ *   loss = tr(dW H dW^T) = sum_i dW_i H dW_i^T  (Sec. 3.4, L-full; H ~ X X^T)
+ * H: dev m x m float32 (symmetric).  labels: dev uint8 n x m.  loss: dev
+ * float64 scalar.  row_loss: dev float64[n] (the L-full error of each channel),
+ * may be NULL.  The contraction dW*H runs on fp32 MFMA with fp32 accumulation;
+ * the final reductions are float64.  m must be a multiple of 16. */
+skim_status skim_layer_loss(skim_ctx *ctx, const float *W, const float *S, const float *alpha,
+                            const float *H, int64_t n, int64_t m, int64_t ld,
+                            const uint8_t *labels, double *loss, double *row_loss);
+
+/* One optimiser step on alpha with the labels fixed (inner loop of Alg. 2):
+ * the loss above, its gradient with respect to alpha through the centroids,
+ * and an Adam update of alpha / adam_m / adam_v (dev float32[m], in place).
+ * t is the 1-based step number (selects the decayed learning rate and the bias
+ * correction).  loss_before: dev float64 scalar (loss at the incoming alpha).
+ * grad_out: dev float32[m], may be NULL. */
+skim_status skim_scale_step(skim_ctx *ctx, const float *W, const float *S, const float *H,
+                            int64_t n, int64_t m, int64_t ld, const uint8_t *labels, float *alpha,
+                            float *adam_m, float *adam_v, int64_t t, const skim_adam_opts *opts,
+                            double *loss_before, float *grad_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SKIM_H */

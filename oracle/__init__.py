@@ -106,11 +106,12 @@ def error_table(W, S, alpha=None, bmin=1, bmax=4, T=30, count_near=False):
     ca = np.empty((n, stride), np.float64)
     ua = np.empty((n, stride), np.float64)
     near = np.zeros(2, np.int64)
+    near_rows = np.zeros(n, np.int64) if count_near else None
     _check(lib().oracle_error_table(_p(W), _p(S), _p(alpha), C.c_int64(n), C.c_int64(m),
                                     C.c_int64(m), C.c_int(bmin), C.c_int(bmax), C.c_int(T), _p(E),
-                                    _p(ca), _p(ua), _p(near) if count_near else None),
+                                    _p(ca), _p(ua), _p(near) if count_near else None, _p(near_rows)),
            "error_table")
-    return dict(E=E, centroids_all=ca, upper_all=ua, near=near)
+    return dict(E=E, centroids_all=ca, upper_all=ua, near=near, near_rows=near_rows)
 
 
 def cluster_rows(W, S, bits, alpha=None, T=30, count_near=False, want_labels=True):

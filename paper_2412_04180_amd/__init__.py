@@ -1,0 +1,240 @@
+"""Thin Python binding of libskim (gfx950): argument marshalling only.
+
+Every step of the hot path runs inside the HIP library behind the C ABI of
+include/skim.h.  torch is used for device memory and the stream.  There is no
+CPU fallback: importing works anywhere, but creating a context without the
+built library or without a GPU raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libskim.so")
+
+SKIM_OK = 0
+STATUS_NAMES = {0: "SKIM_OK", -1: "SKIM_ERR_ARG", -2: "SKIM_ERR_SHAPE", -3: "SKIM_ERR_BUDGET",
+                -4: "SKIM_ERR_WORKSPACE", -5: "SKIM_ERR_HIP", -6: "SKIM_ERR_NONFINITE"}
+MAX_M = 16384
+
+EXPORTS = ["skim_create", "skim_destroy", "skim_last_error", "skim_workspace_bytes", "skim_set_workspace",
+           "skim_error_table", "skim_cluster_rows", "skim_select_allocated", "skim_greedy_allocate",
+           "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_layer_loss", "skim_scale_step"]
+
+
+class SkimError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {text}")
+        self.status = status
+
+
+class AdamOpts(C.Structure):
+    _fields_ = [("lr0", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("decay", C.c_float), ("decay_every", C.c_int32)]
+
+
+_lib = None
+
+
+def load_library():
+    """dlopen the in-tree libskim.so; raises when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2412_04180_amd._build` "
+                               "(there is no fallback path)")
+        lib = C.CDLL(LIB_PATH)
+        vp, i64, i32, dbl = C.c_void_p, C.c_int64, C.c_int, C.c_double
+        lib.skim_create.argtypes = [C.POINTER(vp), i32, vp]
+        lib.skim_destroy.argtypes = [vp]
+        lib.skim_last_error.argtypes = [vp]
+        lib.skim_last_error.restype = C.c_char_p
+        lib.skim_workspace_bytes.argtypes = [i64, i64]
+        lib.skim_workspace_bytes.restype = C.c_size_t
+        lib.skim_set_workspace.argtypes = [vp, vp, C.c_size_t]
+        lib.skim_error_table.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, vp, vp]
+        lib.skim_cluster_rows.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i32, vp, vp, vp, vp]
+        lib.skim_select_allocated.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+        lib.skim_greedy_allocate.argtypes = [vp, vp, i64, i32, i32, dbl, vp, vp, vp]
+        lib.skim_packed_words.argtypes = [vp, i64, i64]
+        lib.skim_packed_words.restype = i64
+        lib.skim_codebook_entries.argtypes = [vp, i64]
+        lib.skim_codebook_entries.restype = i64
+        lib.skim_pack.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.skim_layer_loss.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp]
+        lib.skim_scale_step.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, i64, C.POINTER(AdamOpts), vp, vp]
+        _lib = lib
+    return _lib
+
+
+def _dp(t):
+    """Device pointer of a torch tensor (None -> NULL)."""
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def greedy_allocate(E, avg_bits, bmin=1, bmax=4, row_cost=None):
+    """skim_greedy_allocate on host arrays.  Returns (bits uint8[n], spent, budget)."""
+    lib = load_library()
+    E = np.ascontiguousarray(E, dtype=np.float64)
+    n = E.shape[0]
+    if E.ndim != 2 or E.shape[1] != bmax - bmin + 1:
+        raise ValueError("E must be n x (bmax-bmin+1)")
+    cost = None if row_cost is None else np.ascontiguousarray(row_cost, dtype=np.int64)
+    bits = np.empty(n, np.uint8)
+    spent, budget = C.c_int64(0), C.c_int64(0)
+    st = lib.skim_greedy_allocate(E.ctypes.data_as(C.c_void_p), None if cost is None else cost.ctypes.data_as(C.c_void_p),
+                                  n, bmin, bmax, float(avg_bits), bits.ctypes.data_as(C.c_void_p),
+                                  C.cast(C.byref(spent), C.c_void_p), C.cast(C.byref(budget), C.c_void_p))
+    if st != SKIM_OK:
+        raise SkimError(st, "skim_greedy_allocate")
+    return bits, spent.value, budget.value
+
+
+def packed_words(bits, m):
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    return int(load_library().skim_packed_words(bits.ctypes.data_as(C.c_void_p), len(bits), m))
+
+
+def codebook_entries(bits):
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    return int(load_library().skim_codebook_entries(bits.ctypes.data_as(C.c_void_p), len(bits)))
+
+
+class Context:
+    """One skim_ctx bound to a torch device and stream."""
+
+    def __init__(self, device=0, stream=None):
+        import torch
+
+        self.torch = torch
+        self.lib = load_library()
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the SKIM hot path has no CPU fallback")
+        self.device = torch.device("cuda", device)
+        torch.cuda.set_device(self.device)
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        h = C.c_void_p()
+        st = self.lib.skim_create(C.byref(h), device, C.c_void_p(self.stream.cuda_stream))
+        if st != SKIM_OK:
+            raise SkimError(st, self.lib.skim_last_error(None).decode())
+        self.h = h
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.skim_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st):
+        if st != SKIM_OK:
+            raise SkimError(st, self.lib.skim_last_error(self.h).decode())
+
+    def workspace_bytes(self, n, m):
+        return int(self.lib.skim_workspace_bytes(n, m))
+
+    def ensure_workspace(self, n, m):
+        need = self.workspace_bytes(n, m)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = self.torch.empty(need, dtype=self.torch.uint8, device=self.device)
+            self._check(self.lib.skim_set_workspace(self.h, _dp(self._ws), need))
+
+    def empty(self, shape, dtype):
+        return self.torch.empty(shape, dtype=dtype, device=self.device)
+
+    # -- clustering -----------------------------------------------------------
+    def error_table(self, W, S, alpha=None, bmin=1, bmax=4, iters=30, want_centroids=True, want_upper=True,
+                    out=None):
+        """W, S: float32 device tensors n x m (row stride = W.stride(0)).  Returns dict of device tensors."""
+        t = self.torch
+        n, m = W.shape
+        assert W.dtype == t.float32 and S.dtype == t.float32 and W.stride(1) == 1 and S.stride() == W.stride()
+        nb = bmax - bmin + 1
+        stride = (2 << bmax) - (1 << bmin)
+        if out is None:
+            out = dict(E=self.empty((n, nb), t.float64),
+                       centroids_all=self.empty((n, stride), t.float64) if want_centroids else None,
+                       upper_all=self.empty((n, stride), t.float32) if want_upper else None)
+        if out.get("centroids_all") is None:
+            self.ensure_workspace(n, m)
+        self._check(self.lib.skim_error_table(self.h, _dp(W), _dp(S), _dp(alpha), n, m, W.stride(0), bmin, bmax,
+                                              iters, _dp(out["E"]), _dp(out.get("centroids_all")),
+                                              _dp(out.get("upper_all"))))
+        return out
+
+    def cluster_rows(self, W, S, bits, alpha=None, iters=30, want_labels=True, out=None):
+        t = self.torch
+        n, m = W.shape
+        assert W.dtype == t.float32 and S.dtype == t.float32 and W.stride(1) == 1 and S.stride() == W.stride()
+        assert bits.dtype == t.uint8 and bits.numel() == n
+        if out is None:
+            out = dict(labels=self.empty((n, m), t.uint8) if want_labels else None,
+                       centroids=self.empty((n, 16), t.float64), upper=self.empty((n, 16), t.float32),
+                       err=self.empty((n,), t.float64))
+        self._check(self.lib.skim_cluster_rows(self.h, _dp(W), _dp(S), _dp(alpha), n, m, W.stride(0), _dp(bits),
+                                               iters, _dp(out.get("labels")), _dp(out["centroids"]),
+                                               _dp(out.get("upper")), _dp(out["err"])))
+        return out
+
+    def select_allocated(self, bits, table, bmin=1, bmax=4):
+        t = self.torch
+        n = bits.numel()
+        cent = self.empty((n, 16), t.float64)
+        upper = self.empty((n, 16), t.float32) if table.get("upper_all") is not None else None
+        err = self.empty((n,), t.float64)
+        self._check(self.lib.skim_select_allocated(self.h, n, bmin, bmax, _dp(bits), _dp(table["E"]),
+                                                   _dp(table["centroids_all"]), _dp(table.get("upper_all")),
+                                                   _dp(cent), _dp(upper), _dp(err)))
+        return dict(centroids=cent, upper=upper, err=err)
+
+    # -- packing --------------------------------------------------------------
+    def pack(self, W, bits, centroids, upper, alpha=None, want_dW=False, bits_host=None):
+        """bits: device uint8[n].  bits_host (numpy) sizes the outputs; copied from the device when omitted."""
+        t = self.torch
+        n, m = W.shape
+        if bits_host is None:
+            bits_host = bits.cpu().numpy()
+        nwords = packed_words(bits_host, m)
+        ncb = codebook_entries(bits_host)
+        if nwords < 0 or ncb < 0:
+            raise ValueError("bits must be in 1..4")
+        self.ensure_workspace(n, m)
+        codes = self.empty((nwords,), t.int32)
+        gwo = self.empty((6,), t.int64)
+        perm = self.empty((n,), t.int32)
+        cbs = self.empty((ncb,), t.int16)
+        dW = self.empty((n, m), t.float32) if want_dW else None
+        self._check(self.lib.skim_pack(self.h, _dp(W), _dp(alpha), n, m, W.stride(0), _dp(bits), _dp(centroids),
+                                       _dp(upper), _dp(codes), _dp(gwo), _dp(perm), _dp(cbs), _dp(dW)))
+        return dict(codes=codes, group_word_offset=gwo, row_perm=perm, codebooks=cbs, dW=dW)
+
+    # -- scaling vector -------------------------------------------------------
+    def layer_loss(self, W, S, H, labels, alpha=None, want_row_loss=True):
+        t = self.torch
+        n, m = W.shape
+        self.ensure_workspace(n, m)
+        loss = self.empty((1,), t.float64)
+        row_loss = self.empty((n,), t.float64) if want_row_loss else None
+        self._check(self.lib.skim_layer_loss(self.h, _dp(W), _dp(S), _dp(alpha), _dp(H), n, m, W.stride(0),
+                                             _dp(labels), _dp(loss), _dp(row_loss)))
+        return dict(loss=loss, row_loss=row_loss)
+
+    def scale_step(self, W, S, H, labels, alpha, adam_m, adam_v, t_step, opts=None, want_grad=True):
+        t = self.torch
+        n, m = W.shape
+        self.ensure_workspace(n, m)
+        o = opts if opts is not None else AdamOpts(0.01, 0.9, 0.999, 1e-8, 0.5, 40)
+        loss = self.empty((1,), t.float64)
+        grad = self.empty((m,), t.float32) if want_grad else None
+        self._check(self.lib.skim_scale_step(self.h, _dp(W), _dp(S), _dp(H), n, m, W.stride(0), _dp(labels),
+                                             _dp(alpha), _dp(adam_m), _dp(adam_v), int(t_step), C.byref(o),
+                                             _dp(loss), _dp(grad)))
+        return dict(loss_before=loss, grad=grad)

@@ -1,0 +1,57 @@
+// Internal declarations shared by the translation units of libskim (gfx950).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "skim.h"
+
+struct skim_ctx {
+    int device;
+    hipStream_t stream;
+    void *ws;
+    size_t ws_bytes;
+    int lds_limit;      // max LDS bytes one workgroup may use on this device
+    int num_cu;
+    char err[512];
+};
+
+#define SKIM_FAIL(ctx, code, ...)                                   \
+    do {                                                            \
+        snprintf((ctx)->err, sizeof((ctx)->err), __VA_ARGS__);      \
+        return (code);                                              \
+    } while (0)
+
+#define SKIM_HIP(ctx, call)                                                                  \
+    do {                                                                                     \
+        hipError_t e_ = (call);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            SKIM_FAIL(ctx, SKIM_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(e_));     \
+    } while (0)
+
+// Makes `device` current for the calling thread; returns SKIM_ERR_HIP on failure.
+static inline skim_status skim_enter(skim_ctx *ctx) {
+    if (!ctx) return SKIM_ERR_ARG;
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) SKIM_FAIL(ctx, SKIM_ERR_HIP, "hipSetDevice failed: %s", hipGetErrorString(e));
+    ctx->err[0] = 0;
+    return SKIM_OK;
+}
+
+// Workspace carving: 256-byte aligned pieces of the registered buffer.
+struct skim_ws_cursor {
+    char *base;
+    size_t off, cap;
+    void *take(size_t bytes) {
+        size_t a = (off + 255) & ~(size_t)255;
+        if (a + bytes > cap) return nullptr;
+        off = a + bytes;
+        return base + a;
+    }
+};
+
+static inline int skim_block_offset(int bmin, int b) {  // start of block b inside a row of the *_all arrays
+    return (1 << b) - (1 << bmin);
+}

@@ -1,0 +1,77 @@
+// Context, workspace registration and error text of libskim.
+#include "skim_common.h"
+
+static char g_create_err[512] = "";
+
+extern "C" skim_status skim_create(skim_ctx **out, int device, void *hip_stream) {
+    if (!out) {
+        snprintf(g_create_err, sizeof(g_create_err), "skim_create: out is NULL");
+        return SKIM_ERR_ARG;
+    }
+    *out = nullptr;
+    int count = 0;
+    hipError_t e = hipGetDeviceCount(&count);
+    if (e != hipSuccess || count <= 0) {
+        snprintf(g_create_err, sizeof(g_create_err), "skim_create: no HIP device (%s)",
+                 e == hipSuccess ? "count is 0" : hipGetErrorString(e));
+        return SKIM_ERR_HIP;
+    }
+    if (device < 0 || device >= count) {
+        snprintf(g_create_err, sizeof(g_create_err), "skim_create: device %d out of range [0,%d)", device, count);
+        return SKIM_ERR_ARG;
+    }
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, device);
+    if (e != hipSuccess) {
+        snprintf(g_create_err, sizeof(g_create_err), "skim_create: hipGetDeviceProperties: %s", hipGetErrorString(e));
+        return SKIM_ERR_HIP;
+    }
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+        snprintf(g_create_err, sizeof(g_create_err),
+                 "skim_create: device %d is %s; this library is built for gfx950 only", device, prop.gcnArchName);
+        return SKIM_ERR_HIP;
+    }
+    e = hipSetDevice(device);
+    if (e != hipSuccess) {
+        snprintf(g_create_err, sizeof(g_create_err), "skim_create: hipSetDevice: %s", hipGetErrorString(e));
+        return SKIM_ERR_HIP;
+    }
+    skim_ctx *c = new skim_ctx();
+    c->device = device;
+    c->stream = (hipStream_t)hip_stream;
+    c->ws = nullptr;
+    c->ws_bytes = 0;
+    c->lds_limit = (int)prop.sharedMemPerBlock;
+    int optin = 0;
+    if (hipDeviceGetAttribute(&optin, hipDeviceAttributeMaxSharedMemoryPerBlock, device) == hipSuccess && optin > c->lds_limit)
+        c->lds_limit = optin;
+    if (c->lds_limit < 160 * 1024) c->lds_limit = 160 * 1024;  // gfx950: 160 KB of LDS per compute unit
+    c->num_cu = prop.multiProcessorCount;
+    c->err[0] = 0;
+    *out = c;
+    return SKIM_OK;
+}
+
+extern "C" skim_status skim_destroy(skim_ctx *ctx) {
+    if (!ctx) return SKIM_ERR_ARG;
+    delete ctx;
+    return SKIM_OK;
+}
+
+extern "C" const char *skim_last_error(const skim_ctx *ctx) { return ctx ? ctx->err : g_create_err; }
+
+extern "C" size_t skim_workspace_bytes(int64_t n, int64_t m) {
+    if (n < 0 || m < 0) return 0;
+    const size_t nm = (size_t)n * (size_t)m;
+    // scale step: dW and P (float32 n x m each), per-row cluster sums (3 x n x 16 float64),
+    // column partials; pack: per-row word/codebook offsets.  Plus alignment slack.
+    return 2 * nm * sizeof(float) + (size_t)n * 16 * 8 * 3 + (size_t)n * 16 + (size_t)m * 8 * 64 + (1u << 16);
+}
+
+extern "C" skim_status skim_set_workspace(skim_ctx *ctx, void *dev_ptr, size_t bytes) {
+    if (!ctx) return SKIM_ERR_ARG;
+    if (dev_ptr && ((uintptr_t)dev_ptr & 255)) SKIM_FAIL(ctx, SKIM_ERR_ARG, "workspace must be 256-byte aligned");
+    ctx->ws = dev_ptr;
+    ctx->ws_bytes = dev_ptr ? bytes : 0;
+    return SKIM_OK;
+}

@@ -1,0 +1,195 @@
+// Packing of mixed-precision rows (Sec. 4.2 last paragraph and App. D.2: rows of
+// equal bit width are gathered and processed together; Sec. 5.4: centroids are
+// stored in lower precision).  Two kernels: a one-workgroup plan that orders the
+// rows by (bits, row index) and lays out the groups, and a row kernel that
+// rebuilds each label from the cluster thresholds and emits the bit stream.
+#include "skim_common.h"
+
+#include <hip/hip_fp16.h>
+#include <math.h>
+
+namespace {
+
+constexpr int PLAN_THREADS = 1024;
+constexpr int PACK_THREADS = 256;
+constexpr int PACK_TILE = 8192;  // columns staged per pass; multiple of 32 so tiles end on word boundaries
+
+struct PackPlan {         // lives in the workspace
+    long long row_start[6];   // first packed position of the b-bit group
+    long long word_start[6];  // == group_word_offset
+    long long cb_start[6];    // first codebook entry of the group
+};
+
+__global__ void __launch_bounds__(PLAN_THREADS) pack_plan_kernel(long long n, long long m, const uint8_t *bits,
+                                                                 int *rowpos, int *row_perm, PackPlan *plan,
+                                                                 long long *group_word_offset) {
+    __shared__ int cnt[4][PLAN_THREADS];
+    __shared__ long long gstart[6];
+    const int t = threadIdx.x;
+    const long long per = (n + PLAN_THREADS - 1) / PLAN_THREADS;
+    const long long i0 = per * t, i1 = min(n, i0 + per);
+    int c[4] = {0, 0, 0, 0};
+    for (long long i = i0; i < i1; ++i) {
+        const int b = bits[i];
+        if (b >= 1 && b <= 4) c[b - 1]++;
+    }
+    for (int b = 0; b < 4; ++b) cnt[b][t] = c[b];
+    __syncthreads();
+    // exclusive scan of each bit width's counts over the threads (one wavefront per bit width)
+    const int wave = t >> 6, lane = t & 63;
+    if (wave < 4) {
+        int run = 0;
+        for (int base = 0; base < PLAN_THREADS; base += 64) {
+            const int v = cnt[wave][base + lane];
+            int inc = v;
+            for (int d = 1; d < 64; d <<= 1) {
+                const int u = __shfl_up(inc, d, 64);
+                if (lane >= d) inc += u;
+            }
+            cnt[wave][base + lane] = run + inc - v;
+            run += __shfl(inc, 63, 64);
+        }
+        if (lane == 0) gstart[wave + 1] = run;  // group sizes for now
+    }
+    __syncthreads();
+    if (t == 0) {
+        long long rows = 0, words = 0, cbs = 0;
+        plan->row_start[0] = plan->word_start[0] = plan->cb_start[0] = 0;
+        group_word_offset[0] = 0;
+        for (int b = 1; b <= 4; ++b) {
+            const long long sz = gstart[b];
+            plan->row_start[b] = rows;
+            plan->word_start[b] = words;
+            plan->cb_start[b] = cbs;
+            group_word_offset[b] = words;
+            gstart[b] = rows;
+            rows += sz;
+            words += sz * ((m * b + 31) / 32);
+            cbs += sz * (1ll << b);
+        }
+        plan->row_start[5] = rows;
+        plan->word_start[5] = words;
+        plan->cb_start[5] = cbs;
+        group_word_offset[5] = words;
+    }
+    __syncthreads();
+    long long pos[4];
+    for (int b = 0; b < 4; ++b) pos[b] = gstart[b + 1] + cnt[b][t];
+    for (long long i = i0; i < i1; ++i) {
+        const int b = bits[i];
+        if (b >= 1 && b <= 4) {
+            const long long p = pos[b - 1]++;
+            rowpos[i] = (int)p;
+            row_perm[p] = (int)i;
+        } else {
+            rowpos[i] = -1;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(PACK_THREADS) pack_rows_kernel(const float *W, const float *alpha, long long m,
+                                                                 long long ld, const uint8_t *bits,
+                                                                 const double *cent, const float *upper,
+                                                                 const int *rowpos, const PackPlan *plan,
+                                                                 uint32_t *codes, uint16_t *codebooks, float *dW) {
+    __shared__ float thr[16];
+    __shared__ int thl[16];
+    __shared__ float cbf[16];
+    __shared__ uint8_t lab[PACK_TILE];
+    const long long row = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int p = rowpos[row];
+    if (p < 0) return;  // bits outside 1..4: row is not part of the packed model
+    const int b = bits[row];
+    const int K = 1 << b;
+    const long long wpr = (m * b + 31) / 32;
+    const long long local = (long long)p - plan->row_start[b];
+    const long long word0 = plan->word_start[b] + local * wpr;
+    const long long cb0 = plan->cb_start[b] + local * K;
+
+    if (tid < 16) {
+        thr[tid] = -INFINITY;
+        thl[tid] = 0;
+    }
+    __syncthreads();
+    if (tid < K) {
+        const float up = upper[row * 16 + tid];
+        int rank = 0;
+        for (int j = 0; j < K; ++j) {
+            const float uj = upper[row * 16 + j];
+            rank += (uj < up || (uj == up && j < tid)) ? 1 : 0;
+        }
+        thr[rank] = up;
+        thl[rank] = tid;
+        const __half h = __float2half_rn((float)cent[row * 16 + tid]);
+        codebooks[cb0 + tid] = __half_as_ushort(h);
+        cbf[tid] = __half2float(h);
+    }
+    __syncthreads();
+    float th[16];
+    int tl[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        th[q] = (q < K) ? thr[q] : -INFINITY;
+        tl[q] = (q < K) ? thl[q] : 0;
+    }
+    const float *Wr = W + row * ld;
+    for (long long t0 = 0; t0 < m; t0 += PACK_TILE) {
+        const int len = (int)min((long long)PACK_TILE, m - t0);
+        for (int j = tid; j < len; j += PACK_THREADS) {
+            const float w = Wr[t0 + j];
+            const float a = alpha ? alpha[t0 + j] : 1.0f;
+            const float wt = alpha ? __fdiv_rn(w, a) : w;
+            int l = -1, last = 0;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const bool nonempty = th[q] != -INFINITY;
+                if (nonempty) last = tl[q];
+                if (l < 0 && nonempty && wt <= th[q]) l = tl[q];
+            }
+            if (l < 0) l = last;
+            lab[j] = (uint8_t)l;
+            if (dW) dW[row * m + t0 + j] = __fmaf_rn(-a, cbf[l], w);
+        }
+        __syncthreads();
+        const int nw = (len * b + 31) / 32;
+        const long long wbase = word0 + (t0 * b) / 32;
+        for (int q = tid; q < nw; q += PACK_THREADS) {
+            const int bit0 = q * 32;
+            int j = bit0 / b;
+            uint32_t word = 0;
+            for (; j < len && j * b < bit0 + 32; ++j) {
+                const uint32_t code = lab[j];
+                const int sh = j * b - bit0;
+                word |= (sh >= 0) ? (code << sh) : (code >> (-sh));
+            }
+            codes[wbase + q] = word;
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace
+
+extern "C" skim_status skim_pack(skim_ctx *ctx, const float *W, const float *alpha, int64_t n, int64_t m,
+                                 int64_t ld, const uint8_t *bits, const double *centroids, const float *upper,
+                                 uint32_t *codes, int64_t *group_word_offset, int32_t *row_perm,
+                                 uint16_t *codebooks_fp16, float *dW) {
+    skim_status st = skim_enter(ctx);
+    if (st != SKIM_OK) return st;
+    if (!W || !bits || !centroids || !upper || !codes || !group_word_offset || !row_perm || !codebooks_fp16)
+        SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_pack: NULL argument");
+    if (n < 1 || n > 0x7fffffff || m < 1 || ld < m) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "skim_pack: bad shape n=%lld m=%lld ld=%lld", (long long)n, (long long)m, (long long)ld);
+    if (m * 4 > 0x7fffffffll * 32) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "skim_pack: row too long");
+    skim_ws_cursor cur{(char *)ctx->ws, 0, ctx->ws_bytes};
+    int *rowpos = (int *)cur.take((size_t)n * sizeof(int));
+    PackPlan *plan = (PackPlan *)cur.take(sizeof(PackPlan));
+    if (!rowpos || !plan) SKIM_FAIL(ctx, SKIM_ERR_WORKSPACE, "skim_pack: workspace missing or smaller than skim_workspace_bytes(n, m)");
+    hipLaunchKernelGGL(pack_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, ctx->stream, (long long)n, (long long)m, bits,
+                       rowpos, row_perm, plan, (long long *)group_word_offset);
+    SKIM_HIP(ctx, hipGetLastError());
+    hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)n), dim3(PACK_THREADS), 0, ctx->stream, W, alpha, (long long)m,
+                       (long long)ld, bits, centroids, upper, rowpos, plan, codes, codebooks_fp16, dW);
+    SKIM_HIP(ctx, hipGetLastError());
+    return SKIM_OK;
+}

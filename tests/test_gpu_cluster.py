@@ -1,0 +1,215 @@
+"""GPU parity: clustering, error table, allocation and packing against the CPU oracle.
+
+Bar: labels, thresholds, allocations, packed codes and codebooks bit-exact;
+centroids and errors within 1e-5 relative (the benchmark spec).  A decision whose oracle
+margin is below 1e-9 may legitimately fall the other way (the two sides sum in
+different orders); the oracle counts such decisions per row, rows with a
+non-zero count are excused from the exact comparisons and the counts are
+reported.  On config 0 the count must be zero.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import skim_synth
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def ctx(gpu_lib):
+    c = gpu_lib.Context(0)
+    yield c
+    c.close()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def rel_close(got, ref, rtol=RTOL):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    scale = np.maximum(np.abs(ref), 1e-300)
+    return np.abs(got - ref) <= rtol * scale + 0.0
+
+
+def check_table(ctx, W, S, alpha=None, iters=30, bmin=1, bmax=4, require_no_near=False):
+    ref = oracle.error_table(W, S, alpha, bmin=bmin, bmax=bmax, T=iters, count_near=True)
+    out = ctx.error_table(dev(W), dev(S), None if alpha is None else dev(alpha), bmin=bmin, bmax=bmax, iters=iters)
+    torch.cuda.synchronize()
+    E = out["E"].cpu().numpy()
+    ca = out["centroids_all"].cpu().numpy()
+    ua = out["upper_all"].cpu().numpy()
+    clean = ref["near_rows"] == 0
+    if require_no_near:
+        assert ref["near"].tolist() == [0, 0]
+    # thresholds are data values: exact on clean rows
+    ueq = ua[clean].astype(np.float64) == ref["upper_all"][clean]
+    assert ueq.all(), f"cluster bounds differ at {np.argwhere(~ueq)[:5].tolist()}"
+    # errors: relative 1e-5, with an absolute floor for rows whose error is exactly zero
+    row_scale = (S.astype(np.float64) * W.astype(np.float64) ** 2).sum(1, keepdims=True) if alpha is None else None
+    ok = rel_close(E[clean], ref["E"][clean])
+    if row_scale is not None:
+        ok |= np.abs(E[clean] - ref["E"][clean]) <= 1e-13 * row_scale[clean]
+    assert ok.all(), f"E mismatch: max rel {np.max(np.abs(E[clean]-ref['E'][clean])/np.maximum(ref['E'][clean],1e-300))}"
+    wscale = np.abs(W).max(1, keepdims=True).astype(np.float64) if alpha is None else np.abs(W / alpha).max(1, keepdims=True).astype(np.float64)
+    cdiff = np.abs(ca[clean] - ref["centroids_all"][clean])
+    cok = cdiff <= RTOL * np.abs(ref["centroids_all"][clean]) + 1e-12 * wscale[clean]
+    assert cok.all(), f"centroid mismatch at {np.argwhere(~cok)[:5].tolist()}, max abs diff {cdiff.max():.3e}"
+    # excused rows still have to be sane
+    assert np.isfinite(E).all() and (E >= 0).all()
+    return ref, out, int((~clean).sum())
+
+
+def test_config0_error_table_allocation_labels_and_pack(ctx, gpu_lib):
+    W, S = skim_synth.make_ws(0)
+    ref, out, excused = check_table(ctx, W, S, require_no_near=True)
+    assert excused == 0
+    E = out["E"].cpu().numpy()
+    # allocation to 3.0 bits through the library's allocator on the GPU's table
+    bits, spent, budget = gpu_lib.greedy_allocate(E, 3.0)
+    g = oracle.greedy(ref["E"], 3.0, count_near=True)
+    assert g["near"] == 0
+    assert np.array_equal(bits, g["bits"]) and spent == g["spent"] == 1536 and budget == 1536
+    # K-means at the allocated widths: labels bit-exact
+    dbits = dev(bits)
+    cr = ctx.cluster_rows(dev(W), dev(S), dbits)
+    torch.cuda.synchronize()
+    rr = oracle.cluster_rows(W, S, bits, count_near=True)
+    assert int(rr["near_rows"].sum()) == 0
+    assert np.array_equal(cr["labels"].cpu().numpy(), rr["labels"])
+    assert np.array_equal(cr["upper"].cpu().numpy().astype(np.float64), rr["upper"])
+    assert rel_close(cr["err"].cpu().numpy(), rr["err"]).all()
+    np.testing.assert_allclose(cr["centroids"].cpu().numpy(), rr["centroids"], rtol=RTOL, atol=1e-14)
+    # the per-bit blocks of the table hold the same clustering (no second K-means needed)
+    sel = ctx.select_allocated(dbits, out)
+    torch.cuda.synchronize()
+    assert torch.equal(sel["centroids"], cr["centroids"]) and torch.equal(sel["upper"], cr["upper"])
+    assert torch.equal(sel["err"], cr["err"])
+    # pack from thresholds
+    pk = ctx.pack(dev(W), dbits, sel["centroids"], sel["upper"], want_dW=True, bits_host=bits)
+    torch.cuda.synchronize()
+    rp = oracle.pack(W, bits, rr["labels"], rr["centroids"], want_dW=True)
+    assert np.array_equal(pk["codes"].cpu().numpy().view(np.uint32), rp["codes"])
+    assert np.array_equal(pk["group_word_offset"].cpu().numpy(), rp["group_word_offset"])
+    assert np.array_equal(pk["row_perm"].cpu().numpy(), rp["row_perm"])
+    assert np.array_equal(pk["codebooks"].cpu().numpy().view(np.uint16), rp["codebooks"])
+    assert np.array_equal(pk["dW"].cpu().numpy(), rp["dW"])
+
+
+@pytest.mark.parametrize("m", [16, 17, 33, 100, 255, 256, 257, 1000, 2049, 4095, 4097])
+def test_ragged_row_lengths(ctx, m):
+    W, S = skim_synth.make_ws_small(m, 24, m)
+    ref, out, excused = check_table(ctx, W, S)
+    assert excused <= 1
+
+
+def test_duplicates_zero_sensitivities_and_dead_rows(ctx):
+    W, S = skim_synth.make_ws_small(7, 64, 300, dup_frac=0.3, zero_s_frac=0.4)
+    S[3] = 0.0                      # a row without any sensitivity mass -> unit weights
+    W[5] = np.float32(0.25)         # a constant row: every cluster but the first is empty
+    W[6, :150] = np.float32(-1.0)   # two distinct values only
+    W[6, 150:] = np.float32(2.0)
+    W[7] = np.round(W[7] * 200) / 200   # few distinct values, many exact ties in the sort
+    W[8, ::2] = 0.0
+    W[8, 1::4] = -0.0               # both zeros are one value
+    ref, out, excused = check_table(ctx, W, S)
+    assert excused <= 8          # rows of few distinct values put elements exactly between two centroids
+    bits = (np.arange(64) % 4 + 1).astype(np.uint8)
+    cr = ctx.cluster_rows(dev(W), dev(S), dev(bits))
+    torch.cuda.synchronize()
+    rr = oracle.cluster_rows(W, S, bits, count_near=True)
+    clean = rr["near_rows"] == 0
+    assert np.array_equal(cr["labels"].cpu().numpy()[clean], rr["labels"][clean])
+    assert np.array_equal(cr["upper"].cpu().numpy().astype(np.float64)[clean], rr["upper"][clean])
+
+
+def test_heavy_element_rows_exercise_rank_repair(ctx):
+    W, S = skim_synth.make_ws_small(9, 32, 500)
+    S[np.arange(32), np.arange(32) * 13 % 500] = 1e9     # one element carries nearly all mass
+    S[4, -1] = 1e12
+    S[5, np.argmax(W[5])] = 1e12                          # the largest element: ranks are pushed down
+    S[6, np.argmin(W[6])] = 1e12
+    ref, out, excused = check_table(ctx, W, S)
+    assert excused <= 1
+
+
+@pytest.mark.parametrize("iters", [1, 2, 7])
+def test_iteration_counts(ctx, iters):
+    W, S = skim_synth.make_ws_small(40 + iters, 40, 777)
+    check_table(ctx, W, S, iters=iters)
+
+
+def test_bit_range_subset(ctx):
+    W, S = skim_synth.make_ws_small(50, 16, 400)
+    check_table(ctx, W, S, bmin=2, bmax=3)
+    check_table(ctx, W, S, bmin=4, bmax=4)
+    check_table(ctx, W, S, bmin=1, bmax=1)
+
+
+def test_scaled_clustering(ctx):
+    W, S = skim_synth.make_ws_small(60, 48, 640)
+    al = skim_synth.make_alpha(3, 640, spread=0.2)
+    ref, out, excused = check_table(ctx, W, S, alpha=al)
+    assert excused <= 1
+    bits = np.full(48, 3, np.uint8)
+    cr = ctx.cluster_rows(dev(W), dev(S), dev(bits), alpha=dev(al))
+    torch.cuda.synchronize()
+    rr = oracle.cluster_rows(W, S, bits, alpha=al, count_near=True)
+    clean = rr["near_rows"] == 0
+    assert np.array_equal(cr["labels"].cpu().numpy()[clean], rr["labels"][clean])
+    # pack with alpha: thresholds live in the scaled domain
+    pk = ctx.pack(dev(W), dev(bits), cr["centroids"], cr["upper"], alpha=dev(al), want_dW=True, bits_host=bits)
+    torch.cuda.synchronize()
+    if clean.all():
+        rp = oracle.pack(W, bits, rr["labels"], rr["centroids"], alpha=al, want_dW=True)
+        assert np.array_equal(pk["codes"].cpu().numpy().view(np.uint32), rp["codes"])
+        assert np.array_equal(pk["codebooks"].cpu().numpy().view(np.uint16), rp["codebooks"])
+        assert np.array_equal(pk["dW"].cpu().numpy(), rp["dW"])
+
+
+def test_row_stride(ctx):
+    W, S = skim_synth.make_ws_small(70, 20, 512)
+    Wd, Sd = dev(W), dev(S)
+    out = ctx.error_table(Wd[:, :300], Sd[:, :300])       # ld = 512, m = 300
+    torch.cuda.synchronize()
+    ref = oracle.error_table(W[:, :300], S[:, :300], count_near=True)
+    clean = ref["near_rows"] == 0
+    assert rel_close(out["E"].cpu().numpy()[clean], ref["E"][clean]).all()
+
+
+def test_pack_mixed_bits_matches_oracle_layout(ctx):
+    n, m = 97, 1111
+    W, S = skim_synth.make_ws_small(80, n, m)
+    bits = np.random.default_rng(0).integers(1, 5, n).astype(np.uint8)
+    cr = ctx.cluster_rows(dev(W), dev(S), dev(bits))
+    torch.cuda.synchronize()
+    rr = oracle.cluster_rows(W, S, bits, count_near=True)
+    pk = ctx.pack(dev(W), dev(bits), cr["centroids"], cr["upper"], bits_host=bits)
+    torch.cuda.synchronize()
+    # pack is compared on the GPU's own labels (isolates the packer from clustering near-ties)
+    rp = oracle.pack(W, bits, cr["labels"].cpu().numpy(), cr["centroids"].cpu().numpy())
+    assert np.array_equal(pk["codes"].cpu().numpy().view(np.uint32), rp["codes"])
+    assert np.array_equal(pk["group_word_offset"].cpu().numpy(), rp["group_word_offset"])
+    assert np.array_equal(pk["row_perm"].cpu().numpy(), rp["row_perm"])
+    assert np.array_equal(pk["codebooks"].cpu().numpy().view(np.uint16), rp["codebooks"])
+    clean = rr["near_rows"] == 0
+    assert np.array_equal(cr["labels"].cpu().numpy()[clean], rr["labels"][clean])
+
+
+def test_argument_errors(ctx, gpu_lib):
+    W, S = skim_synth.make_ws_small(90, 4, 64)
+    with pytest.raises(gpu_lib.SkimError):
+        ctx.error_table(dev(W)[:, :8], dev(S)[:, :8])              # m < 2^bmax
+    with pytest.raises(gpu_lib.SkimError):
+        ctx.error_table(dev(W), dev(S), bmin=0)
+    with pytest.raises(gpu_lib.SkimError):
+        ctx.error_table(dev(W), dev(S), iters=0)
+    big = torch.zeros((1, gpu_lib.MAX_M + 1), dtype=torch.float32, device="cuda")
+    with pytest.raises(gpu_lib.SkimError):
+        ctx.error_table(big, big)
+    with pytest.raises(gpu_lib.SkimError):
+        gpu_lib.greedy_allocate(np.zeros((4, 4)), 5.0)
