@@ -62,10 +62,16 @@ extern "C" const char *skim_last_error(const skim_ctx *ctx) { return ctx ? ctx->
 
 extern "C" size_t skim_workspace_bytes(int64_t n, int64_t m) {
     if (n < 0 || m < 0) return 0;
-    const size_t nm = (size_t)n * (size_t)m;
-    // scale step: dW and P (float32 n x m each), per-row cluster sums (3 x n x 16 float64),
-    // column partials; pack: per-row word/codebook offsets.  Plus alignment slack.
-    return 2 * nm * sizeof(float) + (size_t)n * 16 * 8 * 3 + (size_t)n * 16 + (size_t)m * 8 * 64 + (1u << 16);
+    const size_t N = (size_t)n, M = (size_t)m;
+    const size_t ntile = (M + 127) / 128, nstrip = (N + 15) / 16;
+    size_t b = 0;
+    b += 2 * N * M * sizeof(float);      // scale step: dW and P
+    b += 2 * N * 16 * sizeof(double);    // centroids and masses from fixed labels
+    b += ntile * N * sizeof(double);     // per-tile row sums of the loss
+    b += nstrip * M * sizeof(double);    // per-strip column sums of the gradient
+    b += N * 30 * sizeof(double);        // centroid scratch of skim_error_table when the caller wants none
+    b += N * sizeof(int) + 1024;         // pack: row positions and group table
+    return b + 16 * 256;                 // alignment slack (every piece is 256-byte aligned)
 }
 
 extern "C" skim_status skim_set_workspace(skim_ctx *ctx, void *dev_ptr, size_t bytes) {

@@ -1,13 +1,369 @@
-// placeholder until the contraction kernels land
+// Scaling-vector step of SKIM (Sec. 4.3, Alg. 2 inner loop; Alg. 3 lines 16-22)
+// for gfx950: centroids from fixed labels, the layer-wise (L-full, Sec. 3.4)
+// loss tr(dW H dW^T), its gradient with respect to alpha and the Adam update.
+//
+//   c_ik  = sum_{j in k} s~_ij w~_ij / sum_{j in k} s~_ij      (calc_centroids(W*alpha^-1, L))
+//   dW_ij = w_ij - alpha_j c_{i,L_ij}                           (W - replace(c, L) * alpha)
+//   P     = dW H            fp32 MFMA, fp32 accumulation (the path's one dense contraction)
+//   loss  = sum_ij P_ij dW_ij                                   float64 reduction
+//   dloss/dalpha_l = -2 sum_i [ P_il c_{i,L_il}
+//                    + Q_{i,L_il} s_il (w_il - 2 alpha_l c_{i,L_il}) / D_{i,L_il} ],
+//   Q_ik = sum_{j in k} P_ij alpha_j,  D_ik = sum_{j in k} s~_ij  (gradient through the centroids).
 #include "skim_common.h"
-extern "C" skim_status skim_layer_loss(skim_ctx *ctx, const float *, const float *, const float *, const float *, int64_t,
-                                       int64_t, int64_t, const uint8_t *, double *, double *) {
-    if (!ctx) return SKIM_ERR_ARG;
-    SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_layer_loss: not built yet");
+
+#include <math.h>
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int PREP_THREADS = 256;
+constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int A_STRIDE = BM + 4;   // k-major A tile, padded against bank conflicts of the transposing store
+constexpr int GEMM_THREADS = 256;
+constexpr int STRIP = 16;          // rows per workgroup in the gradient kernel
+
+__device__ __forceinline__ double block_sum_256(double x, double *scratch /* >= 4 doubles */) {
+    for (int d = 32; d >= 1; d >>= 1) x += __shfl_down(x, d, 64);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane == 0) scratch[wave] = x;
+    __syncthreads();
+    return scratch[0] + scratch[1] + scratch[2] + scratch[3];
 }
-extern "C" skim_status skim_scale_step(skim_ctx *ctx, const float *, const float *, const float *, int64_t, int64_t,
-                                       int64_t, const uint8_t *, float *, float *, float *, int64_t,
-                                       const skim_adam_opts *, double *, float *) {
-    if (!ctx) return SKIM_ERR_ARG;
-    SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_scale_step: not built yet");
+
+// Per row: weighted cluster sums with fixed labels -> centroids c (n x 16 float64),
+// masses Den (n x 16 float64), and the row of dW (float32).
+__global__ void __launch_bounds__(PREP_THREADS) row_prep_kernel(const float *W, const float *S, const float *alpha,
+                                                                long long m, long long ld, const uint8_t *labels,
+                                                                double *cent, double *Den, float *dW) {
+    __shared__ double red[2][16][4];
+    __shared__ double csh[16];
+    const long long row = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float *Wr = W + row * ld, *Sr = S + row * ld;
+    const uint8_t *Lr = labels + row * m;
+    double accD[16], accN[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) accD[k] = accN[k] = 0.0;
+    for (long long j = tid; j < m; j += PREP_THREADS) {
+        float wt = Wr[j], st = Sr[j];
+        if (alpha) {
+            const float a = alpha[j];
+            wt = __fdiv_rn(wt, a);
+            st = __fmul_rn(__fmul_rn(st, a), a);
+        }
+        const int l = Lr[j] & 15;
+        const double s = (double)st, sw = (double)st * (double)wt;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            accD[k] += (l == k) ? s : 0.0;
+            accN[k] += (l == k) ? sw : 0.0;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        double d = accD[k], nn = accN[k];
+        for (int o = 32; o >= 1; o >>= 1) {
+            d += __shfl_down(d, o, 64);
+            nn += __shfl_down(nn, o, 64);
+        }
+        if (lane == 0) {
+            red[0][k][wave] = d;
+            red[1][k][wave] = nn;
+        }
+    }
+    __syncthreads();
+    if (tid < 16) {
+        const double d = red[0][tid][0] + red[0][tid][1] + red[0][tid][2] + red[0][tid][3];
+        const double nn = red[1][tid][0] + red[1][tid][1] + red[1][tid][2] + red[1][tid][3];
+        const double c = d > 0.0 ? nn / d : 0.0;
+        csh[tid] = c;
+        cent[row * 16 + tid] = c;
+        Den[row * 16 + tid] = d;
+    }
+    __syncthreads();
+    for (long long j = tid; j < m; j += PREP_THREADS) {
+        const double a = alpha ? (double)alpha[j] : 1.0;
+        dW[row * m + j] = (float)((double)Wr[j] - a * csh[Lr[j] & 15]);
+    }
+}
+
+// P = dW * H on fp32 MFMA (v_mfma_f32_32x32x2_f32), 128 x 128 output tile per
+// workgroup, four wavefronts in a 2 x 2 arrangement of 64 x 64 sub-tiles.
+// Epilogue: optional store of P and, per output row, sum_j P_ij dW_ij over the
+// tile's columns in float64 -> partial[tile_col][row].
+template <bool STORE_P>
+__global__ void __launch_bounds__(GEMM_THREADS) dwh_gemm_kernel(const float *__restrict__ A, const float *__restrict__ H,
+                                                                int n, int m, float *__restrict__ P,
+                                                                double *__restrict__ partial) {
+    __shared__ float As[2][BK][A_STRIDE];
+    __shared__ float Bs[2][BK][BN];
+    __shared__ double rsum[2][BM];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
+    const int row0 = blockIdx.y * BM, col0 = blockIdx.x * BN;
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    // global -> register staging: A tile 128 x 16 (two float4 per thread), B tile 16 x 128 (two float4)
+    const int a_r = tid >> 2, a_k = (tid & 3) * 4;     // rows a_r and a_r + 64
+    const int b_k = tid >> 5, b_c = (tid & 31) * 4;    // k rows b_k and b_k + 8
+    float4 ra[2], rb[2];
+    auto load_tiles = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int r = row0 + a_r + 64 * i;
+            ra[i] = (r < n) ? *(const float4 *)(A + (long long)r * m + k0 + a_k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            const int c = col0 + b_c;
+            const float *src = H + (long long)(k0 + b_k + 8 * i) * m + c;
+            if (c + 3 < m) {
+                rb[i] = *(const float4 *)src;
+            } else {
+                rb[i].x = (c + 0 < m) ? src[0] : 0.f;
+                rb[i].y = (c + 1 < m) ? src[1] : 0.f;
+                rb[i].z = (c + 2 < m) ? src[2] : 0.f;
+                rb[i].w = 0.f;
+            }
+        }
+    };
+    auto store_tiles = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int r = a_r + 64 * i;
+            As[buf][a_k + 0][r] = ra[i].x;
+            As[buf][a_k + 1][r] = ra[i].y;
+            As[buf][a_k + 2][r] = ra[i].z;
+            As[buf][a_k + 3][r] = ra[i].w;
+            *(float4 *)&Bs[buf][b_k + 8 * i][b_c] = rb[i];
+        }
+    };
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const int nk = m / BK;
+    load_tiles(0);
+    store_tiles(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) load_tiles((kt + 1) * BK);
+#pragma unroll
+        for (int kp = 0; kp < BK / 2; ++kp) {
+            const int k = 2 * kp + lhi;
+            const float a0 = As[buf][k][wr * 64 + l32];
+            const float a1 = As[buf][k][wr * 64 + 32 + l32];
+            const float b0 = Bs[buf][k][wc * 64 + l32];
+            const float b1 = Bs[buf][k][wc * 64 + 32 + l32];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+        if (kt + 1 < nk) store_tiles(buf ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue.  Accumulator element e of a 32 x 32 tile: row = 8*(e/4) + 4*(lane/32) + e%4, column = lane%32.
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int rl = wr * 64 + i * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
+            const int r = row0 + rl;
+            double t = 0.0;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int c = col0 + wc * 64 + j * 32 + l32;
+                if (r < n && c < m) {
+                    const float p = acc[i][j][e];
+                    if (STORE_P) P[(long long)r * m + c] = p;
+                    t += (double)p * (double)A[(long long)r * m + c];
+                }
+            }
+            // sum over the 32 lanes that share this row
+            for (int o = 16; o >= 1; o >>= 1) t += __shfl_xor(t, o, 64);
+            if (l32 == 0) rsum[wc][rl] = t;
+        }
+    }
+    __syncthreads();
+    if (tid < BM && row0 + tid < n) partial[(long long)blockIdx.x * n + row0 + tid] = rsum[0][tid] + rsum[1][tid];
+}
+
+// row_loss[i] = sum over column tiles; loss = sum_i row_loss[i] (single workgroup, fixed order).
+__global__ void __launch_bounds__(1024) loss_finish_kernel(const double *partial, int ntile, long long n, double *loss,
+                                                           double *row_loss) {
+    __shared__ double sh[16];
+    double acc = 0.0;
+    for (long long i = threadIdx.x; i < n; i += 1024) {
+        double r = 0.0;
+        for (int t = 0; t < ntile; ++t) r += partial[(long long)t * n + i];
+        if (row_loss) row_loss[i] = r;
+        acc += r;
+    }
+    for (int d = 32; d >= 1; d >>= 1) acc += __shfl_down(acc, d, 64);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double s = 0.0;
+        for (int w = 0; w < 16; ++w) s += sh[w];
+        *loss = s;
+    }
+}
+
+// Gradient terms.  One workgroup walks STRIP consecutive rows; per row it forms
+// Q_ik = sum_{j in k} P_ij alpha_j, then adds each column's term to the thread's
+// private column sums.  gpart[strip][l] is reduced over the strips afterwards.
+__global__ void __launch_bounds__(PREP_THREADS) grad_rows_kernel(const float *W, const float *S, const float *alpha,
+                                                                 long long n, long long m, long long ld,
+                                                                 const uint8_t *labels, const float *P,
+                                                                 const double *cent, const double *Den,
+                                                                 double *gpart) {
+    __shared__ double red[16][4];
+    __shared__ double qsh[16], csh[16], dsh[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long long r0 = (long long)blockIdx.x * STRIP;
+    double *gp = gpart + (long long)blockIdx.x * m;
+    for (long long l = tid; l < m; l += PREP_THREADS) gp[l] = 0.0;
+    for (long long row = r0; row < min(n, r0 + STRIP); ++row) {
+        const float *Pr = P + row * m;
+        const uint8_t *Lr = labels + row * m;
+        double q[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) q[k] = 0.0;
+        for (long long j = tid; j < m; j += PREP_THREADS) {
+            const double pa = (double)Pr[j] * (double)alpha[j];
+            const int l = Lr[j] & 15;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) q[k] += (l == k) ? pa : 0.0;
+        }
+        __syncthreads();  // previous row's qsh/csh/dsh are no longer read
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            double x = q[k];
+            for (int o = 32; o >= 1; o >>= 1) x += __shfl_down(x, o, 64);
+            if (lane == 0) red[k][wave] = x;
+        }
+        __syncthreads();
+        if (tid < 16) {
+            qsh[tid] = red[tid][0] + red[tid][1] + red[tid][2] + red[tid][3];
+            csh[tid] = cent[row * 16 + tid];
+            dsh[tid] = Den[row * 16 + tid];
+        }
+        __syncthreads();
+        const float *Wr = W + row * ld, *Sr = S + row * ld;
+        for (long long l = tid; l < m; l += PREP_THREADS) {
+            const int k = Lr[l] & 15;
+            const double a = (double)alpha[l], c = csh[k], d = dsh[k];
+            double term = (double)Pr[l] * c;
+            if (d > 0.0) term += qsh[k] * (double)Sr[l] * ((double)Wr[l] - 2.0 * a * c) / d;
+            gp[l] += -2.0 * term;   // the same thread owns column l for every row of the strip
+        }
+    }
+}
+
+__global__ void adam_kernel(const double *gpart, int nstrip, long long m, float *alpha, float *am, float *av,
+                            float lr, float beta1, float beta2, float eps, float bc1, float bc2, float *grad_out) {
+    const long long l = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (l >= m) return;
+    double g64 = 0.0;
+    for (int s = 0; s < nstrip; ++s) g64 += gpart[(long long)s * m + l];
+    const float g = (float)g64;
+    if (grad_out) grad_out[l] = g;
+    const float m1 = beta1 * am[l] + (1.0f - beta1) * g;
+    const float v1 = beta2 * av[l] + (1.0f - beta2) * g * g;
+    am[l] = m1;
+    av[l] = v1;
+    const float mh = m1 / bc1, vh = v1 / bc2;
+    alpha[l] = alpha[l] - lr * mh / (sqrtf(vh) + eps);
+}
+
+struct LossWs {
+    float *dW, *P;
+    double *cent, *Den, *partial, *gpart;
+    int ntile, nstrip;
+};
+
+skim_status carve(skim_ctx *ctx, int64_t n, int64_t m, bool need_grad, LossWs &w) {
+    skim_ws_cursor cur{(char *)ctx->ws, 0, ctx->ws_bytes};
+    w.ntile = (int)((m + BN - 1) / BN);
+    w.nstrip = (int)((n + STRIP - 1) / STRIP);
+    w.dW = (float *)cur.take((size_t)n * m * sizeof(float));
+    w.cent = (double *)cur.take((size_t)n * 16 * sizeof(double));
+    w.Den = (double *)cur.take((size_t)n * 16 * sizeof(double));
+    w.partial = (double *)cur.take((size_t)w.ntile * n * sizeof(double));
+    w.P = nullptr;
+    w.gpart = nullptr;
+    bool ok = w.dW && w.cent && w.Den && w.partial;
+    if (need_grad) {
+        w.P = (float *)cur.take((size_t)n * m * sizeof(float));
+        w.gpart = (double *)cur.take((size_t)w.nstrip * m * sizeof(double));
+        ok = ok && w.P && w.gpart;
+    }
+    if (!ok) SKIM_FAIL(ctx, SKIM_ERR_WORKSPACE, "workspace missing or smaller than skim_workspace_bytes(n, m)");
+    return SKIM_OK;
+}
+
+skim_status check_shape(skim_ctx *ctx, int64_t n, int64_t m, int64_t ld) {
+    if (n < 1 || n > 0x7fffffff || m < BK || m > 0x7fffffff || ld < m || (m % BK) != 0)
+        SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "layer loss needs n >= 1, m a multiple of %d, ld >= m (n=%lld m=%lld ld=%lld)", BK,
+                  (long long)n, (long long)m, (long long)ld);
+    return SKIM_OK;
+}
+
+}  // namespace
+
+extern "C" skim_status skim_layer_loss(skim_ctx *ctx, const float *W, const float *S, const float *alpha,
+                                       const float *H, int64_t n, int64_t m, int64_t ld, const uint8_t *labels,
+                                       double *loss, double *row_loss) {
+    skim_status st = skim_enter(ctx);
+    if (st != SKIM_OK) return st;
+    if (!W || !S || !H || !labels || !loss) SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_layer_loss: NULL argument");
+    if ((st = check_shape(ctx, n, m, ld)) != SKIM_OK) return st;
+    if ((uintptr_t)H & 15) SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_layer_loss: H must be 16-byte aligned");
+    LossWs w;
+    if ((st = carve(ctx, n, m, false, w)) != SKIM_OK) return st;
+    hipLaunchKernelGGL(row_prep_kernel, dim3((unsigned)n), dim3(PREP_THREADS), 0, ctx->stream, W, S, alpha, (long long)m,
+                       (long long)ld, labels, w.cent, w.Den, w.dW);
+    hipLaunchKernelGGL(dwh_gemm_kernel<false>, dim3(w.ntile, (unsigned)((n + BM - 1) / BM)), dim3(GEMM_THREADS), 0,
+                       ctx->stream, w.dW, H, (int)n, (int)m, (float *)nullptr, w.partial);
+    hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(1024), 0, ctx->stream, w.partial, w.ntile, (long long)n, loss,
+                       row_loss);
+    SKIM_HIP(ctx, hipGetLastError());
+    return SKIM_OK;
+}
+
+extern "C" skim_status skim_scale_step(skim_ctx *ctx, const float *W, const float *S, const float *H, int64_t n,
+                                       int64_t m, int64_t ld, const uint8_t *labels, float *alpha, float *adam_m,
+                                       float *adam_v, int64_t t, const skim_adam_opts *opts, double *loss_before,
+                                       float *grad_out) {
+    skim_status st = skim_enter(ctx);
+    if (st != SKIM_OK) return st;
+    if (!W || !S || !H || !labels || !alpha || !adam_m || !adam_v || !opts || !loss_before)
+        SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_scale_step: NULL argument");
+    if (t < 1 || opts->decay_every < 1) SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_scale_step: t and decay_every must be >= 1");
+    if ((st = check_shape(ctx, n, m, ld)) != SKIM_OK) return st;
+    if ((uintptr_t)H & 15) SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_scale_step: H must be 16-byte aligned");
+    LossWs w;
+    if ((st = carve(ctx, n, m, true, w)) != SKIM_OK) return st;
+    hipLaunchKernelGGL(row_prep_kernel, dim3((unsigned)n), dim3(PREP_THREADS), 0, ctx->stream, W, S, (const float *)alpha,
+                       (long long)m, (long long)ld, labels, w.cent, w.Den, w.dW);
+    hipLaunchKernelGGL(dwh_gemm_kernel<true>, dim3(w.ntile, (unsigned)((n + BM - 1) / BM)), dim3(GEMM_THREADS), 0,
+                       ctx->stream, w.dW, H, (int)n, (int)m, w.P, w.partial);
+    hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(1024), 0, ctx->stream, w.partial, w.ntile, (long long)n,
+                       loss_before, (double *)nullptr);
+    hipLaunchKernelGGL(grad_rows_kernel, dim3(w.nstrip), dim3(PREP_THREADS), 0, ctx->stream, W, S, (const float *)alpha,
+                       (long long)n, (long long)m, (long long)ld, labels, w.P, w.cent, w.Den, w.gpart);
+    const double lr = (double)opts->lr0 * pow((double)opts->decay, (double)((t - 1) / opts->decay_every));
+    const double bc1 = 1.0 - pow((double)opts->beta1, (double)t), bc2 = 1.0 - pow((double)opts->beta2, (double)t);
+    hipLaunchKernelGGL(adam_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, ctx->stream, w.gpart, w.nstrip,
+                       (long long)m, alpha, adam_m, adam_v, (float)lr, opts->beta1, opts->beta2, opts->eps, (float)bc1,
+                       (float)bc2, grad_out);
+    SKIM_HIP(ctx, hipGetLastError());
+    return SKIM_OK;
 }

@@ -1,0 +1,111 @@
+"""GPU parity: layer loss tr(dW H dW^T), scale gradient and Adam step against the CPU oracle.
+
+Bar (the benchmark spec): loss, per-row loss, gradient and updated alpha within 1e-5
+relative.  The contraction runs on fp32 MFMA with fp32 accumulation; the
+oracle is float64 throughout.  Parity is per call on identical inputs: the
+oracle is fed the same W, S, H, labels and alpha as the GPU.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import skim_synth
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def ctx(gpu_lib):
+    c = gpu_lib.Context(0)
+    yield c
+    c.close()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def make_case(seed, n, m, K, N=None, with_alpha=True):
+    W, S = skim_synth.make_ws_small(seed, n, m)
+    S = S + np.float32(0.01)
+    rng = np.random.default_rng(seed)
+    labels = rng.integers(0, K, (n, m)).astype(np.uint8)
+    H = skim_synth.make_h_host(3, N or 4 * m, m)
+    H = ((H + H.T) / 2).astype(np.float32)
+    al = skim_synth.make_alpha(seed, m) if with_alpha else None
+    return W, S, labels, H, al
+
+
+@pytest.mark.parametrize("n,m,K", [(1, 16, 2), (37, 48, 4), (130, 144, 8), (257, 272, 16), (128, 512, 16), (300, 1024, 8)])
+@pytest.mark.parametrize("with_alpha", [False, True])
+def test_layer_loss_matches_oracle(ctx, n, m, K, with_alpha):
+    W, S, labels, H, al = make_case(n + m, n, m, K, with_alpha=with_alpha)
+    out = ctx.layer_loss(dev(W), dev(S), dev(H), dev(labels), alpha=None if al is None else dev(al))
+    torch.cuda.synchronize()
+    c, D = oracle.centroids_from_labels(W, S, labels, al)
+    ref = oracle.layer_loss(W, H, labels, c, al)
+    assert out["loss"].item() == pytest.approx(ref["loss"], rel=RTOL)
+    got = out["row_loss"].cpu().numpy()
+    assert np.all(np.abs(got - ref["row_loss"]) <= RTOL * np.abs(ref["row_loss"]) + 1e-9 * ref["loss"] / n)
+
+
+def test_layer_loss_identity_and_diagonal_hessian(ctx):
+    n, m = 64, 256
+    W, S, labels, H, al = make_case(5, n, m, 8)
+    c, D = oracle.centroids_from_labels(W, S, labels, al)
+    dWd = W.astype(np.float64) - al.astype(np.float64)[None, :] * np.take_along_axis(c, labels.astype(np.int64), 1)
+    out = ctx.layer_loss(dev(W), dev(S), dev(np.eye(m, dtype=np.float32)), dev(labels), alpha=dev(al))
+    torch.cuda.synchronize()
+    assert out["loss"].item() == pytest.approx((dWd ** 2).sum(), rel=RTOL)
+    h = np.random.default_rng(0).uniform(0.5, 2, m).astype(np.float32)
+    out = ctx.layer_loss(dev(W), dev(S), dev(np.diag(h)), dev(labels), alpha=dev(al))
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out["row_loss"].cpu().numpy(), (h.astype(np.float64)[None, :] * dWd ** 2).sum(1), rtol=RTOL)
+
+
+@pytest.mark.parametrize("n,m,K", [(5, 32, 4), (40, 144, 8), (130, 512, 16)])
+@pytest.mark.parametrize("t_step", [1, 41])
+def test_scale_step_matches_oracle(ctx, gpu_lib, n, m, K, t_step):
+    W, S, labels, H, al = make_case(100 + n, n, m, K)
+    rng = np.random.default_rng(n)
+    m1 = (rng.standard_normal(m) * 1e-3).astype(np.float32) if t_step > 1 else np.zeros(m, np.float32)
+    m2 = (rng.uniform(0, 1e-6, m)).astype(np.float32) if t_step > 1 else np.zeros(m, np.float32)
+    d_al, d_m1, d_m2 = dev(al), dev(m1), dev(m2)
+    out = ctx.scale_step(dev(W), dev(S), dev(H), dev(labels), d_al, d_m1, d_m2, t_step)
+    torch.cuda.synchronize()
+    ref = oracle.scale_grad(W, S, H, labels, al)
+    assert out["loss_before"].item() == pytest.approx(ref["loss"], rel=RTOL)
+    g = out["grad"].cpu().numpy().astype(np.float64)
+    gscale = np.abs(ref["grad"]).max()
+    assert np.all(np.abs(g - ref["grad"]) <= RTOL * np.abs(ref["grad"]) + 1e-6 * gscale)
+    # optimiser step on the GPU's own gradient (identical inputs on both sides)
+    # the ABI carries the hyper-parameters as float32: the oracle gets the same rounded values
+    f32 = lambda x: float(np.float32(x))
+    a_ref, m1_ref, m2_ref = oracle.adam_step(al, m1, m2, g, t_step, lr0=f32(0.01), beta1=f32(0.9), beta2=f32(0.999),
+                                             eps=f32(1e-8), decay=f32(0.5), decay_every=40)
+    np.testing.assert_allclose(d_al.cpu().numpy(), a_ref, rtol=RTOL)
+    np.testing.assert_allclose(d_m1.cpu().numpy(), m1_ref, rtol=RTOL, atol=1e-6 * np.abs(m1_ref).max())
+    np.testing.assert_allclose(d_m2.cpu().numpy(), m2_ref, rtol=RTOL, atol=1e-6 * np.abs(m2_ref).max())
+
+
+def test_loss_after_clustering_equals_sdiag_error_when_hessian_is_diagonal(ctx):
+    """With H = diag(s_i) the L-full error of a row is its S-diag error; here S is shared by
+    all rows so that one H serves every row (ties Sec. 3.3 and 3.4 together end to end)."""
+    n, m = 32, 512
+    W, _ = skim_synth.make_ws_small(11, n, m)
+    s_row = (np.random.default_rng(1).standard_t(3, m) ** 2).astype(np.float32)
+    S = np.ascontiguousarray(np.broadcast_to(s_row, (n, m)))
+    bits = np.full(n, 3, np.uint8)
+    cr = ctx.cluster_rows(dev(W), dev(S), dev(bits))
+    out = ctx.layer_loss(dev(W), dev(S), dev(np.diag(s_row)), cr["labels"])
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out["row_loss"].cpu().numpy(), cr["err"].cpu().numpy(), rtol=1e-5)
+
+
+def test_loss_argument_errors(ctx, gpu_lib):
+    W, S, labels, H, al = make_case(1, 4, 24, 2)     # m not a multiple of 16
+    with pytest.raises(gpu_lib.SkimError):
+        ctx.layer_loss(dev(W), dev(S), dev(H), dev(labels))
