@@ -1,0 +1,246 @@
+#!/usr/bin/env python3
+"""Benchmark of the SKIM hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One step = one pass of the hot path over the metric layer (LLaMA-7B down-projection
+shape, 4096 x 11008 fp32, synthetic): error table for b = 1..4 (30 Lloyd iterations)
+-> copy of the table to the host -> greedy allocation to 3.2 average bits -> copy of
+the bit widths back -> selection of the allocated clusterings -> packing (codes +
+fp16 codebooks).  Inputs are resident in HBM before the timed region.  Prints ONE
+JSON line ("Measurement").
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+N_ROWS, M_COLS = 4096, 11008
+AVG_BITS = 3.2
+ITERS = 30
+HBM_PEAK_GBS = 8000.0
+# 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one non-packed 32-bit VALU lane-operation per lane per clock
+ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+MFMA_F32_PEAK_TFLOPS = 157.3
+
+
+def alg_lane_ops_per_row(m: int) -> float:
+    """Comparison-sort lower bound of the sorted formulation: m*log2(m) compare-exchanges of
+    (key, payload) pairs at 5 VALU lane-operations each (compare + 4 selects)."""
+    import math
+
+    return 5.0 * m * math.log2(m)
+
+
+def read_traffic():
+    """HBM bytes per launch of the clustering kernel from the committed rocprofv3 counter summary."""
+    p = os.path.join(ROOT, "profiles", "cluster_kernel_4096x11008_hbm_traffic.txt")
+    try:
+        for line in open(p):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-scale-loop", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(no sharding or collectives are part of it)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2412_04180_amd as skim
+    import skim_synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+
+    ctx = skim.Context(0)
+    stream = ctx.stream
+    n, m = N_ROWS, M_COLS
+    W_h, S_h = skim_synth.make_ws(2, 2)           # config 2, third matrix: 4096 x 11008
+    assert W_h.shape == (n, m)
+    W = torch.from_numpy(W_h).cuda()
+    S = torch.from_numpy(S_h).cuda()
+
+    table = dict(E=ctx.empty((n, 4), torch.float64), centroids_all=ctx.empty((n, 30), torch.float64),
+                 upper_all=ctx.empty((n, 30), torch.float32))
+    E_host = torch.empty((n, 4), dtype=torch.float64, pin_memory=True)
+    bits_host_t = torch.empty((n,), dtype=torch.uint8, pin_memory=True)
+    bits_dev = ctx.empty((n,), torch.uint8)
+    ctx.ensure_workspace(n, m)
+
+    ev_a = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ev_b = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ev_c = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ev_d = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    t_alloc = [0.0]
+
+    def step(i=None):
+        if i is not None:
+            ev_a[i].record(stream)
+        ctx.error_table(W, S, iters=ITERS, out=table)
+        if i is not None:
+            ev_b[i].record(stream)
+        E_host.copy_(table["E"], non_blocking=True)
+        stream.synchronize()
+        t0 = time.perf_counter()
+        bits, spent, budget = skim.greedy_allocate(E_host.numpy(), AVG_BITS)
+        t_alloc[0] += time.perf_counter() - t0
+        bits_host_t.numpy()[:] = bits
+        bits_dev.copy_(bits_host_t, non_blocking=True)
+        if i is not None:
+            ev_c[i].record(stream)
+        sel = ctx.select_allocated(bits_dev, table)
+        pk = ctx.pack(W, bits_dev, sel["centroids"], sel["upper"], bits_host=bits)
+        if i is not None:
+            ev_d[i].record(stream)
+        return bits, spent, budget, pk
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_alloc[0] = 0.0
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        bits, spent, budget, pk = step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    total_s = t1 - t0
+    ms_per_step = total_s / args.steps * 1e3
+    ms_table = sum(a.elapsed_time(b) for a, b in zip(ev_a, ev_b)) / args.steps
+    ms_pack = sum(a.elapsed_time(b) for a, b in zip(ev_c, ev_d)) / args.steps
+    ms_alloc = t_alloc[0] / args.steps * 1e3
+
+    rows_per_s = n / (ms_per_step * 1e-3)
+    alg_ops = alg_lane_ops_per_row(m) * n
+    achieved_alu = alg_ops / (ms_table * 1e-3) / 1e12
+    alg_bytes = 8.0 * n * m
+    hbm_gbs = alg_bytes / (ms_table * 1e-3) / 1e9
+    roofline = {
+        "bound": "alu", "kernel": "cluster_kernel (skim_error_table)",
+        "achieved": round(achieved_alu, 4), "peak": round(ALU_PEAK_TLANEOPS, 2), "unit": "Tlaneop/s",
+        "frac": round(achieved_alu / ALU_PEAK_TLANEOPS, 5),
+        "traffic": read_traffic(),
+        "kernel_ms": round(ms_table, 4),
+        "algorithmic_lane_ops_per_launch": alg_ops,
+        "hbm_algorithmic_bytes_per_launch": alg_bytes,
+        "hbm_achieved_GBps": round(hbm_gbs, 1), "hbm_frac": round(hbm_gbs / HBM_PEAK_GBS, 5),
+    }
+
+    out = {
+        "metric": "rows/s for b=1..4 K-means error table, 4096x11008 fp32; % of roofline",
+        "value": round(rows_per_s, 1), "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "config 2, matrix 2: LLaMA-7B down_proj shape 4096x11008 fp32; error table b=1..4, "
+                               "30 Lloyd iterations, greedy allocation to 3.2 bits, pack with fp16 codebooks",
+                   "rows": n, "cols": m, "avg_bits": AVG_BITS, "iters": ITERS},
+        "weights_per_s": round(rows_per_s * m, 1),
+        "error_table_only_rows_per_s": round(n / (ms_table * 1e-3), 1),
+        "breakdown_ms": {"error_table_kernel": round(ms_table, 4), "greedy_host": round(ms_alloc, 4),
+                         "select_and_pack": round(ms_pack, 4)},
+        "allocation": {"spent": int(spent), "budget": int(budget),
+                       "rows_per_bit": np.bincount(bits, minlength=5)[1:].tolist()},
+        "roofline": roofline,
+    }
+
+    if not args.no_scale_loop:
+        out["scale_loop"] = bench_scale_loop(ctx, torch, np, skim_synth)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(W_h, S_h, np)
+    print(json.dumps(out))
+
+
+def bench_scale_loop(ctx, torch, np, skim_synth, iters=3):
+    """Config-3 shape (4096 x 4096, H 4096^2): one iteration = scale step (loss + gradient + Adam),
+    re-clustering at 3 bits, layer loss.  H here is X^T X / N from 8192 synthetic activations."""
+    n = m = 4096
+    W_h, S_h = skim_synth.make_ws(3, 0)
+    W, S = torch.from_numpy(W_h).cuda(), torch.from_numpy(S_h).cuda()
+    acc = torch.zeros((m, m), dtype=torch.float32, device="cuda")
+    N = 8192
+    for x in skim_synth.make_x(3, N, m, chunk=4096):
+        xd = torch.from_numpy(x).cuda()
+        acc += xd.T @ xd
+    H = (acc / N).contiguous()
+    H = ((H + H.T) / 2).contiguous()
+    bits = torch.full((n,), 3, dtype=torch.uint8, device="cuda")
+    alpha = torch.ones(m, device="cuda")
+    am, av = torch.zeros(m, device="cuda"), torch.zeros(m, device="cuda")
+    cr = ctx.cluster_rows(W, S, bits, alpha=alpha)
+    ctx.ensure_workspace(n, m)
+    ctx.scale_step(W, S, H, cr["labels"], alpha, am, av, 1)
+    ctx.layer_loss(W, S, H, cr["labels"], alpha=alpha)
+    torch.cuda.synchronize()
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    t_step = t_cluster = t_loss = 0.0
+    losses = []
+    for it in range(iters):
+        e[0].record(ctx.stream)
+        o = ctx.scale_step(W, S, H, cr["labels"], alpha, am, av, it + 2)
+        e[1].record(ctx.stream)
+        cr = ctx.cluster_rows(W, S, bits, alpha=alpha, out=cr)
+        e[2].record(ctx.stream)
+        l = ctx.layer_loss(W, S, H, cr["labels"], alpha=alpha, want_row_loss=False)
+        e[3].record(ctx.stream)
+        torch.cuda.synchronize()
+        t_step += e[0].elapsed_time(e[1])
+        t_cluster += e[1].elapsed_time(e[2])
+        t_loss += e[2].elapsed_time(e[3])
+        losses.append(l["loss"].item())
+    flops = 2.0 * n * m * m
+    return {"workload": "4096x4096, H 4096^2, 3 bits", "scale_step_ms": round(t_step / iters, 4),
+            "recluster_ms": round(t_cluster / iters, 4), "layer_loss_ms": round(t_loss / iters, 4),
+            "layer_loss_tflops": round(flops / (t_loss / iters * 1e-3) / 1e12, 2),
+            "mfma_f32_peak_tflops": MFMA_F32_PEAK_TFLOPS,
+            "layer_loss_frac_of_mfma_peak": round(flops / (t_loss / iters * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS, 4),
+            "loss_after_each_iteration": losses}
+
+
+def cpu_baseline(W_h, S_h, np, target_s=12.0):
+    """The fp64 oracle, as it stands, on the host cores of this machine, on the first R rows of the same
+    matrix (R sized for about target_s seconds): error table b = 1..4, greedy, labels, pack."""
+    import oracle
+
+    n = W_h.shape[0]
+    probe = 128
+    t0 = time.perf_counter()
+    oracle.error_table(W_h[:probe], S_h[:probe])
+    rate = probe / (time.perf_counter() - t0)
+    R = int(min(n, max(probe, rate * target_s * 0.75)))
+    Ws, Ss = np.ascontiguousarray(W_h[:R]), np.ascontiguousarray(S_h[:R])
+    t0 = time.perf_counter()
+    tab = oracle.error_table(Ws, Ss)
+    t_tab = time.perf_counter() - t0
+    g = oracle.greedy(tab["E"], AVG_BITS)
+    cr = oracle.cluster_rows(Ws, Ss, g["bits"])
+    oracle.pack(Ws, g["bits"], cr["labels"], cr["centroids"])
+    t_all = time.perf_counter() - t0
+    return {"value": round(R / t_all, 2), "unit": "rows/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {R} of {n} rows of the same 4096x11008 matrix: error table b=1..4 (30 iterations), "
+                      f"greedy 3.2 bits, labels at the allocated widths, pack",
+            "error_table_only_rows_per_s": round(R / t_tab, 2), "seconds": round(t_all, 2)}
+
+
+if __name__ == "__main__":
+    main()

@@ -588,7 +588,7 @@ int oracle_layer_loss(const float *W, const float *alpha, const float *H, int64_
 int oracle_scale_grad(const float *W, const float *S, const float *alpha, const float *H, int64_t n,
                       int64_t m, int64_t ld, const uint8_t *labels, double *loss, double *grad,
                       double *c_out) {
-    double *c = (double *)malloc((size_t)n * 16 * sizeof(double));
+    double *c = (double *)calloc((size_t)n * 16 + 1, sizeof(double));
     double *Dn = (double *)malloc((size_t)n * 16 * sizeof(double));
     double *P = (double *)malloc((size_t)n * (size_t)m * sizeof(double));
     for (int64_t i = 0; i < n; ++i) {

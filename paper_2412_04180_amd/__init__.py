@@ -46,6 +46,10 @@ def load_library():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2412_04180_amd._build` "
                                "(there is no fallback path)")
+        # torch owns device memory and streams: load it first so that the library binds to the
+        # HIP runtime torch has already loaded (one runtime per process)
+        import torch  # noqa: F401
+
         lib = C.CDLL(LIB_PATH)
         vp, i64, i32, dbl = C.c_void_p, C.c_int64, C.c_int, C.c_double
         lib.skim_create.argtypes = [C.POINTER(vp), i32, vp]
