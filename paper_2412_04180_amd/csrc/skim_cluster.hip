@@ -23,7 +23,8 @@ typedef unsigned long long u64;
 namespace {
 
 constexpr int EPT = 16;           // sorted elements owned by one thread
-constexpr int MIN_THREADS = 256;  // four wavefronts: one per bit width in the Lloyd phase
+constexpr int MIN_THREADS = 256;
+constexpr unsigned long long NEUTRAL_KEY = 0x8000000000000000ull;  // encodes (w = +0, s = +0)  // four wavefronts: one per bit width in the Lloyd phase
 
 struct ClusterParams {
     const float *W, *S, *alpha;
@@ -172,6 +173,28 @@ __device__ void sort_row(u64 *lds, int logP, uint32_t tid) {
 
 __device__ __forceinline__ double shfl_d(double x, int src) { return __shfl(x, src, 64); }
 
+// Cross-lane moves that stay inside the VALU (DPP): lane i reads lane i^1, lane i^2, its
+// mirror inside its group of 8, its mirror inside its row of 16.
+template <int CTRL>
+__device__ __forceinline__ double dpp_move_d(double x) {
+    int lo = __double2loint(x), hi = __double2hiint(x);
+    lo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xF, 0xF, false);
+    hi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+// Sum over the G consecutive lanes of a group; every lane of the group gets the same bits
+// (each step adds a lane's value and its partner's, and the partner adds the same two).
+template <int G>
+__device__ __forceinline__ double group_sum(double x) {
+    if (G >= 2) x += dpp_move_d<0xB1>(x);    // quad_perm [1,0,3,2]
+    if (G >= 4) x += dpp_move_d<0x4E>(x);    // quad_perm [2,3,0,1]
+    if (G >= 8) x += dpp_move_d<0x141>(x);   // row_half_mirror
+    if (G >= 16) x += dpp_move_d<0x140>(x);  // row_mirror
+    if (G >= 32) x += __shfl_xor(x, 16, 64);
+    return x;
+}
+
 // Sums of s and s*w over the sorted ranks [a, b), shared out over the G lanes of
 // a group (lane g) and reduced so that every lane of the group gets the result.
 // The range is cut into aligned pieces whose sums were each formed from their
@@ -179,54 +202,49 @@ __device__ __forceinline__ double shfl_d(double x, int src) { return __shfl(x, s
 // nothing outside [a, b) enters, so a cluster of tiny weight mass next to a
 // heavy element keeps full relative precision (a difference of running prefix
 // sums would not).
+template <int G>
 __device__ __forceinline__ void range_sum(const u64 *sorted, const double2 *csum, const double2 *bsum, int a,
-                                          int b, int g, int G, double &D, double &N) {
+                                          int b, int g, double &D, double &N) {
+    constexpr int T = (16 + G - 1) / G;   // loads per lane that cover one 16-wide piece
+    // piece boundaries: elements [a, e0) and [e1, b); chunks [c0, c1) and [c2, c3); blocks [b0, b1)
+    const int e0 = min(b, (a + 15) & ~15);
+    const int e1 = max(e0, b & ~15);
+    const int c0 = e0 >> 4, c3 = e1 >> 4;
+    const int c1 = (c0 < c3) ? min(c3, (c0 + 15) & ~15) : c0;
+    const int c2 = (c0 < c3) ? max(c1, c3 & ~15) : c0;
+    const int b0 = c1 >> 4, b1 = (c0 < c3) ? (c2 >> 4) : b0;
+    // issue every load first (predicated), then add in a fixed order: one LDS round trip
+    u64 el[2 * T];
+    double2 ch[2 * T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const int r0 = a + g + t * G, r1 = e1 + g + t * G;
+        el[t] = (r0 < e0) ? sorted[swz((uint32_t)r0)] : NEUTRAL_KEY;
+        el[T + t] = (r1 < b) ? sorted[swz((uint32_t)r1)] : NEUTRAL_KEY;
+        const int q0 = c0 + g + t * G, q1 = c2 + g + t * G;
+        ch[t] = (q0 < c1) ? csum[q0] : make_double2(0.0, 0.0);
+        ch[T + t] = (q1 < c3 && c0 < c3) ? csum[q1] : make_double2(0.0, 0.0);
+    }
     double d = 0.0, n = 0.0;
-    {   // single elements up to the first / from the last chunk boundary
-        const int lo_end = min(b, (a + 15) & ~15);
-        for (int r = a + g; r < lo_end; r += G) {
-            const u64 el = sorted[swz((uint32_t)r)];
-            const double s = (double)elem_s(el);
-            d += s;
-            n = fma(s, (double)elem_w(el), n);
-        }
-        const int hi_start = max(lo_end, b & ~15);
-        for (int r = hi_start + g; r < b; r += G) {
-            const u64 el = sorted[swz((uint32_t)r)];
-            const double s = (double)elem_s(el);
-            d += s;
-            n = fma(s, (double)elem_w(el), n);
-        }
-        a = lo_end >> 4;
-        b = hi_start >> 4;
+#pragma unroll
+    for (int t = 0; t < 2 * T; ++t) {
+        // a skipped slot holds (w = +0, s = +0) and adds nothing
+        const double s = (double)elem_s(el[t]);
+        d += s;
+        n = fma(s, (double)elem_w(el[t]), n);
     }
-    if (a < b) {   // whole chunks up to the first / from the last block boundary
-        const int lo_end = min(b, (a + 15) & ~15);
-        for (int q = a + g; q < lo_end; q += G) {
-            const double2 t = csum[q];
-            d += t.x;
-            n += t.y;
-        }
-        const int hi_start = max(lo_end, b & ~15);
-        for (int q = hi_start + g; q < b; q += G) {
-            const double2 t = csum[q];
-            d += t.x;
-            n += t.y;
-        }
-        a = lo_end >> 4;
-        b = hi_start >> 4;
-        for (int q = a + g; q < b; q += G) {   // whole blocks
-            const double2 t = bsum[q];
-            d += t.x;
-            n += t.y;
-        }
+#pragma unroll
+    for (int t = 0; t < 2 * T; ++t) {
+        d += ch[t].x;
+        n += ch[t].y;
     }
-    for (int off = G >> 1; off >= 1; off >>= 1) {
-        d += __shfl_xor(d, off, 64);
-        n += __shfl_xor(n, off, 64);
+    for (int q = b0 + g; q < b1; q += G) {   // whole 256-element blocks (only for ranges beyond 4096 ranks)
+        const double2 t = bsum[q];
+        d += t.x;
+        n += t.y;
     }
-    D = d;
-    N = n;
+    D = group_sum<G>(d);
+    N = group_sum<G>(n);
 }
 
 // First rank whose inclusive running sum of s reaches tau (weighted-quantile start).
@@ -253,25 +271,26 @@ __device__ __forceinline__ int quantile_rank(const u64 *sorted, const double *cp
     return found;
 }
 
-// Lloyd iterations for one bit width on one wavefront.  Position p (sorted
-// order of centroid values) is handled by the G = 64/K lanes [p*G, (p+1)*G),
-// which search its lower boundary together ((G+1)-ary search).
+// Lloyd iterations for one bit width (K = 2^B centroids) on one wavefront.  Position p
+// (sorted order of centroid values) is handled by the G = 64/K lanes [p*G, (p+1)*G), which
+// search its lower boundary together: first a round of probes around the boundary of the
+// previous iteration, then a (G+1)-ary search of what is left.
+template <int B>
 __device__ void lloyd_wave(const u64 *sorted, const double2 *csum, const double2 *bsum, const double *cpre, int m,
-                           int b, int iters, double total, BitState *out) {
-    const int K = 1 << b;
-    const int gshift = 6 - b;
-    const int G = 1 << gshift;
+                           int iters, double total, BitState *out) {
+    constexpr int K = 1 << B, GS = 6 - B, G = 1 << GS, HALF = G / 2, HM1 = (HALF > 1) ? HALF - 1 : 1;
+    constexpr u64 gmask = (1ull << G) - 1ull;
     const int lane = threadIdx.x & 63;
-    const int p = lane >> gshift;
+    const int p = lane >> GS;
     const int g = lane & (G - 1);
-    const u64 gmask = (G == 64) ? ~0ull : ((1ull << G) - 1ull);
 
     // weighted-quantile start with strictly increasing ranks
     const double tau = total * (double)(2 * p + 1) / (double)(2 * K);
     int r = quantile_rank(sorted, cpre, m, tau);
     int prev = -1;
+#pragma unroll
     for (int k = 0; k < K; ++k) {
-        int rk = __shfl(r, k << gshift, 64);
+        int rk = __builtin_amdgcn_readlane(r, k << GS);
         rk = max(rk, prev + 1);
         rk = min(rk, m - K + k);
         if (p == k) r = rk;
@@ -279,62 +298,78 @@ __device__ void lloyd_wave(const u64 *sorted, const double2 *csum, const double2
     }
     double v = (double)elem_w(sorted[swz((uint32_t)r)]);
     int idx = p;
-    int B = 0, Bold = -1, idxold = -1;
+    int Bcur = 0, Bold = -1, idxold = -1, Wd = 2;
+
+    // offset of probe gg of the warm round relative to the previous boundary:
+    // HALF probes in [-Wd, -1], HALF probes in [0, Wd-1], ascending in gg
+    auto warm_off = [&](int gg) -> int {
+        return gg < HALF ? -1 - ((HALF - 1 - gg) * (Wd - 1)) / HM1 : ((gg - HALF) * (Wd - 1)) / HM1;
+    };
 
     for (int it = 0; it < iters; ++it) {
-        // keep positions ordered by (value, cluster index)
-        {
-            const double vp = shfl_d(v, lane - G);
-            const int ip = __shfl(idx, lane - G, 64);
-            const bool ok = (p == 0) || (vp < v) || (vp == v && ip < idx);
+        double vlo = shfl_d(v, lane - G);
+        int ilo = __shfl(idx, lane - G, 64);
+        {   // keep positions ordered by (value, cluster index)
+            const bool ok = (p == 0) || (vlo < v) || (vlo == v && ilo < idx);
             if (__ballot(!ok)) {
                 int rank = 0;
                 for (int q = 0; q < K; ++q) {
-                    const double vq = shfl_d(v, q << gshift);
-                    const int iq = __shfl(idx, q << gshift, 64);
+                    const double vq = shfl_d(v, q << GS);
+                    const int iq = __shfl(idx, q << GS, 64);
                     rank += (vq < v || (vq == v && iq < idx)) ? 1 : 0;
                 }
                 int src = 0;
                 for (int q = 0; q < K; ++q) {
-                    const int rq = __shfl(rank, q << gshift, 64);
+                    const int rq = __shfl(rank, q << GS, 64);
                     if (rq == p) src = q;
                 }
-                v = shfl_d(v, src << gshift);
-                idx = __shfl(idx, src << gshift, 64);
+                v = shfl_d(v, src << GS);
+                idx = __shfl(idx, src << GS, 64);
+                vlo = shfl_d(v, lane - G);
+                ilo = __shfl(idx, lane - G, 64);
             }
         }
-        const double vlo = shfl_d(v, lane - G);
-        const int ilo = __shfl(idx, lane - G, 64);
         const bool dup = (p > 0) && (vlo == v);
         int rep = idx;       // lowest cluster index among the positions sharing this value
-        bool anydup = __ballot(dup) != 0;
+        const bool anydup = __ballot(dup) != 0;
+        int replo = ilo;
         if (anydup) {
             int rs = p;      // first position of this position's run of equal values
             for (int k = 1; k < K; ++k) {
-                const int d = __shfl((int)dup, k << gshift, 64);
-                const int rsp = __shfl(rs, (k - 1) << gshift, 64);
+                const int d = __shfl((int)dup, k << GS, 64);
+                const int rsp = __shfl(rs, (k - 1) << GS, 64);
                 if (p == k && d) rs = rsp;
             }
-            rep = __shfl(idx, rs << gshift, 64);
+            rep = __shfl(idx, rs << GS, 64);
+            replo = __shfl(rep, lane - G, 64);
         }
-        const int replo = anydup ? __shfl(rep, lane - G, 64) : ilo;
         const bool searching = (p > 0) && !dup;
         const bool tie_lo = replo < rep;  // equal distances go to the lower cluster index
+        auto nearer_lo = [&](int rank) -> bool {
+            const double x = (double)elem_w(sorted[swz((uint32_t)rank)]);
+            const double dl = fabs(x - vlo), dh = fabs(x - v);
+            return tie_lo ? (dl <= dh) : (dl < dh);
+        };
 
-        // (G+1)-ary search for the first rank that is not nearer to the lower centroid
+        // first rank that is not nearer to the lower centroid: invariant lo <= answer <= hi
         int lo = 0, hi = searching ? m : 0;
+        if (it > 0) {
+            const int pr = min(max(Bold + warm_off(g), 0), m - 1);
+            const bool pt = searching && nearer_lo(pr);
+            const u64 bal = __ballot(pt);
+            const int tc = __popcll((bal >> (p << GS)) & gmask);
+            if (searching) {
+                if (tc > 0) lo = min(max(Bold + warm_off(tc - 1), 0), m - 1) + 1;
+                if (tc < G) hi = min(max(Bold + warm_off(tc), 0), m - 1);
+            }
+        }
         for (;;) {
             const int len = hi - lo;
             if (__ballot(len > 0) == 0) break;
             const int pr = lo + ((g + 1) * len) / (G + 1);
-            bool pt = false;
-            if (len > 0) {
-                const double x = (double)elem_w(sorted[swz((uint32_t)pr)]);
-                const double dl = fabs(x - vlo), dh = fabs(x - v);
-                pt = tie_lo ? (dl <= dh) : (dl < dh);
-            }
+            const bool pt = (len > 0) && nearer_lo(pr);
             const u64 bal = __ballot(pt);
-            const int tc = __popcll((bal >> (p << gshift)) & gmask);
+            const int tc = __popcll((bal >> (p << GS)) & gmask);
             const int pl = lo + (tc * len) / (G + 1);
             const int ph = lo + ((tc + 1) * len) / (G + 1);
             if (len > 0) {
@@ -342,27 +377,31 @@ __device__ void lloyd_wave(const u64 *sorted, const double2 *csum, const double2
                 if (tc < G) hi = ph;
             }
         }
-        B = lo;  // p == 0: 0
+        Bcur = lo;  // p == 0: 0
         if (anydup) {
             // a position sharing its value with the one before it owns nothing:
             // its range starts where the next distinct value's range starts
-            if (dup) B = (p == K - 1) ? m : -1;
+            if (dup) Bcur = (p == K - 1) ? m : -1;
             for (int k = K - 2; k >= 1; --k) {
-                const int bn = __shfl(B, (k + 1) << gshift, 64);
-                if (p == k && B < 0) B = bn;
+                const int bn = __shfl(Bcur, (k + 1) << GS, 64);
+                if (p == k && Bcur < 0) Bcur = bn;
             }
         }
         // the assignment is unchanged: every later iteration would repeat this state
-        const bool same = (B == Bold) && (idx == idxold);
+        const bool same = (Bcur == Bold) && (idx == idxold);
         if (it > 0 && __ballot(!same) == 0) break;
-        Bold = B;
+        {   // next warm round: twice the last move, at least 2
+            const int mv = (Bold < 0) ? (m >> B) : abs(Bcur - Bold);
+            Wd = min(max(2 * mv + 2, 2), 1 << 14);
+        }
+        Bold = Bcur;
         idxold = idx;
 
         // (the shuffle must run with every lane active: no lane-dependent branch around it)
-        int Bnext = __shfl(B, lane + G, 64);
+        int Bnext = __shfl(Bcur, lane + G, 64);
         if (p == K - 1) Bnext = m;
         double D, N;
-        range_sum(sorted, csum, bsum, B, Bnext, g, G, D, N);
+        range_sum<G>(sorted, csum, bsum, Bcur, Bnext, g, D, N);
         if (D > 0.0) v = N / D;
     }
 
@@ -477,7 +516,12 @@ __global__ void __launch_bounds__(1024) cluster_kernel(ClusterParams prm) {
         const int b = wave + 1;
         const bool on = prm.bits ? (b == rowbits) : (b >= prm.bmin && b <= prm.bmax);
         if (on) {
-            lloyd_wave(sorted, csum, bsum, cpre, m, b, prm.iters, total, &bs[wave]);
+            switch (b) {
+                case 1: lloyd_wave<1>(sorted, csum, bsum, cpre, m, prm.iters, total, &bs[wave]); break;
+                case 2: lloyd_wave<2>(sorted, csum, bsum, cpre, m, prm.iters, total, &bs[wave]); break;
+                case 3: lloyd_wave<3>(sorted, csum, bsum, cpre, m, prm.iters, total, &bs[wave]); break;
+                default: lloyd_wave<4>(sorted, csum, bsum, cpre, m, prm.iters, total, &bs[wave]); break;
+            }
             if (lane == 0) bs[wave].active = 1;
         }
     }
