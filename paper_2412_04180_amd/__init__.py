@@ -167,8 +167,7 @@ class Context:
             out = dict(E=self.empty((n, nb), t.float64),
                        centroids_all=self.empty((n, stride), t.float64) if want_centroids else None,
                        upper_all=self.empty((n, stride), t.float32) if want_upper else None)
-        if out.get("centroids_all") is None:
-            self.ensure_workspace(n, m)
+        self.ensure_workspace(n, m)
         self._check(self.lib.skim_error_table(self.h, _dp(W), _dp(S), _dp(alpha), n, m, W.stride(0), bmin, bmax,
                                               iters, _dp(out["E"]), _dp(out.get("centroids_all")),
                                               _dp(out.get("upper_all"))))
@@ -179,6 +178,7 @@ class Context:
         n, m = W.shape
         assert W.dtype == t.float32 and S.dtype == t.float32 and W.stride(1) == 1 and S.stride() == W.stride()
         assert bits.dtype == t.uint8 and bits.numel() == n
+        self.ensure_workspace(n, m)
         if out is None:
             out = dict(labels=self.empty((n, m), t.uint8) if want_labels else None,
                        centroids=self.empty((n, 16), t.float64), upper=self.empty((n, 16), t.float32),

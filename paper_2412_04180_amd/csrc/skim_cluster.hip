@@ -1,19 +1,21 @@
 // Per-row sensitivity-weighted 1-D K-means (Alg. 3 lines 2-10 and 12-15; the
 // re-clustering of W * alpha^-1 in Alg. 2) for gfx950.
 //
-// One workgroup owns one row.  The row's (w~, s~) pairs are staged in LDS as
-// 64-bit keys (order-preserving image of w~ in the high word, bits of s~ in the
-// low word), sorted once, and float64 sums of s~ and s~ w~ are kept per aligned
-// 16-element chunk and 256-element block of the sorted order.  In sorted order
-// every cluster of a 1-D K-means is a contiguous rank range, so one Lloyd
-// iteration is: per pair of neighbouring centroids a search for the rank where
-// the nearer centroid changes, then centroid = (sum of s~ w~) / (sum of s~) over
-// the range, assembled from those aligned pieces.  The four bit widths run
-// concurrently, one wavefront each, on the same sorted row.
+// Two kernels per call.
+//  sort_kernel   one workgroup per row: the row's (w~, s~) pairs become 64-bit keys
+//                (order-preserving image of w~ in the high word, bits of s~ in the low word),
+//                are sorted once in LDS and written to scratch together with float64 sums of
+//                s~ and s~ w~ per aligned 16-key chunk, 256-key block and 4096-key super-block.
+//  lloyd_kernel  two wavefronts per row, many rows in flight per compute unit.  In sorted order
+//                every cluster of a 1-D K-means is a contiguous rank range, so one Lloyd
+//                iteration is: per pair of neighbouring centroids a search for the rank where
+//                the nearer centroid changes (four lanes per boundary, warm-started from the
+//                previous iteration), then centroid = (sum of s~ w~) / (sum of s~) over the
+//                range, assembled from the aligned pieces.  All four bit widths run at once.
 //
-// Arithmetic on every decision path is float64 and uses the same predicates as
-// the definition: |w - c_lo| versus |w - c_hi| with the lower cluster index
-// winning equal distances; centroids with no weight mass keep their value.
+// Arithmetic on every decision path is float64 and uses the same predicates as the
+// definition: |w - c_lo| versus |w - c_hi| with the lower cluster index winning equal
+// distances; centroids with no weight mass keep their value.
 #include "skim_common.h"
 
 #include <math.h>
@@ -38,9 +40,14 @@ struct ClusterParams {
     float *upper;         // same layout as cent, may be null
     uint8_t *labels;      // rows mode only, may be null
     int stride;           // entries per row in cent/upper
+    // scratch written by sort_kernel, read by lloyd_kernel (per row: m keys, n1/n2/n3 sums, n1+1 running sums)
+    u64 *keys;
+    double2 *L1, *L2, *L3;
+    double *cpre;
+    int n1, n2, n3;
 };
 
-struct BitState {  // what the Lloyd wavefront of one bit width leaves for the epilogue
+struct BitState {  // what the Lloyd lanes of one bit width leave for the epilogue
     double cent[16];  // by sorted position
     int idx[16];      // cluster index at that position
     int B[17];        // first rank of each position's range, B[K] = m
@@ -173,259 +180,40 @@ __device__ void sort_row(u64 *lds, int logP, uint32_t tid) {
 
 __device__ __forceinline__ double shfl_d(double x, int src) { return __shfl(x, src, 64); }
 
-// Cross-lane moves that stay inside the VALU (DPP): lane i reads lane i^1, lane i^2, its
-// mirror inside its group of 8, its mirror inside its row of 16.
+// Cross-lane moves that stay inside the VALU (DPP): lane i reads lane i^1 / lane i^2.
+template <int CTRL>
+__device__ __forceinline__ int dpp_move_i(int x) {
+    return __builtin_amdgcn_update_dpp(x, x, CTRL, 0xF, 0xF, false);
+}
 template <int CTRL>
 __device__ __forceinline__ double dpp_move_d(double x) {
     int lo = __double2loint(x), hi = __double2hiint(x);
-    lo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xF, 0xF, false);
-    hi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xF, 0xF, false);
+    lo = dpp_move_i<CTRL>(lo);
+    hi = dpp_move_i<CTRL>(hi);
     return __hiloint2double(hi, lo);
 }
-
-// Sum over the G consecutive lanes of a group; every lane of the group gets the same bits
-// (each step adds a lane's value and its partner's, and the partner adds the same two).
-template <int G>
-__device__ __forceinline__ double group_sum(double x) {
-    if (G >= 2) x += dpp_move_d<0xB1>(x);    // quad_perm [1,0,3,2]
-    if (G >= 4) x += dpp_move_d<0x4E>(x);    // quad_perm [2,3,0,1]
-    if (G >= 8) x += dpp_move_d<0x141>(x);   // row_half_mirror
-    if (G >= 16) x += dpp_move_d<0x140>(x);  // row_mirror
-    if (G >= 32) x += __shfl_xor(x, 16, 64);
+// Sum over the four lanes of a quad; every lane of the quad gets the same bits.
+__device__ __forceinline__ double quad_sum(double x) {
+    x += dpp_move_d<0xB1>(x);  // quad_perm [1,0,3,2]
+    x += dpp_move_d<0x4E>(x);  // quad_perm [2,3,0,1]
+    return x;
+}
+__device__ __forceinline__ int quad_sum(int x) {
+    x += dpp_move_i<0xB1>(x);
+    x += dpp_move_i<0x4E>(x);
     return x;
 }
 
-// Sums of s and s*w over the sorted ranks [a, b), shared out over the G lanes of
-// a group (lane g) and reduced so that every lane of the group gets the result.
-// The range is cut into aligned pieces whose sums were each formed from their
-// own members only (single elements, 16-element chunks, 256-element blocks):
-// nothing outside [a, b) enters, so a cluster of tiny weight mass next to a
-// heavy element keeps full relative precision (a difference of running prefix
-// sums would not).
-template <int G>
-__device__ __forceinline__ void range_sum(const u64 *sorted, const double2 *csum, const double2 *bsum, int a,
-                                          int b, int g, double &D, double &N) {
-    constexpr int T = (16 + G - 1) / G;   // loads per lane that cover one 16-wide piece
-    // piece boundaries: elements [a, e0) and [e1, b); chunks [c0, c1) and [c2, c3); blocks [b0, b1)
-    const int e0 = min(b, (a + 15) & ~15);
-    const int e1 = max(e0, b & ~15);
-    const int c0 = e0 >> 4, c3 = e1 >> 4;
-    const int c1 = (c0 < c3) ? min(c3, (c0 + 15) & ~15) : c0;
-    const int c2 = (c0 < c3) ? max(c1, c3 & ~15) : c0;
-    const int b0 = c1 >> 4, b1 = (c0 < c3) ? (c2 >> 4) : b0;
-    // issue every load first (predicated), then add in a fixed order: one LDS round trip
-    u64 el[2 * T];
-    double2 ch[2 * T];
-#pragma unroll
-    for (int t = 0; t < T; ++t) {
-        const int r0 = a + g + t * G, r1 = e1 + g + t * G;
-        el[t] = (r0 < e0) ? sorted[swz((uint32_t)r0)] : NEUTRAL_KEY;
-        el[T + t] = (r1 < b) ? sorted[swz((uint32_t)r1)] : NEUTRAL_KEY;
-        const int q0 = c0 + g + t * G, q1 = c2 + g + t * G;
-        ch[t] = (q0 < c1) ? csum[q0] : make_double2(0.0, 0.0);
-        ch[T + t] = (q1 < c3 && c0 < c3) ? csum[q1] : make_double2(0.0, 0.0);
-    }
-    double d = 0.0, n = 0.0;
-#pragma unroll
-    for (int t = 0; t < 2 * T; ++t) {
-        // a skipped slot holds (w = +0, s = +0) and adds nothing
-        const double s = (double)elem_s(el[t]);
-        d += s;
-        n = fma(s, (double)elem_w(el[t]), n);
-    }
-#pragma unroll
-    for (int t = 0; t < 2 * T; ++t) {
-        d += ch[t].x;
-        n += ch[t].y;
-    }
-    for (int q = b0 + g; q < b1; q += G) {   // whole 256-element blocks (only for ranges beyond 4096 ranks)
-        const double2 t = bsum[q];
-        d += t.x;
-        n += t.y;
-    }
-    D = group_sum<G>(d);
-    N = group_sum<G>(n);
-}
-
-// First rank whose inclusive running sum of s reaches tau (weighted-quantile start).
-// cpre[q] = running sum of s over the ranks before chunk q.
-__device__ __forceinline__ int quantile_rank(const u64 *sorted, const double *cpre, int m, double tau) {
-    const int nchunk = (m + 15) >> 4;
-    int lo = 0, hi = nchunk - 1;  // largest q with cpre[q] < tau; cpre[0] = 0 < tau
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (cpre[mid] < tau) lo = mid; else hi = mid - 1;
-    }
-    double acc = cpre[lo];
-    const int r0 = lo * 16;
-    int found = min(r0 + 15, m - 1);
-    for (int j = 0; j < 16; ++j) {
-        const int r = r0 + j;
-        if (r >= m) break;
-        acc += (double)elem_s(sorted[swz((uint32_t)r)]);
-        if (acc >= tau) {
-            found = r;
-            break;
-        }
-    }
-    return found;
-}
-
-// Lloyd iterations for one bit width (K = 2^B centroids) on one wavefront.  Position p
-// (sorted order of centroid values) is handled by the G = 64/K lanes [p*G, (p+1)*G), which
-// search its lower boundary together: first a round of probes around the boundary of the
-// previous iteration, then a (G+1)-ary search of what is left.
-template <int B>
-__device__ void lloyd_wave(const u64 *sorted, const double2 *csum, const double2 *bsum, const double *cpre, int m,
-                           int iters, double total, BitState *out) {
-    constexpr int K = 1 << B, GS = 6 - B, G = 1 << GS, HALF = G / 2, HM1 = (HALF > 1) ? HALF - 1 : 1;
-    constexpr u64 gmask = (1ull << G) - 1ull;
-    const int lane = threadIdx.x & 63;
-    const int p = lane >> GS;
-    const int g = lane & (G - 1);
-
-    // weighted-quantile start with strictly increasing ranks
-    const double tau = total * (double)(2 * p + 1) / (double)(2 * K);
-    int r = quantile_rank(sorted, cpre, m, tau);
-    int prev = -1;
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-        int rk = __builtin_amdgcn_readlane(r, k << GS);
-        rk = max(rk, prev + 1);
-        rk = min(rk, m - K + k);
-        if (p == k) r = rk;
-        prev = rk;
-    }
-    double v = (double)elem_w(sorted[swz((uint32_t)r)]);
-    int idx = p;
-    int Bcur = 0, Bold = -1, idxold = -1, Wd = 2;
-
-    // offset of probe gg of the warm round relative to the previous boundary:
-    // HALF probes in [-Wd, -1], HALF probes in [0, Wd-1], ascending in gg
-    auto warm_off = [&](int gg) -> int {
-        return gg < HALF ? -1 - ((HALF - 1 - gg) * (Wd - 1)) / HM1 : ((gg - HALF) * (Wd - 1)) / HM1;
-    };
-
-    for (int it = 0; it < iters; ++it) {
-        double vlo = shfl_d(v, lane - G);
-        int ilo = __shfl(idx, lane - G, 64);
-        {   // keep positions ordered by (value, cluster index)
-            const bool ok = (p == 0) || (vlo < v) || (vlo == v && ilo < idx);
-            if (__ballot(!ok)) {
-                int rank = 0;
-                for (int q = 0; q < K; ++q) {
-                    const double vq = shfl_d(v, q << GS);
-                    const int iq = __shfl(idx, q << GS, 64);
-                    rank += (vq < v || (vq == v && iq < idx)) ? 1 : 0;
-                }
-                int src = 0;
-                for (int q = 0; q < K; ++q) {
-                    const int rq = __shfl(rank, q << GS, 64);
-                    if (rq == p) src = q;
-                }
-                v = shfl_d(v, src << GS);
-                idx = __shfl(idx, src << GS, 64);
-                vlo = shfl_d(v, lane - G);
-                ilo = __shfl(idx, lane - G, 64);
-            }
-        }
-        const bool dup = (p > 0) && (vlo == v);
-        int rep = idx;       // lowest cluster index among the positions sharing this value
-        const bool anydup = __ballot(dup) != 0;
-        int replo = ilo;
-        if (anydup) {
-            int rs = p;      // first position of this position's run of equal values
-            for (int k = 1; k < K; ++k) {
-                const int d = __shfl((int)dup, k << GS, 64);
-                const int rsp = __shfl(rs, (k - 1) << GS, 64);
-                if (p == k && d) rs = rsp;
-            }
-            rep = __shfl(idx, rs << GS, 64);
-            replo = __shfl(rep, lane - G, 64);
-        }
-        const bool searching = (p > 0) && !dup;
-        const bool tie_lo = replo < rep;  // equal distances go to the lower cluster index
-        auto nearer_lo = [&](int rank) -> bool {
-            const double x = (double)elem_w(sorted[swz((uint32_t)rank)]);
-            const double dl = fabs(x - vlo), dh = fabs(x - v);
-            return tie_lo ? (dl <= dh) : (dl < dh);
-        };
-
-        // first rank that is not nearer to the lower centroid: invariant lo <= answer <= hi
-        int lo = 0, hi = searching ? m : 0;
-        if (it > 0) {
-            const int pr = min(max(Bold + warm_off(g), 0), m - 1);
-            const bool pt = searching && nearer_lo(pr);
-            const u64 bal = __ballot(pt);
-            const int tc = __popcll((bal >> (p << GS)) & gmask);
-            if (searching) {
-                if (tc > 0) lo = min(max(Bold + warm_off(tc - 1), 0), m - 1) + 1;
-                if (tc < G) hi = min(max(Bold + warm_off(tc), 0), m - 1);
-            }
-        }
-        for (;;) {
-            const int len = hi - lo;
-            if (__ballot(len > 0) == 0) break;
-            const int pr = lo + ((g + 1) * len) / (G + 1);
-            const bool pt = (len > 0) && nearer_lo(pr);
-            const u64 bal = __ballot(pt);
-            const int tc = __popcll((bal >> (p << GS)) & gmask);
-            const int pl = lo + (tc * len) / (G + 1);
-            const int ph = lo + ((tc + 1) * len) / (G + 1);
-            if (len > 0) {
-                if (tc > 0) lo = pl + 1;
-                if (tc < G) hi = ph;
-            }
-        }
-        Bcur = lo;  // p == 0: 0
-        if (anydup) {
-            // a position sharing its value with the one before it owns nothing:
-            // its range starts where the next distinct value's range starts
-            if (dup) Bcur = (p == K - 1) ? m : -1;
-            for (int k = K - 2; k >= 1; --k) {
-                const int bn = __shfl(Bcur, (k + 1) << GS, 64);
-                if (p == k && Bcur < 0) Bcur = bn;
-            }
-        }
-        // the assignment is unchanged: every later iteration would repeat this state
-        const bool same = (Bcur == Bold) && (idx == idxold);
-        if (it > 0 && __ballot(!same) == 0) break;
-        {   // next warm round: twice the last move, at least 2
-            const int mv = (Bold < 0) ? (m >> B) : abs(Bcur - Bold);
-            Wd = min(max(2 * mv + 2, 2), 1 << 14);
-        }
-        Bold = Bcur;
-        idxold = idx;
-
-        // (the shuffle must run with every lane active: no lane-dependent branch around it)
-        int Bnext = __shfl(Bcur, lane + G, 64);
-        if (p == K - 1) Bnext = m;
-        double D, N;
-        range_sum<G>(sorted, csum, bsum, Bcur, Bnext, g, D, N);
-        if (D > 0.0) v = N / D;
-    }
-
-    if (g == 0) {
-        out->cent[p] = v;
-        out->idx[p] = idx;
-        out->B[p] = Bold;
-        if (p == K - 1) out->B[K] = m;
-    }
-}
-
-__global__ void __launch_bounds__(1024) cluster_kernel(ClusterParams prm) {
+// ---------------------------------------------------------------------------------------------
+// Kernel 1: load + scale + encode, bitonic sort in LDS, sums, write-out.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int P = prm.P, m = prm.m;
-    const int nchunkP = P >> 4;
+    const int n1 = prm.n1;
     u64 *sorted = (u64 *)smem;
-    double2 *csum = (double2 *)(smem + (size_t)P * 8);               // per 16-element chunk: (sum s, sum s*w)
-    double2 *bsum = csum + nchunkP;                                  // per 256-element block (at least one entry)
-    double *cpre = (double *)(bsum + ((nchunkP + 15) >> 4));         // nchunkP + 1 running sums of s
-    double *wtot = cpre + nchunkP + 1;                               // 16 wave totals + 1
-    BitState *bs = (BitState *)(wtot + 17);                          // 4 entries
-    double *red = (double *)(bs + 4);                                // 4 x 16 partial errors
-    float *thr = (float *)(red + 64);                                // 16 thresholds (labels)
-    int *thl = (int *)(thr + 16);                                    // 16 labels + count
+    double2 *wsum = (double2 *)(smem + (size_t)P * 8);   // per-wavefront sums (16)
+    double *wpre = (double *)(wsum + 16);                // per-wavefront running sums of s (16) + total
 
     const int tid = threadIdx.x, nth = blockDim.x;
     const int lane = tid & 63, wave = tid >> 6, nwave = nth >> 6;
@@ -433,7 +221,6 @@ __global__ void __launch_bounds__(1024) cluster_kernel(ClusterParams prm) {
     const float *Wr = prm.W + row * prm.ld;
     const float *Sr = prm.S + row * prm.ld;
 
-    // ---- load, scale, encode ------------------------------------------------
     for (int j = tid; j < P; j += nth) {
         u64 key = ~0ull;
         if (j < m) {
@@ -444,17 +231,17 @@ __global__ void __launch_bounds__(1024) cluster_kernel(ClusterParams prm) {
         }
         sorted[swz((uint32_t)j)] = key;
     }
-    if (tid < 4) bs[tid].active = 0;
     __syncthreads();
 
-    // ---- sort by (w~, s~) ---------------------------------------------------
     sort_row(sorted, prm.logP, (uint32_t)tid);
 
-    // ---- prefix sums of s~ and s~ w~ in sorted order -----------------------
-    double total = 0.0;
+    double2 *L1 = prm.L1 + row * prm.n1;
+    double2 *L2 = prm.L2 + row * prm.n2;
+    double2 *L3 = prm.L3 + row * prm.n3;
+    double *cpre = prm.cpre + row * (prm.n1 + 1);
     for (int pass = 0; pass < 2; ++pass) {
         double c = 0.0, q = 0.0;
-        if (tid < nchunkP) {
+        if (tid < n1) {
             for (int e = 0; e < EPT; ++e) {
                 const int r = tid * EPT + e;
                 if (r < m) {
@@ -464,159 +251,441 @@ __global__ void __launch_bounds__(1024) cluster_kernel(ClusterParams prm) {
                     q = fma(s, w, q);
                 }
             }
-            csum[tid] = make_double2(c, q);
         }
-        {   // 256-element block sums: 16 neighbouring chunks
-            double bc = c, bq = q;
-            for (int d = 8; d >= 1; d >>= 1) {
-                bc += __shfl_down(bc, d, 16);
-                bq += __shfl_down(bq, d, 16);
-            }
-            if ((lane & 15) == 0 && tid < nchunkP) bsum[tid >> 4] = make_double2(bc, bq);
+        double bc = c, bq = q;       // 16 neighbouring chunks = one 256-key block (valid on lanes 0, 16, 32, 48)
+        for (int d = 8; d >= 1; d >>= 1) {
+            bc += __shfl_down(bc, d, 16);
+            bq += __shfl_down(bq, d, 16);
         }
-        // running sum of s over the chunks (for the weighted-quantile start)
-        double ic = c;
+        // the wavefront's four blocks, added in a fixed order
+        const double c1 = __shfl(bc, 16, 64), c2 = __shfl(bc, 32, 64), c3 = __shfl(bc, 48, 64);
+        const double q1 = __shfl(bq, 16, 64), q2 = __shfl(bq, 32, 64), q3 = __shfl(bq, 48, 64);
+        const double c0 = __shfl(bc, 0, 64), q0 = __shfl(bq, 0, 64);
+        const double wc = ((c0 + c1) + c2) + c3, wq = ((q0 + q1) + q2) + q3;
+        double ic = c;               // inclusive running sum of s inside the wavefront
         for (int d = 1; d < 64; d <<= 1) {
             const double uc = __shfl_up(ic, d, 64);
             if (lane >= d) ic += uc;
         }
-        if (lane == 63) wtot[wave] = ic;
+        double xc = __shfl_up(ic, 1, 64);   // exclusive
+        if (lane == 0) xc = 0.0;
+        if (lane == 0) {
+            wsum[wave] = make_double2(wc, wq);
+            wpre[wave] = wc;
+        }
         __syncthreads();
-        if (wave == 0) {
-            const double t = (lane < nwave) ? wtot[lane] : 0.0;
-            double sc = t;
-            for (int d = 1; d < 16; d <<= 1) {
-                const double uc = __shfl_up(sc, d, 64);
-                if (lane >= d) sc += uc;
+        double total = 0.0, before = 0.0;
+        for (int w2 = 0; w2 < nwave; ++w2) {   // same order in every thread
+            if (w2 == wave) before = total;
+            total += wpre[w2];
+        }
+        if (total == 0.0 && pass == 0) {
+            // no sensitivity mass in this row: cluster with unit weights
+            __syncthreads();
+            for (int j = tid; j < m; j += nth) {
+                const uint32_t a = swz((uint32_t)j);
+                sorted[a] = (sorted[a] & 0xFFFFFFFF00000000ull) | 0x3F800000ull;
             }
-            if (lane < nwave) wtot[lane] = sc - t;  // exclusive
-            if (lane == nwave - 1) wtot[16] = sc;
+            __syncthreads();
+            continue;
         }
-        __syncthreads();
-        {
-            double xc = __shfl_up(ic, 1, 64);
-            if (lane == 0) xc = 0.0;
-            if (tid < nchunkP) cpre[tid] = wtot[wave] + xc;
+        if (tid < n1) {
+            L1[tid] = make_double2(c, q);
+            cpre[tid] = before + xc;
+            if ((lane & 15) == 0) L2[tid >> 4] = make_double2(bc, bq);
         }
-        total = wtot[16];
-        if (tid == 0) cpre[nchunkP] = total;
-        __syncthreads();
-        if (total != 0.0 || pass == 1) break;
-        // no sensitivity mass in this row: cluster with unit weights
-        for (int j = tid; j < m; j += nth) {
-            const uint32_t a = swz((uint32_t)j);
-            sorted[a] = (sorted[a] & 0xFFFFFFFF00000000ull) | 0x3F800000ull;
+        if (tid == 0) cpre[n1] = total;
+        if (tid < prm.n3) {                    // one super-block = four wavefronts
+            double sc = 0.0, sq = 0.0;
+            for (int w2 = 4 * tid; w2 < min(nwave, 4 * tid + 4); ++w2) {
+                sc += wsum[w2].x;
+                sq += wsum[w2].y;
+            }
+            L3[tid] = make_double2(sc, sq);
         }
-        __syncthreads();
+        break;
+    }
+    // sorted keys, compact and in rank order
+    u64 *keys = prm.keys + row * (long long)m;
+    for (int j = tid; j < m; j += nth) keys[j] = sorted[swz((uint32_t)j)];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernel 2: Lloyd iterations, errors, centroids, thresholds, labels.
+// ---------------------------------------------------------------------------------------------
+
+// Sums of s and s*w over the sorted ranks [a, b), shared out over the four lanes of a quad
+// (lane g) and reduced so that every lane of the quad gets the result.  The range is cut into
+// aligned pieces whose sums were each formed from their own members only (single keys, 16-key
+// chunks, 256-key blocks, 4096-key super-blocks): nothing outside [a, b) enters, so a cluster of
+// tiny weight mass next to a heavy element keeps full relative precision (a difference of
+// running prefix sums would not).  Keys come from global memory, sums from LDS.
+__device__ __forceinline__ void range_sum(const u64 *__restrict__ keys, const double2 *L1, const double2 *L2,
+                                          const double2 *L3, int a, int b, int g, double &D, double &N) {
+    constexpr int G = 4, T = 4;
+    const int e0 = min(b, (a + 15) & ~15), e1 = max(e0, b & ~15);
+    const int c0 = e0 >> 4, c3 = e1 >> 4;
+    const bool has1 = c0 < c3;
+    const int c1 = has1 ? min(c3, (c0 + 15) & ~15) : c0, c2 = has1 ? max(c1, c3 & ~15) : c0;
+    const int b0 = c1 >> 4, b3 = has1 ? (c2 >> 4) : b0;
+    const bool has2 = b0 < b3;
+    const int b1 = has2 ? min(b3, (b0 + 15) & ~15) : b0, b2 = has2 ? max(b1, b3 & ~15) : b0;
+    const int s0 = b1 >> 4, s1 = has2 ? (b2 >> 4) : s0;
+    // issue every load first (predicated), then add in a fixed order
+    u64 el[2 * T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const int o = g + t * G;
+        el[t] = (a + o < e0) ? keys[a + o] : NEUTRAL_KEY;
+        el[T + t] = (e1 + o < b) ? keys[e1 + o] : NEUTRAL_KEY;
+    }
+    double d = 0.0, n = 0.0;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const int o = g + t * G;
+        if (has1) {
+            if (c0 + o < c1) { const double2 x = L1[c0 + o]; d += x.x; n += x.y; }
+            if (c2 + o < c3) { const double2 x = L1[c2 + o]; d += x.x; n += x.y; }
+        }
+        if (has2) {
+            if (b0 + o < b1) { const double2 x = L2[b0 + o]; d += x.x; n += x.y; }
+            if (b2 + o < b3) { const double2 x = L2[b2 + o]; d += x.x; n += x.y; }
+        }
+    }
+    for (int q = s0 + g; q < s1; q += G) {
+        const double2 x = L3[q];
+        d += x.x;
+        n += x.y;
+    }
+#pragma unroll
+    for (int t = 0; t < 2 * T; ++t) {
+        // a skipped slot holds (w = +0, s = +0) and adds nothing
+        const double s = (double)elem_s(el[t]);
+        d += s;
+        n = fma(s, (double)elem_w(el[t]), n);
+    }
+    D = quad_sum(d);
+    N = quad_sum(n);
+}
+
+// First rank whose inclusive running sum of s reaches tau (weighted-quantile start).
+// cpre[q] = running sum of s over the ranks before chunk q (global memory).
+__device__ __forceinline__ int quantile_rank(const u64 *__restrict__ keys, const double *__restrict__ cpre, int m,
+                                             double tau) {
+    const int nchunk = (m + 15) >> 4;
+    int lo = 0, hi = nchunk - 1;  // largest q with cpre[q] < tau; cpre[0] = 0 < tau
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (cpre[mid] < tau) lo = mid; else hi = mid - 1;
+    }
+    const int r0 = lo * 16;
+    u64 el[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) el[j] = (r0 + j < m) ? keys[r0 + j] : NEUTRAL_KEY;
+    double acc = cpre[lo];
+    int found = min(r0 + 15, m - 1);
+    bool hit = false;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        acc += (double)elem_s(el[j]);
+        if (!hit && r0 + j < m && acc >= tau) {
+            found = r0 + j;
+            hit = true;
+        }
+    }
+    return found;
+}
+
+constexpr int LLOYD_THREADS = 128;
+
+// Two wavefronts per row.  Wavefront 0 carries the bit widths 1, 2, 3 (lanes 0-7, 8-23, 24-55),
+// wavefront 1 the bit width 4 (64 lanes).  Position p (sorted order of centroid values) of a
+// bit width is a quad of lanes which searches its lower boundary together and shares its sums.
+__global__ void __launch_bounds__(LLOYD_THREADS) lloyd_kernel(ClusterParams prm) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int m = prm.m;
+    const int n1u = (m + 15) >> 4, n2u = (n1u + 15) >> 4, n3u = (n2u + 15) >> 4;
+    double2 *L1 = (double2 *)smem;
+    double2 *L2 = L1 + n1u;
+    double2 *L3 = L2 + n2u;
+    BitState *bs = (BitState *)(L3 + n3u);
+    double *red = (double *)(bs + 4);        // 4 x 2 partial errors
+    float *thr = (float *)(red + 8);         // 16 thresholds (labels)
+    int *thl = (int *)(thr + 16);            // 16 labels
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long long row = blockIdx.x;
+    const u64 *__restrict__ keys = prm.keys + row * (long long)m;
+    const double *__restrict__ cpre = prm.cpre + row * (prm.n1 + 1);
+    {
+        const double2 *g1 = prm.L1 + row * prm.n1, *g2 = prm.L2 + row * prm.n2, *g3 = prm.L3 + row * prm.n3;
+        for (int j = tid; j < n1u; j += LLOYD_THREADS) L1[j] = g1[j];
+        for (int j = tid; j < n2u; j += LLOYD_THREADS) L2[j] = g2[j];
+        for (int j = tid; j < n3u; j += LLOYD_THREADS) L3[j] = g3[j];
+        if (tid < 4) bs[tid].active = 0;
+    }
+    __syncthreads();
+    const double total = cpre[prm.n1];
+
+    // lane -> (bit width, position, lane in quad)
+    int b, q, L0;
+    if (wave == 1) { b = 4; q = lane; L0 = 0; }
+    else if (lane < 8) { b = 1; q = lane; L0 = 0; }
+    else if (lane < 24) { b = 2; q = lane - 8; L0 = 8; }
+    else { b = 3; q = lane - 24; L0 = 24; }       // lanes 56..63 of wavefront 0 stay idle (q >= 32)
+    const int K = 1 << b;
+    const int p = q >> 2, g = q & 3;
+    const int rowbits = prm.bits ? (int)prm.bits[row] : 0;
+    const bool on = (p < K) && (prm.bits ? (b == rowbits) : (b >= prm.bmin && b <= prm.bmax));
+    const u64 maskb = (wave == 1) ? ~0ull : (((1ull << (4 * K)) - 1ull) << L0);
+    auto from_pos = [&](int k) -> int { return min(L0 + 4 * k, 63); };   // first lane of position k of this bit width
+
+    // ---- weighted-quantile start with strictly increasing ranks --------------
+    int r = 0;
+    {
+        const double tau = total * (double)(2 * p + 1) / (double)(2 * K);
+        if (on) r = quantile_rank(keys, cpre, m, tau);
+        int prev = -1;
+        for (int k = 0; k < 16; ++k) {
+            int rk = __shfl(r, from_pos(k), 64);
+            if (k < K) {
+                rk = max(rk, prev + 1);
+                rk = min(rk, m - K + k);
+                if (p == k) r = rk;
+                prev = rk;
+            }
+        }
+    }
+    double v = on ? (double)elem_w(keys[r]) : 0.0;
+    int idx = p;
+    int Bcur = 0, Bold = -1, idxold = -1, Wd = 1;
+    bool done = !on;
+
+    for (int it = 0; it < prm.iters; ++it) {
+        if (__ballot(!done) == 0) break;
+        double vlo = shfl_d(v, lane - 4);
+        int ilo = __shfl(idx, lane - 4, 64);
+        {   // keep positions ordered by (value, cluster index)
+            const bool ok = done || (p == 0) || (vlo < v) || (vlo == v && ilo < idx);
+            if (__ballot(!ok)) {
+                int rank = 0;
+                for (int k = 0; k < 16; ++k) {
+                    const double vq = shfl_d(v, from_pos(k));
+                    const int iq = __shfl(idx, from_pos(k), 64);
+                    if (k < K) rank += (vq < v || (vq == v && iq < idx)) ? 1 : 0;
+                }
+                int src = p;
+                for (int k = 0; k < 16; ++k) {
+                    const int rq = __shfl(rank, from_pos(k), 64);
+                    if (k < K && rq == p) src = k;
+                }
+                const double nv = shfl_d(v, from_pos(src));
+                const int ni = __shfl(idx, from_pos(src), 64);
+                if (!done) {
+                    v = nv;
+                    idx = ni;
+                }
+                vlo = shfl_d(v, lane - 4);
+                ilo = __shfl(idx, lane - 4, 64);
+            }
+        }
+        const bool dup = !done && (p > 0) && (vlo == v);
+        int rep = idx;       // lowest cluster index among the positions sharing this value
+        int replo = ilo;
+        const bool anydup = __ballot(dup) != 0;
+        if (anydup) {
+            int rs = p;      // first position of this position's run of equal values
+            for (int k = 1; k < 16; ++k) {
+                const int dk = __shfl((int)dup, from_pos(k), 64);
+                const int rsp = __shfl(rs, from_pos(k - 1), 64);
+                if (k < K && p == k && dk) rs = rsp;
+            }
+            rep = __shfl(idx, from_pos(rs), 64);
+            replo = __shfl(rep, lane - 4, 64);
+        }
+        const bool searching = !done && (p > 0) && !dup;
+        const bool tie_lo = replo < rep;  // equal distances go to the lower cluster index
+        auto nearer_lo = [&](int rank) -> bool {
+            const double x = (double)elem_w(keys[rank]);
+            const double dl = fabs(x - vlo), dh = fabs(x - v);
+            return tie_lo ? (dl <= dh) : (dl < dh);
+        };
+
+        // first rank that is not nearer to the lower centroid: invariant lo <= answer <= hi.
+        // mode 0: probes spread evenly; 1: answer expected just below hi; 2: just above lo.
+        int lo = 0, hi = 0, mode = 0;
+        if (it == 0) {
+            // the starting centroids are the keys at ranks r: the boundary lies in (r_{p-1}, r_p]
+            const int rlo = __shfl(r, lane - 4, 64);
+            if (searching) {
+                lo = rlo + 1;
+                hi = r;
+            }
+        } else {
+            const int x0 = min(max(Bold - Wd, 0), m - 1), x1 = min(max(Bold - 1, 0), m - 1);
+            const int x2 = min(max(Bold, 0), m - 1), x3 = min(max(Bold + Wd - 1, 0), m - 1);
+            const int x = (g == 0) ? x0 : (g == 1) ? x1 : (g == 2) ? x2 : x3;
+            const int tc = quad_sum((int)(searching && nearer_lo(x)));
+            if (searching) {
+                hi = m;
+                if (tc == 0) { hi = x0; mode = 1; }
+                else if (tc == 1) { lo = x0 + 1; hi = x1; }
+                else if (tc == 2) { lo = x1 + 1; hi = x2; }
+                else if (tc == 3) { lo = x2 + 1; hi = x3; }
+                else { lo = x3 + 1; mode = 2; }
+            }
+        }
+        int step = max(Wd, 1);
+        for (;;) {
+            const int len = hi - lo;
+            if (__ballot(len > 0) == 0) break;
+            int x0, x1, x2, x3;
+            if (mode == 1) {
+                x3 = max(lo, hi - step); x2 = max(lo, hi - 2 * step); x1 = max(lo, hi - 4 * step); x0 = max(lo, hi - 8 * step);
+            } else if (mode == 2) {
+                x0 = min(hi - 1, lo + step - 1); x1 = min(hi - 1, lo + 2 * step - 1);
+                x2 = min(hi - 1, lo + 4 * step - 1); x3 = min(hi - 1, lo + 8 * step - 1);
+            } else {
+                x0 = lo + len / 5; x1 = lo + (2 * len) / 5; x2 = lo + (3 * len) / 5; x3 = lo + (4 * len) / 5;
+            }
+            const int x = (g == 0) ? x0 : (g == 1) ? x1 : (g == 2) ? x2 : x3;
+            const int tc = quad_sum((int)((len > 0) && nearer_lo(min(max(x, 0), m - 1))));
+            if (len > 0) {
+                if (tc == 0) {
+                    hi = x0;
+                    if (mode == 1) step = min(step * 16, 1 << 20); else mode = 0;
+                } else if (tc == 4) {
+                    lo = x3 + 1;
+                    if (mode == 2) step = min(step * 16, 1 << 20); else mode = 0;
+                } else {
+                    lo = ((tc == 1) ? x0 : (tc == 2) ? x1 : x2) + 1;
+                    hi = (tc == 1) ? x1 : (tc == 2) ? x2 : x3;
+                    mode = 0;
+                }
+            }
+        }
+        Bcur = lo;  // p == 0: 0
+        if (anydup) {
+            // a position sharing its value with the one before it owns nothing:
+            // its range starts where the next distinct value's range starts
+            if (dup) Bcur = (p == K - 1) ? m : -1;
+            for (int k = 14; k >= 1; --k) {
+                const int bn = __shfl(Bcur, from_pos(k + 1), 64);
+                if (k <= K - 2 && p == k && Bcur < 0) Bcur = bn;
+            }
+        }
+        {   // the assignment of a bit width is unchanged: every later iteration would repeat this state
+            const bool same = (Bcur == Bold) && (idx == idxold);
+            const u64 moving = __ballot(!done && !same);
+            if (it > 0 && (moving & maskb) == 0) done = true;
+        }
+        int Bnext = __shfl(done ? Bold : Bcur, lane + 4, 64);
+        if (p == K - 1) Bnext = m;
+        if (!done) {
+            Wd = (Bold < 0) ? max(1, m >> (b + 2)) : max(1, abs(Bcur - Bold));
+            Bold = Bcur;
+            idxold = idx;
+        }
+        double D = 0.0, N = 0.0;
+        range_sum(keys, L1, L2, L3, done ? 0 : Bcur, done ? 0 : Bnext, g, D, N);
+        if (!done && D > 0.0) v = N / D;
     }
 
-    // ---- Lloyd: one wavefront per bit width --------------------------------
-    const int rowbits = prm.bits ? (int)prm.bits[row] : 0;
-    if (wave < 4) {
-        const int b = wave + 1;
-        const bool on = prm.bits ? (b == rowbits) : (b >= prm.bmin && b <= prm.bmax);
-        if (on) {
-            switch (b) {
-                case 1: lloyd_wave<1>(sorted, csum, bsum, cpre, m, prm.iters, total, &bs[wave]); break;
-                case 2: lloyd_wave<2>(sorted, csum, bsum, cpre, m, prm.iters, total, &bs[wave]); break;
-                case 3: lloyd_wave<3>(sorted, csum, bsum, cpre, m, prm.iters, total, &bs[wave]); break;
-                default: lloyd_wave<4>(sorted, csum, bsum, cpre, m, prm.iters, total, &bs[wave]); break;
-            }
-            if (lane == 0) bs[wave].active = 1;
+    if (on && g == 0) {
+        BitState *o = &bs[b - 1];
+        o->cent[p] = v;
+        o->idx[p] = idx;
+        o->B[p] = Bold;
+        if (p == K - 1) {
+            o->B[K] = m;
+            o->active = 1;
         }
     }
     __syncthreads();
 
-    // ---- epilogue: errors, centroids, bounds, labels -----------------------
+    // ---- errors: sum s (w - c)^2 over the sorted row, every key once ----------
     double e4[4] = {0.0, 0.0, 0.0, 0.0};
-    if (tid < nchunkP && tid * EPT < m) {
-        const int r0 = tid * EPT;
-        u64 el[EPT];
+    int pc[4] = {0, 0, 0, 0};
+    for (int base = wave * 64; base < m; base += LLOYD_THREADS) {
+        const int rk = base + lane;
+        const u64 el = (rk < m) ? keys[rk] : NEUTRAL_KEY;
+        const double w = (double)elem_w(el), s = (double)elem_s(el);
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) el[e] = sorted[swz((uint32_t)(r0 + e))];
         for (int bi = 0; bi < 4; ++bi) {
             if (!bs[bi].active) continue;
-            const int K = 2 << bi;
-            int p = 0;
-            while (p + 1 < K && bs[bi].B[p + 1] <= r0) ++p;
-            int nextB = bs[bi].B[p + 1];
-            double c = bs[bi].cent[p];
-            double acc = 0.0;
-#pragma unroll
-            for (int e = 0; e < EPT; ++e) {
-                const int r = r0 + e;
-                if (r < m) {
-                    while (r >= nextB) {
-                        ++p;
-                        nextB = bs[bi].B[p + 1];
-                        c = bs[bi].cent[p];
-                    }
-                    const double d = (double)elem_w(el[e]) - c;
-                    acc += (double)elem_s(el[e]) * d * d;
-                }
+            const int Kb = 2 << bi;
+            int pp = pc[bi];                       // same in every lane: cluster of the first key of this stretch
+            while (pp + 1 < Kb && bs[bi].B[pp + 1] <= base) ++pp;
+            pc[bi] = pp;
+            if (rk < m) {
+                while (pp + 1 < Kb && bs[bi].B[pp + 1] <= rk) ++pp;
+                const double dlt = w - bs[bi].cent[pp];
+                e4[bi] += s * dlt * dlt;
             }
-            e4[bi] = acc;
         }
     }
 #pragma unroll
     for (int bi = 0; bi < 4; ++bi) {
         double x = e4[bi];
         for (int d = 32; d >= 1; d >>= 1) x += __shfl_down(x, d, 64);
-        if (lane == 0) red[bi * 16 + wave] = x;
+        if (lane == 0) red[bi * 2 + wave] = x;
     }
     __syncthreads();
 
+    // ---- outputs ------------------------------------------------------------------
     const int nb = prm.bmax - prm.bmin + 1;
-    if (wave < 4 && bs[wave].active) {
-        const int bi = wave, b = wave + 1, K = 1 << b;
-        double x = (lane < nwave) ? red[bi * 16 + lane] : 0.0;
-        for (int d = 8; d >= 1; d >>= 1) x += __shfl_down(x, d, 64);
-        long long obase;
-        if (prm.bits) {
-            if (lane == 0) prm.E[row] = x;
-            obase = row * 16;
-        } else {
-            if (lane == 0) prm.E[row * nb + (b - prm.bmin)] = x;
-            obase = row * prm.stride + ((1 << b) - (1 << prm.bmin));
-        }
-        if (lane < K) {
-            const int p = lane;
-            const int k = bs[bi].idx[p];
-            const int b0 = bs[bi].B[p], b1 = bs[bi].B[p + 1];
-            const float up = (b1 > b0) ? elem_w(sorted[swz((uint32_t)(b1 - 1))]) : -INFINITY;
-            prm.cent[obase + k] = bs[bi].cent[p];
-            if (prm.upper) prm.upper[obase + k] = up;
+    if (wave == 0) {
+        for (int bi = 0; bi < 4; ++bi) {
+            if (!bs[bi].active) continue;
+            const int bb = bi + 1, Kb = 1 << bb;
+            const double err = red[bi * 2] + red[bi * 2 + 1];
+            long long obase;
             if (prm.bits) {
-                thr[p] = up;
-                thl[p] = k;
+                if (lane == 0) prm.E[row] = err;
+                obase = row * 16;
+            } else {
+                if (lane == 0) prm.E[row * nb + (bb - prm.bmin)] = err;
+                obase = row * prm.stride + ((1 << bb) - (1 << prm.bmin));
             }
-        } else if (prm.bits && lane < 16) {
-            prm.cent[obase + lane] = 0.0;
-            if (prm.upper) prm.upper[obase + lane] = -INFINITY;
+            if (lane < Kb) {
+                const int k = bs[bi].idx[lane];
+                const int b0 = bs[bi].B[lane], b1 = bs[bi].B[lane + 1];
+                const float up = (b1 > b0) ? elem_w(keys[b1 - 1]) : -INFINITY;
+                prm.cent[obase + k] = bs[bi].cent[lane];
+                if (prm.upper) prm.upper[obase + k] = up;
+                if (prm.bits) {
+                    thr[lane] = up;
+                    thl[lane] = k;
+                }
+            } else if (prm.bits && lane < 16) {
+                prm.cent[obase + lane] = 0.0;
+                if (prm.upper) prm.upper[obase + lane] = -INFINITY;
+            }
         }
     }
     if (prm.bits && prm.labels) {
         __syncthreads();
         // label of a column: the cluster whose value range holds w~ (ranges are
         // disjoint and ordered by position; empty ones have upper = -inf)
-        const int K = 1 << rowbits;
+        const int Kr = 1 << rowbits;
         float th[16];
         int tl[16];
 #pragma unroll
-        for (int p = 0; p < 16; ++p) {
-            th[p] = (p < K) ? thr[p] : -INFINITY;
-            tl[p] = (p < K) ? thl[p] : 0;
+        for (int k = 0; k < 16; ++k) {
+            th[k] = (k < Kr) ? thr[k] : -INFINITY;
+            tl[k] = (k < Kr) ? thl[k] : 0;
         }
+        const float *Wr = prm.W + row * prm.ld;
         uint8_t *Lr = prm.labels + row * (long long)m;
-        for (int j = tid; j < m; j += nth) {
-            float wt, st;
-            scaled_pair(Wr[j], Sr[j], prm.alpha, j, wt, st);
+        for (int j = tid; j < m; j += LLOYD_THREADS) {
+            const float w = Wr[j];
+            const float wt = prm.alpha ? __fdiv_rn(w, prm.alpha[j]) : w;
             int lab = -1, last = 0;
 #pragma unroll
-            for (int p = 0; p < 16; ++p) {
-                const bool nonempty = th[p] != -INFINITY;
-                if (nonempty) last = tl[p];
-                if (lab < 0 && nonempty && wt <= th[p]) lab = tl[p];
+            for (int k = 0; k < 16; ++k) {
+                const bool nonempty = th[k] != -INFINITY;
+                if (nonempty) last = tl[k];
+                if (lab < 0 && nonempty && wt <= th[k]) lab = tl[k];
             }
             Lr[j] = (uint8_t)(lab < 0 ? last : lab);
         }
@@ -640,31 +709,52 @@ __global__ void select_kernel(long long n, int bmin, int bmax, const uint8_t *bi
     if (err && k == 0) err[i] = E[i * nb + (b - bmin)];
 }
 
-size_t cluster_lds_bytes(int P) {
-    const int nchunkP = P >> 4;
-    size_t b = (size_t)P * 8 + (size_t)nchunkP * 16 + (size_t)((nchunkP + 15) >> 4) * 16 + (size_t)(nchunkP + 1) * 8 +
-               17 * 8 + 4 * sizeof(BitState) + 64 * 8 + 16 * 4 + 17 * 4;
-    return (b + 15) & ~(size_t)15;
+size_t sort_lds_bytes(int P) { return (size_t)P * 8 + 16 * 16 + 17 * 8; }
+
+size_t lloyd_lds_bytes(int m) {
+    const int n1u = (m + 15) >> 4, n2u = (n1u + 15) >> 4, n3u = (n2u + 15) >> 4;
+    return (size_t)(n1u + n2u + n3u) * 16 + 4 * sizeof(BitState) + 8 * 8 + 16 * 4 + 16 * 4;
+}
+
+// Scratch layout of one call (inside the caller's workspace).
+skim_status carve_cluster_ws(skim_ctx *ctx, ClusterParams &prm, int64_t n, double **cent_scratch) {
+    int logP = 6;
+    while ((1 << logP) < prm.m) ++logP;
+    if (logP < 10) logP = 10;   // at least 1024 keys = one wavefront of 16-key threads
+    prm.logP = logP;
+    prm.P = 1 << logP;
+    prm.n1 = prm.P / EPT;
+    prm.n2 = (prm.n1 + 15) / 16;
+    prm.n3 = (prm.n2 + 15) / 16;
+    skim_ws_cursor cur{(char *)ctx->ws, 0, ctx->ws_bytes};
+    prm.keys = (u64 *)cur.take((size_t)n * prm.m * sizeof(u64));
+    prm.L1 = (double2 *)cur.take((size_t)n * prm.n1 * sizeof(double2));
+    prm.L2 = (double2 *)cur.take((size_t)n * prm.n2 * sizeof(double2));
+    prm.L3 = (double2 *)cur.take((size_t)n * prm.n3 * sizeof(double2));
+    prm.cpre = (double *)cur.take((size_t)n * (prm.n1 + 1) * sizeof(double));
+    bool ok = prm.keys && prm.L1 && prm.L2 && prm.L3 && prm.cpre;
+    if (cent_scratch) {
+        *cent_scratch = (double *)cur.take((size_t)n * prm.stride * sizeof(double));
+        ok = ok && *cent_scratch;
+    }
+    if (!ok) SKIM_FAIL(ctx, SKIM_ERR_WORKSPACE, "workspace missing or smaller than skim_workspace_bytes(n, m)");
+    return SKIM_OK;
 }
 
 skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n) {
-    int logP = 4;
-    while ((1 << logP) < prm.m) ++logP;
-    if (logP < 8) logP = 8;  // at least 256 keys: keeps the four Lloyd wavefronts' thread count simple
-    prm.logP = logP;
-    prm.P = 1 << logP;
     int threads = prm.P / EPT;
     if (threads < MIN_THREADS) threads = MIN_THREADS;
-    const size_t lds = cluster_lds_bytes(prm.P);
+    const size_t lds = sort_lds_bytes(prm.P);
     if ((int64_t)lds > ctx->lds_limit)
         SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "row length %d needs %zu bytes of LDS, device allows %d", prm.m, lds, ctx->lds_limit);
     static size_t lds_enabled = 0;
     if (lds > 65536 && lds > lds_enabled) {
-        SKIM_HIP(ctx, hipFuncSetAttribute((const void *)cluster_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ctx->lds_limit));
+        SKIM_HIP(ctx, hipFuncSetAttribute((const void *)sort_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ctx->lds_limit));
         lds_enabled = (size_t)ctx->lds_limit;
     }
     if (n == 0) return SKIM_OK;
-    hipLaunchKernelGGL(cluster_kernel, dim3((unsigned)n), dim3(threads), lds, ctx->stream, prm);
+    hipLaunchKernelGGL(sort_kernel, dim3((unsigned)n), dim3(threads), lds, ctx->stream, prm);
+    hipLaunchKernelGGL(lloyd_kernel, dim3((unsigned)n), dim3(LLOYD_THREADS), lloyd_lds_bytes(prm.m), ctx->stream, prm);
     SKIM_HIP(ctx, hipGetLastError());
     return SKIM_OK;
 }
@@ -687,12 +777,11 @@ extern "C" skim_status skim_error_table(skim_ctx *ctx, const float *W, const flo
     prm.bmin = bmin; prm.bmax = bmax; prm.bits = nullptr; prm.E = E;
     prm.stride = (2 << bmax) - (1 << bmin);
     // the kernel always records centroids; give it a place when the caller wants none
-    if (!centroids_all) {
-        skim_ws_cursor cur{(char *)ctx->ws, 0, ctx->ws_bytes};
-        centroids_all = (double *)cur.take((size_t)n * prm.stride * sizeof(double));
-        if (!centroids_all) SKIM_FAIL(ctx, SKIM_ERR_WORKSPACE, "workspace too small for the centroid scratch");
-    }
-    prm.cent = centroids_all; prm.upper = upper_all; prm.labels = nullptr;
+    double *scratch = nullptr;
+    if ((st = carve_cluster_ws(ctx, prm, n, centroids_all ? nullptr : &scratch)) != SKIM_OK) return st;
+    prm.cent = centroids_all ? centroids_all : scratch;
+    prm.upper = upper_all;
+    prm.labels = nullptr;
     return launch_cluster(ctx, prm, n);
 }
 
@@ -710,6 +799,7 @@ extern "C" skim_status skim_cluster_rows(skim_ctx *ctx, const float *W, const fl
     prm.W = W; prm.S = S; prm.alpha = alpha; prm.ld = ld; prm.m = (int)m; prm.iters = iters;
     prm.bmin = 1; prm.bmax = 4; prm.bits = bits; prm.E = err; prm.cent = centroids; prm.upper = upper;
     prm.labels = labels; prm.stride = 16;
+    if ((st = carve_cluster_ws(ctx, prm, n, nullptr)) != SKIM_OK) return st;
     return launch_cluster(ctx, prm, n);
 }
 
