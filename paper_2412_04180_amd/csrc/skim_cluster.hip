@@ -2,10 +2,11 @@
 // re-clustering of W * alpha^-1 in Alg. 2) for gfx950.
 //
 // Two kernels per call.
-//  sort_kernel   one workgroup per row: the row's (w~, s~) pairs become 64-bit keys
-//                (order-preserving image of w~ in the high word, bits of s~ in the low word),
-//                are sorted once in LDS and written to scratch together with float64 sums of
-//                s~ and s~ w~ per aligned 16-key chunk, 256-key block and 4096-key super-block.
+//  sort_kernel   one workgroup per row: the row's (w~, s~) pairs become 64-bit keys whose bit
+//                pattern, read as a float64, orders like (w~, s~); they are sorted once in LDS
+//                (bitonic network, compare-exchange = v_min_f64 + v_max_f64) and written to
+//                scratch together with float64 sums of s~ and s~ w~ per aligned 16-key chunk,
+//                256-key block and 4096-key super-block.
 //  lloyd_kernel  two wavefronts per row, many rows in flight per compute unit.  In sorted order
 //                every cluster of a 1-D K-means is a contiguous rank range, so one Lloyd
 //                iteration is: per pair of neighbouring centroids a search for the rank where
@@ -25,8 +26,9 @@ typedef unsigned long long u64;
 namespace {
 
 constexpr int EPT = 16;           // sorted elements owned by one thread
-constexpr int MIN_THREADS = 256;
-constexpr unsigned long long NEUTRAL_KEY = 0x8000000000000000ull;  // encodes (w = +0, s = +0)  // four wavefronts: one per bit width in the Lloyd phase
+constexpr int MIN_THREADS = 64;
+constexpr u64 NEUTRAL_KEY = 0ull;                    // encodes (w = +0, s = +0)
+constexpr u64 PAD_KEY = 0x7FF0000000000000ull;       // +infinity: above every key of finite w
 
 struct ClusterParams {
     const float *W, *S, *alpha;
@@ -56,17 +58,29 @@ struct BitState {  // what the Lloyd lanes of one bit width leave for the epilog
 
 __device__ __forceinline__ uint32_t swz(uint32_t i) { return i ^ ((i >> 4) & 15u); }
 
-__device__ __forceinline__ uint32_t w_to_key(float w) {
-    if (w == 0.0f) w = 0.0f;  // -0 and +0 are one value
-    uint32_t u = __float_as_uint(w);
-    return u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+// Key of a (w, s) pair, s >= 0, both finite.  High word = the bits of w (-0 folded into +0), low
+// word = the bits of s, complemented when w is negative.  Read as a float64 the key is finite
+// (its exponent field is all ones only for w = inf/nan) and orders like (w, s): positive keys
+// grow with (high, low); negative keys fall with their magnitude, i.e. with |w| and, for equal
+// w, with the complemented s.  Two keys are equal only when w and s are.
+__device__ __forceinline__ u64 make_key(float w, float s) {
+    if (w == 0.0f) w = 0.0f;
+    if (s == 0.0f) s = 0.0f;
+    const uint32_t hi = __float_as_uint(w);
+    uint32_t lo = __float_as_uint(s);
+    if (hi >> 31) lo = ~lo;
+    return ((u64)hi << 32) | (u64)lo;
 }
-__device__ __forceinline__ float key_to_w(uint32_t k) {
-    uint32_t u = k ^ ((k >> 31) ? 0x80000000u : 0xFFFFFFFFu);
-    return __uint_as_float(u);
+__device__ __forceinline__ float elem_w(u64 e) { return __uint_as_float((uint32_t)(e >> 32)); }
+__device__ __forceinline__ float elem_s(u64 e) {
+    const uint32_t lo = (uint32_t)e;
+    return __uint_as_float((e >> 63) ? ~lo : lo);
 }
-__device__ __forceinline__ float elem_w(u64 e) { return key_to_w((uint32_t)(e >> 32)); }
-__device__ __forceinline__ float elem_s(u64 e) { return __uint_as_float((uint32_t)e); }
+// same key with s replaced by 1 (unit weights)
+__device__ __forceinline__ u64 unit_weight_key(u64 e) {
+    const uint32_t one = 0x3F800000u;
+    return (e & 0xFFFFFFFF00000000ull) | (u64)((e >> 63) ? ~one : one);
+}
 
 // Column scaling ahead of the clustering (Sec. 4.3): w~ = w / alpha and
 // s~ = (s * alpha) * alpha, each a single-precision IEEE operation.
@@ -81,87 +95,119 @@ __device__ __forceinline__ void scaled_pair(float w, float s, const float *alpha
     }
 }
 
-__device__ __forceinline__ void ce(u64 &a, u64 &b, bool desc) {
-    const bool sw = (a > b) != desc;
-    const u64 x = sw ? b : a;
-    const u64 y = sw ? a : b;
-    a = x;
-    b = y;
+// Compare-exchange, smaller key to a: two full-rate VALU instructions on the float64 view of
+// the keys (min/max return one of their finite operands bit for bit).
+__device__ __forceinline__ void ce(double &a, double &b) {
+    double lo, hi;
+    asm("v_min_f64 %0, %1, %2" : "=v"(lo) : "v"(a), "v"(b));
+    asm("v_max_f64 %0, %1, %2" : "=v"(hi) : "v"(a), "v"(b));
+    a = lo;
+    b = hi;
 }
 
-// One pass over LDS of the bitonic network: the thread holds the 16 elements
-// whose indices differ in bits [wb, wb+4) and runs the compare-exchange stages
-// of merge size 2^klog for index bits wb+RB_HI down to wb+RB_LO.
-template <int RB_HI, int RB_LO>
-__device__ __forceinline__ void sort_round(u64 *lds, uint32_t t, int wb, int klog) {
+// Bitonic sorting network in its direction-free form: the merge of size 2^klog starts with a
+// "flip" stage that pairs index i with i ^ (2^klog - 1), followed by the stages i <-> i ^ 2^b for
+// b = klog-2 .. 0; every comparator sends the smaller key to the lower index.  Padding keys
+// (+inf at the top indices) therefore never move.
+//
+// One pass over LDS: the thread holds the 16 keys whose indices differ in bits [wb, wb+4) and
+// runs up to 4 consecutive stages in registers.  In a pass that opens a merge (FLIP >= 0 is the
+// window bit of the flip stage) the registers with that bit set are taken from the thread whose
+// low wb index bits are complemented, so that both keys of every flip pair sit in one thread.
+template <int FLIP, int HI, int LO>
+__device__ __forceinline__ void sort_pass(double *lds, uint32_t t, int wb, int m) {
     const uint32_t lowmask = (1u << wb) - 1u;
     const uint32_t base = ((t >> wb) << (wb + 4)) | (t & lowmask);
-    u64 v[EPT];
+    if ((int)(base & ~lowmask) >= m) return;   // all 16 keys are padding
+    const uint32_t fbase = base ^ lowmask;
+    uint32_t addr[EPT];
+    double v[EPT];
 #pragma unroll
-    for (int r = 0; r < EPT; ++r) v[r] = lds[swz(base | ((uint32_t)r << wb))];
+    for (int r = 0; r < EPT; ++r) {
+        const bool flipped = (FLIP >= 0) && (r & (1 << (FLIP >= 0 ? FLIP : 0)));
+        addr[r] = swz((flipped ? fbase : base) | ((uint32_t)r << wb));
+        v[r] = lds[addr[r]];
+    }
+    if (FLIP >= 0) {
 #pragma unroll
-    for (int rb = RB_HI; rb >= RB_LO; --rb) {
-#pragma unroll
-        for (int r = 0; r < EPT; ++r) {
-            if (!(r & (1 << rb))) {
-                const uint32_t i = base | ((uint32_t)r << wb);
-                const bool desc = (i >> klog) & 1u;
-                ce(v[r], v[r | (1 << rb)], desc);
-            }
-        }
+        for (int r = 0; r < EPT; ++r)
+            if (!(r & (1 << (FLIP >= 0 ? FLIP : 0)))) ce(v[r], v[r ^ ((2 << (FLIP >= 0 ? FLIP : 0)) - 1)]);
     }
 #pragma unroll
-    for (int r = 0; r < EPT; ++r) lds[swz(base | ((uint32_t)r << wb))] = v[r];
+    for (int rb = HI; rb >= LO; --rb) {
+#pragma unroll
+        for (int r = 0; r < EPT; ++r)
+            if (!(r & (1 << rb))) ce(v[r], v[r | (1 << rb)]);
+    }
+#pragma unroll
+    for (int r = 0; r < EPT; ++r) lds[addr[r]] = v[r];
 }
 
 // The merges of size 2, 4, 8, 16 in one pass (index bits 0..3 are in-thread).
-__device__ __forceinline__ void sort_first_round(u64 *lds, uint32_t t) {
+__device__ __forceinline__ void sort_first_pass(double *lds, uint32_t t, int m) {
     const uint32_t base = t << 4;
-    u64 v[EPT];
+    if ((int)base >= m) return;
+    double v[EPT];
 #pragma unroll
     for (int r = 0; r < EPT; ++r) v[r] = lds[swz(base | (uint32_t)r)];
 #pragma unroll
-    for (int klog = 1; klog <= 4; ++klog) {
+    for (int tb = 0; tb < 4; ++tb) {
 #pragma unroll
-        for (int rb = klog - 1; rb >= 0; --rb) {
+        for (int r = 0; r < EPT; ++r)
+            if (!(r & (1 << tb))) ce(v[r], v[r ^ ((2 << tb) - 1)]);
 #pragma unroll
-            for (int r = 0; r < EPT; ++r) {
-                if (!(r & (1 << rb))) {
-                    const uint32_t i = base | (uint32_t)r;
-                    const bool desc = (i >> klog) & 1u;
-                    ce(v[r], v[r | (1 << rb)], desc);
-                }
-            }
+        for (int rb = tb - 1; rb >= 0; --rb) {
+#pragma unroll
+            for (int r = 0; r < EPT; ++r)
+                if (!(r & (1 << rb))) ce(v[r], v[r | (1 << rb)]);
         }
     }
 #pragma unroll
     for (int r = 0; r < EPT; ++r) lds[swz(base | (uint32_t)r)] = v[r];
 }
 
-__device__ __forceinline__ void dispatch_round(u64 *lds, uint32_t t, int wb, int rb_hi, int rb_lo, int klog) {
-    switch (rb_hi * 4 + rb_lo) {
-        case 0: sort_round<0, 0>(lds, t, wb, klog); break;
-        case 4: sort_round<1, 0>(lds, t, wb, klog); break;
-        case 5: sort_round<1, 1>(lds, t, wb, klog); break;
-        case 8: sort_round<2, 0>(lds, t, wb, klog); break;
-        case 9: sort_round<2, 1>(lds, t, wb, klog); break;
-        case 10: sort_round<2, 2>(lds, t, wb, klog); break;
-        case 12: sort_round<3, 0>(lds, t, wb, klog); break;
-        case 13: sort_round<3, 1>(lds, t, wb, klog); break;
-        case 14: sort_round<3, 2>(lds, t, wb, klog); break;
-        case 15: sort_round<3, 3>(lds, t, wb, klog); break;
-        default: break;
+// flip < 0: plain pass over window bits hi..lo; flip >= 0: flip stage on window bit `flip`, then bits flip-1..lo
+__device__ __forceinline__ void dispatch_pass(double *lds, uint32_t t, int wb, int flip, int hi, int lo, int m) {
+    if (flip < 0) {
+        switch (hi * 4 + lo) {
+            case 0: sort_pass<-1, 0, 0>(lds, t, wb, m); break;
+            case 4: sort_pass<-1, 1, 0>(lds, t, wb, m); break;
+            case 5: sort_pass<-1, 1, 1>(lds, t, wb, m); break;
+            case 8: sort_pass<-1, 2, 0>(lds, t, wb, m); break;
+            case 9: sort_pass<-1, 2, 1>(lds, t, wb, m); break;
+            case 10: sort_pass<-1, 2, 2>(lds, t, wb, m); break;
+            case 12: sort_pass<-1, 3, 0>(lds, t, wb, m); break;
+            case 13: sort_pass<-1, 3, 1>(lds, t, wb, m); break;
+            case 14: sort_pass<-1, 3, 2>(lds, t, wb, m); break;
+            case 15: sort_pass<-1, 3, 3>(lds, t, wb, m); break;
+            default: break;
+        }
+    } else {
+        switch (flip * 4 + lo) {
+            case 0: sort_pass<0, -1, 0>(lds, t, wb, m); break;
+            case 4: sort_pass<1, 0, 0>(lds, t, wb, m); break;
+            case 5: sort_pass<1, 0, 1>(lds, t, wb, m); break;
+            case 8: sort_pass<2, 1, 0>(lds, t, wb, m); break;
+            case 9: sort_pass<2, 1, 1>(lds, t, wb, m); break;
+            case 10: sort_pass<2, 1, 2>(lds, t, wb, m); break;
+            case 12: sort_pass<3, 2, 0>(lds, t, wb, m); break;
+            case 13: sort_pass<3, 2, 1>(lds, t, wb, m); break;
+            case 14: sort_pass<3, 2, 2>(lds, t, wb, m); break;
+            case 15: sort_pass<3, 2, 3>(lds, t, wb, m); break;
+            default: break;
+        }
     }
 }
 
-// Bitonic sort of P = 2^logP keys in LDS, P/16 working threads.
-__device__ void sort_row(u64 *lds, int logP, uint32_t tid) {
+// Sort of P = 2^logP keys in LDS (the last P - m of them padding), P/16 working threads.
+__device__ void sort_row(double *lds, int logP, uint32_t tid, int m) {
     const uint32_t nwork = 1u << (logP - 4);
     const int topbase = (logP >> 2) << 2;  // bits >= topbase live in the shifted top window when logP % 4 != 0
-    if (tid < nwork) sort_first_round(lds, tid);
+    if (tid < nwork) sort_first_pass(lds, tid, m);
     __syncthreads();
     for (int klog = 5; klog <= logP; ++klog) {
         int b = klog - 1;
+        bool first = true;
         while (b >= 0) {
             int wb, lo;
             if ((logP & 3) && b >= topbase) {
@@ -171,8 +217,9 @@ __device__ void sort_row(u64 *lds, int logP, uint32_t tid) {
                 wb = (b >> 2) << 2;
                 lo = wb;
             }
-            if (tid < nwork) dispatch_round(lds, tid, wb, b - wb, lo - wb, klog);
+            if (tid < nwork) dispatch_pass(lds, tid, wb, first ? b - wb : -1, b - wb, lo - wb, m);
             __syncthreads();
+            first = false;
             b = lo - 1;
         }
     }
@@ -222,18 +269,17 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     const float *Sr = prm.S + row * prm.ld;
 
     for (int j = tid; j < P; j += nth) {
-        u64 key = ~0ull;
+        u64 key = PAD_KEY;
         if (j < m) {
             float wt, st;
             scaled_pair(Wr[j], Sr[j], prm.alpha, j, wt, st);
-            if (st == 0.0f) st = 0.0f;
-            key = ((u64)w_to_key(wt) << 32) | (u64)__float_as_uint(st);
+            key = make_key(wt, st);
         }
         sorted[swz((uint32_t)j)] = key;
     }
     __syncthreads();
 
-    sort_row(sorted, prm.logP, (uint32_t)tid);
+    sort_row((double *)sorted, prm.logP, (uint32_t)tid, m);
 
     double2 *L1 = prm.L1 + row * prm.n1;
     double2 *L2 = prm.L2 + row * prm.n2;
@@ -284,7 +330,7 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
             __syncthreads();
             for (int j = tid; j < m; j += nth) {
                 const uint32_t a = swz((uint32_t)j);
-                sorted[a] = (sorted[a] & 0xFFFFFFFF00000000ull) | 0x3F800000ull;
+                sorted[a] = unit_weight_key(sorted[a]);
             }
             __syncthreads();
             continue;
@@ -605,23 +651,36 @@ __global__ void __launch_bounds__(LLOYD_THREADS) lloyd_kernel(ClusterParams prm)
 
     // ---- errors: sum s (w - c)^2 over the sorted row, every key once ----------
     double e4[4] = {0.0, 0.0, 0.0, 0.0};
-    int pc[4] = {0, 0, 0, 0};
+    // per bit width, the same in every lane: cluster of the first key of the current stretch of 64
+    // ranks, the rank where that cluster ends, its centroid
+    int pcur[4] = {0, 0, 0, 0}, nxt[4] = {0, 0, 0, 0};
+    double ccur[4] = {0.0, 0.0, 0.0, 0.0};
+    int act[4];
+#pragma unroll
+    for (int bi = 0; bi < 4; ++bi) act[bi] = __builtin_amdgcn_readfirstlane(bs[bi].active);
     for (int base = wave * 64; base < m; base += LLOYD_THREADS) {
         const int rk = base + lane;
-        const u64 el = (rk < m) ? keys[rk] : NEUTRAL_KEY;
+        const u64 el = (rk < m) ? keys[rk] : NEUTRAL_KEY;   // ranks past the row carry s = 0 and add nothing
         const double w = (double)elem_w(el), s = (double)elem_s(el);
 #pragma unroll
         for (int bi = 0; bi < 4; ++bi) {
-            if (!bs[bi].active) continue;
+            if (!act[bi]) continue;
             const int Kb = 2 << bi;
-            int pp = pc[bi];                       // same in every lane: cluster of the first key of this stretch
-            while (pp + 1 < Kb && bs[bi].B[pp + 1] <= base) ++pp;
-            pc[bi] = pp;
-            if (rk < m) {
-                while (pp + 1 < Kb && bs[bi].B[pp + 1] <= rk) ++pp;
-                const double dlt = w - bs[bi].cent[pp];
-                e4[bi] += s * dlt * dlt;
+            if (base >= nxt[bi]) {
+                int pp = pcur[bi];
+                while (pp + 1 < Kb && __builtin_amdgcn_readfirstlane(bs[bi].B[pp + 1]) <= base) ++pp;
+                pcur[bi] = pp;
+                nxt[bi] = __builtin_amdgcn_readfirstlane(bs[bi].B[pp + 1]);
+                ccur[bi] = bs[bi].cent[pp];
             }
+            double c = ccur[bi];
+            if (base + 64 > nxt[bi]) {   // a boundary falls inside this stretch: look the cluster up per lane
+                int pp = pcur[bi];
+                while (pp + 1 < Kb && bs[bi].B[pp + 1] <= rk) ++pp;
+                c = bs[bi].cent[pp];
+            }
+            const double dlt = w - c;
+            e4[bi] += s * dlt * dlt;
         }
     }
 #pragma unroll
