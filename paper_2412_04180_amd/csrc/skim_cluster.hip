@@ -199,30 +199,44 @@ __device__ __forceinline__ void dispatch_pass(double *lds, uint32_t t, int wb, i
     }
 }
 
-// Sort of P = 2^logP keys in LDS (the last P - m of them padding), P/16 working threads.
-__device__ void sort_row(double *lds, int logP, uint32_t tid, int m) {
-    const uint32_t nwork = 1u << (logP - 4);
-    const int topbase = (logP >> 2) << 2;  // bits >= topbase live in the shifted top window when logP % 4 != 0
-    if (tid < nwork) sort_first_pass(lds, tid, m);
-    __syncthreads();
-    for (int klog = 5; klog <= logP; ++klog) {
-        int b = klog - 1;
-        bool first = true;
-        while (b >= 0) {
-            int wb, lo;
-            if ((logP & 3) && b >= topbase) {
-                wb = logP - 4;
-                lo = topbase;
-            } else {
-                wb = (b >> 2) << 2;
-                lo = wb;
-            }
-            if (tid < nwork) dispatch_pass(lds, tid, wb, first ? b - wb : -1, b - wb, lo - wb, m);
-            __syncthreads();
-            first = false;
-            b = lo - 1;
+// Stages on index bits b..0 with windows that stay inside the 2^loc keys of one wavefront's
+// 64 threads: no workgroup barrier is needed between these passes (a wavefront's LDS accesses
+// execute in order).  flip: the first pass opens a merge with the flip stage on bit b.
+__device__ __forceinline__ void local_passes(double *lds, uint32_t tid, bool work, int loc, int b, bool flip, int m) {
+    const int ltop = (loc >> 2) << 2;   // bits >= ltop use the shifted window [loc-4, loc) when loc % 4 != 0
+    bool first = flip;
+    while (b >= 0) {
+        int wb, lo;
+        if ((loc & 3) && b >= ltop) {
+            wb = loc - 4;
+            lo = ltop;
+        } else {
+            wb = (b >> 2) << 2;
+            lo = wb;
         }
+        if (work) dispatch_pass(lds, tid, wb, first ? b - wb : -1, b - wb, lo - wb, m);
+        first = false;
+        b = lo - 1;
     }
+}
+
+// Sort of P = 2^logP keys in LDS (the last P - m of them padding), P/16 working threads.
+// Merges up to 1024 keys run inside one wavefront (its 64 threads own an aligned block of 1024
+// keys); larger merges take one pass over the high index bits between two workgroup barriers
+// and finish inside the wavefronts again.
+__device__ void sort_row(double *lds, int logP, uint32_t tid, int m) {
+    const bool work = tid < (1u << (logP - 4));
+    const int loc = logP < 10 ? logP : 10;
+    if (work) sort_first_pass(lds, tid, m);
+    for (int klog = 5; klog <= loc; ++klog) local_passes(lds, tid, work, loc, klog - 1, true, m);
+    for (int klog = loc + 1; klog <= logP; ++klog) {
+        const int wb = logP - 4;
+        __syncthreads();
+        if (work) dispatch_pass(lds, tid, wb, klog - 1 - wb, klog - 1 - wb, loc - wb, m);
+        __syncthreads();
+        local_passes(lds, tid, work, loc, loc - 1, false, m);
+    }
+    __syncthreads();
 }
 
 __device__ __forceinline__ double shfl_d(double x, int src) { return __shfl(x, src, 64); }
