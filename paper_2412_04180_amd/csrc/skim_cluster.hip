@@ -380,7 +380,7 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
 // chunks, 256-key blocks, 4096-key super-blocks): nothing outside [a, b) enters, so a cluster of
 // tiny weight mass next to a heavy element keeps full relative precision (a difference of
 // running prefix sums would not).  Keys come from global memory, sums from LDS.
-__device__ __forceinline__ void range_sum(const u64 *__restrict__ keys, const double2 *L1, const double2 *L2,
+__device__ __forceinline__ void range_sum(const u64 *__restrict__ keys, const double2 *__restrict__ L1, const double2 *L2,
                                           const double2 *L3, int a, int b, int g, double &D, double &N) {
     constexpr int G = 4, T = 4;
     const int e0 = min(b, (a + 15) & ~15), e1 = max(e0, b & ~15);
@@ -391,26 +391,30 @@ __device__ __forceinline__ void range_sum(const u64 *__restrict__ keys, const do
     const bool has2 = b0 < b3;
     const int b1 = has2 ? min(b3, (b0 + 15) & ~15) : b0, b2 = has2 ? max(b1, b3 & ~15) : b0;
     const int s0 = b1 >> 4, s1 = has2 ? (b2 >> 4) : s0;
-    // issue every load first (predicated), then add in a fixed order
+    // issue every global load first (predicated), then add in a fixed order
     u64 el[2 * T];
+    double2 ch[2 * T];
 #pragma unroll
     for (int t = 0; t < T; ++t) {
         const int o = g + t * G;
         el[t] = (a + o < e0) ? keys[a + o] : NEUTRAL_KEY;
         el[T + t] = (e1 + o < b) ? keys[e1 + o] : NEUTRAL_KEY;
+        ch[t] = (has1 && c0 + o < c1) ? L1[c0 + o] : make_double2(0.0, 0.0);
+        ch[T + t] = (has1 && c2 + o < c3) ? L1[c2 + o] : make_double2(0.0, 0.0);
     }
     double d = 0.0, n = 0.0;
+    if (has2) {
 #pragma unroll
-    for (int t = 0; t < T; ++t) {
-        const int o = g + t * G;
-        if (has1) {
-            if (c0 + o < c1) { const double2 x = L1[c0 + o]; d += x.x; n += x.y; }
-            if (c2 + o < c3) { const double2 x = L1[c2 + o]; d += x.x; n += x.y; }
-        }
-        if (has2) {
+        for (int t = 0; t < T; ++t) {
+            const int o = g + t * G;
             if (b0 + o < b1) { const double2 x = L2[b0 + o]; d += x.x; n += x.y; }
             if (b2 + o < b3) { const double2 x = L2[b2 + o]; d += x.x; n += x.y; }
         }
+    }
+#pragma unroll
+    for (int t = 0; t < 2 * T; ++t) {
+        d += ch[t].x;
+        n += ch[t].y;
     }
     for (int q = s0 + g; q < s1; q += G) {
         const double2 x = L3[q];
@@ -461,12 +465,11 @@ constexpr int LLOYD_THREADS = 128;
 // Two wavefronts per row.  Wavefront 0 carries the bit widths 1, 2, 3 (lanes 0-7, 8-23, 24-55),
 // wavefront 1 the bit width 4 (64 lanes).  Position p (sorted order of centroid values) of a
 // bit width is a quad of lanes which searches its lower boundary together and shares its sums.
-__global__ void __launch_bounds__(LLOYD_THREADS) lloyd_kernel(ClusterParams prm) {
+__global__ void __launch_bounds__(LLOYD_THREADS) __attribute__((amdgpu_waves_per_eu(5, 8))) lloyd_kernel(ClusterParams prm) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int m = prm.m;
     const int n1u = (m + 15) >> 4, n2u = (n1u + 15) >> 4, n3u = (n2u + 15) >> 4;
-    double2 *L1 = (double2 *)smem;
-    double2 *L2 = L1 + n1u;
+    double2 *L2 = (double2 *)smem;
     double2 *L3 = L2 + n2u;
     BitState *bs = (BitState *)(L3 + n3u);
     double *red = (double *)(bs + 4);        // 4 x 2 partial errors
@@ -476,10 +479,10 @@ __global__ void __launch_bounds__(LLOYD_THREADS) lloyd_kernel(ClusterParams prm)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const long long row = blockIdx.x;
     const u64 *__restrict__ keys = prm.keys + row * (long long)m;
+    const double2 *__restrict__ L1 = prm.L1 + row * prm.n1;   // chunk sums stay in global memory (cache-resident)
     const double *__restrict__ cpre = prm.cpre + row * (prm.n1 + 1);
     {
-        const double2 *g1 = prm.L1 + row * prm.n1, *g2 = prm.L2 + row * prm.n2, *g3 = prm.L3 + row * prm.n3;
-        for (int j = tid; j < n1u; j += LLOYD_THREADS) L1[j] = g1[j];
+        const double2 *g2 = prm.L2 + row * prm.n2, *g3 = prm.L3 + row * prm.n3;
         for (int j = tid; j < n2u; j += LLOYD_THREADS) L2[j] = g2[j];
         for (int j = tid; j < n3u; j += LLOYD_THREADS) L3[j] = g3[j];
         if (tid < 4) bs[tid].active = 0;
@@ -786,7 +789,8 @@ size_t sort_lds_bytes(int P) { return (size_t)P * 8 + 16 * 16 + 17 * 8; }
 
 size_t lloyd_lds_bytes(int m) {
     const int n1u = (m + 15) >> 4, n2u = (n1u + 15) >> 4, n3u = (n2u + 15) >> 4;
-    return (size_t)(n1u + n2u + n3u) * 16 + 4 * sizeof(BitState) + 8 * 8 + 16 * 4 + 16 * 4;
+    (void)n1u;
+    return (size_t)(n2u + n3u) * 16 + 4 * sizeof(BitState) + 8 * 8 + 16 * 4 + 16 * 4;
 }
 
 // Scratch layout of one call (inside the caller's workspace).
