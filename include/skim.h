@@ -59,9 +59,9 @@ typedef struct {
 
 #define SKIM_MAX_BITS 4
 #define SKIM_MAX_K 16
-/* Longest row the clustering kernel accepts (row and sensitivities are staged
- * in the 160 KB LDS of one compute unit). */
-#define SKIM_MAX_M 16384
+/* Longest row the clustering accepts (rows up to 16384 weights are sorted in one
+ * LDS pass, longer ones in two halves merged in global memory). */
+#define SKIM_MAX_M 32768
 
 /* ---- context ------------------------------------------------------------ */
 

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libskim.so")
 SKIM_OK = 0
 STATUS_NAMES = {0: "SKIM_OK", -1: "SKIM_ERR_ARG", -2: "SKIM_ERR_SHAPE", -3: "SKIM_ERR_BUDGET",
                 -4: "SKIM_ERR_WORKSPACE", -5: "SKIM_ERR_HIP", -6: "SKIM_ERR_NONFINITE"}
-MAX_M = 16384
+MAX_M = 32768
 
 EXPORTS = ["skim_create", "skim_destroy", "skim_last_error", "skim_workspace_bytes", "skim_set_workspace",
            "skim_error_table", "skim_cluster_rows", "skim_select_allocated", "skim_greedy_allocate",

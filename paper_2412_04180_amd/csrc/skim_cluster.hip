@@ -27,6 +27,7 @@ namespace {
 
 constexpr int EPT = 16;           // sorted elements owned by one thread
 constexpr int MIN_THREADS = 64;
+constexpr int SORT_MAX_KEYS = 16384;  // keys one workgroup sorts in LDS (128 KB)
 constexpr u64 NEUTRAL_KEY = 0ull;                    // encodes (w = +0, s = +0)
 constexpr u64 PAD_KEY = 0x7FF0000000000000ull;       // +infinity: above every key of finite w
 
@@ -47,6 +48,10 @@ struct ClusterParams {
     double2 *L1, *L2, *L3;
     double *cpre;
     int n1, n2, n3;
+    // rows longer than one LDS sort are sorted in nseg segments of seglen columns (keys_seg),
+    // merged into keys, and their sums are taken by a separate kernel
+    int nseg, seglen;
+    u64 *keys_seg;
 };
 
 struct BitState {  // what the Lloyd lanes of one bit width leave for the epilogue
@@ -270,7 +275,7 @@ __device__ __forceinline__ int quad_sum(int x) {
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int P = prm.P, m = prm.m;
+    const int P = prm.P;
     const int n1 = prm.n1;
     u64 *sorted = (u64 *)smem;
     double2 *wsum = (double2 *)(smem + (size_t)P * 8);   // per-wavefront sums (16)
@@ -278,15 +283,18 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
 
     const int tid = threadIdx.x, nth = blockDim.x;
     const int lane = tid & 63, wave = tid >> 6, nwave = nth >> 6;
-    const long long row = blockIdx.x;
-    const float *Wr = prm.W + row * prm.ld;
-    const float *Sr = prm.S + row * prm.ld;
+    const long long row = blockIdx.x / prm.nseg;
+    const int col0 = (int)(blockIdx.x % prm.nseg) * prm.seglen;      // first column of this segment
+    const int m = min(prm.m - col0, prm.seglen);                     // keys sorted by this workgroup
+    const float *Wr = prm.W + row * prm.ld + col0;
+    const float *Sr = prm.S + row * prm.ld + col0;
+    const float *alpha = prm.alpha ? prm.alpha + col0 : nullptr;
 
     for (int j = tid; j < P; j += nth) {
         u64 key = PAD_KEY;
         if (j < m) {
             float wt, st;
-            scaled_pair(Wr[j], Sr[j], prm.alpha, j, wt, st);
+            scaled_pair(Wr[j], Sr[j], alpha, j, wt, st);
             key = make_key(wt, st);
         }
         sorted[swz((uint32_t)j)] = key;
@@ -295,6 +303,12 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
 
     sort_row((double *)sorted, prm.logP, (uint32_t)tid, m);
 
+    if (prm.nseg > 1) {
+        // one segment of a long row: sorted keys only; merge_kernel and sums_kernel do the rest
+        u64 *kseg = prm.keys_seg + row * (long long)prm.m + col0;
+        for (int j = tid; j < m; j += nth) kseg[j] = sorted[swz((uint32_t)j)];
+        return;
+    }
     double2 *L1 = prm.L1 + row * prm.n1;
     double2 *L2 = prm.L2 + row * prm.n2;
     double2 *L3 = prm.L3 + row * prm.n3;
@@ -368,6 +382,130 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     // sorted keys, compact and in rank order
     u64 *keys = prm.keys + row * (long long)m;
     for (int j = tid; j < m; j += nth) keys[j] = sorted[swz((uint32_t)j)];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Rows longer than one LDS sort (m > 16384): two sorted segments are merged in global memory and
+// the sums are taken afterwards.
+// ---------------------------------------------------------------------------------------------
+constexpr int MERGE_THREADS = 256;
+
+// One workgroup per row.  Each thread finds its share of the output by merge-path search and
+// merges it sequentially (keys are compared through their float64 view; ties take the first run).
+__global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(ClusterParams prm) {
+    const long long row = blockIdx.x;
+    const int m = prm.m;
+    const int la = min(prm.seglen, m), lb = m - la;
+    const double *__restrict__ A = (const double *)(prm.keys_seg + row * (long long)m);
+    const double *__restrict__ B = A + la;
+    double *__restrict__ out = (double *)(prm.keys + row * (long long)m);
+    const int q = (m + MERGE_THREADS - 1) / MERGE_THREADS;
+    const int o0 = min(m, (int)threadIdx.x * q), o1 = min(m, o0 + q);
+    if (o0 >= o1) return;
+    int lo = max(0, o0 - lb), hi = min(o0, la);
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (A[mid] <= B[o0 - 1 - mid]) lo = mid + 1; else hi = mid;
+    }
+    int i = lo, j = o0 - lo;
+    const double inf = __longlong_as_double((long long)PAD_KEY);
+    double a = (i < la) ? A[i] : inf, b = (j < lb) ? B[j] : inf;
+    for (int o = o0; o < o1; ++o) {
+        const bool ta = a <= b;
+        out[o] = ta ? a : b;
+        if (ta) {
+            ++i;
+            a = (i < la) ? A[i] : inf;
+        } else {
+            ++j;
+            b = (j < lb) ? B[j] : inf;
+        }
+    }
+}
+
+// One workgroup per row: chunk / block / super-block sums and the running sum of s from the
+// merged keys (same quantities sort_kernel produces for short rows).  m <= 32768.
+__global__ void __launch_bounds__(1024) sums_kernel(ClusterParams prm) {
+    __shared__ double2 l1[2048];
+    __shared__ double2 l2[128];
+    __shared__ double wtot[16];
+    const long long row = blockIdx.x;
+    const int m = prm.m;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n1u = (m + 15) >> 4, n2u = (n1u + 15) >> 4, n3u = (n2u + 15) >> 4;
+    u64 *keys = prm.keys + row * (long long)m;
+    double2 *L1 = prm.L1 + row * prm.n1;
+    double2 *L2 = prm.L2 + row * prm.n2;
+    double2 *L3 = prm.L3 + row * prm.n3;
+    double *cpre = prm.cpre + row * (prm.n1 + 1);
+    for (int pass = 0; pass < 2; ++pass) {
+        double cs[2] = {0.0, 0.0}, qs[2] = {0.0, 0.0};
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int ch = 2 * tid + h;
+            for (int e = 0; e < 16; ++e) {
+                const int r = ch * 16 + e;
+                if (r < m) {
+                    u64 el = keys[r];
+                    if (pass == 1) {            // no sensitivity mass in this row: unit weights
+                        el = unit_weight_key(el);
+                        keys[r] = el;
+                    }
+                    const double s = (double)elem_s(el), w = (double)elem_w(el);
+                    cs[h] += s;
+                    qs[h] = fma(s, w, qs[h]);
+                }
+            }
+            l1[ch] = make_double2(cs[h], qs[h]);
+        }
+        const double pair = cs[0] + cs[1];
+        double ic = pair;
+        for (int d = 1; d < 64; d <<= 1) {
+            const double uc = __shfl_up(ic, d, 64);
+            if (lane >= d) ic += uc;
+        }
+        double xc = __shfl_up(ic, 1, 64);
+        if (lane == 0) xc = 0.0;
+        __syncthreads();                         // previous pass's readers of wtot are done
+        if (lane == 63) wtot[wave] = ic;
+        __syncthreads();
+        double total = 0.0, before = 0.0;
+        for (int w2 = 0; w2 < 16; ++w2) {
+            if (w2 == wave) before = total;
+            total += wtot[w2];
+        }
+        if (total == 0.0 && pass == 0) continue;
+        if (2 * tid < n1u) {
+            L1[2 * tid] = l1[2 * tid];
+            cpre[2 * tid] = before + xc;
+        }
+        if (2 * tid + 1 < n1u) {
+            L1[2 * tid + 1] = l1[2 * tid + 1];
+            cpre[2 * tid + 1] = (before + xc) + cs[0];
+        }
+        if (tid == 0) cpre[prm.n1] = total;
+        if (tid < n2u) {
+            double sc = 0.0, sq = 0.0;
+            for (int k = 0; k < 16; ++k) {
+                sc += l1[16 * tid + k].x;
+                sq += l1[16 * tid + k].y;
+            }
+            l2[tid] = make_double2(sc, sq);
+            L2[tid] = l2[tid];
+        } else if (tid < 128) {
+            l2[tid] = make_double2(0.0, 0.0);
+        }
+        __syncthreads();
+        if (tid < n3u) {
+            double sc = 0.0, sq = 0.0;
+            for (int k = 0; k < 16; ++k) {
+                sc += l2[16 * tid + k].x;
+                sq += l2[16 * tid + k].y;
+            }
+            L3[tid] = make_double2(sc, sq);
+        }
+        break;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -795,12 +933,18 @@ size_t lloyd_lds_bytes(int m) {
 
 // Scratch layout of one call (inside the caller's workspace).
 skim_status carve_cluster_ws(skim_ctx *ctx, ClusterParams &prm, int64_t n, double **cent_scratch) {
+    prm.nseg = 1;
+    prm.seglen = prm.m;
+    if (prm.m > SORT_MAX_KEYS) {   // two sorted halves, merged in global memory
+        prm.nseg = 2;
+        prm.seglen = (((prm.m + 1) / 2) + 15) & ~15;
+    }
     int logP = 6;
-    while ((1 << logP) < prm.m) ++logP;
+    while ((1 << logP) < prm.seglen) ++logP;
     if (logP < 10) logP = 10;   // at least 1024 keys = one wavefront of 16-key threads
     prm.logP = logP;
     prm.P = 1 << logP;
-    prm.n1 = prm.P / EPT;
+    prm.n1 = (prm.nseg == 1) ? prm.P / EPT : (prm.m + 15) / 16;
     prm.n2 = (prm.n1 + 15) / 16;
     prm.n3 = (prm.n2 + 15) / 16;
     skim_ws_cursor cur{(char *)ctx->ws, 0, ctx->ws_bytes};
@@ -810,6 +954,11 @@ skim_status carve_cluster_ws(skim_ctx *ctx, ClusterParams &prm, int64_t n, doubl
     prm.L3 = (double2 *)cur.take((size_t)n * prm.n3 * sizeof(double2));
     prm.cpre = (double *)cur.take((size_t)n * (prm.n1 + 1) * sizeof(double));
     bool ok = prm.keys && prm.L1 && prm.L2 && prm.L3 && prm.cpre;
+    prm.keys_seg = nullptr;
+    if (prm.nseg > 1) {
+        prm.keys_seg = (u64 *)cur.take((size_t)n * prm.m * sizeof(u64));
+        ok = ok && prm.keys_seg;
+    }
     if (cent_scratch) {
         *cent_scratch = (double *)cur.take((size_t)n * prm.stride * sizeof(double));
         ok = ok && *cent_scratch;
@@ -830,7 +979,12 @@ skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n) {
         lds_enabled = (size_t)ctx->lds_limit;
     }
     if (n == 0) return SKIM_OK;
-    hipLaunchKernelGGL(sort_kernel, dim3((unsigned)n), dim3(threads), lds, ctx->stream, prm);
+    if ((int64_t)n * prm.nseg > 0x7fffffff) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "too many rows");
+    hipLaunchKernelGGL(sort_kernel, dim3((unsigned)(n * prm.nseg)), dim3(threads), lds, ctx->stream, prm);
+    if (prm.nseg > 1) {
+        hipLaunchKernelGGL(merge_kernel, dim3((unsigned)n), dim3(MERGE_THREADS), 0, ctx->stream, prm);
+        hipLaunchKernelGGL(sums_kernel, dim3((unsigned)n), dim3(1024), 0, ctx->stream, prm);
+    }
     hipLaunchKernelGGL(lloyd_kernel, dim3((unsigned)n), dim3(LLOYD_THREADS), lloyd_lds_bytes(prm.m), ctx->stream, prm);
     SKIM_HIP(ctx, hipGetLastError());
     return SKIM_OK;

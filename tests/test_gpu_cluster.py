@@ -107,6 +107,21 @@ def test_ragged_row_lengths(ctx, m):
     assert excused <= 1
 
 
+@pytest.mark.parametrize("m", [16385, 16400, 20000, 32768])
+def test_rows_longer_than_one_lds_sort(ctx, m):
+    W, S = skim_synth.make_ws_small(m, 6, m, dup_frac=0.05)
+    S[2] = 0.0                      # no sensitivity mass: unit weights on the merged path too
+    W[3, : m // 2] = np.sort(W[3, : m // 2])        # first half entirely below / interleaved with the second
+    ref, out, excused = check_table(ctx, W, S)
+    assert excused <= 3
+    bits = np.array([1, 2, 3, 4, 3, 2], np.uint8)
+    cr = ctx.cluster_rows(dev(W), dev(S), dev(bits))
+    torch.cuda.synchronize()
+    rr = oracle.cluster_rows(W, S, bits, count_near=True)
+    clean = rr["near_rows"] == 0
+    assert np.array_equal(cr["labels"].cpu().numpy()[clean], rr["labels"][clean])
+
+
 def test_duplicates_zero_sensitivities_and_dead_rows(ctx):
     W, S = skim_synth.make_ws_small(7, 64, 300, dup_frac=0.3, zero_s_frac=0.4)
     S[3] = 0.0                      # a row without any sensitivity mass -> unit weights
