@@ -65,6 +65,23 @@ def test_heap_allocator_equals_linear_scan_oracle(lib, seed):
     assert spent <= budget
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_selection_allocator_with_heavy_ties_and_rising_reductions(lib, seed):
+    """Unit costs use a closed-form order (running minimum of a row's reductions) instead of a
+    heap; integer-valued tables produce many exact ties and rows whose reductions grow with bits."""
+    rng = np.random.default_rng(100 + seed)
+    n = int(rng.integers(1, 60))
+    E = rng.integers(0, 5, (n, 4)).astype(np.float64)
+    for avg in (1.0, 1.3, 2.0, 2.5, 3.0, 3.9, 4.0):
+        bits, spent, budget = skim.greedy_allocate(E, avg)
+        ref = oracle.greedy(E, avg)
+        assert np.array_equal(bits, ref["bits"]) and spent == ref["spent"] == budget == ref["budget"]
+    E3 = rng.uniform(0, 1, (n, 3))
+    bits, spent, budget = skim.greedy_allocate(E3, 2.2, bmin=2, bmax=4)
+    ref = oracle.greedy(E3, 2.2, bmin=2, bmax=4)
+    assert np.array_equal(bits, ref["bits"]) and spent == ref["spent"]
+
+
 def test_allocator_errors(lib):
     with pytest.raises(skim.SkimError):
         skim.greedy_allocate(np.zeros((4, 4)), 0.5)
