@@ -874,6 +874,8 @@ __global__ void __launch_bounds__(LLOYD_THREADS) __attribute__((amdgpu_waves_per
             } else if (prm.bits && lane < 16) {
                 prm.cent[obase + lane] = 0.0;
                 if (prm.upper) prm.upper[obase + lane] = -INFINITY;
+                thr[lane] = INFINITY;
+                thl[lane] = bs[bi].idx[Kb - 1];
             }
         }
     }
@@ -881,27 +883,33 @@ __global__ void __launch_bounds__(LLOYD_THREADS) __attribute__((amdgpu_waves_per
         __syncthreads();
         // label of a column: the cluster whose value range holds w~ (ranges are
         // disjoint and ordered by position; empty ones have upper = -inf)
-        const int Kr = 1 << rowbits;
-        float th[16];
-        int tl[16];
-#pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            th[k] = (k < Kr) ? thr[k] : -INFINITY;
-            tl[k] = (k < Kr) ? thl[k] : 0;
+        // thr[0..K) holds the bounds by position; positions are ordered by centroid, and so are the
+        // bounds of the non-empty ones.  Empty positions (-inf) are skipped by carrying the running
+        // maximum forward, which keeps the array sorted for the binary search.
+        if (tid == 0) {
+            float run = -INFINITY;
+            int lastl = thl[0];
+            for (int k = 0; k < 16; ++k) {
+                if (thr[k] == -INFINITY) {
+                    thr[k] = run;          // an empty range: nothing is <= run that was not caught before
+                    thl[k] = lastl;
+                } else {
+                    run = thr[k];
+                    lastl = thl[k];
+                }
+            }
         }
+        __syncthreads();
         const float *Wr = prm.W + row * prm.ld;
         uint8_t *Lr = prm.labels + row * (long long)m;
         for (int j = tid; j < m; j += LLOYD_THREADS) {
             const float w = Wr[j];
             const float wt = prm.alpha ? __fdiv_rn(w, prm.alpha[j]) : w;
-            int lab = -1, last = 0;
-#pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const bool nonempty = th[k] != -INFINITY;
-                if (nonempty) last = tl[k];
-                if (lab < 0 && nonempty && wt <= th[k]) lab = tl[k];
-            }
-            Lr[j] = (uint8_t)(lab < 0 ? last : lab);
+            int pos = (thr[7] < wt) ? 8 : 0;
+            pos += (thr[pos + 3] < wt) ? 4 : 0;
+            pos += (thr[pos + 1] < wt) ? 2 : 0;
+            pos += (thr[pos] < wt) ? 1 : 0;
+            Lr[j] = (uint8_t)thl[pos];
         }
     }
 }

@@ -108,7 +108,7 @@ __global__ void __launch_bounds__(PACK_THREADS) pack_rows_kernel(const float *W,
     const long long cb0 = plan->cb_start[b] + local * K;
 
     if (tid < 16) {
-        thr[tid] = -INFINITY;
+        thr[tid] = INFINITY;
         thl[tid] = 0;
     }
     __syncthreads();
@@ -126,13 +126,10 @@ __global__ void __launch_bounds__(PACK_THREADS) pack_rows_kernel(const float *W,
         cbf[tid] = __half2float(h);
     }
     __syncthreads();
-    float th[16];
-    int tl[16];
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-        th[q] = (q < K) ? thr[q] : -INFINITY;
-        tl[q] = (q < K) ? thl[q] : 0;
-    }
+    // thr[0..K) ascending (empty clusters, -inf, first), +inf beyond; a value above every bound
+    // (cannot happen for thresholds taken from this row) falls to the cluster of the largest bound
+    if (tid >= K && tid < 16) thl[tid] = thl[K - 1];
+    __syncthreads();
     const float *Wr = W + row * ld;
     for (long long t0 = 0; t0 < m; t0 += PACK_TILE) {
         const int len = (int)min((long long)PACK_TILE, m - t0);
@@ -140,14 +137,12 @@ __global__ void __launch_bounds__(PACK_THREADS) pack_rows_kernel(const float *W,
             const float w = Wr[t0 + j];
             const float a = alpha ? alpha[t0 + j] : 1.0f;
             const float wt = alpha ? __fdiv_rn(w, a) : w;
-            int l = -1, last = 0;
-#pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const bool nonempty = th[q] != -INFINITY;
-                if (nonempty) last = tl[q];
-                if (l < 0 && nonempty && wt <= th[q]) l = tl[q];
-            }
-            if (l < 0) l = last;
+            // first position whose bound is >= wt (binary search over the 16 sorted bounds)
+            int pos = (thr[7] < wt) ? 8 : 0;
+            pos += (thr[pos + 3] < wt) ? 4 : 0;
+            pos += (thr[pos + 1] < wt) ? 2 : 0;
+            pos += (thr[pos] < wt) ? 1 : 0;
+            const int l = thl[pos];
             lab[j] = (uint8_t)l;
             if (dW) dW[row * m + t0 + j] = __fmaf_rn(-a, cbf[l], w);
         }
