@@ -79,6 +79,15 @@ const char *skim_last_error(const skim_ctx *ctx);
 size_t skim_workspace_bytes(int64_t n, int64_t m);
 skim_status skim_set_workspace(skim_ctx *ctx, void *dev_ptr, size_t bytes);
 
+/* Optional timing of the two phases of a clustering call (skim_error_table,
+ * skim_cluster_rows) with HIP events on the context's stream: the sort phase
+ * (load, sort, sums) and the Lloyd phase (iterations, errors, outputs).
+ * skim_profile_last synchronises on the last timed call and returns the two
+ * durations in milliseconds (host pointers, may be NULL).  For benchmarks:
+ * timing is off by default and adds nothing to untimed calls. */
+skim_status skim_profile_enable(skim_ctx *ctx, int on);
+skim_status skim_profile_last(skim_ctx *ctx, float *sort_ms, float *lloyd_ms);
+
 /* ---- clustering --------------------------------------------------------- */
 
 /* Error pre-recording (Alg. 3 lines 2-10): for every row i and every bit

@@ -21,6 +21,7 @@ STATUS_NAMES = {0: "SKIM_OK", -1: "SKIM_ERR_ARG", -2: "SKIM_ERR_SHAPE", -3: "SKI
 MAX_M = 32768
 
 EXPORTS = ["skim_create", "skim_destroy", "skim_last_error", "skim_workspace_bytes", "skim_set_workspace",
+           "skim_profile_enable", "skim_profile_last",
            "skim_error_table", "skim_cluster_rows", "skim_select_allocated", "skim_greedy_allocate",
            "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_layer_loss", "skim_scale_step"]
 
@@ -59,6 +60,8 @@ def load_library():
         lib.skim_workspace_bytes.argtypes = [i64, i64]
         lib.skim_workspace_bytes.restype = C.c_size_t
         lib.skim_set_workspace.argtypes = [vp, vp, C.c_size_t]
+        lib.skim_profile_enable.argtypes = [vp, i32]
+        lib.skim_profile_last.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         lib.skim_error_table.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, vp, vp]
         lib.skim_cluster_rows.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i32, vp, vp, vp, vp]
         lib.skim_select_allocated.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
@@ -150,6 +153,15 @@ class Context:
         if self._ws is None or self._ws.numel() < need:
             self._ws = self.torch.empty(need, dtype=self.torch.uint8, device=self.device)
             self._check(self.lib.skim_set_workspace(self.h, _dp(self._ws), need))
+
+    def profile_enable(self, on=True):
+        self._check(self.lib.skim_profile_enable(self.h, 1 if on else 0))
+
+    def profile_last(self):
+        """(sort_ms, lloyd_ms) of the last clustering call made with profiling on (synchronises)."""
+        a, b = C.c_float(0), C.c_float(0)
+        self._check(self.lib.skim_profile_last(self.h, C.byref(a), C.byref(b)))
+        return a.value, b.value
 
     def empty(self, shape, dtype):
         return self.torch.empty(shape, dtype=dtype, device=self.device)

@@ -988,12 +988,18 @@ skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n) {
     }
     if (n == 0) return SKIM_OK;
     if ((int64_t)n * prm.nseg > 0x7fffffff) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "too many rows");
+    if (ctx->profiling) SKIM_HIP(ctx, hipEventRecord(ctx->ev[0], ctx->stream));
     hipLaunchKernelGGL(sort_kernel, dim3((unsigned)(n * prm.nseg)), dim3(threads), lds, ctx->stream, prm);
     if (prm.nseg > 1) {
         hipLaunchKernelGGL(merge_kernel, dim3((unsigned)n), dim3(MERGE_THREADS), 0, ctx->stream, prm);
         hipLaunchKernelGGL(sums_kernel, dim3((unsigned)n), dim3(1024), 0, ctx->stream, prm);
     }
+    if (ctx->profiling) SKIM_HIP(ctx, hipEventRecord(ctx->ev[1], ctx->stream));
     hipLaunchKernelGGL(lloyd_kernel, dim3((unsigned)n), dim3(LLOYD_THREADS), lloyd_lds_bytes(prm.m), ctx->stream, prm);
+    if (ctx->profiling) {
+        SKIM_HIP(ctx, hipEventRecord(ctx->ev[2], ctx->stream));
+        ctx->ev_valid = 1;
+    }
     SKIM_HIP(ctx, hipGetLastError());
     return SKIM_OK;
 }

@@ -16,6 +16,10 @@ struct skim_ctx {
     int lds_limit;      // max LDS bytes one workgroup may use on this device
     int num_cu;
     char err[512];
+    // optional per-kernel timing of the clustering calls (skim_profile_enable)
+    int profiling;
+    hipEvent_t ev[3];    // before sort, between sort and Lloyd, after Lloyd
+    int ev_valid;
 };
 
 #define SKIM_FAIL(ctx, code, ...)                                   \

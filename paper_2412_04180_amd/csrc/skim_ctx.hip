@@ -47,6 +47,9 @@ extern "C" skim_status skim_create(skim_ctx **out, int device, void *hip_stream)
         c->lds_limit = optin;
     if (c->lds_limit < 160 * 1024) c->lds_limit = 160 * 1024;  // gfx950: 160 KB of LDS per compute unit
     c->num_cu = prop.multiProcessorCount;
+    c->profiling = 0;
+    c->ev_valid = 0;
+    for (int i = 0; i < 3; ++i) c->ev[i] = nullptr;
     c->err[0] = 0;
     *out = c;
     return SKIM_OK;
@@ -54,7 +57,33 @@ extern "C" skim_status skim_create(skim_ctx **out, int device, void *hip_stream)
 
 extern "C" skim_status skim_destroy(skim_ctx *ctx) {
     if (!ctx) return SKIM_ERR_ARG;
+    for (int i = 0; i < 3; ++i)
+        if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
     delete ctx;
+    return SKIM_OK;
+}
+
+extern "C" skim_status skim_profile_enable(skim_ctx *ctx, int on) {
+    skim_status st = skim_enter(ctx);
+    if (st != SKIM_OK) return st;
+    if (on && !ctx->ev[0]) {
+        for (int i = 0; i < 3; ++i) SKIM_HIP(ctx, hipEventCreate(&ctx->ev[i]));
+    }
+    ctx->profiling = on ? 1 : 0;
+    ctx->ev_valid = 0;
+    return SKIM_OK;
+}
+
+extern "C" skim_status skim_profile_last(skim_ctx *ctx, float *sort_ms, float *lloyd_ms) {
+    skim_status st = skim_enter(ctx);
+    if (st != SKIM_OK) return st;
+    if (!ctx->profiling || !ctx->ev_valid) SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_profile_last: no timed clustering call yet");
+    SKIM_HIP(ctx, hipEventSynchronize(ctx->ev[2]));
+    float a = 0.f, b = 0.f;
+    SKIM_HIP(ctx, hipEventElapsedTime(&a, ctx->ev[0], ctx->ev[1]));
+    SKIM_HIP(ctx, hipEventElapsedTime(&b, ctx->ev[1], ctx->ev[2]));
+    if (sort_ms) *sort_ms = a;
+    if (lloyd_ms) *lloyd_ms = b;
     return SKIM_OK;
 }
 
