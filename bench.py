@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-scale-loop", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain elementwise copy of the W matrix (reads and writes n*m*4 bytes): "
+                         "the known-size kernel that calibrates the HBM byte counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -122,6 +125,10 @@ def main():
             ev_d[i].record(stream)
         return bits, spent, budget, pk
 
+    if args.copy_probe:
+        probe_dst = torch.empty_like(W)
+        for _ in range(3):
+            torch.mul(W, 1.0, out=probe_dst)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
