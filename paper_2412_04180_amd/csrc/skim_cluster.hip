@@ -52,6 +52,7 @@ struct ClusterParams {
     // merged into keys, and their sums are taken by a separate kernel
     int nseg, seglen;
     u64 *keys_seg;
+    long long nwork;      // rows x segments: the units of work sort_kernel's workgroups share out
 };
 
 struct BitState {  // what the Lloyd lanes of one bit width leave for the epilogue
@@ -61,7 +62,7 @@ struct BitState {  // what the Lloyd lanes of one bit width leave for the epilog
     int active;
 };
 
-__device__ __forceinline__ uint32_t swz(uint32_t i) { return i ^ ((i >> 4) & 15u); }
+__device__ __forceinline__ uint32_t swz(uint32_t i) { return i ^ ((i >> 4) & 31u); }
 
 // Key of a (w, s) pair, s >= 0, both finite.  High word = the bits of w (-0 folded into +0), low
 // word = the bits of s, complemented when w is negative.  Read as a float64 the key is finite
@@ -124,14 +125,21 @@ __device__ __forceinline__ void sort_pass(double *lds, uint32_t t, int wb, int m
     const uint32_t lowmask = (1u << wb) - 1u;
     const uint32_t base = ((t >> wb) << (wb + 4)) | (t & lowmask);
     if ((int)(base & ~lowmask) >= m) return;   // all 16 keys are padding
-    const uint32_t fbase = base ^ lowmask;
+    // The swizzle is linear over GF(2), so the byte address of register r is the thread's own
+    // swizzled base XOR a constant that is the same for the whole wavefront (scalar registers).
+    uint32_t abase = swz(base) << 3;
+    asm("" : "+v"(abase));
+    const uint32_t fdelta = (FLIP >= 0) ? (swz(lowmask) << 3) : 0u;
+    char *const lb = (char *)lds;
     uint32_t addr[EPT];
     double v[EPT];
 #pragma unroll
     for (int r = 0; r < EPT; ++r) {
         const bool flipped = (FLIP >= 0) && (r & (1 << (FLIP >= 0 ? FLIP : 0)));
-        addr[r] = swz((flipped ? fbase : base) | ((uint32_t)r << wb));
-        v[r] = lds[addr[r]];
+        uint32_t k = (swz((uint32_t)r << wb) << 3) ^ (flipped ? fdelta : 0u);
+        asm("" : "+s"(k));    // keep the constant apart from the per-thread part (one v_xor per address)
+        addr[r] = abase ^ k;
+        v[r] = *(double *)(lb + addr[r]);
     }
     if (FLIP >= 0) {
 #pragma unroll
@@ -145,7 +153,7 @@ __device__ __forceinline__ void sort_pass(double *lds, uint32_t t, int wb, int m
             if (!(r & (1 << rb))) ce(v[r], v[r | (1 << rb)]);
     }
 #pragma unroll
-    for (int r = 0; r < EPT; ++r) lds[addr[r]] = v[r];
+    for (int r = 0; r < EPT; ++r) *(double *)(lb + addr[r]) = v[r];
 }
 
 // The merges of size 2, 4, 8, 16 in one pass (index bits 0..3 are in-thread).
@@ -273,6 +281,22 @@ __device__ __forceinline__ int quad_sum(int x) {
 // ---------------------------------------------------------------------------------------------
 // Kernel 1: load + scale + encode, bitonic sort in LDS, sums, write-out.
 // ---------------------------------------------------------------------------------------------
+// The 16 W and 16 S values a thread contributes to one unit of work (a row, or one segment of a long row).
+__device__ __forceinline__ void fetch_unit(const ClusterParams &prm, long long work, int tid, int nth, float (&pw)[EPT],
+                                           float (&ps)[EPT]) {
+    const long long frow = work / prm.nseg;
+    const int fcol0 = (int)(work % prm.nseg) * prm.seglen;
+    const int fm = min(prm.m - fcol0, prm.seglen);
+    const float *Wr = prm.W + frow * prm.ld + fcol0;
+    const float *Sr = prm.S + frow * prm.ld + fcol0;
+#pragma unroll
+    for (int k = 0; k < EPT; ++k) {
+        const uint32_t j = (uint32_t)tid + (uint32_t)k * (uint32_t)nth;   // 32-bit offset from a uniform base
+        pw[k] = (j < (uint32_t)fm) ? Wr[j] : 0.0f;
+        ps[k] = (j < (uint32_t)fm) ? Sr[j] : 0.0f;
+    }
+}
+
 __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int P = prm.P;
@@ -281,20 +305,35 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     double2 *wsum = (double2 *)(smem + (size_t)P * 8);   // per-wavefront sums (16)
     double *wpre = (double *)(wsum + 16);                // per-wavefront running sums of s (16) + total
 
-    const int tid = threadIdx.x, nth = blockDim.x;
-    const int lane = tid & 63, wave = tid >> 6, nwave = nth >> 6;
-    const long long row = blockIdx.x / prm.nseg;
-    const int col0 = (int)(blockIdx.x % prm.nseg) * prm.seglen;      // first column of this segment
+    const int tid0 = threadIdx.x, nth = blockDim.x;      // nth == P / 16
+    const int nwave = nth >> 6;
+
+    // A workgroup takes the units of work blockIdx.x, blockIdx.x + gridDim.x, ...  The W and S values
+    // of the next unit are fetched into registers (all loads in flight at once) while the sums of
+    // the current one are taken and its keys written out, which hides most of their HBM latency
+    // (a 16384-key row fills the LDS of a compute unit: no second workgroup is resident to overlap
+    // with, and the sort itself leaves no registers to hold the values any earlier).
+    float pw[EPT], ps[EPT];
+    if ((long long)blockIdx.x < prm.nwork) fetch_unit(prm, blockIdx.x, tid0, nth, pw, ps);
+
+    for (long long work = blockIdx.x; work < prm.nwork; work += gridDim.x) {
+    // the thread index is made opaque per unit: per-thread addresses are recomputed where they are
+    // used instead of being hoisted out of this loop and held in registers through the sort
+    int tid = tid0;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = tid >> 6;
+    const long long row = work / prm.nseg;
+    const int col0 = (int)(work % prm.nseg) * prm.seglen;            // first column of this segment
     const int m = min(prm.m - col0, prm.seglen);                     // keys sorted by this workgroup
-    const float *Wr = prm.W + row * prm.ld + col0;
-    const float *Sr = prm.S + row * prm.ld + col0;
     const float *alpha = prm.alpha ? prm.alpha + col0 : nullptr;
 
-    for (int j = tid; j < P; j += nth) {
+#pragma unroll
+    for (int k = 0; k < EPT; ++k) {
+        const int j = tid + k * nth;
         u64 key = PAD_KEY;
         if (j < m) {
             float wt, st;
-            scaled_pair(Wr[j], Sr[j], alpha, j, wt, st);
+            scaled_pair(pw[k], ps[k], alpha, j, wt, st);
             key = make_key(wt, st);
         }
         sorted[swz((uint32_t)j)] = key;
@@ -302,12 +341,14 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     __syncthreads();
 
     sort_row((double *)sorted, prm.logP, (uint32_t)tid, m);
+    if (work + gridDim.x < prm.nwork) fetch_unit(prm, work + gridDim.x, tid, nth, pw, ps);
 
     if (prm.nseg > 1) {
         // one segment of a long row: sorted keys only; merge_kernel and sums_kernel do the rest
         u64 *kseg = prm.keys_seg + row * (long long)prm.m + col0;
         for (int j = tid; j < m; j += nth) kseg[j] = sorted[swz((uint32_t)j)];
-        return;
+        __syncthreads();   // the LDS is refilled for the next unit
+        continue;
     }
     double2 *L1 = prm.L1 + row * prm.n1;
     double2 *L2 = prm.L2 + row * prm.n2;
@@ -382,6 +423,8 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     // sorted keys, compact and in rank order
     u64 *keys = prm.keys + row * (long long)m;
     for (int j = tid; j < m; j += nth) keys[j] = sorted[swz((uint32_t)j)];
+    __syncthreads();       // the LDS is refilled for the next unit
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -988,8 +1031,16 @@ skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n) {
     }
     if (n == 0) return SKIM_OK;
     if ((int64_t)n * prm.nseg > 0x7fffffff) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "too many rows");
+    prm.nwork = (long long)n * prm.nseg;
+    // as many workgroups as the device holds at once (LDS and thread limits), each looping over its units
+    int per_cu = (int)(ctx->lds_limit / (int64_t)lds);
+    if (per_cu > 2048 / threads) per_cu = 2048 / threads;
+    if (per_cu < 1) per_cu = 1;
+    if (per_cu > 8) per_cu = 8;
+    long long sort_grid = (long long)ctx->num_cu * per_cu;
+    if (sort_grid > prm.nwork) sort_grid = prm.nwork;
     if (ctx->profiling) SKIM_HIP(ctx, hipEventRecord(ctx->ev[0], ctx->stream));
-    hipLaunchKernelGGL(sort_kernel, dim3((unsigned)(n * prm.nseg)), dim3(threads), lds, ctx->stream, prm);
+    hipLaunchKernelGGL(sort_kernel, dim3((unsigned)sort_grid), dim3(threads), lds, ctx->stream, prm);
     if (prm.nseg > 1) {
         hipLaunchKernelGGL(merge_kernel, dim3((unsigned)n), dim3(MERGE_THREADS), 0, ctx->stream, prm);
         hipLaunchKernelGGL(sums_kernel, dim3((unsigned)n), dim3(1024), 0, ctx->stream, prm);
