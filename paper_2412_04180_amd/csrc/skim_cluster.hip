@@ -856,29 +856,40 @@ __global__ void __launch_bounds__(LLOYD_THREADS) __attribute__((amdgpu_waves_per
     int act[4];
 #pragma unroll
     for (int bi = 0; bi < 4; ++bi) act[bi] = __builtin_amdgcn_readfirstlane(bs[bi].active);
-    for (int base = wave * 64; base < m; base += LLOYD_THREADS) {
-        const int rk = base + lane;
-        const u64 el = (rk < m) ? keys[rk] : NEUTRAL_KEY;   // ranks past the row carry s = 0 and add nothing
-        const double w = (double)elem_w(el), s = (double)elem_s(el);
+    constexpr int EU = 4;   // stretches of 64 ranks whose loads are in flight together
+    for (int base0 = wave * 64; base0 < m; base0 += EU * LLOYD_THREADS) {
+        u64 els[EU];
 #pragma unroll
-        for (int bi = 0; bi < 4; ++bi) {
-            if (!act[bi]) continue;
-            const int Kb = 2 << bi;
-            if (base >= nxt[bi]) {
-                int pp = pcur[bi];
-                while (pp + 1 < Kb && __builtin_amdgcn_readfirstlane(bs[bi].B[pp + 1]) <= base) ++pp;
-                pcur[bi] = pp;
-                nxt[bi] = __builtin_amdgcn_readfirstlane(bs[bi].B[pp + 1]);
-                ccur[bi] = bs[bi].cent[pp];
+        for (int u = 0; u < EU; ++u) {
+            const int rk = base0 + u * LLOYD_THREADS + lane;
+            els[u] = (rk < m) ? keys[rk] : NEUTRAL_KEY;   // ranks past the row carry s = 0 and add nothing
+        }
+#pragma unroll
+        for (int u = 0; u < EU; ++u) {
+            const int base = base0 + u * LLOYD_THREADS;
+            if (base >= m) break;
+            const int rk = base + lane;
+            const double w = (double)elem_w(els[u]), s = (double)elem_s(els[u]);
+#pragma unroll
+            for (int bi = 0; bi < 4; ++bi) {
+                if (!act[bi]) continue;
+                const int Kb = 2 << bi;
+                if (base >= nxt[bi]) {
+                    int pp = pcur[bi];
+                    while (pp + 1 < Kb && __builtin_amdgcn_readfirstlane(bs[bi].B[pp + 1]) <= base) ++pp;
+                    pcur[bi] = pp;
+                    nxt[bi] = __builtin_amdgcn_readfirstlane(bs[bi].B[pp + 1]);
+                    ccur[bi] = bs[bi].cent[pp];
+                }
+                double c = ccur[bi];
+                if (base + 64 > nxt[bi]) {   // a boundary falls inside this stretch: look the cluster up per lane
+                    int pp = pcur[bi];
+                    while (pp + 1 < Kb && bs[bi].B[pp + 1] <= rk) ++pp;
+                    c = bs[bi].cent[pp];
+                }
+                const double dlt = w - c;
+                e4[bi] += s * dlt * dlt;
             }
-            double c = ccur[bi];
-            if (base + 64 > nxt[bi]) {   // a boundary falls inside this stretch: look the cluster up per lane
-                int pp = pcur[bi];
-                while (pp + 1 < Kb && bs[bi].B[pp + 1] <= rk) ++pp;
-                c = bs[bi].cent[pp];
-            }
-            const double dlt = w - c;
-            e4[bi] += s * dlt * dlt;
         }
     }
 #pragma unroll
