@@ -1,18 +1,20 @@
 // Per-row sensitivity-weighted 1-D K-means (Alg. 3 lines 2-10 and 12-15; the
 // re-clustering of W * alpha^-1 in Alg. 2) for gfx950.
 //
-// Two kernels per call.
-//  sort_kernel   one workgroup per row: the row's (w~, s~) pairs become 64-bit keys whose bit
-//                pattern, read as a float64, orders like (w~, s~); they are sorted once in LDS
-//                (bitonic network, compare-exchange = v_min_f64 + v_max_f64) and written to
-//                scratch together with float64 sums of s~ and s~ w~ per aligned 16-key chunk,
-//                256-key block and 4096-key super-block.
-//  lloyd_kernel  two wavefronts per row, many rows in flight per compute unit.  In sorted order
-//                every cluster of a 1-D K-means is a contiguous rank range, so one Lloyd
-//                iteration is: per pair of neighbouring centroids a search for the rank where
-//                the nearer centroid changes (four lanes per boundary, warm-started from the
-//                previous iteration), then centroid = (sum of s~ w~) / (sum of s~) over the
-//                range, assembled from the aligned pieces.  All four bit widths run at once.
+// Three kernels per call.
+//  sort_kernel       one workgroup per row at a time: the row's (w~, s~) pairs become 64-bit keys
+//                    whose bit pattern, read as a float64, orders like (w~, s~); they are sorted
+//                    once in LDS (bitonic network, compare-exchange = v_min_f64 + v_max_f64) and
+//                    written to scratch together with float64 sums of s~ and s~ w~ per aligned
+//                    16-key chunk and the weight of every chunk's first key.
+//  lloyd_iter_kernel one lane per cluster, two rows per wavefront, all four bit widths at once.
+//                    In sorted order every cluster of a 1-D K-means is a contiguous rank range,
+//                    so one Lloyd iteration is: per pair of neighbouring centroids a search for
+//                    the rank where the nearer centroid changes (chunk by a search in LDS, rank
+//                    inside the chunk from its keys), then centroid = (sum of s~ w~) / (sum of
+//                    s~) over the range, assembled from aligned pieces of a radix-4 sum tree.
+//  finish_kernel     one workgroup per row: errors by direct evaluation over the sorted keys,
+//                    centroids, thresholds, labels.
 //
 // Arithmetic on every decision path is float64 and uses the same predicates as the
 // definition: |w - c_lo| versus |w - c_hi| with the lower cluster index winning equal
@@ -31,6 +33,8 @@ constexpr int SORT_MAX_KEYS = 16384;  // keys one workgroup sorts in LDS (128 KB
 constexpr u64 NEUTRAL_KEY = 0ull;                    // encodes (w = +0, s = +0)
 constexpr u64 PAD_KEY = 0x7FF0000000000000ull;       // +infinity: above every key of finite w
 
+struct BitState;
+
 struct ClusterParams {
     const float *W, *S, *alpha;
     long long ld;
@@ -43,10 +47,12 @@ struct ClusterParams {
     float *upper;         // same layout as cent, may be null
     uint8_t *labels;      // rows mode only, may be null
     int stride;           // entries per row in cent/upper
-    // scratch written by sort_kernel, read by lloyd_kernel (per row: m keys, n1/n2/n3 sums, n1+1 running sums)
+    // scratch written by sort_kernel, read by the Lloyd kernels (per row: m keys, n1/n2/n3 sums, n1+1 running sums)
     u64 *keys;
     double2 *L1, *L2, *L3;
     double *cpre;
+    float *w16;           // weight of the first key of every 16-key chunk (n1 per row)
+    BitState *bstate;  // final state of the Lloyd lanes: 4 per row (bit widths 1..4)
     int n1, n2, n3;
     // rows longer than one LDS sort are sorted in nseg segments of seglen columns (keys_seg),
     // merged into keys, and their sums are taken by a separate kernel
@@ -406,6 +412,7 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
         }
         if (tid < n1) {
             L1[tid] = make_double2(c, q);
+            prm.w16[row * prm.n1 + tid] = (tid * EPT < m) ? elem_w(sorted[swz((uint32_t)(tid * EPT))]) : 0.0f;
             cpre[tid] = before + xc;
             if ((lane & 15) == 0) L2[tid >> 4] = make_double2(bc, bq);
         }
@@ -521,10 +528,12 @@ __global__ void __launch_bounds__(1024) sums_kernel(ClusterParams prm) {
         if (2 * tid < n1u) {
             L1[2 * tid] = l1[2 * tid];
             cpre[2 * tid] = before + xc;
+            prm.w16[row * prm.n1 + 2 * tid] = elem_w(keys[32 * tid]);
         }
         if (2 * tid + 1 < n1u) {
             L1[2 * tid + 1] = l1[2 * tid + 1];
             cpre[2 * tid + 1] = (before + xc) + cs[0];
+            prm.w16[row * prm.n1 + 2 * tid + 1] = elem_w(keys[32 * tid + 16]);
         }
         if (tid == 0) cpre[prm.n1] = total;
         if (tid < n2u) {
@@ -552,143 +561,196 @@ __global__ void __launch_bounds__(1024) sums_kernel(ClusterParams prm) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Kernel 2: Lloyd iterations, errors, centroids, thresholds, labels.
+// Kernel 2: Lloyd iterations.
 // ---------------------------------------------------------------------------------------------
 
-// Sums of s and s*w over the sorted ranks [a, b), shared out over the four lanes of a quad
-// (lane g) and reduced so that every lane of the quad gets the result.  The range is cut into
-// aligned pieces whose sums were each formed from their own members only (single keys, 16-key
-// chunks, 256-key blocks, 4096-key super-blocks): nothing outside [a, b) enters, so a cluster of
-// tiny weight mass next to a heavy element keeps full relative precision (a difference of
-// running prefix sums would not).  Keys come from global memory, sums from LDS.
-__device__ __forceinline__ void range_sum(const u64 *__restrict__ keys, const double2 *__restrict__ L1, const double2 *L2,
-                                          const double2 *L3, int a, int b, int g, double &D, double &N) {
-    constexpr int G = 4, T = 4;
-    const int e0 = min(b, (a + 15) & ~15), e1 = max(e0, b & ~15);
-    const int c0 = e0 >> 4, c3 = e1 >> 4;
-    const bool has1 = c0 < c3;
-    const int c1 = has1 ? min(c3, (c0 + 15) & ~15) : c0, c2 = has1 ? max(c1, c3 & ~15) : c0;
-    const int b0 = c1 >> 4, b3 = has1 ? (c2 >> 4) : b0;
-    const bool has2 = b0 < b3;
-    const int b1 = has2 ? min(b3, (b0 + 15) & ~15) : b0, b2 = has2 ? max(b1, b3 & ~15) : b0;
-    const int s0 = b1 >> 4, s1 = has2 ? (b2 >> 4) : s0;
-    // issue every global load first (predicated), then add in a fixed order
-    u64 el[2 * T];
-    double2 ch[2 * T];
-#pragma unroll
-    for (int t = 0; t < T; ++t) {
-        const int o = g + t * G;
-        el[t] = (a + o < e0) ? keys[a + o] : NEUTRAL_KEY;
-        el[T + t] = (e1 + o < b) ? keys[e1 + o] : NEUTRAL_KEY;
-        ch[t] = (has1 && c0 + o < c1) ? L1[c0 + o] : make_double2(0.0, 0.0);
-        ch[T + t] = (has1 && c2 + o < c3) ? L1[c2 + o] : make_double2(0.0, 0.0);
-    }
-    double d = 0.0, n = 0.0;
-    if (has2) {
-#pragma unroll
-        for (int t = 0; t < T; ++t) {
-            const int o = g + t * G;
-            if (b0 + o < b1) { const double2 x = L2[b0 + o]; d += x.x; n += x.y; }
-            if (b2 + o < b3) { const double2 x = L2[b2 + o]; d += x.x; n += x.y; }
-        }
-    }
-#pragma unroll
-    for (int t = 0; t < 2 * T; ++t) {
-        d += ch[t].x;
-        n += ch[t].y;
-    }
-    for (int q = s0 + g; q < s1; q += G) {
-        const double2 x = L3[q];
-        d += x.x;
-        n += x.y;
-    }
-#pragma unroll
-    for (int t = 0; t < 2 * T; ++t) {
-        // a skipped slot holds (w = +0, s = +0) and adds nothing
-        const double s = (double)elem_s(el[t]);
-        d += s;
-        n = fma(s, (double)elem_w(el[t]), n);
-    }
-    D = quad_sum(d);
-    N = quad_sum(n);
+// Sums above the 16-key chunks form a radix-4 tree: level 0 = chunk sums (global memory),
+// level l = sums of 4 entries of level l-1, up to a single root.  A workgroup keeps, per row, the
+// levels >= 1, the first weight of every chunk and the running sum of s ahead of every level-1
+// group in LDS.
+struct LevelMap {
+    int nlev;        // levels 0 .. nlev-1
+    int n[8];        // entries per level
+    int off[8];      // byte offset of level >= 1 inside the row's LDS block
+    int w16_off, pre_off, bytes;
+};
+__host__ __device__ inline LevelMap level_map(int n1u) {
+    LevelMap L;
+    L.w16_off = 0;
+    int o = (n1u * 4 + 15) & ~15;
+    L.n[0] = n1u;
+    L.off[0] = 0;
+    int lv = 0, n = n1u;
+    do {
+        n = (n + 3) >> 2;
+        ++lv;
+        L.n[lv] = n;
+        L.off[lv] = o;
+        o += n * 16;
+    } while (n > 1);
+    for (int k = lv + 1; k < 8; ++k) { L.n[k] = 0; L.off[k] = 0; }
+    L.nlev = lv + 1;
+    L.pre_off = o;
+    o += (L.n[1] + 1) * 8;
+    L.bytes = (o + 15) & ~15;
+    return L;
 }
 
-// First rank whose inclusive running sum of s reaches tau (weighted-quantile start).
-// cpre[q] = running sum of s over the ranks before chunk q (global memory).
-__device__ __forceinline__ int quantile_rank(const u64 *__restrict__ keys, const double *__restrict__ cpre, int m,
-                                             double tau) {
-    const int nchunk = (m + 15) >> 4;
-    int lo = 0, hi = nchunk - 1;  // largest q with cpre[q] < tau; cpre[0] = 0 < tau
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (cpre[mid] < tau) lo = mid; else hi = mid - 1;
-    }
-    const int r0 = lo * 16;
-    u64 el[16];
-#pragma unroll
-    for (int j = 0; j < 16; ++j) el[j] = (r0 + j < m) ? keys[r0 + j] : NEUTRAL_KEY;
-    double acc = cpre[lo];
-    int found = min(r0 + 15, m - 1);
-    bool hit = false;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        acc += (double)elem_s(el[j]);
-        if (!hit && r0 + j < m && acc >= tau) {
-            found = r0 + j;
-            hit = true;
-        }
-    }
-    return found;
-}
+constexpr int ITER_THREADS = 64;   // one wavefront serves two rows
+constexpr int MAX_LEVELS = 8;
 
-constexpr int LLOYD_THREADS = 128;
-
-// Two wavefronts per row.  Wavefront 0 carries the bit widths 1, 2, 3 (lanes 0-7, 8-23, 24-55),
-// wavefront 1 the bit width 4 (64 lanes).  Position p (sorted order of centroid values) of a
-// bit width is a quad of lanes which searches its lower boundary together and shares its sums.
-__global__ void __launch_bounds__(LLOYD_THREADS) __attribute__((amdgpu_waves_per_eu(5, 8))) lloyd_kernel(ClusterParams prm) {
+// One lane per cluster.  A row takes 30 lanes of a half wavefront: bit width 1 on lanes 0-1, 2 on
+// 2-5, 3 on 6-13, 4 on 14-29 (position p = centroids ordered by value); two rows per wavefront.
+// Per iteration a lane finds the lower boundary of its cluster in two steps -- the chunk that
+// holds it, by a search over the chunks' first weights in LDS, then the rank inside that chunk
+// from its 16 keys (one round of global loads) -- and adds up its range from: the keys of its own
+// boundary chunk, the lower part of the next cluster's boundary chunk (handed over by that lane),
+// and the whole chunks in between as aligned pieces of the radix-4 tree.  Nothing outside the
+// range enters a sum, so a cluster of tiny weight mass next to a heavy element keeps full
+// relative precision (a difference of running prefix sums would not).
+__global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams prm, long long nrows) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int m = prm.m;
-    const int n1u = (m + 15) >> 4, n2u = (n1u + 15) >> 4, n3u = (n2u + 15) >> 4;
-    double2 *L2 = (double2 *)smem;
-    double2 *L3 = L2 + n2u;
-    BitState *bs = (BitState *)(L3 + n3u);
-    double *red = (double *)(bs + 4);        // 4 x 2 partial errors
-    float *thr = (float *)(red + 8);         // 16 thresholds (labels)
-    int *thl = (int *)(thr + 16);            // 16 labels
+    const int n1u = (m + 15) >> 4;
+    const LevelMap LM = level_map(n1u);
+    const int lane = threadIdx.x;
+    const int h = lane >> 5, l5 = lane & 31;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const long long row = blockIdx.x;
-    const u64 *__restrict__ keys = prm.keys + row * (long long)m;
-    const double2 *__restrict__ L1 = prm.L1 + row * prm.n1;   // chunk sums stay in global memory (cache-resident)
-    const double *__restrict__ cpre = prm.cpre + row * (prm.n1 + 1);
-    {
-        const double2 *g2 = prm.L2 + row * prm.n2, *g3 = prm.L3 + row * prm.n3;
-        for (int j = tid; j < n2u; j += LLOYD_THREADS) L2[j] = g2[j];
-        for (int j = tid; j < n3u; j += LLOYD_THREADS) L3[j] = g3[j];
-        if (tid < 4) bs[tid].active = 0;
+    // ---- prologue: both rows' trees, first weights and running sums into LDS -------------------
+    for (int hh = 0; hh < 2; ++hh) {
+        const long long rr = 2ll * blockIdx.x + hh;
+        if (rr >= nrows) break;
+        unsigned char *blk = smem + (size_t)hh * LM.bytes;
+        float *w16 = (float *)(blk + LM.w16_off);
+        const float *gw = prm.w16 + rr * prm.n1;
+        for (int j = lane; j < n1u; j += ITER_THREADS) w16[j] = gw[j];
+        const double2 *g1 = prm.L1 + rr * prm.n1;
+        double2 *l1 = (double2 *)(blk + LM.off[1]);
+        for (int q = lane; q < LM.n[1]; q += ITER_THREADS) {
+            double d = 0.0, nn = 0.0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (4 * q + k < n1u) {
+                    const double2 x = g1[4 * q + k];
+                    d += x.x;
+                    nn += x.y;
+                }
+            }
+            l1[q] = make_double2(d, nn);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int lv = 2; lv < MAX_LEVELS; ++lv) {
+            if (lv < LM.nlev) {
+                const double2 *src = (const double2 *)(blk + LM.off[lv - 1]);
+                double2 *dst = (double2 *)(blk + LM.off[lv]);
+                for (int q = lane; q < LM.n[lv]; q += ITER_THREADS) {
+                    double d = 0.0, nn = 0.0;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        if (4 * q + k < LM.n[lv - 1]) {
+                            const double2 x = src[4 * q + k];
+                            d += x.x;
+                            nn += x.y;
+                        }
+                    }
+                    dst[q] = make_double2(d, nn);
+                }
+                __syncthreads();
+            }
+        }
+        // running sum of s ahead of each level-1 group (64 keys); pre[n[1]] = total
+        double *pre = (double *)(blk + LM.pre_off);
+        double carry = 0.0;
+        for (int q0 = 0; q0 < LM.n[1]; q0 += ITER_THREADS) {
+            const int q = q0 + lane;
+            const double mine = (q < LM.n[1]) ? l1[q].x : 0.0;
+            double inc = mine;
+            for (int d = 1; d < 64; d <<= 1) {
+                const double u = __shfl_up(inc, d, 64);
+                if (lane >= d) inc += u;
+            }
+            if (q < LM.n[1]) pre[q] = carry + (inc - mine);
+            carry += __shfl(inc, 63, 64);
+        }
+        if (lane == 0) pre[LM.n[1]] = carry;
+        __syncthreads();
     }
-    __syncthreads();
-    const double total = cpre[prm.n1];
 
-    // lane -> (bit width, position, lane in quad)
-    int b, q, L0;
-    if (wave == 1) { b = 4; q = lane; L0 = 0; }
-    else if (lane < 8) { b = 1; q = lane; L0 = 0; }
-    else if (lane < 24) { b = 2; q = lane - 8; L0 = 8; }
-    else { b = 3; q = lane - 24; L0 = 24; }       // lanes 56..63 of wavefront 0 stay idle (q >= 32)
+    // ---- lane -> (row, bit width, position) ------------------------------------------------------
+    const long long row = 2ll * blockIdx.x + h;
+    const bool rowok = row < nrows;
+    int b, p, L0;
+    if (l5 < 2) { b = 1; p = l5; L0 = 0; }
+    else if (l5 < 6) { b = 2; p = l5 - 2; L0 = 2; }
+    else if (l5 < 14) { b = 3; p = l5 - 6; L0 = 6; }
+    else if (l5 < 30) { b = 4; p = l5 - 14; L0 = 14; }
+    else { b = 0; p = 0; L0 = 30; }
+    L0 += 32 * h;
     const int K = 1 << b;
-    const int p = q >> 2, g = q & 3;
-    const int rowbits = prm.bits ? (int)prm.bits[row] : 0;
-    const bool on = (p < K) && (prm.bits ? (b == rowbits) : (b >= prm.bmin && b <= prm.bmax));
-    const u64 maskb = (wave == 1) ? ~0ull : (((1ull << (4 * K)) - 1ull) << L0);
-    auto from_pos = [&](int k) -> int { return min(L0 + 4 * k, 63); };   // first lane of position k of this bit width
+    const long long rowc = rowok ? row : 0;
+    const int rowbits = (prm.bits && rowok) ? (int)prm.bits[row] : 0;
+    const bool on = rowok && b > 0 && (prm.bits ? (b == rowbits) : (b >= prm.bmin && b <= prm.bmax));
+    const u64 maskb = ((1ull << K) - 1ull) << L0;
+    auto from_pos = [&](int k) -> int { return min(L0 + k, 63); };   // lane of position k of this bit width
 
-    // ---- weighted-quantile start with strictly increasing ranks --------------
+    const unsigned char *blk = smem + (size_t)h * LM.bytes;
+    const float *w16 = (const float *)(blk + LM.w16_off);
+    const double *pre = (const double *)(blk + LM.pre_off);
+    const u64 *__restrict__ keys = prm.keys + rowc * (long long)m;
+    const double2 *__restrict__ L1 = prm.L1 + rowc * prm.n1;
+
+    // ---- weighted-quantile start with strictly increasing ranks ---------------------------------
     int r = 0;
     {
+        const int ng = LM.n[1];
+        const double total = pre[ng];
         const double tau = total * (double)(2 * p + 1) / (double)(2 * K);
-        if (on) r = quantile_rank(keys, cpre, m, tau);
+        // largest group g with pre[g] < tau (pre[0] = 0 < tau)
+        int lo = 0, hi = on ? ng - 1 : 0;
+        while (__ballot(lo < hi)) {
+            const int mid = (lo + hi + 1) >> 1;
+            const double x = pre[min(mid, ng)];
+            if (lo < hi) {
+                if (x < tau) lo = mid; else hi = mid - 1;
+            }
+        }
+        // chunk inside the group: largest chunk whose running sum ahead of it is < tau
+        int chunk = 4 * lo;
+        double acc = pre[lo];
+        if (on) {
+            double dch[3];
+#pragma unroll
+            for (int k = 0; k < 3; ++k) dch[k] = (chunk + k + 1 < n1u) ? L1[chunk + k].x : 0.0;
+            bool go = true;
+            const int c0 = chunk;
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                const double nx = acc + dch[k];
+                const bool t = go && (c0 + k + 1 < n1u) && (nx < tau);
+                if (t) {
+                    acc = nx;
+                    chunk = c0 + k + 1;
+                } else {
+                    go = false;
+                }
+            }
+            const int r0 = chunk * 16;
+            u64 el[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) el[j] = (r0 + j < m) ? keys[r0 + j] : NEUTRAL_KEY;
+            int found = min(r0 + 15, m - 1);
+            bool hit = false;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                acc += (double)elem_s(el[j]);
+                if (!hit && r0 + j < m && acc >= tau) {
+                    found = r0 + j;
+                    hit = true;
+                }
+            }
+            r = found;
+        }
         int prev = -1;
         for (int k = 0; k < 16; ++k) {
             int rk = __shfl(r, from_pos(k), 64);
@@ -702,13 +764,13 @@ __global__ void __launch_bounds__(LLOYD_THREADS) __attribute__((amdgpu_waves_per
     }
     double v = on ? (double)elem_w(keys[r]) : 0.0;
     int idx = p;
-    int Bcur = 0, Bold = -1, idxold = -1, Wd = 1;
+    int Bcur = 0, Bold = -1, idxold = -1, cold = 0;
     bool done = !on;
 
     for (int it = 0; it < prm.iters; ++it) {
         if (__ballot(!done) == 0) break;
-        double vlo = shfl_d(v, lane - 4);
-        int ilo = __shfl(idx, lane - 4, 64);
+        double vlo = shfl_d(v, lane - 1);
+        int ilo = __shfl(idx, lane - 1, 64);
         {   // keep positions ordered by (value, cluster index)
             const bool ok = done || (p == 0) || (vlo < v) || (vlo == v && ilo < idx);
             if (__ballot(!ok)) {
@@ -729,8 +791,8 @@ __global__ void __launch_bounds__(LLOYD_THREADS) __attribute__((amdgpu_waves_per
                     v = nv;
                     idx = ni;
                 }
-                vlo = shfl_d(v, lane - 4);
-                ilo = __shfl(idx, lane - 4, 64);
+                vlo = shfl_d(v, lane - 1);
+                ilo = __shfl(idx, lane - 1, 64);
             }
         }
         const bool dup = !done && (p > 0) && (vlo == v);
@@ -745,70 +807,100 @@ __global__ void __launch_bounds__(LLOYD_THREADS) __attribute__((amdgpu_waves_per
                 if (k < K && p == k && dk) rs = rsp;
             }
             rep = __shfl(idx, from_pos(rs), 64);
-            replo = __shfl(rep, lane - 4, 64);
+            replo = __shfl(rep, lane - 1, 64);
         }
         const bool searching = !done && (p > 0) && !dup;
         const bool tie_lo = replo < rep;  // equal distances go to the lower cluster index
-        auto nearer_lo = [&](int rank) -> bool {
-            const double x = (double)elem_w(keys[rank]);
+        auto nearer_lo = [&](float xf) -> bool {
+            const double x = (double)xf;
             const double dl = fabs(x - vlo), dh = fabs(x - v);
             return tie_lo ? (dl <= dh) : (dl < dh);
         };
 
-        // first rank that is not nearer to the lower centroid: invariant lo <= answer <= hi.
-        // mode 0: probes spread evenly; 1: answer expected just below hi; 2: just above lo.
-        int lo = 0, hi = 0, mode = 0;
+        // ---- chunk of the boundary: cnt = number of chunks whose first key is nearer to the lower
+        // centroid (a prefix of the chunks); invariant lo <= cnt <= hi -----------------------------
+        const int rlo = __shfl(r, lane - 1, 64);
+        int lo = 0, hi = 0, mode = 0, step = 1;
         if (it == 0) {
             // the starting centroids are the keys at ranks r: the boundary lies in (r_{p-1}, r_p]
-            const int rlo = __shfl(r, lane - 4, 64);
             if (searching) {
-                lo = rlo + 1;
-                hi = r;
+                lo = (rlo >> 4) + 1;
+                hi = (r + 15) >> 4;
             }
         } else {
-            const int x0 = min(max(Bold - Wd, 0), m - 1), x1 = min(max(Bold - 1, 0), m - 1);
-            const int x2 = min(max(Bold, 0), m - 1), x3 = min(max(Bold + Wd - 1, 0), m - 1);
-            const int x = (g == 0) ? x0 : (g == 1) ? x1 : (g == 2) ? x2 : x3;
-            const int tc = quad_sum((int)(searching && nearer_lo(x)));
+            // two probes next to the previous answer; a miss gallops away from it
+            const int ia = min(max(cold - 1, 0), n1u - 1), ib = min(cold, n1u - 1);
+            const bool ta = nearer_lo(w16[ia]), tb = nearer_lo(w16[ib]);
             if (searching) {
-                hi = m;
-                if (tc == 0) { hi = x0; mode = 1; }
-                else if (tc == 1) { lo = x0 + 1; hi = x1; }
-                else if (tc == 2) { lo = x1 + 1; hi = x2; }
-                else if (tc == 3) { lo = x2 + 1; hi = x3; }
-                else { lo = x3 + 1; mode = 2; }
-            }
-        }
-        int step = max(Wd, 1);
-        for (;;) {
-            const int len = hi - lo;
-            if (__ballot(len > 0) == 0) break;
-            int x0, x1, x2, x3;
-            if (mode == 1) {
-                x3 = max(lo, hi - step); x2 = max(lo, hi - 2 * step); x1 = max(lo, hi - 4 * step); x0 = max(lo, hi - 8 * step);
-            } else if (mode == 2) {
-                x0 = min(hi - 1, lo + step - 1); x1 = min(hi - 1, lo + 2 * step - 1);
-                x2 = min(hi - 1, lo + 4 * step - 1); x3 = min(hi - 1, lo + 8 * step - 1);
-            } else {
-                x0 = lo + len / 5; x1 = lo + (2 * len) / 5; x2 = lo + (3 * len) / 5; x3 = lo + (4 * len) / 5;
-            }
-            const int x = (g == 0) ? x0 : (g == 1) ? x1 : (g == 2) ? x2 : x3;
-            const int tc = quad_sum((int)((len > 0) && nearer_lo(min(max(x, 0), m - 1))));
-            if (len > 0) {
-                if (tc == 0) {
-                    hi = x0;
-                    if (mode == 1) step = min(step * 16, 1 << 20); else mode = 0;
-                } else if (tc == 4) {
-                    lo = x3 + 1;
-                    if (mode == 2) step = min(step * 16, 1 << 20); else mode = 0;
-                } else {
-                    lo = ((tc == 1) ? x0 : (tc == 2) ? x1 : x2) + 1;
-                    hi = (tc == 1) ? x1 : (tc == 2) ? x2 : x3;
-                    mode = 0;
+                lo = 0;
+                hi = n1u;
+                bool below = false;
+                if (cold >= 1) {
+                    if (ta) lo = cold; else { hi = cold - 1; mode = 1; below = true; }
+                }
+                if (!below && cold < n1u) {
+                    if (tb) { lo = cold + 1; mode = 2; } else hi = cold;
                 }
             }
         }
-        Bcur = lo;  // p == 0: 0
+        for (;;) {
+            const int len = hi - lo;
+            if (__ballot(len > 0) == 0) break;
+            int mid;
+            if (mode == 1) mid = max(lo, hi - step);
+            else if (mode == 2) mid = min(hi - 1, lo + step - 1);
+            else mid = lo + (len >> 1);
+            mid = min(max(mid, 0), n1u - 1);
+            const bool t = nearer_lo(w16[mid]);
+            if (len > 0) {
+                if (t) {
+                    lo = mid + 1;
+                    if (mode == 2) step <<= 2; else mode = 0;
+                } else {
+                    hi = mid;
+                    if (mode == 1) step <<= 2; else mode = 0;
+                }
+            }
+        }
+        if (searching) cold = lo;
+        int cl = searching ? lo - 1 : -1;          // chunk that holds the boundary (-1: boundary at rank 0)
+        // what the cluster below sees of this position: its chunk, boundary and the sums of the
+        // keys of that chunk below the boundary; a position that repeats the value below it owns
+        // nothing and passes on what the next distinct position shows
+        int xcl = cl;
+        if (anydup) {
+            if (dup) xcl = (p == K - 1) ? n1u : -2;
+            for (int k = 14; k >= 1; --k) {
+                const int nx = __shfl(xcl, from_pos(k + 1), 64);
+                if (k <= K - 2 && p == k && xcl == -2) xcl = nx;
+            }
+        }
+        int cl_next = __shfl(xcl, lane + 1, 64);
+        if (p == K - 1) cl_next = n1u;
+        const bool summing = !done && !dup;
+        cl_next = max(cl_next, cl);
+        // whole chunks between the two boundary chunks: [a0, b0) in chunk units
+        int a0 = summing ? cl + 1 : 0, b0 = summing ? cl_next : 0;
+        b0 = max(b0, a0);
+
+        // ---- one round of global loads: the boundary chunk's keys and the level-0 pieces ----------
+        u64 el[16];
+        const int rbase = cl * 16;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) el[j] = (cl >= 0 && rbase + j < m) ? keys[rbase + j] : NEUTRAL_KEY;
+        const int la0 = min(b0, (a0 + 3) & ~3), rb0 = max(la0, b0 & ~3);
+        double2 pc[6];
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            pc[k] = (a0 + k < la0) ? L1[a0 + k] : make_double2(0.0, 0.0);
+            pc[3 + k] = (rb0 + k < b0) ? L1[rb0 + k] : make_double2(0.0, 0.0);
+        }
+
+        int tc = 0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) tc += (cl >= 0 && rbase + j < m && nearer_lo(elem_w(el[j]))) ? 1 : 0;
+        const int Bs = searching ? rbase + tc : 0;
+        Bcur = Bs;  // p == 0: 0
         if (anydup) {
             // a position sharing its value with the one before it owns nothing:
             // its range starts where the next distinct value's range starts
@@ -823,20 +915,74 @@ __global__ void __launch_bounds__(LLOYD_THREADS) __attribute__((amdgpu_waves_per
             const u64 moving = __ballot(!done && !same);
             if (it > 0 && (moving & maskb) == 0) done = true;
         }
-        int Bnext = __shfl(done ? Bold : Bcur, lane + 4, 64);
+        int Bnext = __shfl(done ? Bold : Bcur, lane + 1, 64);
         if (p == K - 1) Bnext = m;
+        Bnext = max(Bnext, Bcur);
         if (!done) {
-            Wd = (Bold < 0) ? max(1, m >> (b + 2)) : max(1, abs(Bcur - Bold));
             Bold = Bcur;
             idxold = idx;
         }
-        double D = 0.0, N = 0.0;
-        range_sum(keys, L1, L2, L3, done ? 0 : Bcur, done ? 0 : Bnext, g, D, N);
-        if (!done && D > 0.0) v = N / D;
+
+        // own chunk: keys below the boundary go to the cluster below, keys from it on (and below
+        // the next boundary) are this cluster's
+        double lowD = 0.0, lowN = 0.0, D = 0.0, N = 0.0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int rk = rbase + j;
+            const double s = (double)elem_s(el[j]);      // a skipped slot holds (w = +0, s = +0)
+            const double sw = s * (double)elem_w(el[j]);  // exact: two floats
+            const bool isl = rk < Bs;
+            const bool ish = !isl && rk < Bnext;
+            lowD += isl ? s : 0.0;
+            lowN += isl ? sw : 0.0;
+            D += ish ? s : 0.0;
+            N += ish ? sw : 0.0;
+        }
+        if (anydup) {
+            double xd = lowD, xn = lowN;
+            int tag = dup ? ((p == K - 1) ? 1 : -2) : 0;   // -2: waiting for the next distinct position
+            if (dup) { xd = 0.0; xn = 0.0; }
+            for (int k = 14; k >= 1; --k) {
+                const double nd = shfl_d(xd, from_pos(k + 1));
+                const double nn = shfl_d(xn, from_pos(k + 1));
+                const int nt = __shfl(tag, from_pos(k + 1), 64);
+                if (k <= K - 2 && p == k && tag == -2) { xd = nd; xn = nn; tag = nt; }
+            }
+            lowD = xd;
+            lowN = xn;
+        }
+        double nD = shfl_d(lowD, lane + 1), nN = shfl_d(lowN, lane + 1);
+        if (p == K - 1 || cl_next <= cl) { nD = 0.0; nN = 0.0; }
+        D += nD;
+        N += nN;
+        // level-0 pieces, then the levels in LDS
+#pragma unroll
+        for (int k = 0; k < 6; ++k) {
+            D += pc[k].x;
+            N += pc[k].y;
+        }
+        int a = la0 >> 2, bq = rb0 >> 2;
+        if (la0 >= rb0) { a = 0; bq = 0; }
+#pragma unroll
+        for (int lv = 1; lv < MAX_LEVELS; ++lv) {
+            if (lv < LM.nlev) {
+                if (__ballot(a < bq) != 0) {
+                    const double2 *L = (const double2 *)(blk + LM.off[lv]);
+                    const int la = min(bq, (a + 3) & ~3), rb = max(la, bq & ~3);
+#pragma unroll
+                    for (int k = 0; k < 3; ++k) {
+                        if (a + k < la) { const double2 x = L[a + k]; D += x.x; N += x.y; }
+                        if (rb + k < bq) { const double2 x = L[rb + k]; D += x.x; N += x.y; }
+                    }
+                    if (la < rb) { a = la >> 2; bq = rb >> 2; } else { a = 0; bq = 0; }
+                }
+            }
+        }
+        if (summing && !done && D > 0.0) v = N / D;
     }
 
-    if (on && g == 0) {
-        BitState *o = &bs[b - 1];
+    if (on) {
+        BitState *o = prm.bstate + row * 4 + (b - 1);
         o->cent[p] = v;
         o->idx[p] = idx;
         o->B[p] = Bold;
@@ -844,6 +990,34 @@ __global__ void __launch_bounds__(LLOYD_THREADS) __attribute__((amdgpu_waves_per
             o->B[K] = m;
             o->active = 1;
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernel 3: errors, centroids, thresholds, labels from the final boundaries.
+// ---------------------------------------------------------------------------------------------
+constexpr int FIN_THREADS = 256;
+constexpr int FIN_WAVES = FIN_THREADS / 64;
+
+__global__ void __launch_bounds__(FIN_THREADS) finish_kernel(ClusterParams prm) {
+    __shared__ BitState bs[4];
+    __shared__ double red[4 * FIN_WAVES];
+    __shared__ float thr[16];
+    __shared__ int thl[16];
+    const int m = prm.m;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long long row = blockIdx.x;
+    const u64 *__restrict__ keys = prm.keys + row * (long long)m;
+    const int rowbits = prm.bits ? (int)prm.bits[row] : 0;
+    {
+        const int *src = (const int *)(prm.bstate + row * 4);
+        int *dst = (int *)bs;
+        for (int j = tid; j < (int)(4 * sizeof(BitState) / 4); j += FIN_THREADS) dst[j] = src[j];
+    }
+    __syncthreads();
+    if (tid < 4) {
+        const int bb = tid + 1;
+        bs[tid].active = prm.bits ? (bb == rowbits) : (bb >= prm.bmin && bb <= prm.bmax);
     }
     __syncthreads();
 
@@ -857,16 +1031,16 @@ __global__ void __launch_bounds__(LLOYD_THREADS) __attribute__((amdgpu_waves_per
 #pragma unroll
     for (int bi = 0; bi < 4; ++bi) act[bi] = __builtin_amdgcn_readfirstlane(bs[bi].active);
     constexpr int EU = 4;   // stretches of 64 ranks whose loads are in flight together
-    for (int base0 = wave * 64; base0 < m; base0 += EU * LLOYD_THREADS) {
+    for (int base0 = wave * 64; base0 < m; base0 += EU * FIN_THREADS) {
         u64 els[EU];
 #pragma unroll
         for (int u = 0; u < EU; ++u) {
-            const int rk = base0 + u * LLOYD_THREADS + lane;
+            const int rk = base0 + u * FIN_THREADS + lane;
             els[u] = (rk < m) ? keys[rk] : NEUTRAL_KEY;   // ranks past the row carry s = 0 and add nothing
         }
 #pragma unroll
         for (int u = 0; u < EU; ++u) {
-            const int base = base0 + u * LLOYD_THREADS;
+            const int base = base0 + u * FIN_THREADS;
             if (base >= m) break;
             const int rk = base + lane;
             const double w = (double)elem_w(els[u]), s = (double)elem_s(els[u]);
@@ -896,7 +1070,7 @@ __global__ void __launch_bounds__(LLOYD_THREADS) __attribute__((amdgpu_waves_per
     for (int bi = 0; bi < 4; ++bi) {
         double x = e4[bi];
         for (int d = 32; d >= 1; d >>= 1) x += __shfl_down(x, d, 64);
-        if (lane == 0) red[bi * 2 + wave] = x;
+        if (lane == 0) red[bi * FIN_WAVES + wave] = x;
     }
     __syncthreads();
 
@@ -906,7 +1080,8 @@ __global__ void __launch_bounds__(LLOYD_THREADS) __attribute__((amdgpu_waves_per
         for (int bi = 0; bi < 4; ++bi) {
             if (!bs[bi].active) continue;
             const int bb = bi + 1, Kb = 1 << bb;
-            const double err = red[bi * 2] + red[bi * 2 + 1];
+            double err = 0.0;
+            for (int w2 = 0; w2 < FIN_WAVES; ++w2) err += red[bi * FIN_WAVES + w2];
             long long obase;
             if (prm.bits) {
                 if (lane == 0) prm.E[row] = err;
@@ -956,7 +1131,7 @@ __global__ void __launch_bounds__(LLOYD_THREADS) __attribute__((amdgpu_waves_per
         __syncthreads();
         const float *Wr = prm.W + row * prm.ld;
         uint8_t *Lr = prm.labels + row * (long long)m;
-        for (int j = tid; j < m; j += LLOYD_THREADS) {
+        for (int j = tid; j < m; j += FIN_THREADS) {
             const float w = Wr[j];
             const float wt = prm.alpha ? __fdiv_rn(w, prm.alpha[j]) : w;
             int pos = (thr[7] < wt) ? 8 : 0;
@@ -987,11 +1162,7 @@ __global__ void select_kernel(long long n, int bmin, int bmax, const uint8_t *bi
 
 size_t sort_lds_bytes(int P) { return (size_t)P * 8 + 16 * 16 + 17 * 8; }
 
-size_t lloyd_lds_bytes(int m) {
-    const int n1u = (m + 15) >> 4, n2u = (n1u + 15) >> 4, n3u = (n2u + 15) >> 4;
-    (void)n1u;
-    return (size_t)(n2u + n3u) * 16 + 4 * sizeof(BitState) + 8 * 8 + 16 * 4 + 16 * 4;
-}
+size_t lloyd_lds_bytes(int m) { return 2 * (size_t)level_map((m + 15) >> 4).bytes; }
 
 // Scratch layout of one call (inside the caller's workspace).
 skim_status carve_cluster_ws(skim_ctx *ctx, ClusterParams &prm, int64_t n, double **cent_scratch) {
@@ -1015,7 +1186,9 @@ skim_status carve_cluster_ws(skim_ctx *ctx, ClusterParams &prm, int64_t n, doubl
     prm.L2 = (double2 *)cur.take((size_t)n * prm.n2 * sizeof(double2));
     prm.L3 = (double2 *)cur.take((size_t)n * prm.n3 * sizeof(double2));
     prm.cpre = (double *)cur.take((size_t)n * (prm.n1 + 1) * sizeof(double));
-    bool ok = prm.keys && prm.L1 && prm.L2 && prm.L3 && prm.cpre;
+    prm.w16 = (float *)cur.take((size_t)n * prm.n1 * sizeof(float));
+    prm.bstate = (BitState *)cur.take((size_t)n * 4 * sizeof(BitState));
+    bool ok = prm.keys && prm.L1 && prm.L2 && prm.L3 && prm.cpre && prm.w16 && prm.bstate;
     prm.keys_seg = nullptr;
     if (prm.nseg > 1) {
         prm.keys_seg = (u64 *)cur.take((size_t)n * prm.m * sizeof(u64));
@@ -1057,7 +1230,9 @@ skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n) {
         hipLaunchKernelGGL(sums_kernel, dim3((unsigned)n), dim3(1024), 0, ctx->stream, prm);
     }
     if (ctx->profiling) SKIM_HIP(ctx, hipEventRecord(ctx->ev[1], ctx->stream));
-    hipLaunchKernelGGL(lloyd_kernel, dim3((unsigned)n), dim3(LLOYD_THREADS), lloyd_lds_bytes(prm.m), ctx->stream, prm);
+    hipLaunchKernelGGL(lloyd_iter_kernel, dim3((unsigned)((n + 1) / 2)), dim3(ITER_THREADS), lloyd_lds_bytes(prm.m),
+                       ctx->stream, prm, (long long)n);
+    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)n), dim3(FIN_THREADS), 0, ctx->stream, prm);
     if (ctx->profiling) {
         SKIM_HIP(ctx, hipEventRecord(ctx->ev[2], ctx->stream));
         ctx->ev_valid = 1;
