@@ -68,7 +68,11 @@ struct BitState {  // what the Lloyd lanes of one bit width leave for the epilog
     int active;
 };
 
-__device__ __forceinline__ uint32_t swz(uint32_t i) { return i ^ ((i >> 4) & 31u); }
+// LDS slot of key index i: one spare slot after every 16 keys.  The skew makes the access patterns
+// of all passes (almost) free of bank conflicts, and it is additive: the 16 keys of a thread that
+// differ in index bits [wb, wb+4) sit at a fixed stride, so their addresses are one per-thread base
+// plus compile-time offsets that go into the instructions' offset fields.
+__device__ __forceinline__ uint32_t swz(uint32_t i) { return i + (i >> 4); }
 
 // Key of a (w, s) pair, s >= 0, both finite.  High word = the bits of w (-0 folded into +0), low
 // word = the bits of s, complemented when w is negative.  Read as a float64 the key is finite
@@ -122,35 +126,31 @@ __device__ __forceinline__ void ce(double &a, double &b) {
 // b = klog-2 .. 0; every comparator sends the smaller key to the lower index.  Padding keys
 // (+inf at the top indices) therefore never move.
 //
-// One pass over LDS: the thread holds the 16 keys whose indices differ in bits [wb, wb+4) and
+// One pass over LDS: the thread holds the 16 keys whose indices differ in bits [WB, WB+4) and
 // runs up to 4 consecutive stages in registers.  In a pass that opens a merge (FLIP >= 0 is the
 // window bit of the flip stage) the registers with that bit set are taken from the thread whose
-// low wb index bits are complemented, so that both keys of every flip pair sit in one thread.
-template <int FLIP, int HI, int LO>
-__device__ __forceinline__ void sort_pass(double *lds, uint32_t t, int wb, int m) {
-    const uint32_t lowmask = (1u << wb) - 1u;
-    const uint32_t base = ((t >> wb) << (wb + 4)) | (t & lowmask);
+// low WB index bits are complemented, so that both keys of every flip pair sit in one thread.
+// Stages run on window bits HI .. LO after the flip stage.
+template <int WB, int FLIP, int HI, int LO>
+__device__ __forceinline__ void sort_pass(double *lds, uint32_t t, int m) {
+    static_assert(WB == 0 || WB >= 4, "window below bit 4 must start at bit 0");
+    constexpr uint32_t lowmask = (1u << WB) - 1u;
+    constexpr uint32_t STRIDE = ((1u << WB) + (WB >= 4 ? (1u << (WB - 4)) : 0u)) * 8u;   // bytes between registers
+    constexpr int FB = FLIP >= 0 ? FLIP : 0;
+    const uint32_t base = ((t >> WB) << (WB + 4)) | (t & lowmask);
     if ((int)(base & ~lowmask) >= m) return;   // all 16 keys are padding
-    // The swizzle is linear over GF(2), so the byte address of register r is the thread's own
-    // swizzled base XOR a constant that is the same for the whole wavefront (scalar registers).
-    uint32_t abase = swz(base) << 3;
-    asm("" : "+v"(abase));
-    const uint32_t fdelta = (FLIP >= 0) ? (swz(lowmask) << 3) : 0u;
-    char *const lb = (char *)lds;
-    uint32_t addr[EPT];
+    char *const pa = (char *)lds + swz(base) * 8u;
+    char *const pf = (char *)lds + swz(base ^ lowmask) * 8u;
     double v[EPT];
 #pragma unroll
     for (int r = 0; r < EPT; ++r) {
-        const bool flipped = (FLIP >= 0) && (r & (1 << (FLIP >= 0 ? FLIP : 0)));
-        uint32_t k = (swz((uint32_t)r << wb) << 3) ^ (flipped ? fdelta : 0u);
-        asm("" : "+s"(k));    // keep the constant apart from the per-thread part (one v_xor per address)
-        addr[r] = abase ^ k;
-        v[r] = *(double *)(lb + addr[r]);
+        const bool flipped = (FLIP >= 0) && (r & (1 << FB));
+        v[r] = *(const double *)((flipped ? pf : pa) + r * STRIDE);
     }
     if (FLIP >= 0) {
 #pragma unroll
         for (int r = 0; r < EPT; ++r)
-            if (!(r & (1 << (FLIP >= 0 ? FLIP : 0)))) ce(v[r], v[r ^ ((2 << (FLIP >= 0 ? FLIP : 0)) - 1)]);
+            if (!(r & (1 << FB))) ce(v[r], v[r ^ ((2 << FB) - 1)]);
     }
 #pragma unroll
     for (int rb = HI; rb >= LO; --rb) {
@@ -159,16 +159,20 @@ __device__ __forceinline__ void sort_pass(double *lds, uint32_t t, int wb, int m
             if (!(r & (1 << rb))) ce(v[r], v[r | (1 << rb)]);
     }
 #pragma unroll
-    for (int r = 0; r < EPT; ++r) *(double *)(lb + addr[r]) = v[r];
+    for (int r = 0; r < EPT; ++r) {
+        const bool flipped = (FLIP >= 0) && (r & (1 << FB));
+        *(double *)((flipped ? pf : pa) + r * STRIDE) = v[r];
+    }
 }
 
 // The merges of size 2, 4, 8, 16 in one pass (index bits 0..3 are in-thread).
 __device__ __forceinline__ void sort_first_pass(double *lds, uint32_t t, int m) {
     const uint32_t base = t << 4;
     if ((int)base >= m) return;
+    double *const pa = lds + swz(base);
     double v[EPT];
 #pragma unroll
-    for (int r = 0; r < EPT; ++r) v[r] = lds[swz(base | (uint32_t)r)];
+    for (int r = 0; r < EPT; ++r) v[r] = pa[r];
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb) {
 #pragma unroll
@@ -182,79 +186,53 @@ __device__ __forceinline__ void sort_first_pass(double *lds, uint32_t t, int m) 
         }
     }
 #pragma unroll
-    for (int r = 0; r < EPT; ++r) lds[swz(base | (uint32_t)r)] = v[r];
+    for (int r = 0; r < EPT; ++r) pa[r] = v[r];
 }
 
-// flip < 0: plain pass over window bits hi..lo; flip >= 0: flip stage on window bit `flip`, then bits flip-1..lo
-__device__ __forceinline__ void dispatch_pass(double *lds, uint32_t t, int wb, int flip, int hi, int lo, int m) {
-    if (flip < 0) {
-        switch (hi * 4 + lo) {
-            case 0: sort_pass<-1, 0, 0>(lds, t, wb, m); break;
-            case 4: sort_pass<-1, 1, 0>(lds, t, wb, m); break;
-            case 5: sort_pass<-1, 1, 1>(lds, t, wb, m); break;
-            case 8: sort_pass<-1, 2, 0>(lds, t, wb, m); break;
-            case 9: sort_pass<-1, 2, 1>(lds, t, wb, m); break;
-            case 10: sort_pass<-1, 2, 2>(lds, t, wb, m); break;
-            case 12: sort_pass<-1, 3, 0>(lds, t, wb, m); break;
-            case 13: sort_pass<-1, 3, 1>(lds, t, wb, m); break;
-            case 14: sort_pass<-1, 3, 2>(lds, t, wb, m); break;
-            case 15: sort_pass<-1, 3, 3>(lds, t, wb, m); break;
-            default: break;
-        }
-    } else {
-        switch (flip * 4 + lo) {
-            case 0: sort_pass<0, -1, 0>(lds, t, wb, m); break;
-            case 4: sort_pass<1, 0, 0>(lds, t, wb, m); break;
-            case 5: sort_pass<1, 0, 1>(lds, t, wb, m); break;
-            case 8: sort_pass<2, 1, 0>(lds, t, wb, m); break;
-            case 9: sort_pass<2, 1, 1>(lds, t, wb, m); break;
-            case 10: sort_pass<2, 1, 2>(lds, t, wb, m); break;
-            case 12: sort_pass<3, 2, 0>(lds, t, wb, m); break;
-            case 13: sort_pass<3, 2, 1>(lds, t, wb, m); break;
-            case 14: sort_pass<3, 2, 2>(lds, t, wb, m); break;
-            case 15: sort_pass<3, 2, 3>(lds, t, wb, m); break;
-            default: break;
-        }
+// The last stages of a merge, index bits 9..0, inside the 1024 keys a wavefront owns (windows
+// [6,10) for bits 9..8, [4,8) for bits 7..4, [0,4) for bits 3..0): no workgroup barrier is needed
+// between these passes, because a wavefront's LDS accesses execute in order.
+__device__ __forceinline__ void wave_tail(double *lds, uint32_t tid, int m) {
+    sort_pass<6, -1, 3, 2>(lds, tid, m);
+    sort_pass<4, -1, 3, 0>(lds, tid, m);
+    sort_pass<0, -1, 3, 0>(lds, tid, m);
+}
+
+// Merges of 2^KLOG > 1024 keys: one pass over the top window [LOGP-4, LOGP) between two
+// workgroup barriers (flip stage on index bit KLOG-1, then the bits down to 10), then wave_tail.
+template <int LOGP, int KLOG>
+__device__ __forceinline__ void cross_merges(double *lds, uint32_t tid, int m) {
+    if constexpr (KLOG <= LOGP) {
+        constexpr int WBX = LOGP - 4;
+        __syncthreads();
+        sort_pass<WBX, KLOG - 1 - WBX, KLOG - 2 - WBX, 10 - WBX>(lds, tid, m);
+        __syncthreads();
+        wave_tail(lds, tid, m);
+        cross_merges<LOGP, KLOG + 1>(lds, tid, m);
     }
 }
 
-// Stages on index bits b..0 with windows that stay inside the 2^loc keys of one wavefront's
-// 64 threads: no workgroup barrier is needed between these passes (a wavefront's LDS accesses
-// execute in order).  flip: the first pass opens a merge with the flip stage on bit b.
-__device__ __forceinline__ void local_passes(double *lds, uint32_t tid, bool work, int loc, int b, bool flip, int m) {
-    const int ltop = (loc >> 2) << 2;   // bits >= ltop use the shifted window [loc-4, loc) when loc % 4 != 0
-    bool first = flip;
-    while (b >= 0) {
-        int wb, lo;
-        if ((loc & 3) && b >= ltop) {
-            wb = loc - 4;
-            lo = ltop;
-        } else {
-            wb = (b >> 2) << 2;
-            lo = wb;
-        }
-        if (work) dispatch_pass(lds, tid, wb, first ? b - wb : -1, b - wb, lo - wb, m);
-        first = false;
-        b = lo - 1;
-    }
-}
-
-// Sort of P = 2^logP keys in LDS (the last P - m of them padding), P/16 working threads.
+// Sort of P = 2^LOGP >= 1024 keys in LDS (the last P - m of them padding) by P/16 threads.
 // Merges up to 1024 keys run inside one wavefront (its 64 threads own an aligned block of 1024
-// keys); larger merges take one pass over the high index bits between two workgroup barriers
-// and finish inside the wavefronts again.
-__device__ void sort_row(double *lds, int logP, uint32_t tid, int m) {
-    const bool work = tid < (1u << (logP - 4));
-    const int loc = logP < 10 ? logP : 10;
-    if (work) sort_first_pass(lds, tid, m);
-    for (int klog = 5; klog <= loc; ++klog) local_passes(lds, tid, work, loc, klog - 1, true, m);
-    for (int klog = loc + 1; klog <= logP; ++klog) {
-        const int wb = logP - 4;
-        __syncthreads();
-        if (work) dispatch_pass(lds, tid, wb, klog - 1 - wb, klog - 1 - wb, loc - wb, m);
-        __syncthreads();
-        local_passes(lds, tid, work, loc, loc - 1, false, m);
-    }
+// keys); every pass has its window, its stages and hence its LDS offsets fixed at compile time.
+template <int LOGP>
+__device__ __forceinline__ void sort_row(double *lds, uint32_t tid, int m) {
+    sort_first_pass(lds, tid, m);
+    sort_pass<4, 0, -1, 0>(lds, tid, m);    // merges of 32 keys
+    sort_pass<0, -1, 3, 0>(lds, tid, m);
+    sort_pass<4, 1, 0, 0>(lds, tid, m);     // 64
+    sort_pass<0, -1, 3, 0>(lds, tid, m);
+    sort_pass<4, 2, 1, 0>(lds, tid, m);     // 128
+    sort_pass<0, -1, 3, 0>(lds, tid, m);
+    sort_pass<4, 3, 2, 0>(lds, tid, m);     // 256
+    sort_pass<0, -1, 3, 0>(lds, tid, m);
+    sort_pass<6, 2, 1, 2>(lds, tid, m);     // 512: bit 8 in the window [6,10)
+    sort_pass<4, -1, 3, 0>(lds, tid, m);
+    sort_pass<0, -1, 3, 0>(lds, tid, m);
+    sort_pass<6, 3, 2, 2>(lds, tid, m);     // 1024: bits 9..8
+    sort_pass<4, -1, 3, 0>(lds, tid, m);
+    sort_pass<0, -1, 3, 0>(lds, tid, m);
+    cross_merges<LOGP, 11>(lds, tid, m);
     __syncthreads();
 }
 
@@ -308,7 +286,7 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     const int P = prm.P;
     const int n1 = prm.n1;
     u64 *sorted = (u64 *)smem;
-    double2 *wsum = (double2 *)(smem + (size_t)P * 8);   // per-wavefront sums (16)
+    double2 *wsum = (double2 *)(smem + (size_t)(P + P / 16) * 8);   // per-wavefront sums (16)
     double *wpre = (double *)(wsum + 16);                // per-wavefront running sums of s (16) + total
 
     const int tid0 = threadIdx.x, nth = blockDim.x;      // nth == P / 16
@@ -346,7 +324,13 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     }
     __syncthreads();
 
-    sort_row((double *)sorted, prm.logP, (uint32_t)tid, m);
+    switch (prm.logP) {
+        case 10: sort_row<10>((double *)sorted, (uint32_t)tid, m); break;
+        case 11: sort_row<11>((double *)sorted, (uint32_t)tid, m); break;
+        case 12: sort_row<12>((double *)sorted, (uint32_t)tid, m); break;
+        case 13: sort_row<13>((double *)sorted, (uint32_t)tid, m); break;
+        default: sort_row<14>((double *)sorted, (uint32_t)tid, m); break;
+    }
     if (work + gridDim.x < prm.nwork) fetch_unit(prm, work + gridDim.x, tid, nth, pw, ps);
 
     if (prm.nseg > 1) {
@@ -1160,7 +1144,7 @@ __global__ void select_kernel(long long n, int bmin, int bmax, const uint8_t *bi
     if (err && k == 0) err[i] = E[i * nb + (b - bmin)];
 }
 
-size_t sort_lds_bytes(int P) { return (size_t)P * 8 + 16 * 16 + 17 * 8; }
+size_t sort_lds_bytes(int P) { return (size_t)(P + P / 16) * 8 + 16 * 16 + 17 * 8; }
 
 size_t lloyd_lds_bytes(int m) { return 2 * (size_t)level_map((m + 15) >> 4).bytes; }
 
