@@ -47,13 +47,12 @@ struct ClusterParams {
     float *upper;         // same layout as cent, may be null
     uint8_t *labels;      // rows mode only, may be null
     int stride;           // entries per row in cent/upper
-    // scratch written by sort_kernel, read by the Lloyd kernels (per row: m keys, n1/n2/n3 sums, n1+1 running sums)
+    // scratch written by sort_kernel, read by the Lloyd kernels (per row: m keys, n1 chunk sums and first weights)
     u64 *keys;
-    double2 *L1, *L2, *L3;
-    double *cpre;
+    double2 *L1;          // (sum of s, sum of s*w) of every 16-key chunk (n1 per row)
     float *w16;           // weight of the first key of every 16-key chunk (n1 per row)
     BitState *bstate;  // final state of the Lloyd lanes: 4 per row (bit widths 1..4)
-    int n1, n2, n3;
+    int n1;
     // rows longer than one LDS sort are sorted in nseg segments of seglen columns (keys_seg),
     // merged into keys, and their sums are taken by a separate kernel
     int nseg, seglen;
@@ -147,6 +146,7 @@ __device__ __forceinline__ void sort_pass(double *lds, uint32_t t, int m) {
         const bool flipped = (FLIP >= 0) && (r & (1 << FB));
         v[r] = *(const double *)((flipped ? pf : pa) + r * STRIDE);
     }
+    __builtin_amdgcn_sched_barrier(0);   // all 16 reads are issued before the first compare-exchange
     if (FLIP >= 0) {
 #pragma unroll
         for (int r = 0; r < EPT; ++r)
@@ -283,14 +283,9 @@ __device__ __forceinline__ void fetch_unit(const ClusterParams &prm, long long w
 
 __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int P = prm.P;
-    const int n1 = prm.n1;
     u64 *sorted = (u64 *)smem;
-    double2 *wsum = (double2 *)(smem + (size_t)(P + P / 16) * 8);   // per-wavefront sums (16)
-    double *wpre = (double *)(wsum + 16);                // per-wavefront running sums of s (16) + total
 
     const int tid0 = threadIdx.x, nth = blockDim.x;      // nth == P / 16
-    const int nwave = nth >> 6;
 
     // A workgroup takes the units of work blockIdx.x, blockIdx.x + gridDim.x, ...  The W and S values
     // of the next unit are fetched into registers (all loads in flight at once) while the sums of
@@ -305,12 +300,12 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     // used instead of being hoisted out of this loop and held in registers through the sort
     int tid = tid0;
     asm volatile("" : "+v"(tid));
-    const int lane = tid & 63, wave = tid >> 6;
     const long long row = work / prm.nseg;
     const int col0 = (int)(work % prm.nseg) * prm.seglen;            // first column of this segment
     const int m = min(prm.m - col0, prm.seglen);                     // keys sorted by this workgroup
     const float *alpha = prm.alpha ? prm.alpha + col0 : nullptr;
 
+    bool mass = false;
 #pragma unroll
     for (int k = 0; k < EPT; ++k) {
         const int j = tid + k * nth;
@@ -319,10 +314,23 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
             float wt, st;
             scaled_pair(pw[k], ps[k], alpha, j, wt, st);
             key = make_key(wt, st);
+            mass = mass || (st != 0.0f);
         }
         sorted[swz((uint32_t)j)] = key;
     }
-    __syncthreads();
+    // (segments of a long row cannot tell on their own: sums_kernel sees the whole row)
+    if (!__syncthreads_or((int)mass) && prm.nseg == 1) {
+        // no sensitivity mass in this row: cluster with unit weights
+#pragma unroll
+        for (int k = 0; k < EPT; ++k) {
+            const int j = tid + k * nth;
+            if (j < m) {
+                const uint32_t a = swz((uint32_t)j);
+                sorted[a] = unit_weight_key(sorted[a]);
+            }
+        }
+        __syncthreads();
+    }
 
     switch (prm.logP) {
         case 10: sort_row<10>((double *)sorted, (uint32_t)tid, m); break;
@@ -340,76 +348,22 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
         __syncthreads();   // the LDS is refilled for the next unit
         continue;
     }
-    double2 *L1 = prm.L1 + row * prm.n1;
-    double2 *L2 = prm.L2 + row * prm.n2;
-    double2 *L3 = prm.L3 + row * prm.n3;
-    double *cpre = prm.cpre + row * (prm.n1 + 1);
-    for (int pass = 0; pass < 2; ++pass) {
+    // sums of s and s*w over each 16-key chunk (s*w of two floats is exact in float64) and the
+    // weight of the chunk's first key
+    if (tid * EPT < m) {
+        const u64 *mine = sorted + swz((uint32_t)(tid * EPT));
         double c = 0.0, q = 0.0;
-        if (tid < n1) {
-            for (int e = 0; e < EPT; ++e) {
-                const int r = tid * EPT + e;
-                if (r < m) {
-                    const u64 el = sorted[swz((uint32_t)r)];
-                    const double s = (double)elem_s(el), w = (double)elem_w(el);
-                    c += s;
-                    q = fma(s, w, q);
-                }
-            }
+        float w0 = 0.0f;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const u64 el = (tid * EPT + e < m) ? mine[e] : NEUTRAL_KEY;
+            const double sv = (double)elem_s(el), wv = (double)elem_w(el);
+            if (e == 0) w0 = elem_w(el);
+            c += sv;
+            q = fma(sv, wv, q);
         }
-        double bc = c, bq = q;       // 16 neighbouring chunks = one 256-key block (valid on lanes 0, 16, 32, 48)
-        for (int d = 8; d >= 1; d >>= 1) {
-            bc += __shfl_down(bc, d, 16);
-            bq += __shfl_down(bq, d, 16);
-        }
-        // the wavefront's four blocks, added in a fixed order
-        const double c1 = __shfl(bc, 16, 64), c2 = __shfl(bc, 32, 64), c3 = __shfl(bc, 48, 64);
-        const double q1 = __shfl(bq, 16, 64), q2 = __shfl(bq, 32, 64), q3 = __shfl(bq, 48, 64);
-        const double c0 = __shfl(bc, 0, 64), q0 = __shfl(bq, 0, 64);
-        const double wc = ((c0 + c1) + c2) + c3, wq = ((q0 + q1) + q2) + q3;
-        double ic = c;               // inclusive running sum of s inside the wavefront
-        for (int d = 1; d < 64; d <<= 1) {
-            const double uc = __shfl_up(ic, d, 64);
-            if (lane >= d) ic += uc;
-        }
-        double xc = __shfl_up(ic, 1, 64);   // exclusive
-        if (lane == 0) xc = 0.0;
-        if (lane == 0) {
-            wsum[wave] = make_double2(wc, wq);
-            wpre[wave] = wc;
-        }
-        __syncthreads();
-        double total = 0.0, before = 0.0;
-        for (int w2 = 0; w2 < nwave; ++w2) {   // same order in every thread
-            if (w2 == wave) before = total;
-            total += wpre[w2];
-        }
-        if (total == 0.0 && pass == 0) {
-            // no sensitivity mass in this row: cluster with unit weights
-            __syncthreads();
-            for (int j = tid; j < m; j += nth) {
-                const uint32_t a = swz((uint32_t)j);
-                sorted[a] = unit_weight_key(sorted[a]);
-            }
-            __syncthreads();
-            continue;
-        }
-        if (tid < n1) {
-            L1[tid] = make_double2(c, q);
-            prm.w16[row * prm.n1 + tid] = (tid * EPT < m) ? elem_w(sorted[swz((uint32_t)(tid * EPT))]) : 0.0f;
-            cpre[tid] = before + xc;
-            if ((lane & 15) == 0) L2[tid >> 4] = make_double2(bc, bq);
-        }
-        if (tid == 0) cpre[n1] = total;
-        if (tid < prm.n3) {                    // one super-block = four wavefronts
-            double sc = 0.0, sq = 0.0;
-            for (int w2 = 4 * tid; w2 < min(nwave, 4 * tid + 4); ++w2) {
-                sc += wsum[w2].x;
-                sq += wsum[w2].y;
-            }
-            L3[tid] = make_double2(sc, sq);
-        }
-        break;
+        prm.L1[row * prm.n1 + tid] = make_double2(c, q);
+        prm.w16[row * prm.n1 + tid] = w0;
     }
     // sorted keys, compact and in rank order
     u64 *keys = prm.keys + row * (long long)m;
@@ -457,21 +411,15 @@ __global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(ClusterParams prm)
     }
 }
 
-// One workgroup per row: chunk / block / super-block sums and the running sum of s from the
-// merged keys (same quantities sort_kernel produces for short rows).  m <= 32768.
+// One workgroup per row: chunk sums and first weights from the merged keys (the quantities
+// sort_kernel produces for short rows), and the switch to unit weights for a row without
+// sensitivity mass.  m <= 32768, two chunks per thread.
 __global__ void __launch_bounds__(1024) sums_kernel(ClusterParams prm) {
-    __shared__ double2 l1[2048];
-    __shared__ double2 l2[128];
-    __shared__ double wtot[16];
     const long long row = blockIdx.x;
     const int m = prm.m;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n1u = (m + 15) >> 4, n2u = (n1u + 15) >> 4, n3u = (n2u + 15) >> 4;
+    const int tid = threadIdx.x;
+    const int n1u = (m + 15) >> 4;
     u64 *keys = prm.keys + row * (long long)m;
-    double2 *L1 = prm.L1 + row * prm.n1;
-    double2 *L2 = prm.L2 + row * prm.n2;
-    double2 *L3 = prm.L3 + row * prm.n3;
-    double *cpre = prm.cpre + row * (prm.n1 + 1);
     for (int pass = 0; pass < 2; ++pass) {
         double cs[2] = {0.0, 0.0}, qs[2] = {0.0, 0.0};
 #pragma unroll
@@ -490,55 +438,15 @@ __global__ void __launch_bounds__(1024) sums_kernel(ClusterParams prm) {
                     qs[h] = fma(s, w, qs[h]);
                 }
             }
-            l1[ch] = make_double2(cs[h], qs[h]);
         }
-        const double pair = cs[0] + cs[1];
-        double ic = pair;
-        for (int d = 1; d < 64; d <<= 1) {
-            const double uc = __shfl_up(ic, d, 64);
-            if (lane >= d) ic += uc;
-        }
-        double xc = __shfl_up(ic, 1, 64);
-        if (lane == 0) xc = 0.0;
-        __syncthreads();                         // previous pass's readers of wtot are done
-        if (lane == 63) wtot[wave] = ic;
-        __syncthreads();
-        double total = 0.0, before = 0.0;
-        for (int w2 = 0; w2 < 16; ++w2) {
-            if (w2 == wave) before = total;
-            total += wtot[w2];
-        }
-        if (total == 0.0 && pass == 0) continue;
-        if (2 * tid < n1u) {
-            L1[2 * tid] = l1[2 * tid];
-            cpre[2 * tid] = before + xc;
-            prm.w16[row * prm.n1 + 2 * tid] = elem_w(keys[32 * tid]);
-        }
-        if (2 * tid + 1 < n1u) {
-            L1[2 * tid + 1] = l1[2 * tid + 1];
-            cpre[2 * tid + 1] = (before + xc) + cs[0];
-            prm.w16[row * prm.n1 + 2 * tid + 1] = elem_w(keys[32 * tid + 16]);
-        }
-        if (tid == 0) cpre[prm.n1] = total;
-        if (tid < n2u) {
-            double sc = 0.0, sq = 0.0;
-            for (int k = 0; k < 16; ++k) {
-                sc += l1[16 * tid + k].x;
-                sq += l1[16 * tid + k].y;
+        if (pass == 0 && !__syncthreads_or((int)(cs[0] + cs[1] != 0.0))) continue;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int ch = 2 * tid + h;
+            if (ch < n1u) {
+                prm.L1[row * prm.n1 + ch] = make_double2(cs[h], qs[h]);
+                prm.w16[row * prm.n1 + ch] = elem_w(keys[16 * ch]);
             }
-            l2[tid] = make_double2(sc, sq);
-            L2[tid] = l2[tid];
-        } else if (tid < 128) {
-            l2[tid] = make_double2(0.0, 0.0);
-        }
-        __syncthreads();
-        if (tid < n3u) {
-            double sc = 0.0, sq = 0.0;
-            for (int k = 0; k < 16; ++k) {
-                sc += l2[16 * tid + k].x;
-                sq += l2[16 * tid + k].y;
-            }
-            L3[tid] = make_double2(sc, sq);
         }
         break;
     }
@@ -1144,7 +1052,7 @@ __global__ void select_kernel(long long n, int bmin, int bmax, const uint8_t *bi
     if (err && k == 0) err[i] = E[i * nb + (b - bmin)];
 }
 
-size_t sort_lds_bytes(int P) { return (size_t)(P + P / 16) * 8 + 16 * 16 + 17 * 8; }
+size_t sort_lds_bytes(int P) { return (size_t)(P + P / 16) * 8; }
 
 size_t lloyd_lds_bytes(int m) { return 2 * (size_t)level_map((m + 15) >> 4).bytes; }
 
@@ -1162,17 +1070,12 @@ skim_status carve_cluster_ws(skim_ctx *ctx, ClusterParams &prm, int64_t n, doubl
     prm.logP = logP;
     prm.P = 1 << logP;
     prm.n1 = (prm.nseg == 1) ? prm.P / EPT : (prm.m + 15) / 16;
-    prm.n2 = (prm.n1 + 15) / 16;
-    prm.n3 = (prm.n2 + 15) / 16;
     skim_ws_cursor cur{(char *)ctx->ws, 0, ctx->ws_bytes};
     prm.keys = (u64 *)cur.take((size_t)n * prm.m * sizeof(u64));
     prm.L1 = (double2 *)cur.take((size_t)n * prm.n1 * sizeof(double2));
-    prm.L2 = (double2 *)cur.take((size_t)n * prm.n2 * sizeof(double2));
-    prm.L3 = (double2 *)cur.take((size_t)n * prm.n3 * sizeof(double2));
-    prm.cpre = (double *)cur.take((size_t)n * (prm.n1 + 1) * sizeof(double));
     prm.w16 = (float *)cur.take((size_t)n * prm.n1 * sizeof(float));
     prm.bstate = (BitState *)cur.take((size_t)n * 4 * sizeof(BitState));
-    bool ok = prm.keys && prm.L1 && prm.L2 && prm.L3 && prm.cpre && prm.w16 && prm.bstate;
+    bool ok = prm.keys && prm.L1 && prm.w16 && prm.bstate;
     prm.keys_seg = nullptr;
     if (prm.nseg > 1) {
         prm.keys_seg = (u64 *)cur.take((size_t)n * prm.m * sizeof(u64));
@@ -1194,8 +1097,8 @@ skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n) {
         SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "row length %d needs %zu bytes of LDS, device allows %d", prm.m, lds, ctx->lds_limit);
     static size_t lds_enabled = 0;
     if (lds > 65536 && lds > lds_enabled) {
-        SKIM_HIP(ctx, hipFuncSetAttribute((const void *)sort_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ctx->lds_limit));
-        lds_enabled = (size_t)ctx->lds_limit;
+        SKIM_HIP(ctx, hipFuncSetAttribute((const void *)sort_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        lds_enabled = lds;
     }
     if (n == 0) return SKIM_OK;
     if ((int64_t)n * prm.nseg > 0x7fffffff) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "too many rows");
