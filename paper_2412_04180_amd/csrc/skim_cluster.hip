@@ -50,6 +50,8 @@ struct ClusterParams {
     // scratch written by sort_kernel, read by the Lloyd kernels (per row: m keys, n1 chunk sums and first weights)
     u64 *keys;
     double2 *L1;          // (sum of s, sum of s*w) of every 16-key chunk (n1 per row)
+    double2 *Q;           // the same sums over every group of 4 chunks (nq = n1 / 4 per row)
+    int nq;
     float *w16;           // weight of the first key of every 16-key chunk (n1 per row)
     BitState *bstate;  // final state of the Lloyd lanes: 4 per row (bit widths 1..4)
     int n1;
@@ -348,10 +350,11 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
         __syncthreads();   // the LDS is refilled for the next unit
         continue;
     }
-    // sums of s and s*w over each 16-key chunk (s*w of two floats is exact in float64) and the
-    // weight of the chunk's first key
-    if (tid * EPT < m) {
-        const u64 *mine = sorted + swz((uint32_t)(tid * EPT));
+    // sums of s and s*w over each 16-key chunk (s*w of two floats is exact in float64), the weight
+    // of the chunk's first key, and the sums over each group of 4 chunks (4 neighbouring threads)
+    {
+        const bool mine_ok = tid * EPT < m;
+        const u64 *mine = sorted + swz((uint32_t)(mine_ok ? tid * EPT : 0));
         double c = 0.0, q = 0.0;
         float w0 = 0.0f;
 #pragma unroll
@@ -362,8 +365,12 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
             c += sv;
             q = fma(sv, wv, q);
         }
-        prm.L1[row * prm.n1 + tid] = make_double2(c, q);
-        prm.w16[row * prm.n1 + tid] = w0;
+        if (mine_ok) {
+            prm.L1[row * prm.n1 + tid] = make_double2(c, q);
+            prm.w16[row * prm.n1 + tid] = w0;
+        }
+        const double c4 = quad_sum(c), q4 = quad_sum(q);   // threads past the row add zeros
+        if (mine_ok && (tid & 3) == 0) prm.Q[row * prm.nq + (tid >> 2)] = make_double2(c4, q4);
     }
     // sorted keys, compact and in rank order
     u64 *keys = prm.keys + row * (long long)m;
@@ -448,6 +455,12 @@ __global__ void __launch_bounds__(1024) sums_kernel(ClusterParams prm) {
                 prm.w16[row * prm.n1 + ch] = elem_w(keys[16 * ch]);
             }
         }
+        {   // groups of 4 chunks = 2 neighbouring threads
+            double c2 = cs[0] + cs[1], q2 = qs[0] + qs[1];
+            c2 += dpp_move_d<0xB1>(c2);   // quad_perm [1,0,3,2]
+            q2 += dpp_move_d<0xB1>(q2);
+            if ((tid & 1) == 0 && 2 * tid < n1u) prm.Q[row * prm.nq + (tid >> 1)] = make_double2(c2, q2);
+        }
         break;
     }
 }
@@ -464,7 +477,7 @@ struct LevelMap {
     int nlev;        // levels 0 .. nlev-1
     int n[8];        // entries per level
     int off[8];      // byte offset of level >= 1 inside the row's LDS block
-    int w16_off, pre_off, bytes;
+    int w16_off, pre_off, zero_off, bytes;   // zero_off: an entry (0, 0) for the slots a lane does not need
 };
 __host__ __device__ inline LevelMap level_map(int n1u) {
     LevelMap L;
@@ -484,7 +497,10 @@ __host__ __device__ inline LevelMap level_map(int n1u) {
     L.nlev = lv + 1;
     L.pre_off = o;
     o += (L.n[1] + 1) * 8;
-    L.bytes = (o + 15) & ~15;
+    o = (o + 15) & ~15;
+    L.zero_off = o;
+    o += 16;
+    L.bytes = o;
     return L;
 }
 
@@ -500,6 +516,22 @@ constexpr int MAX_LEVELS = 8;
 // and the whole chunks in between as aligned pieces of the radix-4 tree.  Nothing outside the
 // range enters a sum, so a cluster of tiny weight mass next to a heavy element keeps full
 // relative precision (a difference of running prefix sums would not).
+typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+typedef u64x2 __attribute__((aligned(8))) u64x2_a8;
+
+// Quotient n / d for d > 0 within about one unit in the last place (reciprocal estimate, two
+// Newton steps, one correction): the centroid update needs no correctly rounded division, its
+// operands already carry the rounding of the sums.
+__device__ __forceinline__ double quick_div(double n, double d) {
+    double r = __builtin_amdgcn_rcp(d);
+    r = fma(fma(-d, r, 1.0), r, r);
+    r = fma(fma(-d, r, 1.0), r, r);
+    const double q = n * r;
+    return fma(fma(-d, q, n), r, q);
+}
+
+// RAGGED: the row length is not a multiple of 16, so the last chunk holds fewer than 16 keys.
+template <bool RAGGED>
 __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams prm, long long nrows) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int m = prm.m;
@@ -509,33 +541,51 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
     const int h = lane >> 5, l5 = lane & 31;
 
     // ---- prologue: both rows' trees, first weights and running sums into LDS -------------------
-    for (int hh = 0; hh < 2; ++hh) {
+    // (all global loads of a batch are in flight together; level 1 comes ready-made from the sort)
+    const int nhalf = (2ll * blockIdx.x + 1 < nrows) ? 2 : 1;
+    for (int hh = 0; hh < nhalf; ++hh) {
         const long long rr = 2ll * blockIdx.x + hh;
-        if (rr >= nrows) break;
-        unsigned char *blk = smem + (size_t)hh * LM.bytes;
-        float *w16 = (float *)(blk + LM.w16_off);
+        unsigned char *blkw = smem + (size_t)hh * LM.bytes;
+        float *w16w = (float *)(blkw + LM.w16_off);
         const float *gw = prm.w16 + rr * prm.n1;
-        for (int j = lane; j < n1u; j += ITER_THREADS) w16[j] = gw[j];
-        const double2 *g1 = prm.L1 + rr * prm.n1;
-        double2 *l1 = (double2 *)(blk + LM.off[1]);
-        for (int q = lane; q < LM.n[1]; q += ITER_THREADS) {
-            double d = 0.0, nn = 0.0;
+        for (int j0 = 0; j0 < n1u; j0 += 8 * ITER_THREADS) {
+            float t8[8];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                if (4 * q + k < n1u) {
-                    const double2 x = g1[4 * q + k];
-                    d += x.x;
-                    nn += x.y;
-                }
+            for (int u = 0; u < 8; ++u) {
+                const int j = j0 + u * ITER_THREADS + lane;
+                t8[u] = (j < n1u) ? gw[j] : 0.0f;
             }
-            l1[q] = make_double2(d, nn);
-        }
-        __syncthreads();
 #pragma unroll
-        for (int lv = 2; lv < MAX_LEVELS; ++lv) {
-            if (lv < LM.nlev) {
-                const double2 *src = (const double2 *)(blk + LM.off[lv - 1]);
-                double2 *dst = (double2 *)(blk + LM.off[lv]);
+            for (int u = 0; u < 8; ++u) {
+                const int j = j0 + u * ITER_THREADS + lane;
+                if (j < n1u) w16w[j] = t8[u];
+            }
+        }
+        const double2 *gq = prm.Q + rr * prm.nq;
+        double2 *l1 = (double2 *)(blkw + LM.off[1]);
+        for (int q0 = 0; q0 < LM.n[1]; q0 += 4 * ITER_THREADS) {
+            double2 t4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int q = q0 + u * ITER_THREADS + lane;
+                t4[u] = (q < LM.n[1]) ? gq[q] : make_double2(0.0, 0.0);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int q = q0 + u * ITER_THREADS + lane;
+                if (q < LM.n[1]) l1[q] = t4[u];
+            }
+        }
+        if (lane == 0) *(double2 *)(blkw + LM.zero_off) = make_double2(0.0, 0.0);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int lv = 2; lv < MAX_LEVELS; ++lv) {
+        if (lv < LM.nlev) {
+            for (int hh = 0; hh < nhalf; ++hh) {
+                unsigned char *blkw = smem + (size_t)hh * LM.bytes;
+                const double2 *src = (const double2 *)(blkw + LM.off[lv - 1]);
+                double2 *dst = (double2 *)(blkw + LM.off[lv]);
                 for (int q = lane; q < LM.n[lv]; q += ITER_THREADS) {
                     double d = 0.0, nn = 0.0;
 #pragma unroll
@@ -548,26 +598,40 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
                     }
                     dst[q] = make_double2(d, nn);
                 }
-                __syncthreads();
             }
+            __syncthreads();
         }
-        // running sum of s ahead of each level-1 group (64 keys); pre[n[1]] = total
-        double *pre = (double *)(blk + LM.pre_off);
-        double carry = 0.0;
-        for (int q0 = 0; q0 < LM.n[1]; q0 += ITER_THREADS) {
-            const int q = q0 + lane;
-            const double mine = (q < LM.n[1]) ? l1[q].x : 0.0;
+    }
+    {   // running sum of s ahead of each level-1 group (64 keys); pre[n[1]] = total.  A lane takes
+        // `per` consecutive groups; one scan over the lanes per row.
+        const int ng = LM.n[1];
+        const int per = (ng + ITER_THREADS - 1) / ITER_THREADS;
+        for (int hh = 0; hh < nhalf; ++hh) {
+            unsigned char *blkw = smem + (size_t)hh * LM.bytes;
+            const double2 *l1 = (const double2 *)(blkw + LM.off[1]);
+            double *prew = (double *)(blkw + LM.pre_off);
+            double mine = 0.0;
+            for (int k = 0; k < per; ++k) {
+                const int q = lane * per + k;
+                if (q < ng) mine += l1[q].x;
+            }
             double inc = mine;
             for (int d = 1; d < 64; d <<= 1) {
                 const double u = __shfl_up(inc, d, 64);
                 if (lane >= d) inc += u;
             }
-            if (q < LM.n[1]) pre[q] = carry + (inc - mine);
-            carry += __shfl(inc, 63, 64);
+            double run = inc - mine;
+            for (int k = 0; k < per; ++k) {
+                const int q = lane * per + k;
+                if (q < ng) {
+                    prew[q] = run;
+                    run += l1[q].x;
+                }
+            }
+            if (lane == 63) prew[ng] = inc;
         }
-        if (lane == 0) pre[LM.n[1]] = carry;
-        __syncthreads();
     }
+    __syncthreads();
 
     // ---- lane -> (row, bit width, position) ------------------------------------------------------
     const long long row = 2ll * blockIdx.x + h;
@@ -776,10 +840,18 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
         b0 = max(b0, a0);
 
         // ---- one round of global loads: the boundary chunk's keys and the level-0 pieces ----------
+        // (lanes without a boundary chunk read the row's first chunk and ignore it)
         u64 el[16];
         const int rbase = cl * 16;
+        {
+            const u64x2_a8 *kv = (const u64x2_a8 *)(keys + (cl >= 0 ? rbase : 0));
 #pragma unroll
-        for (int j = 0; j < 16; ++j) el[j] = (cl >= 0 && rbase + j < m) ? keys[rbase + j] : NEUTRAL_KEY;
+            for (int j = 0; j < 8; ++j) {
+                const u64x2 t2 = kv[j];
+                el[2 * j] = t2.x;
+                el[2 * j + 1] = t2.y;
+            }
+        }
         const int la0 = min(b0, (a0 + 3) & ~3), rb0 = max(la0, b0 & ~3);
         double2 pc[6];
 #pragma unroll
@@ -789,10 +861,19 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
         }
 
         int tc = 0;
+        if (RAGGED) {
+            const int nvalid = m - rbase;   // keys past the end of the row are not this row's
 #pragma unroll
-        for (int j = 0; j < 16; ++j) tc += (cl >= 0 && rbase + j < m && nearer_lo(elem_w(el[j]))) ? 1 : 0;
-        const int Bs = searching ? rbase + tc : 0;
-        Bcur = Bs;  // p == 0: 0
+            for (int j = 0; j < 16; ++j) {
+                if (j >= nvalid) el[j] = NEUTRAL_KEY;
+                tc += (j < nvalid && nearer_lo(elem_w(el[j]))) ? 1 : 0;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) tc += nearer_lo(elem_w(el[j])) ? 1 : 0;
+        }
+        if (cl < 0) tc = 0;
+        Bcur = (searching && cl >= 0) ? rbase + tc : 0;  // p == 0 or no chunk below the boundary: 0
         if (anydup) {
             // a position sharing its value with the one before it owns nothing:
             // its range starts where the next distinct value's range starts
@@ -815,20 +896,23 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
             idxold = idx;
         }
 
-        // own chunk: keys below the boundary go to the cluster below, keys from it on (and below
-        // the next boundary) are this cluster's
+        // own chunk: its first tl keys (below the boundary) go to the cluster below, the keys from
+        // there up to th (the next boundary, if it falls into this chunk) are this cluster's
+        const bool own = searching && cl >= 0;
+        const int tl = own ? tc : 0;
+        const int th = own ? min(16, Bnext - rbase) : 0;
         double lowD = 0.0, lowN = 0.0, D = 0.0, N = 0.0;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            const int rk = rbase + j;
-            const double s = (double)elem_s(el[j]);      // a skipped slot holds (w = +0, s = +0)
-            const double sw = s * (double)elem_w(el[j]);  // exact: two floats
-            const bool isl = rk < Bs;
-            const bool ish = !isl && rk < Bnext;
-            lowD += isl ? s : 0.0;
-            lowN += isl ? sw : 0.0;
-            D += ish ? s : 0.0;
-            N += ish ? sw : 0.0;
+            const float sf = elem_s(el[j]);
+            const double wd = (double)elem_w(el[j]);
+            const float sl = (j < tl) ? sf : 0.0f;
+            const float sh = (j >= tl && j < th) ? sf : 0.0f;
+            const double sld = (double)sl, shd = (double)sh;
+            lowD += sld;
+            lowN = fma(sld, wd, lowN);     // s * w of two floats is exact
+            D += shd;
+            N = fma(shd, wd, N);
         }
         if (anydup) {
             double xd = lowD, xn = lowN;
@@ -859,18 +943,24 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
         for (int lv = 1; lv < MAX_LEVELS; ++lv) {
             if (lv < LM.nlev) {
                 if (__ballot(a < bq) != 0) {
-                    const double2 *L = (const double2 *)(blk + LM.off[lv]);
                     const int la = min(bq, (a + 3) & ~3), rb = max(la, bq & ~3);
 #pragma unroll
                     for (int k = 0; k < 3; ++k) {
-                        if (a + k < la) { const double2 x = L[a + k]; D += x.x; N += x.y; }
-                        if (rb + k < bq) { const double2 x = L[rb + k]; D += x.x; N += x.y; }
+                        // a slot that is not needed reads the zero entry instead
+                        const int o1 = (a + k < la) ? LM.off[lv] + (a + k) * 16 : LM.zero_off;
+                        const int o2 = (rb + k < bq) ? LM.off[lv] + (rb + k) * 16 : LM.zero_off;
+                        const double2 x1 = *(const double2 *)(blk + o1);
+                        const double2 x2 = *(const double2 *)(blk + o2);
+                        D += x1.x;
+                        N += x1.y;
+                        D += x2.x;
+                        N += x2.y;
                     }
                     if (la < rb) { a = la >> 2; bq = rb >> 2; } else { a = 0; bq = 0; }
                 }
             }
         }
-        if (summing && !done && D > 0.0) v = N / D;
+        if (summing && !done && D > 0.0) v = quick_div(N, D);
     }
 
     if (on) {
@@ -1073,9 +1163,11 @@ skim_status carve_cluster_ws(skim_ctx *ctx, ClusterParams &prm, int64_t n, doubl
     skim_ws_cursor cur{(char *)ctx->ws, 0, ctx->ws_bytes};
     prm.keys = (u64 *)cur.take((size_t)n * prm.m * sizeof(u64));
     prm.L1 = (double2 *)cur.take((size_t)n * prm.n1 * sizeof(double2));
+    prm.nq = (prm.n1 + 3) / 4;
+    prm.Q = (double2 *)cur.take((size_t)n * prm.nq * sizeof(double2));
     prm.w16 = (float *)cur.take((size_t)n * prm.n1 * sizeof(float));
     prm.bstate = (BitState *)cur.take((size_t)n * 4 * sizeof(BitState));
-    bool ok = prm.keys && prm.L1 && prm.w16 && prm.bstate;
+    bool ok = prm.keys && prm.L1 && prm.Q && prm.w16 && prm.bstate;
     prm.keys_seg = nullptr;
     if (prm.nseg > 1) {
         prm.keys_seg = (u64 *)cur.take((size_t)n * prm.m * sizeof(u64));
@@ -1117,8 +1209,12 @@ skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n) {
         hipLaunchKernelGGL(sums_kernel, dim3((unsigned)n), dim3(1024), 0, ctx->stream, prm);
     }
     if (ctx->profiling) SKIM_HIP(ctx, hipEventRecord(ctx->ev[1], ctx->stream));
-    hipLaunchKernelGGL(lloyd_iter_kernel, dim3((unsigned)((n + 1) / 2)), dim3(ITER_THREADS), lloyd_lds_bytes(prm.m),
-                       ctx->stream, prm, (long long)n);
+    if (prm.m & 15)
+        hipLaunchKernelGGL(lloyd_iter_kernel<true>, dim3((unsigned)((n + 1) / 2)), dim3(ITER_THREADS),
+                           lloyd_lds_bytes(prm.m), ctx->stream, prm, (long long)n);
+    else
+        hipLaunchKernelGGL(lloyd_iter_kernel<false>, dim3((unsigned)((n + 1) / 2)), dim3(ITER_THREADS),
+                           lloyd_lds_bytes(prm.m), ctx->stream, prm, (long long)n);
     hipLaunchKernelGGL(finish_kernel, dim3((unsigned)n), dim3(FIN_THREADS), 0, ctx->stream, prm);
     if (ctx->profiling) {
         SKIM_HIP(ctx, hipEventRecord(ctx->ev[2], ctx->stream));
