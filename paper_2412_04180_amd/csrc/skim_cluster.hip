@@ -252,6 +252,16 @@ __device__ __forceinline__ double dpp_move_d(double x) {
     hi = dpp_move_i<CTRL>(hi);
     return __hiloint2double(hi, lo);
 }
+// Neighbouring lanes of the whole wavefront inside the VALU: lane i reads lane i-1 / lane i+1
+// (lane 0 / lane 63 keep their own value).
+__device__ __forceinline__ int lane_below(int x) { return __builtin_amdgcn_update_dpp(x, x, 0x138, 0xF, 0xF, false); }
+__device__ __forceinline__ int lane_above(int x) { return __builtin_amdgcn_update_dpp(x, x, 0x130, 0xF, 0xF, false); }
+__device__ __forceinline__ double lane_below(double x) {
+    return __hiloint2double(lane_below(__double2hiint(x)), lane_below(__double2loint(x)));
+}
+__device__ __forceinline__ double lane_above(double x) {
+    return __hiloint2double(lane_above(__double2hiint(x)), lane_above(__double2loint(x)));
+}
 // Sum over the four lanes of a quad; every lane of the quad gets the same bits.
 __device__ __forceinline__ double quad_sum(double x) {
     x += dpp_move_d<0xB1>(x);  // quad_perm [1,0,3,2]
@@ -721,12 +731,14 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
     double v = on ? (double)elem_w(keys[r]) : 0.0;
     int idx = p;
     int Bcur = 0, Bold = -1, idxold = -1, cold = 0;
+    int ca3 = -1, cb3 = -1;          // range at the 1024-key level whose sums cD3, cN3 hold
+    double cD3 = 0.0, cN3 = 0.0;
     bool done = !on;
 
     for (int it = 0; it < prm.iters; ++it) {
         if (__ballot(!done) == 0) break;
-        double vlo = shfl_d(v, lane - 1);
-        int ilo = __shfl(idx, lane - 1, 64);
+        double vlo = lane_below(v);
+        int ilo = lane_below(idx);
         {   // keep positions ordered by (value, cluster index)
             const bool ok = done || (p == 0) || (vlo < v) || (vlo == v && ilo < idx);
             if (__ballot(!ok)) {
@@ -747,8 +759,8 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
                     v = nv;
                     idx = ni;
                 }
-                vlo = shfl_d(v, lane - 1);
-                ilo = __shfl(idx, lane - 1, 64);
+                vlo = lane_below(v);
+                ilo = lane_below(idx);
             }
         }
         const bool dup = !done && (p > 0) && (vlo == v);
@@ -763,19 +775,22 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
                 if (k < K && p == k && dk) rs = rsp;
             }
             rep = __shfl(idx, from_pos(rs), 64);
-            replo = __shfl(rep, lane - 1, 64);
+            replo = lane_below(rep);
         }
         const bool searching = !done && (p > 0) && !dup;
         const bool tie_lo = replo < rep;  // equal distances go to the lower cluster index
+        // |x - vlo| < |x - v|, or <= when the lower cluster wins ties: the difference of the two
+        // distances is zero exactly when they are equal, and no double lies between zero and the
+        // smallest subnormal, so "<= 0" is "< smallest subnormal"
+        const double thr = tie_lo ? __longlong_as_double(1ll) : 0.0;
         auto nearer_lo = [&](float xf) -> bool {
             const double x = (double)xf;
-            const double dl = fabs(x - vlo), dh = fabs(x - v);
-            return tie_lo ? (dl <= dh) : (dl < dh);
+            return (fabs(x - vlo) - fabs(x - v)) < thr;
         };
 
         // ---- chunk of the boundary: cnt = number of chunks whose first key is nearer to the lower
         // centroid (a prefix of the chunks); invariant lo <= cnt <= hi -----------------------------
-        const int rlo = __shfl(r, lane - 1, 64);
+        const int rlo = lane_below(r);
         int lo = 0, hi = 0, mode = 0, step = 1;
         if (it == 0) {
             // the starting centroids are the keys at ranks r: the boundary lies in (r_{p-1}, r_p]
@@ -831,7 +846,7 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
                 if (k <= K - 2 && p == k && xcl == -2) xcl = nx;
             }
         }
-        int cl_next = __shfl(xcl, lane + 1, 64);
+        int cl_next = lane_above(xcl);
         if (p == K - 1) cl_next = n1u;
         const bool summing = !done && !dup;
         cl_next = max(cl_next, cl);
@@ -888,7 +903,7 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
             const u64 moving = __ballot(!done && !same);
             if (it > 0 && (moving & maskb) == 0) done = true;
         }
-        int Bnext = __shfl(done ? Bold : Bcur, lane + 1, 64);
+        int Bnext = lane_above(done ? Bold : Bcur);
         if (p == K - 1) Bnext = m;
         Bnext = max(Bnext, Bcur);
         if (!done) {
@@ -927,7 +942,7 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
             lowD = xd;
             lowN = xn;
         }
-        double nD = shfl_d(lowD, lane + 1), nN = shfl_d(lowN, lane + 1);
+        double nD = lane_above(lowD), nN = lane_above(lowN);
         if (p == K - 1 || cl_next <= cl) { nD = 0.0; nN = 0.0; }
         D += nD;
         N += nN;
@@ -939,25 +954,47 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
         }
         int a = la0 >> 2, bq = rb0 >> 2;
         if (la0 >= rb0) { a = 0; bq = 0; }
+        // one level of the tree: up to 3 entries at either end of [a, bq), then the range one level up
+        auto level_step = [&](int off, int &ra, int &rb_, double &sd, double &sn) {
+            const int la = min(rb_, (ra + 3) & ~3), rb = max(la, rb_ & ~3);
 #pragma unroll
-        for (int lv = 1; lv < MAX_LEVELS; ++lv) {
-            if (lv < LM.nlev) {
-                if (__ballot(a < bq) != 0) {
-                    const int la = min(bq, (a + 3) & ~3), rb = max(la, bq & ~3);
+            for (int k2 = 0; k2 < 3; ++k2) {
+                // a slot that is not needed reads the zero entry instead
+                const int o1 = (ra + k2 < la) ? off + (ra + k2) * 16 : LM.zero_off;
+                const int o2 = (rb + k2 < rb_) ? off + (rb + k2) * 16 : LM.zero_off;
+                const double2 x1 = *(const double2 *)(blk + o1);
+                const double2 x2 = *(const double2 *)(blk + o2);
+                sd += x1.x;
+                sn += x1.y;
+                sd += x2.x;
+                sn += x2.y;
+            }
+            if (la < rb) { ra = la >> 2; rb_ = rb >> 2; } else { ra = 0; rb_ = 0; }
+        };
 #pragma unroll
-                    for (int k = 0; k < 3; ++k) {
-                        // a slot that is not needed reads the zero entry instead
-                        const int o1 = (a + k < la) ? LM.off[lv] + (a + k) * 16 : LM.zero_off;
-                        const int o2 = (rb + k < bq) ? LM.off[lv] + (rb + k) * 16 : LM.zero_off;
-                        const double2 x1 = *(const double2 *)(blk + o1);
-                        const double2 x2 = *(const double2 *)(blk + o2);
-                        D += x1.x;
-                        N += x1.y;
-                        D += x2.x;
-                        N += x2.y;
-                    }
-                    if (la < rb) { a = la >> 2; bq = rb >> 2; } else { a = 0; bq = 0; }
+        for (int lv = 1; lv < 3; ++lv) {
+            if (lv < LM.nlev && __ballot(a < bq) != 0) level_step(LM.off[lv], a, bq, D, N);
+        }
+        if (LM.nlev > 3) {
+            // levels from 1024 keys up change rarely from one iteration to the next: their part of
+            // the sum is kept per lane together with the range it belongs to
+            const bool need = a < bq;
+            const bool miss = need && (a != ca3 || bq != cb3);
+            if (__ballot(miss) != 0) {
+                double tD = 0.0, tN = 0.0;
+                int a3 = a, b3 = bq;
+#pragma unroll
+                for (int lv = 3; lv < MAX_LEVELS; ++lv) {
+                    if (lv < LM.nlev && __ballot(a3 < b3) != 0) level_step(LM.off[lv], a3, b3, tD, tN);
                 }
+                ca3 = a;
+                cb3 = bq;
+                cD3 = tD;
+                cN3 = tN;
+            }
+            if (need) {
+                D += cD3;
+                N += cN3;
             }
         }
         if (summing && !done && D > 0.0) v = quick_div(N, D);
