@@ -132,6 +132,9 @@ __device__ __forceinline__ void ce(double &a, double &b) {
 // window bit of the flip stage) the registers with that bit set are taken from the thread whose
 // low WB index bits are complemented, so that both keys of every flip pair sit in one thread.
 // Stages run on window bits HI .. LO after the flip stage.
+typedef __attribute__((address_space(3))) volatile double lds_vdouble;
+typedef __attribute__((address_space(3))) char lds_char;
+
 template <int WB, int FLIP, int HI, int LO>
 __device__ __forceinline__ void sort_pass(double *lds, uint32_t t, int m) {
     static_assert(WB == 0 || WB >= 4, "window below bit 4 must start at bit 0");
@@ -140,15 +143,16 @@ __device__ __forceinline__ void sort_pass(double *lds, uint32_t t, int m) {
     constexpr int FB = FLIP >= 0 ? FLIP : 0;
     const uint32_t base = ((t >> WB) << (WB + 4)) | (t & lowmask);
     if ((int)(base & ~lowmask) >= m) return;   // all 16 keys are padding
-    char *const pa = (char *)lds + swz(base) * 8u;
-    char *const pf = (char *)lds + swz(base ^ lowmask) * 8u;
+    lds_char *const pa = (lds_char *)lds + swz(base) * 8u;
+    lds_char *const pf = (lds_char *)lds + swz(base ^ lowmask) * 8u;
     double v[EPT];
 #pragma unroll
     for (int r = 0; r < EPT; ++r) {
         const bool flipped = (FLIP >= 0) && (r & (1 << FB));
-        v[r] = *(const double *)((flipped ? pf : pa) + r * STRIDE);
+        // (volatile keeps 16 single 8-byte accesses: the paired ds_read2/ds_write2 forms the
+        // compiler would merge them into move fewer bytes per clock on this LDS)
+        v[r] = *(lds_vdouble *)((flipped ? pf : pa) + r * STRIDE);
     }
-    __builtin_amdgcn_sched_barrier(0);   // all 16 reads are issued before the first compare-exchange
     if (FLIP >= 0) {
 #pragma unroll
         for (int r = 0; r < EPT; ++r)
@@ -163,7 +167,7 @@ __device__ __forceinline__ void sort_pass(double *lds, uint32_t t, int m) {
 #pragma unroll
     for (int r = 0; r < EPT; ++r) {
         const bool flipped = (FLIP >= 0) && (r & (1 << FB));
-        *(double *)((flipped ? pf : pa) + r * STRIDE) = v[r];
+        *(lds_vdouble *)((flipped ? pf : pa) + r * STRIDE) = v[r];
     }
 }
 
@@ -171,7 +175,7 @@ __device__ __forceinline__ void sort_pass(double *lds, uint32_t t, int m) {
 __device__ __forceinline__ void sort_first_pass(double *lds, uint32_t t, int m) {
     const uint32_t base = t << 4;
     if ((int)base >= m) return;
-    double *const pa = lds + swz(base);
+    lds_vdouble *const pa = (lds_vdouble *)lds + swz(base);
     double v[EPT];
 #pragma unroll
     for (int r = 0; r < EPT; ++r) v[r] = pa[r];
