@@ -226,7 +226,17 @@ def bench_scale_loop(ctx, torch, np, skim_synth, iters=3):
         t_loss += e[2].elapsed_time(e[3])
         losses.append(l["loss"].item())
     flops = 2.0 * n * m * m
+    # layer-wise (L-full) error table of the same layer: clustering + one contraction per bit width
+    lf = ctx.error_table_lfull(W, S, H)
+    torch.cuda.synchronize()
+    e[0].record(ctx.stream)
+    ctx.error_table_lfull(W, S, H, out=lf)
+    e[1].record(ctx.stream)
+    torch.cuda.synchronize()
+    t_lfull = e[0].elapsed_time(e[1])
     return {"workload": "4096x4096, H 4096^2, 3 bits", "scale_step_ms": round(t_step / iters, 4),
+            "lfull_error_table_ms": round(t_lfull, 4),
+            "lfull_error_table_tflops": round(4 * flops / (t_lfull * 1e-3) / 1e12, 2),
             "recluster_ms": round(t_cluster / iters, 4), "layer_loss_ms": round(t_loss / iters, 4),
             "layer_loss_tflops": round(flops / (t_loss / iters * 1e-3) / 1e12, 2),
             "mfma_f32_peak_tflops": MFMA_F32_PEAK_TFLOPS,

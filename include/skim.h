@@ -178,6 +178,24 @@ skim_status skim_layer_loss(skim_ctx *ctx, const float *W, const float *S, const
                             const float *H, int64_t n, int64_t m, int64_t ld,
                             const uint8_t *labels, double *loss, double *row_loss);
 
+/* Error pre-recording with the layer-wise error (Alg. 3 lines 2-10 read with
+ * "Err(.) refers to the L-full form", Sec. 4.2 and Sec. 3.4): the rows are
+ * clustered for every b in [bmin, bmax] exactly as in skim_error_table, and
+ *   E_full[i][b-bmin] = dW_i H dW_i^T,  dW_i = w_i - alpha * c_{i, L_i}
+ * with L the labels of that clustering and c the weighted means of its clusters
+ * (one fp32-MFMA contraction dW * H per bit width, float64 reductions).
+ * E_full: dev float64 n x nb.  E_sdiag: dev float64 n x nb, the S-diag errors
+ * of the same clusterings (what skim_error_table returns), may be NULL.
+ * centroids_all, upper_all: as in skim_error_table, required.  labels_work:
+ * dev uint8 n x m scratch (holds the labels of the last bit width on return).
+ * H: dev m x m float32, 16-byte aligned; m must be a multiple of 16 (the limits
+ * of skim_layer_loss).  The workspace must hold skim_workspace_bytes(n, m). */
+skim_status skim_error_table_lfull(skim_ctx *ctx, const float *W, const float *S, const float *alpha,
+                                   const float *H, int64_t n, int64_t m, int64_t ld,
+                                   int bmin, int bmax, int iters,
+                                   double *E_full, double *E_sdiag, double *centroids_all,
+                                   float *upper_all, uint8_t *labels_work);
+
 /* One optimiser step on alpha with the labels fixed (inner loop of Alg. 2):
  * the loss above, its gradient with respect to alpha through the centroids,
  * and an Adam update of alpha / adam_m / adam_v (dev float32[m], in place).

@@ -211,6 +211,23 @@ def layer_loss(W, H, labels, c, alpha=None, want_P=False):
     return dict(loss=loss.value, row_loss=row_loss, P=P)
 
 
+def error_table_lfull(W, S, H, alpha=None, bmin=1, bmax=4, iters=30, count_near=False):
+    """Error pre-recording with the layer-wise error (Alg. 3 lines 2-10, Err(.) in its L-full form):
+    for each b the rows are clustered (K = 2^b), and E[i][b-bmin] = dW_i H dW_i^T with
+    dW_i = w_i - alpha * replace(c, L)_i for the labels L and centroids c the clustering returned."""
+    W = _f32(W)
+    n, m = W.shape
+    nb = bmax - bmin + 1
+    E = np.empty((n, nb), np.float64)
+    near_rows = np.zeros(n, np.int64)
+    for b in range(bmin, bmax + 1):
+        cr = cluster_rows(W, S, np.full(n, b, np.uint8), alpha=alpha, T=iters, count_near=count_near)
+        E[:, b - bmin] = layer_loss(W, H, cr["labels"], cr["centroids"], alpha)["row_loss"]
+        if count_near:
+            near_rows += cr["near_rows"]
+    return dict(E=E, near_rows=near_rows)
+
+
 def scale_grad(W, S, H, labels, alpha=None):
     W, S, alpha, H = _f32(W), _f32(S), _f32(alpha), _f32(H)
     n, m = W.shape

@@ -22,7 +22,7 @@ MAX_M = 32768
 
 EXPORTS = ["skim_create", "skim_destroy", "skim_last_error", "skim_workspace_bytes", "skim_set_workspace",
            "skim_profile_enable", "skim_profile_last",
-           "skim_error_table", "skim_cluster_rows", "skim_select_allocated", "skim_greedy_allocate",
+           "skim_error_table", "skim_error_table_lfull", "skim_cluster_rows", "skim_select_allocated", "skim_greedy_allocate",
            "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_layer_loss", "skim_scale_step"]
 
 
@@ -63,6 +63,7 @@ def load_library():
         lib.skim_profile_enable.argtypes = [vp, i32]
         lib.skim_profile_last.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         lib.skim_error_table.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, vp, vp]
+        lib.skim_error_table_lfull.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, vp, vp, vp, vp]
         lib.skim_cluster_rows.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i32, vp, vp, vp, vp]
         lib.skim_select_allocated.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         lib.skim_greedy_allocate.argtypes = [vp, vp, i64, i32, i32, dbl, vp, vp, vp]
@@ -183,6 +184,25 @@ class Context:
         self._check(self.lib.skim_error_table(self.h, _dp(W), _dp(S), _dp(alpha), n, m, W.stride(0), bmin, bmax,
                                               iters, _dp(out["E"]), _dp(out.get("centroids_all")),
                                               _dp(out.get("upper_all"))))
+        return out
+
+    def error_table_lfull(self, W, S, H, alpha=None, bmin=1, bmax=4, iters=30, out=None):
+        """Error table with the layer-wise (L-full) error of every clustering; H: float32 device m x m."""
+        t = self.torch
+        n, m = W.shape
+        assert W.dtype == t.float32 and S.dtype == t.float32 and W.stride(1) == 1 and S.stride() == W.stride()
+        assert H.dtype == t.float32 and H.shape == (m, m) and H.is_contiguous()
+        nb = bmax - bmin + 1
+        stride = (2 << bmax) - (1 << bmin)
+        if out is None:
+            out = dict(E_full=self.empty((n, nb), t.float64), E=self.empty((n, nb), t.float64),
+                       centroids_all=self.empty((n, stride), t.float64), upper_all=self.empty((n, stride), t.float32),
+                       labels_work=self.empty((n, m), t.uint8))
+        self.ensure_workspace(n, m)
+        self._check(self.lib.skim_error_table_lfull(self.h, _dp(W), _dp(S), _dp(alpha), _dp(H), n, m, W.stride(0),
+                                                    bmin, bmax, iters, _dp(out["E_full"]), _dp(out.get("E")),
+                                                    _dp(out["centroids_all"]), _dp(out["upper_all"]),
+                                                    _dp(out["labels_work"])))
         return out
 
     def cluster_rows(self, W, S, bits, alpha=None, iters=30, want_labels=True, out=None):

@@ -59,3 +59,8 @@ struct skim_ws_cursor {
 static inline int skim_block_offset(int bmin, int b) {  // start of block b inside a row of the *_all arrays
     return (1 << b) - (1 << bmin);
 }
+
+// skim_layer_loss with the per-row losses written at a stride (row i at row_loss[i * row_stride]).
+skim_status skim_layer_loss_strided(skim_ctx *ctx, const float *W, const float *S, const float *alpha, const float *H,
+                                    int64_t n, int64_t m, int64_t ld, const uint8_t *labels, double *loss,
+                                    double *row_loss, int64_t row_stride);

@@ -197,13 +197,13 @@ __global__ void __launch_bounds__(GEMM_THREADS) dwh_gemm_kernel(const float *__r
 
 // row_loss[i] = sum over column tiles; loss = sum_i row_loss[i] (single workgroup, fixed order).
 __global__ void __launch_bounds__(1024) loss_finish_kernel(const double *partial, int ntile, long long n, double *loss,
-                                                           double *row_loss) {
+                                                           double *row_loss, long long row_stride) {
     __shared__ double sh[16];
     double acc = 0.0;
     for (long long i = threadIdx.x; i < n; i += 1024) {
         double r = 0.0;
         for (int t = 0; t < ntile; ++t) r += partial[(long long)t * n + i];
-        if (row_loss) row_loss[i] = r;
+        if (row_loss) row_loss[i * row_stride] = r;
         acc += r;
     }
     for (int d = 32; d >= 1; d >>= 1) acc += __shfl_down(acc, d, 64);
@@ -321,6 +321,12 @@ skim_status check_shape(skim_ctx *ctx, int64_t n, int64_t m, int64_t ld) {
 extern "C" skim_status skim_layer_loss(skim_ctx *ctx, const float *W, const float *S, const float *alpha,
                                        const float *H, int64_t n, int64_t m, int64_t ld, const uint8_t *labels,
                                        double *loss, double *row_loss) {
+    return skim_layer_loss_strided(ctx, W, S, alpha, H, n, m, ld, labels, loss, row_loss, 1);
+}
+
+skim_status skim_layer_loss_strided(skim_ctx *ctx, const float *W, const float *S, const float *alpha, const float *H,
+                                    int64_t n, int64_t m, int64_t ld, const uint8_t *labels, double *loss,
+                                    double *row_loss, int64_t row_stride) {
     skim_status st = skim_enter(ctx);
     if (st != SKIM_OK) return st;
     if (!W || !S || !H || !labels || !loss) SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_layer_loss: NULL argument");
@@ -333,7 +339,7 @@ extern "C" skim_status skim_layer_loss(skim_ctx *ctx, const float *W, const floa
     hipLaunchKernelGGL(dwh_gemm_kernel<false>, dim3(w.ntile, (unsigned)((n + BM - 1) / BM)), dim3(GEMM_THREADS), 0,
                        ctx->stream, w.dW, H, (int)n, (int)m, (float *)nullptr, w.partial);
     hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(1024), 0, ctx->stream, w.partial, w.ntile, (long long)n, loss,
-                       row_loss);
+                       row_loss, (long long)row_stride);
     SKIM_HIP(ctx, hipGetLastError());
     return SKIM_OK;
 }
@@ -356,7 +362,7 @@ extern "C" skim_status skim_scale_step(skim_ctx *ctx, const float *W, const floa
     hipLaunchKernelGGL(dwh_gemm_kernel<true>, dim3(w.ntile, (unsigned)((n + BM - 1) / BM)), dim3(GEMM_THREADS), 0,
                        ctx->stream, w.dW, H, (int)n, (int)m, w.P, w.partial);
     hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(1024), 0, ctx->stream, w.partial, w.ntile, (long long)n,
-                       loss_before, (double *)nullptr);
+                       loss_before, (double *)nullptr, 1ll);
     hipLaunchKernelGGL(grad_rows_kernel, dim3(w.nstrip), dim3(PREP_THREADS), 0, ctx->stream, W, S, (const float *)alpha,
                        (long long)n, (long long)m, (long long)ld, labels, w.P, w.cent, w.Den, w.gpart);
     const double lr = (double)opts->lr0 * pow((double)opts->decay, (double)((t - 1) / opts->decay_every));

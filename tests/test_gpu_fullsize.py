@@ -187,3 +187,32 @@ def test_config3_scale_loop_per_call_parity(ctx, gpu_lib):
         assert ll["loss"].item() == pytest.approx(rl["loss"], rel=RTOL)
         losses.append(ll["loss"].item())
     print("\nfree-running loss after each iteration:", losses)
+
+
+def test_config3_lfull_error_table_slice(ctx, gpu_lib):
+    """Layer-wise error table on a 512-row slice of the config-3 layer (H 4096 x 4096 from 4096 synthetic
+    activations): every entry of clean rows against the oracle's naive float64 dW H dW^T."""
+    W, S = skim_synth.make_ws(3, 0)
+    W, S = np.ascontiguousarray(W[:512]), np.ascontiguousarray(S[:512])
+    n, m = W.shape
+    acc = torch.zeros((m, m), dtype=torch.float32, device="cuda")
+    N = 4096
+    for x in skim_synth.make_x(3, N, m, chunk=2048):
+        xd = dev(x)
+        acc += xd.T @ xd
+    Hd = (acc / N)
+    Hd = ((Hd + Hd.T) / 2).contiguous()
+    H = Hd.cpu().numpy()
+    ref = oracle.error_table_lfull(W, S, H, count_near=True)
+    out = ctx.error_table_lfull(dev(W), dev(S), Hd)
+    torch.cuda.synchronize()
+    clean = ref["near_rows"] == 0
+    assert clean.sum() >= n - n // 8
+    got = out["E_full"].cpu().numpy()
+    rel = np.abs(got[clean] - ref["E"][clean]) / ref["E"][clean]
+    assert rel.max() <= RTOL, f"max rel diff {rel.max():.3e}"
+    # allocation on the layer-wise table: the library's allocator and the oracle's agree on the same table
+    bits, spent, budget = gpu_lib.greedy_allocate(got, 3.0)
+    g = oracle.greedy(got, 3.0)
+    assert np.array_equal(bits, g["bits"]) and spent == g["spent"] == budget
+    print(f"\n[L-full table 512x4096] rows excused {int((~clean).sum())}, max rel err {rel.max():.2e}")

@@ -109,3 +109,25 @@ def test_loss_argument_errors(ctx, gpu_lib):
     W, S, labels, H, al = make_case(1, 4, 24, 2)     # m not a multiple of 16
     with pytest.raises(gpu_lib.SkimError):
         ctx.layer_loss(dev(W), dev(S), dev(H), dev(labels))
+
+
+@pytest.mark.parametrize("n,m,with_alpha", [(40, 144, False), (130, 512, True), (64, 1024, True)])
+def test_lfull_error_table_matches_oracle(ctx, n, m, with_alpha):
+    """Error pre-recording with the layer-wise error: every (row, bit width) entry against the oracle
+    (clustering + naive float64 dW H dW^T); rows in which the oracle met a near-tie are excused."""
+    W, S = skim_synth.make_ws_small(21, n, m)
+    H = skim_synth.make_h_host(3, 4 * m, m)
+    al = skim_synth.make_alpha(3, m) if with_alpha else None
+    ref = oracle.error_table_lfull(W, S, H, alpha=al, count_near=True)
+    sd = oracle.error_table(W, S, alpha=al)
+    out = ctx.error_table_lfull(dev(W), dev(S), dev(H), alpha=None if al is None else dev(al))
+    torch.cuda.synchronize()
+    clean = ref["near_rows"] == 0
+    assert clean.sum() >= n - 4
+    got = out["E_full"].cpu().numpy()
+    np.testing.assert_allclose(got[clean], ref["E"][clean], rtol=RTOL)
+    np.testing.assert_allclose(out["E"].cpu().numpy()[clean], sd["E"][clean], rtol=RTOL)
+    # the S-diag table of the same call equals the plain entry point's, bit for bit
+    plain = ctx.error_table(dev(W), dev(S), alpha=None if al is None else dev(al))
+    torch.cuda.synchronize()
+    assert torch.equal(plain["E"], out["E"]) and torch.equal(plain["upper_all"], out["upper_all"])

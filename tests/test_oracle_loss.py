@@ -149,3 +149,31 @@ def test_adam_first_step_moves_by_lr_against_gradient_sign():
     np.testing.assert_allclose(a, 1.0 - 0.01 * np.sign(g), rtol=1e-5)
     np.testing.assert_allclose(m1, 0.1 * g, rtol=1e-6)
     np.testing.assert_allclose(m2, 0.001 * g * g, rtol=1e-6)
+
+
+def test_lfull_error_table_reduces_to_sdiag_when_hessian_is_diagonal():
+    """Sec. 3.4: with H = diag(h) the layer-wise error of channel i is sum_j h_j dW_ij^2; if every
+    channel's sensitivity row equals h this is the S-diag objective the K-means minimises, so the two
+    tables coincide (a dropped row, a transposed H or labels of the wrong bit width would break it)."""
+    n, m = 12, 96
+    W, _ = skim_synth.make_ws_small(11, n, m)
+    rng = np.random.default_rng(5)
+    h = (rng.standard_normal(m) ** 2 + 0.01).astype(np.float32)
+    S = np.tile(h, (n, 1))
+    full = oracle.error_table_lfull(W, S, np.diag(h).astype(np.float32))
+    sdiag = oracle.error_table(W, S)
+    np.testing.assert_allclose(full["E"], sdiag["E"], rtol=1e-12)
+
+
+def test_lfull_error_table_by_definition_on_a_tiny_case():
+    """Brute force: E[i][b] = sum_jl dW_ij H_jl dW_il with dW from the labels and centroids of the b-bit clustering."""
+    n, m = 5, 32
+    W, S = skim_synth.make_ws_small(12, n, m)
+    H = skim_synth.make_h_host(3, 64, m).astype(np.float64)
+    al = skim_synth.make_alpha(4, m)
+    full = oracle.error_table_lfull(W, S, H.astype(np.float32), alpha=al)
+    for b in (1, 2, 3, 4):
+        cr = oracle.cluster_rows(W, S, np.full(n, b, np.uint8), alpha=al)
+        d = W.astype(np.float64) - al.astype(np.float64)[None, :] * np.take_along_axis(cr["centroids"], cr["labels"].astype(np.int64), 1)
+        ref = np.einsum("ij,jl,il->i", d, H.astype(np.float32).astype(np.float64), d)
+        np.testing.assert_allclose(full["E"][:, b - 1], ref, rtol=1e-12)
