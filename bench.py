@@ -234,7 +234,18 @@ def bench_scale_loop(ctx, torch, np, skim_synth, iters=3):
     e[1].record(ctx.stream)
     torch.cuda.synchronize()
     t_lfull = e[0].elapsed_time(e[1])
+    # Alg. 2 as one call: clustering + 120 optimiser steps + final loss
+    a2 = torch.ones(m, device="cuda")
+    m2, v2 = torch.zeros(m, device="cuda"), torch.zeros(m, device="cuda")
+    e[2].record(ctx.stream)
+    tr = ctx.train_scale(W, S, H, bits, a2, m2, v2, steps=120)
+    e[3].record(ctx.stream)
+    torch.cuda.synchronize()
+    t_train = e[2].elapsed_time(e[3])
+    trace = tr["loss_trace"].cpu().numpy()
     return {"workload": "4096x4096, H 4096^2, 3 bits", "scale_step_ms": round(t_step / iters, 4),
+            "train_scale_120_steps_ms": round(t_train, 3),
+            "train_scale_loss_first_last": [float(trace[0]), float(trace[-1])],
             "lfull_error_table_ms": round(t_lfull, 4),
             "lfull_error_table_tflops": round(4 * flops / (t_lfull * 1e-3) / 1e12, 2),
             "recluster_ms": round(t_cluster / iters, 4), "layer_loss_ms": round(t_loss / iters, 4),

@@ -207,6 +207,22 @@ skim_status skim_scale_step(skim_ctx *ctx, const float *W, const float *S, const
                             float *adam_m, float *adam_v, int64_t t, const skim_adam_opts *opts,
                             double *loss_before, float *grad_out);
 
+/* Scaling-vector training, Alg. 2 as a whole: `outer` rounds (the algorithm's I) of
+ *   L = labels of Kmeans(W * alpha^-1) at the bit widths bits[i]   (skim_cluster_rows)
+ *   `steps` optimiser steps on alpha with L fixed                    (skim_scale_step)
+ * and on return c = calc_centroids(W * alpha^-1, L) at the final alpha.  The paper
+ * trains until "converged" with at most 120 steps (Sec. 5.1); this call runs exactly
+ * `steps` steps per round.  Step numbers (learning-rate decay, bias correction) run
+ * t0, t0+1, ... across the rounds; alpha, adam_m, adam_v: dev float32[m], in/out.
+ * labels: dev uint8 n x m (out), centroids: dev float64 n x 16 (out).
+ * loss_trace: dev float64[outer*steps + 1]: the loss before every step, then the loss
+ * at the returned alpha.  Limits of skim_layer_loss apply (m multiple of 16, H aligned). */
+skim_status skim_train_scale(skim_ctx *ctx, const float *W, const float *S, const float *H,
+                             int64_t n, int64_t m, int64_t ld, const uint8_t *bits,
+                             int kmeans_iters, int outer, int steps, int64_t t0,
+                             const skim_adam_opts *opts, float *alpha, float *adam_m, float *adam_v,
+                             uint8_t *labels, double *centroids, double *loss_trace);
+
 #ifdef __cplusplus
 }
 #endif

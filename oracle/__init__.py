@@ -257,3 +257,28 @@ def adam_step(alpha, m1, m2, grad, t, **opts):
                                   C.c_double(o["beta2"]), C.c_double(o["eps"]),
                                   C.c_double(o["decay"]), C.c_int64(o["decay_every"])), "adam_step")
     return alpha, m1, m2
+
+
+def train_scale(W, S, H, bits, alpha, steps=120, outer=1, t0=1, T=30, **opts):
+    """Alg. 2 as a whole: `outer` rounds of {labels = K-means of W * alpha^-1 at bits; `steps` Adam steps on
+    alpha with the labels fixed}; then c = calc_centroids(W * alpha^-1, L) at the final alpha.  alpha and the
+    Adam moments are float32 vectors (as in adam_step); gradients and losses are float64."""
+    W, S, H = _f32(W), _f32(S), _f32(H)
+    n, m = W.shape
+    alpha = np.ascontiguousarray(alpha, dtype=np.float32).copy()
+    m1 = np.zeros(m, np.float32)
+    m2 = np.zeros(m, np.float32)
+    trace = []
+    t = t0
+    labels = None
+    for _ in range(outer):
+        labels = cluster_rows(W, S, bits, alpha=alpha, T=T)["labels"]
+        for _k in range(steps):
+            g = scale_grad(W, S, H, labels, alpha)
+            trace.append(g["loss"])
+            alpha, m1, m2 = adam_step(alpha, m1, m2, g["grad"], t, **opts)
+            t += 1
+    c, _ = centroids_from_labels(W, S, labels, alpha)
+    trace.append(layer_loss(W, H, labels, c, alpha)["loss"])
+    return dict(alpha=alpha, labels=labels, centroids=c, loss_trace=np.array(trace))
+

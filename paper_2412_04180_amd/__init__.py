@@ -23,7 +23,7 @@ MAX_M = 32768
 EXPORTS = ["skim_create", "skim_destroy", "skim_last_error", "skim_workspace_bytes", "skim_set_workspace",
            "skim_profile_enable", "skim_profile_last",
            "skim_error_table", "skim_error_table_lfull", "skim_cluster_rows", "skim_select_allocated", "skim_greedy_allocate",
-           "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_layer_loss", "skim_scale_step"]
+           "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_layer_loss", "skim_scale_step", "skim_train_scale"]
 
 
 class SkimError(RuntimeError):
@@ -74,6 +74,8 @@ def load_library():
         lib.skim_pack.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.skim_layer_loss.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp]
         lib.skim_scale_step.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, i64, C.POINTER(AdamOpts), vp, vp]
+        lib.skim_train_scale.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i32, i32, i32, i64, C.POINTER(AdamOpts),
+                                         vp, vp, vp, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -262,6 +264,20 @@ class Context:
         self._check(self.lib.skim_layer_loss(self.h, _dp(W), _dp(S), _dp(alpha), _dp(H), n, m, W.stride(0),
                                              _dp(labels), _dp(loss), _dp(row_loss)))
         return dict(loss=loss, row_loss=row_loss)
+
+    def train_scale(self, W, S, H, bits, alpha, adam_m, adam_v, steps=120, outer=1, t0=1, kmeans_iters=30, opts=None):
+        """Alg. 2 as one call; alpha, adam_m, adam_v are updated in place.  Returns labels, centroids, loss_trace."""
+        t = self.torch
+        n, m = W.shape
+        self.ensure_workspace(n, m)
+        o = opts if opts is not None else AdamOpts(0.01, 0.9, 0.999, 1e-8, 0.5, 40)
+        out = dict(labels=self.empty((n, m), t.uint8), centroids=self.empty((n, 16), t.float64),
+                   loss_trace=self.empty((outer * steps + 1,), t.float64))
+        self._check(self.lib.skim_train_scale(self.h, _dp(W), _dp(S), _dp(H), n, m, W.stride(0), _dp(bits),
+                                              int(kmeans_iters), int(outer), int(steps), int(t0), C.byref(o),
+                                              _dp(alpha), _dp(adam_m), _dp(adam_v), _dp(out["labels"]),
+                                              _dp(out["centroids"]), _dp(out["loss_trace"])))
+        return out
 
     def scale_step(self, W, S, H, labels, alpha, adam_m, adam_v, t_step, opts=None, want_grad=True):
         t = self.torch

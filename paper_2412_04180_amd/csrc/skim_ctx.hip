@@ -103,6 +103,7 @@ extern "C" size_t skim_workspace_bytes(int64_t n, int64_t m) {
     if (M > 16384) b += N * 8 * M;       // rows sorted in two halves: the unmerged keys
     b += N * sizeof(int) + 1024;         // pack: row positions and group table
     b += N * 4 * sizeof(double) + 1024;  // L-full error table: S-diag errors and the loss scalar at the tail
+    b += N * (16 * sizeof(float) + sizeof(double)) + 1024;   // scale training: thresholds and errors of the re-clustering
     return b + 16 * 256;                 // alignment slack (every piece is 256-byte aligned)
 }
 

@@ -373,3 +373,47 @@ extern "C" skim_status skim_scale_step(skim_ctx *ctx, const float *W, const floa
     SKIM_HIP(ctx, hipGetLastError());
     return SKIM_OK;
 }
+
+// Scaling-vector training (Alg. 2): `outer` rounds of { labels = K-means of W * alpha^-1 at the given bit
+// widths; `steps` optimiser steps on alpha with the labels fixed }, then the centroids and the loss at the
+// final alpha.  Composition of skim_cluster_rows, skim_scale_step and the layer-loss kernels.
+extern "C" skim_status skim_train_scale(skim_ctx *ctx, const float *W, const float *S, const float *H, int64_t n,
+                                        int64_t m, int64_t ld, const uint8_t *bits, int kmeans_iters, int outer,
+                                        int steps, int64_t t0, const skim_adam_opts *opts, float *alpha,
+                                        float *adam_m, float *adam_v, uint8_t *labels, double *centroids,
+                                        double *loss_trace) {
+    skim_status st = skim_enter(ctx);
+    if (st != SKIM_OK) return st;
+    if (!W || !S || !H || !bits || !opts || !alpha || !adam_m || !adam_v || !labels || !centroids || !loss_trace)
+        SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_train_scale: NULL argument");
+    if (outer < 1 || steps < 0 || t0 < 1 || kmeans_iters < 1)
+        SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_train_scale: need outer >= 1, steps >= 0, t0 >= 1, kmeans_iters >= 1");
+    if (ctx->ws_bytes < skim_workspace_bytes(n, m))
+        SKIM_FAIL(ctx, SKIM_ERR_WORKSPACE, "workspace missing or smaller than skim_workspace_bytes(n, m)");
+    // per-row clustering outputs that the caller does not ask for live at the tail of the workspace
+    // (the calls below carve from its start)
+    const size_t tail_bytes = (((size_t)n * 16 * sizeof(float) + 255) & ~(size_t)255) +
+                              (((size_t)n * sizeof(double) + 255) & ~(size_t)255);
+    char *tail = (char *)ctx->ws + ((ctx->ws_bytes - tail_bytes) & ~(size_t)255);
+    float *upper = (float *)tail;
+    double *err = (double *)(tail + (((size_t)n * 16 * sizeof(float) + 255) & ~(size_t)255));
+    int64_t t = t0;
+    int64_t slot = 0;
+    for (int round = 0; round < outer; ++round) {
+        if ((st = skim_cluster_rows(ctx, W, S, alpha, n, m, ld, bits, kmeans_iters, labels, centroids, upper, err)) !=
+            SKIM_OK)
+            return st;
+        for (int k = 0; k < steps; ++k, ++t, ++slot) {
+            if ((st = skim_scale_step(ctx, W, S, H, n, m, ld, labels, alpha, adam_m, adam_v, t, opts,
+                                      loss_trace + slot, nullptr)) != SKIM_OK)
+                return st;
+        }
+    }
+    // centroids of the fixed labels at the final alpha, and the loss there
+    if ((st = check_shape(ctx, n, m, ld)) != SKIM_OK) return st;
+    LossWs w;
+    if ((st = carve(ctx, n, m, false, w)) != SKIM_OK) return st;
+    if ((st = skim_layer_loss(ctx, W, S, alpha, H, n, m, ld, labels, loss_trace + slot, nullptr)) != SKIM_OK) return st;
+    SKIM_HIP(ctx, hipMemcpyAsync(centroids, w.cent, (size_t)n * 16 * sizeof(double), hipMemcpyDeviceToDevice, ctx->stream));
+    return SKIM_OK;
+}

@@ -131,3 +131,51 @@ def test_lfull_error_table_matches_oracle(ctx, n, m, with_alpha):
     plain = ctx.error_table(dev(W), dev(S), alpha=None if al is None else dev(al))
     torch.cuda.synchronize()
     assert torch.equal(plain["E"], out["E"]) and torch.equal(plain["upper_all"], out["upper_all"])
+
+
+def test_train_scale_is_the_composition_of_its_steps_and_tracks_the_oracle(ctx, gpu_lib):
+    """skim_train_scale against (a) the same sequence of library calls made one by one: bit-exact; (b) the
+    oracle's free-running Alg. 2 on a small, well-conditioned layer: loss trace and alpha within 1e-4 over
+    30 steps (per-step parity at 1e-5 is covered by test_scale_step_matches_oracle; a free-running optimiser
+    amplifies rounding differences of the fp32 contraction, hence the looser bound here)."""
+    n, m = 48, 144
+    W, S = skim_synth.make_ws_small(41, n, m)
+    S = S + np.float32(0.05)
+    H = skim_synth.make_h_host(3, 4 * m, m)
+    bits_h = np.full(n, 3, np.uint8)
+    Wd, Sd, Hd, bd = dev(W), dev(S), dev(H), dev(bits_h)
+    steps = 30
+    alpha = torch.ones(m, device="cuda")
+    am, av = torch.zeros(m, device="cuda"), torch.zeros(m, device="cuda")
+    out = ctx.train_scale(Wd, Sd, Hd, bd, alpha, am, av, steps=steps, outer=2)
+    torch.cuda.synchronize()
+    # (a) manual composition
+    a2 = torch.ones(m, device="cuda")
+    m2, v2 = torch.zeros(m, device="cuda"), torch.zeros(m, device="cuda")
+    trace = []
+    t = 1
+    for _ in range(2):
+        cr = ctx.cluster_rows(Wd, Sd, bd, alpha=a2)
+        for _k in range(steps):
+            o = ctx.scale_step(Wd, Sd, Hd, cr["labels"], a2, m2, v2, t, want_grad=False)
+            trace.append(o["loss_before"].clone())
+            t += 1
+    ll = ctx.layer_loss(Wd, Sd, Hd, cr["labels"], alpha=a2)
+    trace.append(ll["loss"].clone())
+    torch.cuda.synchronize()
+    assert torch.equal(alpha, a2) and torch.equal(am, m2) and torch.equal(av, v2)
+    assert torch.equal(out["labels"], cr["labels"])
+    assert torch.equal(out["loss_trace"], torch.cat([x.reshape(1) for x in trace]))
+    c_ref, _ = oracle.centroids_from_labels(W, S, out["labels"].cpu().numpy(), alpha.cpu().numpy())
+    np.testing.assert_allclose(out["centroids"].cpu().numpy(), c_ref, rtol=RTOL, atol=1e-12)
+    # (b) oracle, free running, one round
+    alpha = torch.ones(m, device="cuda")
+    am, av = torch.zeros(m, device="cuda"), torch.zeros(m, device="cuda")
+    out1 = ctx.train_scale(Wd, Sd, Hd, bd, alpha, am, av, steps=steps)
+    torch.cuda.synchronize()
+    f32 = lambda x: float(np.float32(x))
+    ref = oracle.train_scale(W, S, H, bits_h, np.ones(m, np.float32), steps=steps, lr0=f32(0.01), beta1=f32(0.9),
+                             beta2=f32(0.999), eps=f32(1e-8), decay=f32(0.5), decay_every=40)
+    np.testing.assert_allclose(out1["loss_trace"].cpu().numpy(), ref["loss_trace"], rtol=1e-4)
+    np.testing.assert_allclose(alpha.cpu().numpy(), ref["alpha"], rtol=1e-4)
+    assert ref["loss_trace"][-1] < ref["loss_trace"][0]

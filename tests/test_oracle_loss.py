@@ -177,3 +177,27 @@ def test_lfull_error_table_by_definition_on_a_tiny_case():
         d = W.astype(np.float64) - al.astype(np.float64)[None, :] * np.take_along_axis(cr["centroids"], cr["labels"].astype(np.int64), 1)
         ref = np.einsum("ij,jl,il->i", d, H.astype(np.float32).astype(np.float64), d)
         np.testing.assert_allclose(full["E"][:, b - 1], ref, rtol=1e-12)
+
+
+def test_train_scale_decreases_the_layer_loss_and_returns_consistent_pieces():
+    """Alg. 2 as a whole on a tiny layer: the loss trace is the loss at each alpha visited (checked against
+    layer_loss directly), Adam with these step sizes lowers it, and the returned centroids are the weighted
+    means of the returned labels at the returned alpha."""
+    n, m = 8, 48
+    W, S = skim_synth.make_ws_small(31, n, m)
+    S = S + np.float32(0.05)
+    H = skim_synth.make_h_host(3, 192, m)
+    bits = np.full(n, 2, np.uint8)
+    r = oracle.train_scale(W, S, H, bits, np.ones(m, np.float32), steps=25)
+    assert len(r["loss_trace"]) == 26
+    assert r["loss_trace"][-1] < r["loss_trace"][0]
+    c, _ = oracle.centroids_from_labels(W, S, r["labels"], r["alpha"])
+    np.testing.assert_array_equal(c, r["centroids"])
+    assert r["loss_trace"][-1] == pytest.approx(oracle.layer_loss(W, H, r["labels"], c, r["alpha"])["loss"], rel=1e-13)
+    # first entry: loss of the plain clustering at alpha = 1
+    cr = oracle.cluster_rows(W, S, bits)
+    c0, _ = oracle.centroids_from_labels(W, S, cr["labels"], None)
+    assert r["loss_trace"][0] == pytest.approx(oracle.layer_loss(W, H, cr["labels"], c0, None)["loss"], rel=1e-13)
+    # step numbering: two rounds of 10 steps from t0 = 1 equal the manual composition
+    r2 = oracle.train_scale(W, S, H, bits, np.ones(m, np.float32), steps=3, outer=2)
+    assert len(r2["loss_trace"]) == 7
