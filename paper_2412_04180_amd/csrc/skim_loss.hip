@@ -90,11 +90,13 @@ __global__ void __launch_bounds__(PREP_THREADS) row_prep_kernel(const float *W, 
 }
 
 // P = dW * H on fp32 MFMA (v_mfma_f32_32x32x2_f32), 128 x 128 output tile per
-// workgroup, four wavefronts in a 2 x 2 arrangement of 64 x 64 sub-tiles.
+// workgroup, four wavefronts in a 2 x 2 arrangement of 64 x 64 sub-tiles.  Four workgroups
+// per compute unit (register budget 128 per lane): the 1024 tiles of a 4096 x 4096 layer are
+// then resident at once instead of leaving a quarter of them for a thin second round.
 // Epilogue: optional store of P and, per output row, sum_j P_ij dW_ij over the
 // tile's columns in float64 -> partial[tile_col][row].
 template <bool STORE_P>
-__global__ void __launch_bounds__(GEMM_THREADS) dwh_gemm_kernel(const float *__restrict__ A, const float *__restrict__ H,
+__global__ void __launch_bounds__(GEMM_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) dwh_gemm_kernel(const float *__restrict__ A, const float *__restrict__ H,
                                                                 int n, int m, float *__restrict__ P,
                                                                 double *__restrict__ partial) {
     __shared__ float As[2][BK][A_STRIDE];
