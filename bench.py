@@ -181,6 +181,21 @@ def main():
         "roofline": roofline,
     }
 
+    # consumer of the packed layout: codebook-lookup matrix-vector product over the packed layer
+    xv = torch.randn(m, device="cuda")
+    yv = ctx.dequant_matvec(pk, m, xv)
+    torch.cuda.synchronize()
+    mv0, mv1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    mv0.record(stream)
+    for _ in range(10):
+        ctx.dequant_matvec(pk, m, xv, out=yv)
+    mv1.record(stream)
+    torch.cuda.synchronize()
+    mv_ms = mv0.elapsed_time(mv1) / 10
+    packed_bytes = pk["codes"].numel() * 4 + pk["codebooks"].numel() * 2
+    out["dequant_matvec"] = {"ms": round(mv_ms, 4), "packed_bytes": int(packed_bytes),
+                             "GBps": round(packed_bytes / (mv_ms * 1e-3) / 1e9, 1),
+                             "frac_of_hbm_peak": round(packed_bytes / (mv_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     if not args.no_scale_loop:
         out["scale_loop"] = bench_scale_loop(ctx, torch, np, skim_synth)
     if not args.no_cpu_baseline:

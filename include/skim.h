@@ -164,6 +164,26 @@ skim_status skim_pack(skim_ctx *ctx, const float *W, const float *alpha, int64_t
                       uint32_t *codes, int64_t *group_word_offset, int32_t *row_perm,
                       uint16_t *codebooks_fp16, float *dW);
 
+/* ---- readers of the packed model ------------------------------------------ */
+
+/* Dequantisation of what skim_pack wrote (same layout, dev pointers):
+ *   Wq[i][j] = fl32(alpha_j * f32(codebook_i[code_ij]))   (alpha NULL: f32(codebook))
+ * Wq: dev float32 n x m, stride m, original row order.  Rows whose bit width the
+ * packed model does not hold (bits outside 1..4 at pack time) are not written. */
+skim_status skim_unpack(skim_ctx *ctx, const uint32_t *codes, const int64_t *group_word_offset,
+                        const int32_t *row_perm, const uint16_t *codebooks_fp16, const float *alpha,
+                        int64_t n, int64_t m, float *Wq);
+
+/* Matrix-vector product with the packed model, bit-width group by group, every
+ * weight looked up in its row's binary16 codebook (the inference-side use of
+ * the layout, Sec. 4.2 last paragraph, App. D.2):
+ *   y[i] = sum_j Wq[i][j] * x[j],  Wq as above, products and sum in float64.
+ * n = number of packed rows (group_word_offset and row_perm describe them).
+ * x: dev float32[m].  y: dev float64, indexed by original row. */
+skim_status skim_dequant_matvec(skim_ctx *ctx, const uint32_t *codes, const int64_t *group_word_offset,
+                                const int32_t *row_perm, const uint16_t *codebooks_fp16,
+                                const float *alpha, int64_t n, int64_t m, const float *x, double *y);
+
 /* ---- scaling vector ----------------------------------------------------- */
 
 /* Layer-wise (L-full) loss of Alg. 2 with fixed labels:

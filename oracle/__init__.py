@@ -173,6 +173,43 @@ def pack(W, bits, labels, centroids, alpha=None, want_dW=False):
     return dict(codes=codes, group_word_offset=gwo, row_perm=perm, codebooks=cbs, dW=dW)
 
 
+def unpack(codes, group_word_offset, row_perm, codebooks, m, alpha=None):
+    """Dense matrix of a packed model (layout of Sec. 4.2 / App. D.2 as `pack` writes it): rows by (bits, row),
+    a b-bit row = ceil(m*b/32) little-endian uint32 words, column j at bit j*b; codebooks binary16, 2^b per row.
+    Wq[i][j] = fl32(alpha_j * f32(codebook_i[code_ij])).  Rows the model does not hold stay NaN."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint32)
+    gwo = np.asarray(group_word_offset, dtype=np.int64)
+    perm = np.asarray(row_perm, dtype=np.int64)
+    cbs = np.ascontiguousarray(codebooks, dtype=np.uint16).view(np.float16).astype(np.float32)
+    n = len(perm)
+    a = None if alpha is None else np.ascontiguousarray(alpha, dtype=np.float32)
+    Wq = np.full((n, m), np.nan, np.float32)
+    p = 0
+    cb = 0
+    j = np.arange(m, dtype=np.int64)
+    for b in (1, 2, 3, 4):
+        wpr = (m * b + 31) // 32
+        rows = int((gwo[b + 1] - gwo[b]) // wpr)
+        bit = j * b
+        wi, sh = bit >> 5, (bit & 31).astype(np.uint64)
+        for r in range(rows):
+            w = codes[gwo[b] + r * wpr: gwo[b] + (r + 1) * wpr].astype(np.uint64)
+            w = np.concatenate([w, np.zeros(1, np.uint64)])
+            two = w[wi] | (w[wi + 1] << np.uint64(32))          # the 64 bits starting at the word of bit j*b
+            code = ((two >> sh) & np.uint64((1 << b) - 1)).astype(np.int64)
+            q = cbs[cb + code]
+            Wq[perm[p]] = q if a is None else (a * q).astype(np.float32)
+            p += 1
+            cb += 1 << b
+    return Wq
+
+
+def dequant_matvec(codes, group_word_offset, row_perm, codebooks, m, x, alpha=None):
+    """y = Wq x in float64 with Wq = unpack(...) (float32 weights, float32 x, products and sums float64)."""
+    Wq = unpack(codes, group_word_offset, row_perm, codebooks, m, alpha)
+    return Wq.astype(np.float64) @ np.ascontiguousarray(x, dtype=np.float32).astype(np.float64)
+
+
 def f32_to_f16(x):
     x = np.ascontiguousarray(x, dtype=np.float32).ravel()
     f = lib().oracle_f32_to_f16

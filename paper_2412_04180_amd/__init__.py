@@ -23,7 +23,7 @@ MAX_M = 32768
 EXPORTS = ["skim_create", "skim_destroy", "skim_last_error", "skim_workspace_bytes", "skim_set_workspace",
            "skim_profile_enable", "skim_profile_last",
            "skim_error_table", "skim_error_table_lfull", "skim_cluster_rows", "skim_select_allocated", "skim_greedy_allocate",
-           "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_layer_loss", "skim_scale_step", "skim_train_scale"]
+           "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_layer_loss", "skim_scale_step", "skim_train_scale", "skim_unpack", "skim_dequant_matvec"]
 
 
 class SkimError(RuntimeError):
@@ -74,6 +74,8 @@ def load_library():
         lib.skim_pack.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.skim_layer_loss.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp]
         lib.skim_scale_step.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, i64, C.POINTER(AdamOpts), vp, vp]
+        lib.skim_unpack.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, vp]
+        lib.skim_dequant_matvec.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, vp, vp]
         lib.skim_train_scale.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i32, i32, i32, i64, C.POINTER(AdamOpts),
                                          vp, vp, vp, vp, vp, vp]
         _lib = lib
@@ -264,6 +266,23 @@ class Context:
         self._check(self.lib.skim_layer_loss(self.h, _dp(W), _dp(S), _dp(alpha), _dp(H), n, m, W.stride(0),
                                              _dp(labels), _dp(loss), _dp(row_loss)))
         return dict(loss=loss, row_loss=row_loss)
+
+    def unpack(self, pk, m, alpha=None):
+        """Dense float32 n x m matrix of the packed model `pk` (the dict Context.pack returns)."""
+        n = pk["row_perm"].numel()
+        Wq = self.empty((n, m), self.torch.float32)
+        self._check(self.lib.skim_unpack(self.h, _dp(pk["codes"]), _dp(pk["group_word_offset"]), _dp(pk["row_perm"]),
+                                         _dp(pk["codebooks"]), _dp(alpha), n, m, _dp(Wq)))
+        return Wq
+
+    def dequant_matvec(self, pk, m, x, alpha=None, out=None):
+        """y = Wq x for the packed model `pk`; y float64[n] in original row order."""
+        n = pk["row_perm"].numel()
+        y = out if out is not None else self.empty((n,), self.torch.float64)
+        self._check(self.lib.skim_dequant_matvec(self.h, _dp(pk["codes"]), _dp(pk["group_word_offset"]),
+                                                 _dp(pk["row_perm"]), _dp(pk["codebooks"]), _dp(alpha), n, m,
+                                                 _dp(x), _dp(y)))
+        return y
 
     def train_scale(self, W, S, H, bits, alpha, adam_m, adam_v, steps=120, outer=1, t0=1, kmeans_iters=30, opts=None):
         """Alg. 2 as one call; alpha, adam_m, adam_v are updated in place.  Returns labels, centroids, loss_trace."""

@@ -228,3 +228,28 @@ def test_argument_errors(ctx, gpu_lib):
         ctx.error_table(big, big)
     with pytest.raises(gpu_lib.SkimError):
         gpu_lib.greedy_allocate(np.zeros((4, 4)), 5.0)
+
+
+@pytest.mark.parametrize("n,m,with_alpha", [(37, 100, False), (64, 257, True), (130, 1500, True), (16, 11008, False)])
+def test_unpack_and_dequant_matvec_match_oracle(ctx, gpu_lib, n, m, with_alpha):
+    """The packed model read back on the GPU: dense weights bit-exact, matrix-vector product (float64
+    accumulation, different summation order) to 1e-12 of the sum of magnitudes."""
+    W, S = skim_synth.make_ws_small(77, n, m)
+    al = skim_synth.make_alpha(5, m) if with_alpha else None
+    rng = np.random.default_rng(n * 1000 + m)
+    bits = rng.integers(1, 5, n).astype(np.uint8)
+    Wd, Sd, bd = dev(W), dev(S), dev(bits)
+    ald = None if al is None else dev(al)
+    cr = ctx.cluster_rows(Wd, Sd, bd, alpha=ald)
+    pk = ctx.pack(Wd, bd, cr["centroids"], cr["upper"], alpha=ald, bits_host=bits)
+    x = rng.standard_normal(m).astype(np.float32)
+    Wq = ctx.unpack(pk, m, alpha=ald)
+    y = ctx.dequant_matvec(pk, m, dev(x), alpha=ald)
+    torch.cuda.synchronize()
+    args = (pk["codes"].cpu().numpy().view(np.uint32), pk["group_word_offset"].cpu().numpy(),
+            pk["row_perm"].cpu().numpy(), pk["codebooks"].cpu().numpy().view(np.uint16), m)
+    ref = oracle.unpack(*args, alpha=al)
+    assert np.array_equal(Wq.cpu().numpy(), ref)
+    yref = oracle.dequant_matvec(*args, x, alpha=al)
+    scale = np.abs(ref.astype(np.float64)) @ np.abs(x.astype(np.float64))
+    assert np.all(np.abs(y.cpu().numpy() - yref) <= 1e-12 * scale)

@@ -218,3 +218,29 @@ def test_pack_with_alpha_uses_single_rounding():
     # astronomically rare cases -> compare after float rounding, allow 0 mismatches
     ref = (W.astype(np.float64) - al.astype(np.float64)[None, :] * np.take_along_axis(cb, labels.astype(np.int64), 1))
     assert np.array_equal(pk["dW"], ref.astype(np.float32))
+
+
+@pytest.mark.parametrize("m", [16, 33, 100, 257])
+def test_unpack_and_matvec_read_back_what_pack_wrote(m):
+    """The dense matrix read back from the packed model is alpha * (binary16 codebook value of the label), element
+    by element (labels checked through the independent integer reader above); the product with x is the plain
+    float64 matrix-vector product of that matrix."""
+    rng = np.random.default_rng(100 + m)
+    n = 19
+    bits = rng.integers(1, 5, n).astype(np.uint8)
+    labels = (rng.integers(0, 16, (n, m)) % (1 << bits)[:, None]).astype(np.uint8)
+    cent = rng.standard_normal((n, 16))
+    W = rng.standard_normal((n, m)).astype(np.float32)
+    alpha = np.exp(rng.standard_normal(m) * 0.1).astype(np.float32)
+    pk = oracle.pack(W, bits, labels, cent, alpha=alpha)
+    Wq = oracle.unpack(pk["codes"], pk["group_word_offset"], pk["row_perm"], pk["codebooks"], m, alpha)
+    c16 = cent.astype(np.float32).astype(np.float16).astype(np.float32)
+    ref = (alpha[None, :] * np.take_along_axis(c16, labels.astype(np.int64), 1)).astype(np.float32)
+    assert np.array_equal(Wq, ref)
+    x = rng.standard_normal(m).astype(np.float32)
+    y = oracle.dequant_matvec(pk["codes"], pk["group_word_offset"], pk["row_perm"], pk["codebooks"], m, x, alpha)
+    yref = np.array([sum(float(ref[i, j]) * float(x[j]) for j in range(m)) for i in range(n)])
+    np.testing.assert_allclose(y, yref, rtol=1e-12, atol=1e-12)
+    # without alpha the weights are the codebook values themselves
+    Wq1 = oracle.unpack(pk["codes"], pk["group_word_offset"], pk["row_perm"], pk["codebooks"], m)
+    assert np.array_equal(Wq1, np.take_along_axis(c16, labels.astype(np.int64), 1))
