@@ -36,40 +36,24 @@ __device__ __forceinline__ RowPlace place_row(const long long *gwo, long long m,
     return r;   // b == 0: p is past the last row
 }
 
-// Codes of the 32 columns [32 g, 32 g + 32) of a B-bit row: exactly B words.
-template <int B>
-__device__ __forceinline__ void load_group(const uint32_t *row_words, long long wpr, long long g, uint32_t (&w)[5]) {
-#pragma unroll
-    for (int k = 0; k < B; ++k) w[k] = (g * B + k < wpr) ? row_words[g * B + k] : 0u;
-    w[B] = 0u;
-}
-template <int B>
-__device__ __forceinline__ uint32_t code_at(const uint32_t (&w)[5], int jj) {
-    const int bit = jj * B, wi = bit >> 5, sh = bit & 31;
-    uint32_t v = w[wi] >> sh;
-    if (sh + B > 32) v |= w[wi + 1] << (32 - sh);
-    return v & ((1u << B) - 1u);
-}
-
+// Column j of a B-bit row: bits [j*B, j*B + B) of the row's little-endian word stream.  Neighbouring
+// threads take neighbouring columns, so the loads of x, alpha and the code words coalesce.
 template <int B, bool MATVEC>
-__device__ __forceinline__ void row_body(const uint32_t *row_words, long long m, const float *cbf, const float *alpha,
-                                         const float *x, float *Wq_row, double &acc) {
-    const long long wpr = (m * B + 31) / 32;
-    const long long ngroups = (m + 31) / 32;
-    for (long long g = threadIdx.x; g < ngroups; g += UNPACK_THREADS) {
-        uint32_t w[5];
-        load_group<B>(row_words, wpr, g, w);
-        const long long j0 = g * 32;
-#pragma unroll
-        for (int jj = 0; jj < 32; ++jj) {
-            const long long j = j0 + jj;
-            if (j < m) {
-                const float c = cbf[code_at<B>(w, jj)];
-                const float q = alpha ? __fmul_rn(alpha[j], c) : c;   // the dequantised weight, float32
-                if (MATVEC) acc = fma((double)q, (double)x[j], acc);
-                else Wq_row[j] = q;
-            }
-        }
+__device__ __forceinline__ void row_body(const uint32_t *__restrict__ row_words, long long m, const float *cbf,
+                                         const float *__restrict__ alpha, const float *__restrict__ x,
+                                         float *__restrict__ Wq_row, double &acc) {
+    const uint32_t mm = (uint32_t)m;   // m * 4 < 2^31 * 32 is checked on the host: bit offsets fit 32 bits for m < 2^29
+#pragma unroll 4
+    for (uint32_t j = threadIdx.x; j < mm; j += UNPACK_THREADS) {
+        const uint32_t bit = j * B;
+        const uint32_t wi = bit >> 5;
+        const int sh = (int)(bit & 31);
+        uint32_t v = row_words[wi] >> sh;
+        if ((32 % B) != 0 && sh + B > 32) v |= row_words[wi + 1] << (32 - sh);   // only 3-bit codes straddle words
+        const float c = cbf[v & ((1u << B) - 1u)];
+        const float q = alpha ? __fmul_rn(alpha[j], c) : c;   // the dequantised weight, float32
+        if (MATVEC) acc = fma((double)q, (double)x[j], acc);
+        else Wq_row[j] = q;
     }
 }
 
@@ -111,7 +95,7 @@ __global__ void __launch_bounds__(UNPACK_THREADS) packed_rows_kernel(const uint3
 skim_status check_packed(skim_ctx *ctx, const void *codes, const void *gwo, const void *perm, const void *cbs, int64_t n,
                          int64_t m, const char *who) {
     if (!codes || !gwo || !perm || !cbs) SKIM_FAIL(ctx, SKIM_ERR_ARG, "%s: NULL argument", who);
-    if (n < 1 || n > 0x7fffffff || m < 1 || m * 4 > 0x7fffffffll * 32)
+    if (n < 1 || n > 0x7fffffff || m < 1 || m >= (1ll << 29))
         SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "%s: bad shape n=%lld m=%lld", who, (long long)n, (long long)m);
     return SKIM_OK;
 }
