@@ -209,13 +209,22 @@ def bench_scale_loop(ctx, torch, np, skim_synth, iters=3):
     n = m = 4096
     W_h, S_h = skim_synth.make_ws(3, 0)
     W, S = torch.from_numpy(W_h).cuda(), torch.from_numpy(S_h).cuda()
-    acc = torch.zeros((m, m), dtype=torch.float32, device="cuda")
     N = 8192
-    for x in skim_synth.make_x(3, N, m, chunk=4096):
-        xd = torch.from_numpy(x).cuda()
-        acc += xd.T @ xd
-    H = (acc / N).contiguous()
-    H = ((H + H.T) / 2).contiguous()
+    Xb = torch.cat([torch.from_numpy(x).cuda().to(torch.bfloat16) for x in skim_synth.make_x(3, N, m, chunk=4096)])
+    H = ctx.hessian_from_activations(Xb)           # H = X^T X / N on bf16 MFMA
+    del Xb
+    # the same kernel at the size of the paper's calibration set: 131072 activation vectors
+    Nbig = 131072
+    Xbig = torch.randn((Nbig, m), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    Hbig = ctx.hessian_from_activations(Xbig)
+    torch.cuda.synchronize()
+    eh0, eh1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    eh0.record(ctx.stream)
+    ctx.hessian_from_activations(Xbig, out=Hbig)
+    eh1.record(ctx.stream)
+    torch.cuda.synchronize()
+    t_h = eh0.elapsed_time(eh1)
+    del Xbig, Hbig
     bits = torch.full((n,), 3, dtype=torch.uint8, device="cuda")
     alpha = torch.ones(m, device="cuda")
     am, av = torch.zeros(m, device="cuda"), torch.zeros(m, device="cuda")
@@ -259,6 +268,9 @@ def bench_scale_loop(ctx, torch, np, skim_synth, iters=3):
     t_train = e[2].elapsed_time(e[3])
     trace = tr["loss_trace"].cpu().numpy()
     return {"workload": "4096x4096, H 4096^2, 3 bits", "scale_step_ms": round(t_step / iters, 4),
+            "hessian_131072x4096_ms": round(t_h, 3),
+            "hessian_tflops": round(2.0 * Nbig * m * m / (t_h * 1e-3) / 1e12, 1),
+            "hessian_frac_of_bf16_mfma_peak": round(2.0 * Nbig * m * m / (t_h * 1e-3) / 1e12 / 2500.0, 4),
             "train_scale_120_steps_ms": round(t_train, 3),
             "train_scale_loss_first_last": [float(trace[0]), float(trace[-1])],
             "lfull_error_table_ms": round(t_lfull, 4),

@@ -186,6 +186,14 @@ skim_status skim_dequant_matvec(skim_ctx *ctx, const uint32_t *codes, const int6
 
 /* ---- scaling vector ----------------------------------------------------- */
 
+/* Layer-wise Hessian proxy from calibration activations (Sec. 3.4):
+ *   H = X^T X / N,  X: dev N x m bfloat16 (bit patterns, row-major, one activation
+ *   vector per row; 4-byte aligned, m even),  H: dev m x m float32.
+ * bf16 MFMA with float32 accumulation over chunks of 512 activations, the chunks
+ * summed in float64; H comes out symmetric bit for bit. */
+skim_status skim_hessian_from_activations(skim_ctx *ctx, const uint16_t *X_bf16, int64_t N, int64_t m,
+                                          float *H);
+
 /* Layer-wise (L-full) loss of Alg. 2 with fixed labels:
  *   c   = calc_centroids(W * alpha^-1, L)      (weighted means, weights S alpha^2)
  *   dW  = W - replace(c, L) * alpha

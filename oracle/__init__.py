@@ -296,6 +296,13 @@ def adam_step(alpha, m1, m2, grad, t, **opts):
     return alpha, m1, m2
 
 
+def hessian_from_activations(X):
+    """Layer-wise Hessian proxy of Sec. 3.4 from N activation vectors (rows of X, values exactly representable
+    in bfloat16): H = X^T X / N in float64, returned as float32."""
+    X = np.ascontiguousarray(X, dtype=np.float32).astype(np.float64)
+    return ((X.T @ X) / X.shape[0]).astype(np.float32)
+
+
 def train_scale(W, S, H, bits, alpha, steps=120, outer=1, t0=1, T=30, **opts):
     """Alg. 2 as a whole: `outer` rounds of {labels = K-means of W * alpha^-1 at bits; `steps` Adam steps on
     alpha with the labels fixed}; then c = calc_centroids(W * alpha^-1, L) at the final alpha.  alpha and the

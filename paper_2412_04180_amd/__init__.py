@@ -23,7 +23,7 @@ MAX_M = 32768
 EXPORTS = ["skim_create", "skim_destroy", "skim_last_error", "skim_workspace_bytes", "skim_set_workspace",
            "skim_profile_enable", "skim_profile_last",
            "skim_error_table", "skim_error_table_lfull", "skim_cluster_rows", "skim_select_allocated", "skim_greedy_allocate",
-           "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_layer_loss", "skim_scale_step", "skim_train_scale", "skim_unpack", "skim_dequant_matvec"]
+           "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_layer_loss", "skim_scale_step", "skim_train_scale", "skim_unpack", "skim_dequant_matvec", "skim_hessian_from_activations"]
 
 
 class SkimError(RuntimeError):
@@ -74,6 +74,7 @@ def load_library():
         lib.skim_pack.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.skim_layer_loss.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp]
         lib.skim_scale_step.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, i64, C.POINTER(AdamOpts), vp, vp]
+        lib.skim_hessian_from_activations.argtypes = [vp, vp, i64, i64, vp]
         lib.skim_unpack.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, vp]
         lib.skim_dequant_matvec.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, vp, vp]
         lib.skim_train_scale.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i32, i32, i32, i64, C.POINTER(AdamOpts),
@@ -266,6 +267,14 @@ class Context:
         self._check(self.lib.skim_layer_loss(self.h, _dp(W), _dp(S), _dp(alpha), _dp(H), n, m, W.stride(0),
                                              _dp(labels), _dp(loss), _dp(row_loss)))
         return dict(loss=loss, row_loss=row_loss)
+
+    def hessian_from_activations(self, X_bf16, out=None):
+        """H = X^T X / N for X: device tensor N x m of dtype bfloat16 (or its int16/uint16 bit patterns)."""
+        N, m = X_bf16.shape
+        assert X_bf16.is_contiguous() and X_bf16.element_size() == 2
+        H = out if out is not None else self.empty((m, m), self.torch.float32)
+        self._check(self.lib.skim_hessian_from_activations(self.h, _dp(X_bf16), N, m, _dp(H)))
+        return H
 
     def unpack(self, pk, m, alpha=None):
         """Dense float32 n x m matrix of the packed model `pk` (the dict Context.pack returns)."""

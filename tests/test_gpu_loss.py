@@ -179,3 +179,19 @@ def test_train_scale_is_the_composition_of_its_steps_and_tracks_the_oracle(ctx, 
     np.testing.assert_allclose(out1["loss_trace"].cpu().numpy(), ref["loss_trace"], rtol=1e-4)
     np.testing.assert_allclose(alpha.cpu().numpy(), ref["alpha"], rtol=1e-4)
     assert ref["loss_trace"][-1] < ref["loss_trace"][0]
+
+
+@pytest.mark.parametrize("N,m", [(40, 12), (300, 130), (1000, 256), (4096, 640)])
+def test_hessian_from_activations_matches_oracle(ctx, N, m):
+    """H = X^T X / N from bfloat16 activations against the float64 definition: every entry within 1e-5 of the
+    entry's natural scale sqrt(H_jj H_ll) (float32 accumulation over 512 activations, float64 across chunks)."""
+    X = np.concatenate(list(skim_synth.make_x(3, N, m)))        # float32 values that are exact in bfloat16
+    ref = oracle.hessian_from_activations(X).astype(np.float64)
+    Xb = torch.from_numpy(X).cuda().to(torch.bfloat16)
+    assert torch.equal(Xb.float().cpu(), torch.from_numpy(X))
+    H = ctx.hessian_from_activations(Xb)
+    torch.cuda.synchronize()
+    got = H.cpu().numpy().astype(np.float64)
+    scale = np.sqrt(np.outer(np.diag(ref), np.diag(ref)))
+    assert np.all(np.abs(got - ref) <= RTOL * scale), f"max scaled diff {(np.abs(got - ref) / scale).max():.3e}"
+    assert torch.equal(H, H.T.contiguous())

@@ -201,3 +201,20 @@ def test_train_scale_decreases_the_layer_loss_and_returns_consistent_pieces():
     # step numbering: two rounds of 10 steps from t0 = 1 equal the manual composition
     r2 = oracle.train_scale(W, S, H, bits, np.ones(m, np.float32), steps=3, outer=2)
     assert len(r2["loss_trace"]) == 7
+
+
+def test_hessian_from_activations_by_definition():
+    """H_jl = (1/N) sum_k x_kj x_kl, checked entry by entry with Python floats; symmetric, and the layer loss
+    written with H equals the mean squared output error ||X dW^T||^2 / N (Sec. 3.4)."""
+    N, m = 40, 12
+    X = np.concatenate(list(skim_synth.make_x(3, N, m)))
+    H = oracle.hessian_from_activations(X)
+    for j in range(m):
+        for l in range(m):
+            ref = sum(float(X[k, j]) * float(X[k, l]) for k in range(N)) / N
+            assert H[j, l] == np.float32(ref)
+    assert np.array_equal(H, H.T)
+    rng = np.random.default_rng(1)
+    d = rng.standard_normal((3, m))
+    out_err = ((X.astype(np.float64) @ d.T) ** 2).sum(0) / N
+    np.testing.assert_allclose(np.einsum("ij,jl,il->i", d, H.astype(np.float64), d), out_err, rtol=1e-6)
