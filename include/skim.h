@@ -141,6 +141,14 @@ skim_status skim_greedy_allocate(const double *E, const int64_t *row_cost, int64
                                  int bmax, double avg_bits, uint8_t *bits_out, int64_t *spent_out,
                                  int64_t *budget_out);
 
+/* The same allocation with unit costs (Alg. 1 as printed) on the device: E, bits
+ * dev pointers, launched on the context's stream, no synchronisation with the
+ * host.  info: dev int64[10]: [b] = rows that got b bits (b = 0..7), [8] = bits
+ * spent, [9] = budget.  Result identical to skim_greedy_allocate(row_cost = NULL).
+ * Uses the start of the workspace (8 bytes per row and possible upgrade). */
+skim_status skim_greedy_allocate_device(skim_ctx *ctx, const double *E, int64_t n, int bmin, int bmax,
+                                        double avg_bits, uint8_t *bits, int64_t *info);
+
 /* ---- packing ------------------------------------------------------------ */
 
 /* Number of 32-bit words / binary16 codebook entries skim_pack writes for the

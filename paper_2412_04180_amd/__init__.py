@@ -22,7 +22,7 @@ MAX_M = 32768
 
 EXPORTS = ["skim_create", "skim_destroy", "skim_last_error", "skim_workspace_bytes", "skim_set_workspace",
            "skim_profile_enable", "skim_profile_last",
-           "skim_error_table", "skim_error_table_lfull", "skim_cluster_rows", "skim_select_allocated", "skim_greedy_allocate",
+           "skim_error_table", "skim_error_table_lfull", "skim_cluster_rows", "skim_select_allocated", "skim_greedy_allocate", "skim_greedy_allocate_device",
            "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_layer_loss", "skim_scale_step", "skim_train_scale", "skim_unpack", "skim_dequant_matvec", "skim_hessian_from_activations"]
 
 
@@ -67,6 +67,7 @@ def load_library():
         lib.skim_cluster_rows.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i32, vp, vp, vp, vp]
         lib.skim_select_allocated.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         lib.skim_greedy_allocate.argtypes = [vp, vp, i64, i32, i32, dbl, vp, vp, vp]
+        lib.skim_greedy_allocate_device.argtypes = [vp, vp, i64, i32, i32, dbl, vp, vp]
         lib.skim_packed_words.argtypes = [vp, i64, i64]
         lib.skim_packed_words.restype = i64
         lib.skim_codebook_entries.argtypes = [vp, i64]
@@ -225,26 +226,52 @@ class Context:
                                                _dp(out.get("upper")), _dp(out["err"])))
         return out
 
-    def select_allocated(self, bits, table, bmin=1, bmax=4):
+    def select_allocated(self, bits, table, bmin=1, bmax=4, out=None):
         t = self.torch
         n = bits.numel()
-        cent = self.empty((n, 16), t.float64)
-        upper = self.empty((n, 16), t.float32) if table.get("upper_all") is not None else None
-        err = self.empty((n,), t.float64)
+        if out is not None:
+            cent, upper, err = out["centroids"], out.get("upper"), out.get("err")
+        else:
+            cent = self.empty((n, 16), t.float64)
+            upper = self.empty((n, 16), t.float32) if table.get("upper_all") is not None else None
+            err = self.empty((n,), t.float64)
         self._check(self.lib.skim_select_allocated(self.h, n, bmin, bmax, _dp(bits), _dp(table["E"]),
                                                    _dp(table["centroids_all"]), _dp(table.get("upper_all")),
                                                    _dp(cent), _dp(upper), _dp(err)))
         return dict(centroids=cent, upper=upper, err=err)
 
     # -- packing --------------------------------------------------------------
-    def pack(self, W, bits, centroids, upper, alpha=None, want_dW=False, bits_host=None):
-        """bits: device uint8[n].  bits_host (numpy) sizes the outputs; copied from the device when omitted."""
+    def greedy_allocate_device(self, E, avg_bits, bmin=1, bmax=4, out=None):
+        """Alg. 1 with unit costs on the device.  Returns dict(bits uint8[n], info int64[10]) of device tensors."""
+        t = self.torch
+        n = E.shape[0]
+        assert E.dtype == t.float64 and E.is_contiguous() and E.shape[1] == bmax - bmin + 1
+        if out is None:
+            out = dict(bits=self.empty((n,), t.uint8), info=self.empty((10,), t.int64))
+        self.ensure_workspace(n, 16)
+        self._check(self.lib.skim_greedy_allocate_device(self.h, _dp(E), n, bmin, bmax, float(avg_bits),
+                                                         _dp(out["bits"]), _dp(out["info"])))
+        return out
+
+    def pack(self, W, bits, centroids, upper, alpha=None, want_dW=False, bits_host=None, max_size=False, out=None):
+        """bits: device uint8[n].  bits_host (numpy) sizes the outputs; copied from the device when omitted.
+        max_size: size the outputs for 4 bits in every row instead (no copy of bits to the host; the used part
+        ends at group_word_offset[5] words)."""
         t = self.torch
         n, m = W.shape
-        if bits_host is None:
-            bits_host = bits.cpu().numpy()
-        nwords = packed_words(bits_host, m)
-        ncb = codebook_entries(bits_host)
+        if out is not None:
+            self.ensure_workspace(n, m)
+            self._check(self.lib.skim_pack(self.h, _dp(W), _dp(alpha), n, m, W.stride(0), _dp(bits), _dp(centroids),
+                                           _dp(upper), _dp(out["codes"]), _dp(out["group_word_offset"]),
+                                           _dp(out["row_perm"]), _dp(out["codebooks"]), _dp(out.get("dW"))))
+            return out
+        if max_size:
+            nwords, ncb = n * ((m * 4 + 31) // 32), n * 16
+        else:
+            if bits_host is None:
+                bits_host = bits.cpu().numpy()
+            nwords = packed_words(bits_host, m)
+            ncb = codebook_entries(bits_host)
         if nwords < 0 or ncb < 0:
             raise ValueError("bits must be in 1..4")
         self.ensure_workspace(n, m)

@@ -253,3 +253,38 @@ def test_unpack_and_dequant_matvec_match_oracle(ctx, gpu_lib, n, m, with_alpha):
     yref = oracle.dequant_matvec(*args, x, alpha=al)
     scale = np.abs(ref.astype(np.float64)) @ np.abs(x.astype(np.float64))
     assert np.all(np.abs(y.cpu().numpy() - yref) <= 1e-12 * scale)
+
+
+def _tables(rng, n, kind):
+    if kind == "smooth":
+        g = np.sort(rng.random((n, 3)), axis=1)[:, ::-1] * rng.random((n, 1))
+    elif kind == "ties":
+        g = rng.integers(0, 4, (n, 3)).astype(np.float64)          # many equal reductions, some zero
+    elif kind == "nonmonotone":
+        g = rng.standard_normal((n, 3))                            # reductions of any sign and order
+    else:
+        g = np.zeros((n, 3))
+    E = np.empty((n, 4))
+    E[:, 3] = rng.random(n)
+    for j in (2, 1, 0):
+        E[:, j] = E[:, j + 1] + g[:, j]
+    return E
+
+
+@pytest.mark.parametrize("kind", ["smooth", "ties", "nonmonotone", "flat"])
+@pytest.mark.parametrize("n,avg", [(1, 2.0), (7, 1.0), (7, 4.0), (100, 2.5), (1000, 3.2), (4096, 3.2), (22016, 2.25)])
+def test_device_greedy_equals_host_and_oracle(ctx, gpu_lib, kind, n, avg):
+    """Alg. 1 on the device: same bits as the host function and as the oracle's linear-scan loop on the same
+    table, including tables full of ties, reductions of either sign, and the two ends of the budget."""
+    rng = np.random.default_rng(n * 7 + len(kind))
+    E = _tables(rng, n, kind)
+    out = ctx.greedy_allocate_device(dev(E), avg)
+    torch.cuda.synchronize()
+    bits_h, spent, budget = gpu_lib.greedy_allocate(E, avg)
+    got = out["bits"].cpu().numpy()
+    info = out["info"].cpu().numpy()
+    assert np.array_equal(got, bits_h)
+    assert info[8] == spent == budget == info[9]
+    assert np.array_equal(info[:8], np.bincount(bits_h, minlength=8))
+    if n <= 4096:
+        assert np.array_equal(got, oracle.greedy(E, avg)["bits"])
