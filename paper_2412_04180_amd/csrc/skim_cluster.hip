@@ -52,6 +52,7 @@ struct ClusterParams {
     double2 *L1;          // (sum of s, sum of s*w) of every 16-key chunk (n1 per row)
     double2 *Q;           // the same sums over every group of 4 chunks (nq = n1 / 4 per row)
     int nq;
+    double *R1, *RQ;      // sum of s*w*w of every chunk (n1 per row) and of every group of 4 chunks (nq per row)
     float *w16;           // weight of the first key of every 16-key chunk (n1 per row)
     BitState *bstate;  // final state of the Lloyd lanes: 4 per row (bit widths 1..4)
     int n1;
@@ -67,6 +68,9 @@ struct BitState {  // what the Lloyd lanes of one bit width leave for the epilog
     int idx[16];      // cluster index at that position
     int B[17];        // first rank of each position's range, B[K] = m
     int active;
+    double err;       // row error from the clusters' second moments
+    int exact;        // nonzero: err lost too many digits to cancellation, evaluate it key by key
+    int pad_;
 };
 
 // LDS slot of key index i: one spare slot after every 16 keys.  The skew makes the access patterns
@@ -369,7 +373,7 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     {
         const bool mine_ok = tid * EPT < m;
         const u64 *mine = sorted + swz((uint32_t)(mine_ok ? tid * EPT : 0));
-        double c = 0.0, q = 0.0;
+        double c = 0.0, q = 0.0, r2 = 0.0;
         float w0 = 0.0f;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
@@ -378,13 +382,18 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
             if (e == 0) w0 = elem_w(el);
             c += sv;
             q = fma(sv, wv, q);
+            r2 = fma(sv * wv, wv, r2);     // second moment, for the row errors
         }
         if (mine_ok) {
             prm.L1[row * prm.n1 + tid] = make_double2(c, q);
+            prm.R1[row * prm.n1 + tid] = r2;
             prm.w16[row * prm.n1 + tid] = w0;
         }
-        const double c4 = quad_sum(c), q4 = quad_sum(q);   // threads past the row add zeros
-        if (mine_ok && (tid & 3) == 0) prm.Q[row * prm.nq + (tid >> 2)] = make_double2(c4, q4);
+        const double c4 = quad_sum(c), q4 = quad_sum(q), r4 = quad_sum(r2);   // threads past the row add zeros
+        if (mine_ok && (tid & 3) == 0) {
+            prm.Q[row * prm.nq + (tid >> 2)] = make_double2(c4, q4);
+            prm.RQ[row * prm.nq + (tid >> 2)] = r4;
+        }
     }
     // sorted keys, compact and in rank order
     u64 *keys = prm.keys + row * (long long)m;
@@ -442,7 +451,7 @@ __global__ void __launch_bounds__(1024) sums_kernel(ClusterParams prm) {
     const int n1u = (m + 15) >> 4;
     u64 *keys = prm.keys + row * (long long)m;
     for (int pass = 0; pass < 2; ++pass) {
-        double cs[2] = {0.0, 0.0}, qs[2] = {0.0, 0.0};
+        double cs[2] = {0.0, 0.0}, qs[2] = {0.0, 0.0}, rs[2] = {0.0, 0.0};
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int ch = 2 * tid + h;
@@ -457,6 +466,7 @@ __global__ void __launch_bounds__(1024) sums_kernel(ClusterParams prm) {
                     const double s = (double)elem_s(el), w = (double)elem_w(el);
                     cs[h] += s;
                     qs[h] = fma(s, w, qs[h]);
+                    rs[h] = fma(s * w, w, rs[h]);
                 }
             }
         }
@@ -466,14 +476,19 @@ __global__ void __launch_bounds__(1024) sums_kernel(ClusterParams prm) {
             const int ch = 2 * tid + h;
             if (ch < n1u) {
                 prm.L1[row * prm.n1 + ch] = make_double2(cs[h], qs[h]);
+                prm.R1[row * prm.n1 + ch] = rs[h];
                 prm.w16[row * prm.n1 + ch] = elem_w(keys[16 * ch]);
             }
         }
         {   // groups of 4 chunks = 2 neighbouring threads
-            double c2 = cs[0] + cs[1], q2 = qs[0] + qs[1];
+            double c2 = cs[0] + cs[1], q2 = qs[0] + qs[1], r2 = rs[0] + rs[1];
             c2 += dpp_move_d<0xB1>(c2);   // quad_perm [1,0,3,2]
             q2 += dpp_move_d<0xB1>(q2);
-            if ((tid & 1) == 0 && 2 * tid < n1u) prm.Q[row * prm.nq + (tid >> 1)] = make_double2(c2, q2);
+            r2 += dpp_move_d<0xB1>(r2);
+            if ((tid & 1) == 0 && 2 * tid < n1u) {
+                prm.Q[row * prm.nq + (tid >> 1)] = make_double2(c2, q2);
+                prm.RQ[row * prm.nq + (tid >> 1)] = r2;
+            }
         }
         break;
     }
@@ -491,6 +506,7 @@ struct LevelMap {
     int nlev;        // levels 0 .. nlev-1
     int n[8];        // entries per level
     int off[8];      // byte offset of level >= 1 inside the row's LDS block
+    int roff[8];     // byte offset of the second-moment sums of level >= 1 (one double per entry)
     int w16_off, pre_off, zero_off, bytes;   // zero_off: an entry (0, 0) for the slots a lane does not need
 };
 __host__ __device__ inline LevelMap level_map(int n1u) {
@@ -509,6 +525,11 @@ __host__ __device__ inline LevelMap level_map(int n1u) {
     } while (n > 1);
     for (int k = lv + 1; k < 8; ++k) { L.n[k] = 0; L.off[k] = 0; }
     L.nlev = lv + 1;
+    L.roff[0] = 0;
+    for (int k = 1; k < 8; ++k) {
+        L.roff[k] = o;
+        o += ((L.n[k] * 8) + 15) & ~15;
+    }
     L.pre_off = o;
     o += (L.n[1] + 1) * 8;
     o = (o + 15) & ~15;
@@ -590,6 +611,9 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
                 if (q < LM.n[1]) l1[q] = t4[u];
             }
         }
+        const double *grq = prm.RQ + rr * prm.nq;
+        double *r1 = (double *)(blkw + LM.roff[1]);
+        for (int q = lane; q < LM.n[1]; q += ITER_THREADS) r1[q] = grq[q];
         if (lane == 0) *(double2 *)(blkw + LM.zero_off) = make_double2(0.0, 0.0);
     }
     __syncthreads();
@@ -611,6 +635,15 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
                         }
                     }
                     dst[q] = make_double2(d, nn);
+                }
+                const double *rsrc = (const double *)(blkw + LM.roff[lv - 1]);
+                double *rdst = (double *)(blkw + LM.roff[lv]);
+                for (int q = lane; q < LM.n[lv]; q += ITER_THREADS) {
+                    double rr2 = 0.0;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        if (4 * q + k < LM.n[lv - 1]) rr2 += rsrc[4 * q + k];
+                    rdst[q] = rr2;
                 }
             }
             __syncthreads();
@@ -737,10 +770,13 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
     int Bcur = 0, Bold = -1, idxold = -1, cold = 0;
     int ca3 = -1, cb3 = -1;          // range at the 1024-key level whose sums cD3, cN3 hold
     double cD3 = 0.0, cN3 = 0.0;
+    double Dk = 0.0, Nk = 0.0;       // sums of this lane's cluster under the last assignment it took part in
+    bool emptyk = false;             // ... in which it owned nothing (its value repeated the one below)
     bool done = !on;
 
     for (int it = 0; it < prm.iters; ++it) {
         if (__ballot(!done) == 0) break;
+        const bool live = !done;     // this lane's bit width still iterates
         double vlo = lane_below(v);
         int ilo = lane_below(idx);
         {   // keep positions ordered by (value, cluster index)
@@ -1001,9 +1037,92 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
                 N += cN3;
             }
         }
+        if (summing) {
+            Dk = D;
+            Nk = N;
+        }
+        if (live) emptyk = dup;
         if (summing && !done && D > 0.0) v = quick_div(N, D);
     }
 
+    // ---- row errors from second moments -------------------------------------------------------------
+    // sum_j s (w - c)^2 over a cluster = R - 2 c N + c^2 D with R = sum s w^2 over the cluster's final rank
+    // range [Bold_p, Bold_{p+1}); D, N are the sums the last iteration formed for the same range.  R comes
+    // from the keys of the two partial chunks and the aligned pieces of the second-moment tree.
+    double Ep = 0.0, Rp = 0.0;
+    {
+        const int a = on ? max(Bold, 0) : 0;
+        int bnd = lane_above(Bold);
+        if (p == K - 1) bnd = m;
+        bnd = on ? max(bnd, a) : a;
+        const int e0 = min(bnd, (a + 15) & ~15), e1 = max(e0, bnd & ~15);
+        const u64x2_a8 *ka = (const u64x2_a8 *)(keys + (a & ~15));        // chunk of a (read whole, masked below)
+        const u64x2_a8 *kb = (const u64x2_a8 *)(keys + (e1 < m ? e1 : 0));  // chunk that starts at e1
+        u64 ea[16], eb[16];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const u64x2 t2 = ka[j], t3 = kb[j];
+            ea[2 * j] = t2.x;
+            ea[2 * j + 1] = t2.y;
+            eb[2 * j] = t3.x;
+            eb[2 * j + 1] = t3.y;
+        }
+        const int c0 = e0 >> 4, c3 = e1 >> 4;                    // whole chunks [c0, c3)
+        const int la0 = min(c3, (c0 + 3) & ~3), rb0 = max(la0, c3 & ~3);
+        const double *R1 = prm.R1 + rowc * prm.n1;
+        double pr[6];
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            pr[k] = (c0 + k < la0) ? R1[c0 + k] : 0.0;
+            pr[3 + k] = (rb0 + k < c3) ? R1[rb0 + k] : 0.0;
+        }
+        const int abase = a & ~15;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const bool ina = (abase + j >= a) && (abase + j < e0);
+            const bool inb = (e1 + j < bnd);
+            const double sa = ina ? (double)elem_s(ea[j]) : 0.0, wa = ina ? (double)elem_w(ea[j]) : 0.0;
+            const double sb = inb ? (double)elem_s(eb[j]) : 0.0, wb = inb ? (double)elem_w(eb[j]) : 0.0;
+            Rp = fma(sa * wa, wa, Rp);
+            Rp = fma(sb * wb, wb, Rp);
+        }
+#pragma unroll
+        for (int k = 0; k < 6; ++k) Rp += pr[k];
+        int ra = la0 >> 2, rb = rb0 >> 2;
+        if (la0 >= rb0) { ra = 0; rb = 0; }
+#pragma unroll
+        for (int lv = 1; lv < MAX_LEVELS; ++lv) {
+            if (lv < LM.nlev && __ballot(ra < rb) != 0) {
+                const double *L = (const double *)(blk + LM.roff[lv]);
+                const int la = min(rb, (ra + 3) & ~3), rbb = max(la, rb & ~3);
+#pragma unroll
+                for (int k = 0; k < 3; ++k) {
+                    if (ra + k < la) Rp += L[ra + k];
+                    if (rbb + k < rb) Rp += L[rbb + k];
+                }
+                if (la < rbb) { ra = la >> 2; rb = rbb >> 2; } else { ra = 0; rb = 0; }
+            }
+        }
+        if (on && !emptyk && Dk > 0.0) Ep = fma(v, fma(v, Dk, -2.0 * Nk), Rp);
+    }
+    // per bit width: the clusters' errors added in position order by the lane of position 0
+    double *escr = (double *)(smem + 2 * (size_t)LM.bytes);
+    __syncthreads();
+    escr[lane] = Ep;
+    escr[64 + lane] = Rp;
+    __syncthreads();
+    double err_b = 0.0;
+    bool exact_b = false;
+    if (on && p == 0) {
+        double rtot = 0.0;
+        for (int k = 0; k < K; ++k) {
+            err_b += escr[lane + k];
+            rtot += escr[64 + lane + k];
+        }
+        // cancellation leaves about 1e-16 * rtot of rounding in err_b: below 1e-9 * rtot (or negative, or
+        // not a number) the error is evaluated key by key instead
+        exact_b = !(err_b >= 1e-9 * rtot) || !(err_b > 0.0);
+    }
     if (on) {
         BitState *o = prm.bstate + row * 4 + (b - 1);
         o->cent[p] = v;
@@ -1012,6 +1131,10 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
         if (p == K - 1) {
             o->B[K] = m;
             o->active = 1;
+        }
+        if (p == 0) {
+            o->err = err_b;
+            o->exact = exact_b ? 1 : 0;
         }
     }
 }
@@ -1043,6 +1166,11 @@ __global__ void __launch_bounds__(FIN_THREADS) finish_kernel(ClusterParams prm) 
         bs[tid].active = prm.bits ? (bb == rowbits) : (bb >= prm.bmin && bb <= prm.bmax);
     }
     __syncthreads();
+    // the row errors normally come from the clusters' second moments (lloyd_iter_kernel); a bit width whose
+    // error drowned in cancellation there is evaluated key by key below
+    int anyexact = 0;
+#pragma unroll
+    for (int bi = 0; bi < 4; ++bi) anyexact |= __builtin_amdgcn_readfirstlane(bs[bi].active && bs[bi].exact);
 
     // ---- errors: sum s (w - c)^2 over the sorted row, every key once ----------
     double e4[4] = {0.0, 0.0, 0.0, 0.0};
@@ -1052,9 +1180,9 @@ __global__ void __launch_bounds__(FIN_THREADS) finish_kernel(ClusterParams prm) 
     double ccur[4] = {0.0, 0.0, 0.0, 0.0};
     int act[4];
 #pragma unroll
-    for (int bi = 0; bi < 4; ++bi) act[bi] = __builtin_amdgcn_readfirstlane(bs[bi].active);
+    for (int bi = 0; bi < 4; ++bi) act[bi] = __builtin_amdgcn_readfirstlane(bs[bi].active && bs[bi].exact);
     constexpr int EU = 4;   // stretches of 64 ranks whose loads are in flight together
-    for (int base0 = wave * 64; base0 < m; base0 += EU * FIN_THREADS) {
+    for (int base0 = wave * 64; anyexact && base0 < m; base0 += EU * FIN_THREADS) {
         u64 els[EU];
 #pragma unroll
         for (int u = 0; u < EU; ++u) {
@@ -1103,8 +1231,11 @@ __global__ void __launch_bounds__(FIN_THREADS) finish_kernel(ClusterParams prm) 
         for (int bi = 0; bi < 4; ++bi) {
             if (!bs[bi].active) continue;
             const int bb = bi + 1, Kb = 1 << bb;
-            double err = 0.0;
-            for (int w2 = 0; w2 < FIN_WAVES; ++w2) err += red[bi * FIN_WAVES + w2];
+            double err = bs[bi].err;
+            if (bs[bi].exact) {
+                err = 0.0;
+                for (int w2 = 0; w2 < FIN_WAVES; ++w2) err += red[bi * FIN_WAVES + w2];
+            }
             long long obase;
             if (prm.bits) {
                 if (lane == 0) prm.E[row] = err;
@@ -1185,7 +1316,7 @@ __global__ void select_kernel(long long n, int bmin, int bmax, const uint8_t *bi
 
 size_t sort_lds_bytes(int P) { return (size_t)(P + P / 16) * 8; }
 
-size_t lloyd_lds_bytes(int m) { return 2 * (size_t)level_map((m + 15) >> 4).bytes; }
+size_t lloyd_lds_bytes(int m) { return 2 * (size_t)level_map((m + 15) >> 4).bytes + 128 * sizeof(double); }
 
 // Scratch layout of one call (inside the caller's workspace).
 skim_status carve_cluster_ws(skim_ctx *ctx, ClusterParams &prm, int64_t n, double **cent_scratch) {
@@ -1206,9 +1337,11 @@ skim_status carve_cluster_ws(skim_ctx *ctx, ClusterParams &prm, int64_t n, doubl
     prm.L1 = (double2 *)cur.take((size_t)n * prm.n1 * sizeof(double2));
     prm.nq = (prm.n1 + 3) / 4;
     prm.Q = (double2 *)cur.take((size_t)n * prm.nq * sizeof(double2));
+    prm.R1 = (double *)cur.take((size_t)n * prm.n1 * sizeof(double));
+    prm.RQ = (double *)cur.take((size_t)n * prm.nq * sizeof(double));
     prm.w16 = (float *)cur.take((size_t)n * prm.n1 * sizeof(float));
     prm.bstate = (BitState *)cur.take((size_t)n * 4 * sizeof(BitState));
-    bool ok = prm.keys && prm.L1 && prm.Q && prm.w16 && prm.bstate;
+    bool ok = prm.keys && prm.L1 && prm.Q && prm.R1 && prm.RQ && prm.w16 && prm.bstate;
     prm.keys_seg = nullptr;
     if (prm.nseg > 1) {
         prm.keys_seg = (u64 *)cur.take((size_t)n * prm.m * sizeof(u64));
