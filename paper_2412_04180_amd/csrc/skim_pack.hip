@@ -2,7 +2,8 @@
 // equal bit width are gathered and processed together; Sec. 5.4: centroids are
 // stored in lower precision).  Two kernels: a one-workgroup plan that orders the
 // rows by (bits, row index) and lays out the groups, and a row kernel that
-// rebuilds each label from the cluster thresholds and emits the bit stream.
+// rebuilds each label from the cluster thresholds and emits the bit stream
+// (32 columns = b whole words per thread, assembled in registers).
 #include "skim_common.h"
 
 #include <hip/hip_fp16.h>
@@ -12,7 +13,6 @@ namespace {
 
 constexpr int PLAN_THREADS = 1024;
 constexpr int PACK_THREADS = 256;
-constexpr int PACK_TILE = 8192;  // columns staged per pass; multiple of 32 so tiles end on word boundaries
 
 struct PackPlan {         // lives in the workspace
     long long row_start[6];   // first packed position of the b-bit group
@@ -87,6 +87,52 @@ __global__ void __launch_bounds__(PLAN_THREADS) pack_plan_kernel(long long n, lo
     }
 }
 
+// One workgroup per row.  A thread takes 32 consecutive columns at a time: their B-bit labels fill
+// exactly B words, assembled in registers and stored without staging (no LDS traffic, no barriers
+// inside the row).
+template <int B>
+__device__ __forceinline__ void pack_row_body(const float *__restrict__ Wr, const float *__restrict__ alpha, long long m,
+                                              const float *thr, const int *thl, const float *cbf,
+                                              uint32_t *__restrict__ out_words, long long wpr, float *__restrict__ dWr) {
+    const long long ngroups = (m + 31) / 32;
+    for (long long g = threadIdx.x; g < ngroups; g += PACK_THREADS) {
+        const long long j0 = g * 32;
+        float w[32];
+        if (j0 + 32 <= m && (((uintptr_t)(Wr + j0)) & 15) == 0) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const float4 v = *(const float4 *)(Wr + j0 + 4 * q);
+                w[4 * q] = v.x; w[4 * q + 1] = v.y; w[4 * q + 2] = v.z; w[4 * q + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int jj = 0; jj < 32; ++jj) w[jj] = (j0 + jj < m) ? Wr[j0 + jj] : 0.0f;
+        }
+        uint32_t words[B + 1];
+#pragma unroll
+        for (int k = 0; k <= B; ++k) words[k] = 0u;
+#pragma unroll
+        for (int jj = 0; jj < 32; ++jj) {
+            const long long j = j0 + jj;
+            const float a = alpha ? alpha[j < m ? j : 0] : 1.0f;
+            const float wt = alpha ? __fdiv_rn(w[jj], a) : w[jj];
+            // first position whose bound is >= wt (binary search over the 16 sorted bounds)
+            int pos = (thr[7] < wt) ? 8 : 0;
+            pos += (thr[pos + 3] < wt) ? 4 : 0;
+            pos += (thr[pos + 1] < wt) ? 2 : 0;
+            pos += (thr[pos] < wt) ? 1 : 0;
+            const uint32_t l = (j < m) ? (uint32_t)thl[pos] : 0u;     // padding bits stay zero
+            const int bit = jj * B, wi = bit >> 5, sh = bit & 31;
+            words[wi] |= l << sh;
+            if (sh + B > 32) words[wi + 1] |= l >> (32 - sh);
+            if (dWr && j < m) dWr[j] = __fmaf_rn(-a, cbf[l], w[jj]);
+        }
+#pragma unroll
+        for (int k = 0; k < B; ++k)
+            if (g * B + k < wpr) out_words[g * B + k] = words[k];
+    }
+}
+
 __global__ void __launch_bounds__(PACK_THREADS) pack_rows_kernel(const float *W, const float *alpha, long long m,
                                                                  long long ld, const uint8_t *bits,
                                                                  const double *cent, const float *upper,
@@ -95,7 +141,6 @@ __global__ void __launch_bounds__(PACK_THREADS) pack_rows_kernel(const float *W,
     __shared__ float thr[16];
     __shared__ int thl[16];
     __shared__ float cbf[16];
-    __shared__ uint8_t lab[PACK_TILE];
     const long long row = blockIdx.x;
     const int tid = threadIdx.x;
     const int p = rowpos[row];
@@ -131,36 +176,13 @@ __global__ void __launch_bounds__(PACK_THREADS) pack_rows_kernel(const float *W,
     if (tid >= K && tid < 16) thl[tid] = thl[K - 1];
     __syncthreads();
     const float *Wr = W + row * ld;
-    for (long long t0 = 0; t0 < m; t0 += PACK_TILE) {
-        const int len = (int)min((long long)PACK_TILE, m - t0);
-        for (int j = tid; j < len; j += PACK_THREADS) {
-            const float w = Wr[t0 + j];
-            const float a = alpha ? alpha[t0 + j] : 1.0f;
-            const float wt = alpha ? __fdiv_rn(w, a) : w;
-            // first position whose bound is >= wt (binary search over the 16 sorted bounds)
-            int pos = (thr[7] < wt) ? 8 : 0;
-            pos += (thr[pos + 3] < wt) ? 4 : 0;
-            pos += (thr[pos + 1] < wt) ? 2 : 0;
-            pos += (thr[pos] < wt) ? 1 : 0;
-            const int l = thl[pos];
-            lab[j] = (uint8_t)l;
-            if (dW) dW[row * m + t0 + j] = __fmaf_rn(-a, cbf[l], w);
-        }
-        __syncthreads();
-        const int nw = (len * b + 31) / 32;
-        const long long wbase = word0 + (t0 * b) / 32;
-        for (int q = tid; q < nw; q += PACK_THREADS) {
-            const int bit0 = q * 32;
-            int j = bit0 / b;
-            uint32_t word = 0;
-            for (; j < len && j * b < bit0 + 32; ++j) {
-                const uint32_t code = lab[j];
-                const int sh = j * b - bit0;
-                word |= (sh >= 0) ? (code << sh) : (code >> (-sh));
-            }
-            codes[wbase + q] = word;
-        }
-        __syncthreads();
+    float *dWr = dW ? dW + row * m : nullptr;
+    uint32_t *ow = codes + word0;
+    switch (b) {
+        case 1: pack_row_body<1>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr); break;
+        case 2: pack_row_body<2>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr); break;
+        case 3: pack_row_body<3>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr); break;
+        default: pack_row_body<4>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr); break;
     }
 }
 
