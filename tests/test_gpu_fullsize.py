@@ -63,6 +63,10 @@ def check_alloc_labels_pack(ctx, gpu_lib, W, S, ref, out, clean, Wd, Sd, avg_bit
     g_ref = oracle.greedy(ref["E"], avg_bits, count_near=True)
     ndiff = int((bits != g_ref["bits"]).sum())
     assert ndiff <= 4 * int((~clean).sum()) + g_ref["near"], f"{ndiff} allocation differences"
+    # the device allocator on the device table: same bits, no copy to the host
+    ga = ctx.greedy_allocate_device(out["E"], avg_bits)
+    torch.cuda.synchronize()
+    assert np.array_equal(ga["bits"].cpu().numpy(), bits) and int(ga["info"][8]) == spent
     dbits = dev(bits)
     cr = ctx.cluster_rows(Wd, Sd, dbits)
     torch.cuda.synchronize()
@@ -83,6 +87,12 @@ def check_alloc_labels_pack(ctx, gpu_lib, W, S, ref, out, clean, Wd, Sd, avg_bit
     assert np.array_equal(pk["codebooks"].cpu().numpy().view(np.uint16), rp["codebooks"])
     if want_dW:
         assert np.array_equal(pk["dW"].cpu().numpy(), rp["dW"])
+    # outputs sized for 4 bits in every row (what a caller does that never looks at the bits on the host)
+    pk4 = ctx.pack(Wd, ga["bits"], sel["centroids"], sel["upper"], max_size=True)
+    torch.cuda.synchronize()
+    nw, ncb = len(rp["codes"]), len(rp["codebooks"])
+    assert torch.equal(pk4["codes"][:nw], pk["codes"]) and torch.equal(pk4["codebooks"][:ncb], pk["codebooks"])
+    assert torch.equal(pk4["group_word_offset"], pk["group_word_offset"]) and torch.equal(pk4["row_perm"], pk["row_perm"])
     print(f"[{n}x{m} @ {avg_bits}] allocation differences vs oracle table = {ndiff}, label rows excused = {int((~ok).sum())}")
     return bits
 
