@@ -147,6 +147,94 @@ def greedy(E, avg_bits, bmin=1, bmax=4, cost=None, count_near=False):
     return dict(bits=bits, spent=spent.value, budget=budget.value, near=int(near[0]))
 
 
+def dp_allocate(E, avg_bits, bmin=1, bmax=4):
+    """Exact solution of the bit allocation problem that Alg. 1 approximates (the knapsack form stated with
+    the mixed-precision problem, unit cost per row and bit): the bits b_i in [bmin, bmax] that minimise
+    sum_i E[i, b_i] subject to sum_i b_i <= floor(avg_bits * n + 1e-9).
+
+    Dynamic programme over the rows in index order: f_i[x] = least error of rows 0..i-1 when they hold
+    exactly x bits above bmin in total; f_{i+1}[x] = min_d f_i[x - d] + E[i, bmin + d], where equal sums keep
+    the smaller d; the answer is the smallest x that attains min_x f_n[x], traced back through the choices.
+    Returns dict(bits, total, spent, budget)."""
+    E = np.ascontiguousarray(E, dtype=np.float64)
+    n, nb = E.shape
+    assert nb == bmax - bmin + 1
+    budget = int(np.floor(avg_bits * n + 1e-9))
+    if budget < n * bmin or budget > n * bmax:
+        raise ValueError("budget outside [n*bmin, n*bmax]")
+    X = budget - n * bmin
+    f = np.full(X + 1, np.inf)
+    f[0] = 0.0
+    choice = np.zeros((n, X + 1), np.uint8)
+    for i in range(n):
+        best = np.full(X + 1, np.inf)
+        for d in range(nb):
+            cand = np.full(X + 1, np.inf)
+            cand[d:] = f[:X + 1 - d] + E[i, d]
+            take = cand < best
+            best[take] = cand[take]
+            choice[i, take] = d
+        f = best
+    x = int(np.argmin(f))
+    total = float(f[x])
+    bits = np.empty(n, np.uint8)
+    spent = n * bmin + x
+    for i in range(n - 1, -1, -1):
+        d = int(choice[i, x])
+        bits[i] = bmin + d
+        x -= d
+    assert x == 0
+    return dict(bits=bits, total=total, spent=spent, budget=budget)
+
+
+def kmeans_optimal_row(w, s, Ks=(2, 4, 8, 16)):
+    """Least weighted squared error sum_j s_j (w_j - c_{l_j})^2 of one row over ALL assignments to at most K
+    clusters, for each K in Ks: the floor under what Lloyd's iterations from any start can reach.
+
+    In one dimension an optimal assignment cuts the values, sorted, into intervals, and the best centroid of an
+    interval is its weighted mean, so with the elements in the order (w, s) and prefix sums A = sum s,
+    B = sum s w, C = sum s w^2:   cost(i, j) = (C_j - C_i) - (B_j - B_i)^2 / (A_j - A_i)   (elements i..j-1;
+    0 when the interval holds no mass; rounding below 0 is clipped),   D_1[j] = cost(0, j),
+    D_k[j] = min_{0 <= i <= j} D_{k-1}[i] + cost(i, j).   All-zero weights count as unit weights, as in the
+    clustering itself.  Returns float64[len(Ks)] of D_K[m]."""
+    w = np.asarray(w, np.float32).astype(np.float64)
+    s = np.asarray(s, np.float32).astype(np.float64)
+    m = len(w)
+    if not np.any(s > 0):
+        s = np.ones(m)
+    order = np.lexsort((s, w))
+    w, s = w[order], s[order]
+    A = np.concatenate(([0.0], np.cumsum(s)))
+    B = np.concatenate(([0.0], np.cumsum(s * w)))
+    Cc = np.concatenate(([0.0], np.cumsum(s * w * w)))
+
+    def cost_to(j):  # cost(i, j) for i = 0..j
+        dA, dB, dC = A[j] - A[:j + 1], B[j] - B[:j + 1], Cc[j] - Cc[:j + 1]
+        with np.errstate(divide="ignore", invalid="ignore"):
+            c = np.where(dA > 0, dC - dB * dB / dA, 0.0)
+        return np.maximum(c, 0.0)
+
+    D = np.array([cost_to(j)[0] for j in range(m + 1)])
+    out, k = [], 1
+    for K in sorted(Ks):
+        while k < K:
+            D = np.array([np.min(D[:j + 1] + cost_to(j)) for j in range(m + 1)])
+            k += 1
+        out.append(D[m])
+    res = dict(zip(sorted(Ks), out))
+    return np.array([res[K] for K in Ks])
+
+
+def kmeans_optimal_table(W, S, alpha=None, bmin=1, bmax=4):
+    """kmeans_optimal_row for every row (of the scaled inputs when alpha is given) and K = 2^b, b = bmin..bmax."""
+    W, S = _f32(W), _f32(S)
+    out = np.empty((W.shape[0], bmax - bmin + 1))
+    for i in range(W.shape[0]):
+        w, s = (W[i], S[i]) if alpha is None else scale_row(W[i], S[i], alpha)
+        out[i] = kmeans_optimal_row(w, s, tuple(1 << b for b in range(bmin, bmax + 1)))
+    return out
+
+
 def words_per_row(m, b):
     return (m * b + 31) // 32
 
