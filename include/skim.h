@@ -149,6 +149,25 @@ skim_status skim_greedy_allocate(const double *E, const int64_t *row_cost, int64
 skim_status skim_greedy_allocate_device(skim_ctx *ctx, const double *E, int64_t n, int bmin, int bmax,
                                         double avg_bits, uint8_t *bits, int64_t *info);
 
+/* The exact optimum of the allocation problem that Alg. 1 approximates (the
+ * bit-constrained sum minimisation stated with the mixed-precision problem,
+ * which the paper notes a dynamic programme solves exactly): bits b_i in
+ * [bmin, bmax], bmax - bmin <= 3, minimising sum_i E[i][b_i] subject to
+ * sum_i b_i <= floor(avg_bits * n + 1e-9), unit costs.  A yardstick for the
+ * greedy result, not a step of the quantisation path.  Rows are taken in
+ * index order, f_{i+1}[x] = min_d f_i[x - d] + E[i][bmin + d] over the bits x
+ * spent above bmin; equal sums keep the smaller d and the least final state
+ * wins, so the result is a function of E alone.  E, bits: dev, as in
+ * skim_greedy_allocate_device.  info: dev float64[3] = least total error, bits
+ * spent, budget.  scratch: dev, 256-byte aligned, at least
+ * skim_dp_allocate_scratch_bytes(...) bytes (about n * (budget - n * bmin)
+ * bytes; 0 is returned for arguments the call would reject).  Launched on
+ * the context's stream, no synchronisation with the host. */
+size_t skim_dp_allocate_scratch_bytes(int64_t n, int bmin, int bmax, double avg_bits);
+skim_status skim_dp_allocate(skim_ctx *ctx, const double *E, int64_t n, int bmin, int bmax,
+                             double avg_bits, uint8_t *bits, double *info, void *scratch,
+                             size_t scratch_bytes);
+
 /* ---- packing ------------------------------------------------------------ */
 
 /* Number of 32-bit words / binary16 codebook entries skim_pack writes for the

@@ -23,6 +23,7 @@ MAX_M = 32768
 EXPORTS = ["skim_create", "skim_destroy", "skim_last_error", "skim_workspace_bytes", "skim_set_workspace",
            "skim_profile_enable", "skim_profile_last",
            "skim_error_table", "skim_error_table_lfull", "skim_cluster_rows", "skim_select_allocated", "skim_greedy_allocate", "skim_greedy_allocate_device",
+           "skim_dp_allocate_scratch_bytes", "skim_dp_allocate",
            "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_layer_loss", "skim_scale_step", "skim_train_scale", "skim_unpack", "skim_dequant_matvec", "skim_hessian_from_activations"]
 
 
@@ -68,6 +69,9 @@ def load_library():
         lib.skim_select_allocated.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         lib.skim_greedy_allocate.argtypes = [vp, vp, i64, i32, i32, dbl, vp, vp, vp]
         lib.skim_greedy_allocate_device.argtypes = [vp, vp, i64, i32, i32, dbl, vp, vp]
+        lib.skim_dp_allocate_scratch_bytes.argtypes = [i64, i32, i32, dbl]
+        lib.skim_dp_allocate_scratch_bytes.restype = C.c_size_t
+        lib.skim_dp_allocate.argtypes = [vp, vp, i64, i32, i32, dbl, vp, vp, vp, C.c_size_t]
         lib.skim_packed_words.argtypes = [vp, i64, i64]
         lib.skim_packed_words.restype = i64
         lib.skim_codebook_entries.argtypes = [vp, i64]
@@ -251,6 +255,22 @@ class Context:
         self.ensure_workspace(n, 16)
         self._check(self.lib.skim_greedy_allocate_device(self.h, _dp(E), n, bmin, bmax, float(avg_bits),
                                                          _dp(out["bits"]), _dp(out["info"])))
+        return out
+
+    def dp_allocate(self, E, avg_bits, bmin=1, bmax=4):
+        """The exact optimum of the allocation problem (knapsack dynamic programme, unit costs) on the device.
+        Returns dict(bits uint8[n], info float64[3] = total error, bits spent, budget) of device tensors."""
+        t = self.torch
+        n = E.shape[0]
+        assert E.dtype == t.float64 and E.is_contiguous() and E.shape[1] == bmax - bmin + 1
+        need = self.lib.skim_dp_allocate_scratch_bytes(n, bmin, bmax, float(avg_bits))
+        if need == 0:
+            raise SkimError(-3, "skim_dp_allocate: bit range or budget not representable")
+        scratch = self.empty((need,), t.uint8)
+        out = dict(bits=self.empty((n,), t.uint8), info=self.empty((3,), t.float64))
+        self._check(self.lib.skim_dp_allocate(self.h, _dp(E), n, bmin, bmax, float(avg_bits), _dp(out["bits"]),
+                                              _dp(out["info"]), _dp(scratch), need))
+        out["_scratch"] = scratch   # the kernels run asynchronously: the buffer lives as long as the result
         return out
 
     def pack(self, W, bits, centroids, upper, alpha=None, want_dW=False, bits_host=None, max_size=False, out=None):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libskim.so")
-SOURCES = ["skim_ctx.hip", "skim_cluster.hip", "skim_alloc.cpp", "skim_alloc_dev.hip", "skim_pack.hip", "skim_unpack.hip", "skim_loss.hip", "skim_lfull.hip", "skim_hessian.hip"]
+SOURCES = ["skim_ctx.hip", "skim_cluster.hip", "skim_alloc.cpp", "skim_alloc_dev.hip", "skim_alloc_dp.hip", "skim_pack.hip", "skim_unpack.hip", "skim_loss.hip", "skim_lfull.hip", "skim_hessian.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

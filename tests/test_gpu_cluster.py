@@ -288,3 +288,39 @@ def test_device_greedy_equals_host_and_oracle(ctx, gpu_lib, kind, n, avg):
     assert np.array_equal(info[:8], np.bincount(bits_h, minlength=8))
     if n <= 4096:
         assert np.array_equal(got, oracle.greedy(E, avg)["bits"])
+
+
+@pytest.mark.parametrize("kind", ["smooth", "ties", "nonmonotone", "flat"])
+@pytest.mark.parametrize("n,avg,bmin,bmax", [(1, 2.0, 1, 4), (7, 1.0, 1, 4), (7, 4.0, 1, 4), (100, 2.5, 1, 4),
+                                             (129, 3.2, 1, 4), (1000, 3.2, 1, 4), (4096, 3.2, 1, 4),
+                                             (3000, 3.999, 1, 4), (5000, 3.4, 3, 4), (300, 2.5, 2, 3)])
+def test_dp_allocation_equals_oracle(ctx, kind, n, avg, bmin, bmax):
+    """The exact allocation: same bits, same total, same spent bits as the oracle's recurrence (same order of
+    additions and the same tie rules, so nothing is left to rounding).  The sizes put the states in one
+    workgroup (n <= 2600 at three extra bits) and in several, and the rows in one launch and in many."""
+    rng = np.random.default_rng(n * 11 + len(kind))
+    E = np.ascontiguousarray(_tables(rng, n, kind)[:, bmin - 1:bmax])
+    out = ctx.dp_allocate(dev(E), avg, bmin=bmin, bmax=bmax)
+    torch.cuda.synchronize()
+    ref = oracle.dp_allocate(E, avg, bmin=bmin, bmax=bmax)
+    info = out["info"].cpu().numpy()
+    assert np.array_equal(out["bits"].cpu().numpy(), ref["bits"])
+    assert info[0] == ref["total"] and info[1] == ref["spent"] and info[2] == ref["budget"]
+    if kind in ("smooth",):
+        # reductions that shrink with the bits: Alg. 1 reaches the same optimum
+        g = ctx.greedy_allocate_device(dev(E), avg, bmin=bmin, bmax=bmax)
+        gb = g["bits"].cpu().numpy()
+        tot = E[np.arange(n), gb - bmin].sum()
+        assert tot == pytest.approx(ref["total"], rel=1e-12)
+
+
+def test_dp_allocation_rejects_bad_arguments(ctx):
+    E = dev(np.zeros((10, 4)))
+    with pytest.raises(Exception):
+        ctx.dp_allocate(E, 0.5)
+    with pytest.raises(Exception):
+        ctx.dp_allocate(E, 4.5)
+    assert ctx.lib.skim_dp_allocate_scratch_bytes(10, 1, 6, 2.0) == 0      # more than three bits apart
+    out = ctx.dp_allocate(E, 2.0)
+    torch.cuda.synchronize()
+    assert np.all(out["bits"].cpu().numpy() == 1) and out["info"][0].item() == 0.0   # nothing to gain: no bit spent
