@@ -127,6 +127,24 @@ skim_status skim_select_allocated(skim_ctx *ctx, int64_t n, int bmin, int bmax, 
                                   const float *upper_all, double *centroids, float *upper,
                                   double *err);
 
+/* The least value of the clustering objective (the S-diag form, as in
+ * skim_error_table) that ANY assignment of a row to at most 2^b clusters can
+ * have, b = bmin..bmax: the floor under what the K-means of Alg. 3 reaches from
+ * its start, a yardstick and not a step of the quantisation path.  In one
+ * dimension the best assignment cuts the sorted values into intervals, which a
+ * dynamic programme over the sorted row finds exactly (filled by halving, using
+ * that the best cut moves right with the prefix).  Arguments as
+ * skim_error_table (alpha may be NULL; a row without sensitivity mass counts
+ * unit weights).  E_opt: dev float64 n x (bmax-bmin+1).  Costs are formed from
+ * float64 prefix sums of s, s w, s w^2, so an entry carries an absolute error of
+ * a few 1e-16 * sum_j s w^2 of its row.  scratch: dev, 256-byte aligned, at
+ * least skim_kmeans_optimal_scratch_bytes(n, m) bytes (44 bytes per column and
+ * resident workgroup); the registered workspace is used for the sort. */
+size_t skim_kmeans_optimal_scratch_bytes(int64_t n, int64_t m);
+skim_status skim_kmeans_optimal(skim_ctx *ctx, const float *W, const float *S, const float *alpha,
+                                int64_t n, int64_t m, int64_t ld, int bmin, int bmax, double *E_opt,
+                                void *scratch, size_t scratch_bytes);
+
 /* ---- allocation --------------------------------------------------------- */
 
 /* Greedy bit allocation (Alg. 1), host memory only.  E: host float64

@@ -23,7 +23,7 @@ MAX_M = 32768
 EXPORTS = ["skim_create", "skim_destroy", "skim_last_error", "skim_workspace_bytes", "skim_set_workspace",
            "skim_profile_enable", "skim_profile_last",
            "skim_error_table", "skim_error_table_lfull", "skim_cluster_rows", "skim_select_allocated", "skim_greedy_allocate", "skim_greedy_allocate_device",
-           "skim_dp_allocate_scratch_bytes", "skim_dp_allocate",
+           "skim_dp_allocate_scratch_bytes", "skim_dp_allocate", "skim_kmeans_optimal_scratch_bytes", "skim_kmeans_optimal",
            "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_layer_loss", "skim_scale_step", "skim_train_scale", "skim_unpack", "skim_dequant_matvec", "skim_hessian_from_activations"]
 
 
@@ -72,6 +72,9 @@ def load_library():
         lib.skim_dp_allocate_scratch_bytes.argtypes = [i64, i32, i32, dbl]
         lib.skim_dp_allocate_scratch_bytes.restype = C.c_size_t
         lib.skim_dp_allocate.argtypes = [vp, vp, i64, i32, i32, dbl, vp, vp, vp, C.c_size_t]
+        lib.skim_kmeans_optimal_scratch_bytes.argtypes = [i64, i64]
+        lib.skim_kmeans_optimal_scratch_bytes.restype = C.c_size_t
+        lib.skim_kmeans_optimal.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, vp, vp, C.c_size_t]
         lib.skim_packed_words.argtypes = [vp, i64, i64]
         lib.skim_packed_words.restype = i64
         lib.skim_codebook_entries.argtypes = [vp, i64]
@@ -256,6 +259,21 @@ class Context:
         self._check(self.lib.skim_greedy_allocate_device(self.h, _dp(E), n, bmin, bmax, float(avg_bits),
                                                          _dp(out["bits"]), _dp(out["info"])))
         return out
+
+    def kmeans_optimal(self, W, S, alpha=None, bmin=1, bmax=4):
+        """Least clustering error any assignment of each row to at most 2^b clusters can have (exact interval
+        dynamic programme on the sorted row).  Returns a device float64 tensor n x (bmax-bmin+1)."""
+        t = self.torch
+        n, m = W.shape
+        assert W.dtype == t.float32 and S.dtype == t.float32 and W.stride(1) == 1 and S.stride() == W.stride()
+        self.ensure_workspace(n, m)
+        need = self.lib.skim_kmeans_optimal_scratch_bytes(n, m)
+        scratch = self.empty((max(need, 256),), t.uint8)
+        E = self.empty((n, bmax - bmin + 1), t.float64)
+        self._check(self.lib.skim_kmeans_optimal(self.h, _dp(W), _dp(S), _dp(alpha), n, m, W.stride(0), bmin, bmax,
+                                                 _dp(E), _dp(scratch), need))
+        self._keep = scratch    # the kernels run asynchronously
+        return E
 
     def dp_allocate(self, E, avg_bits, bmin=1, bmax=4):
         """The exact optimum of the allocation problem (knapsack dynamic programme, unit costs) on the device.

@@ -1314,6 +1314,247 @@ __global__ void select_kernel(long long n, int bmin, int bmax, const uint8_t *bi
     if (err && k == 0) err[i] = E[i * nb + (b - bmin)];
 }
 
+// ---------------------------------------------------------------------------------------------
+// The least error ANY assignment of a row to at most K clusters can have (K = 2^b): the floor under
+// what the Lloyd iterations reach from their quantile start.  In one dimension an optimal assignment
+// cuts the sorted values into intervals, so with prefix sums A = sum s, B = sum s w, C = sum s w^2
+// over the sorted keys
+//     cost(i, j) = (C_j - C_i) - (B_j - B_i)^2 / (A_j - A_i)      (keys i..j-1; 0 without mass)
+//     D_1[j] = cost(0, j),   D_k[j] = min_{0 <= i <= j} D_{k-1}[i] + cost(i, j).
+// The leftmost minimiser opt_k[j] does not decrease with j (the cost is a Monge array), so every
+// layer is filled by halving: j = the odd multiples of a stride h, each searching only
+// opt[j - h] .. opt[j + h], for h = 2^(L-1), 2^(L-2), ..., 1.  One workgroup per row walks the
+// levels; a level's positions are shared out by the length of their ranges (see OPT_S below).  A, B, C and D live in
+// global memory (40 bytes per key: more than the LDS holds), read with consecutive lanes on
+// consecutive i; the cuts opt live in LDS when the row is short enough.
+// ---------------------------------------------------------------------------------------------
+constexpr int OPT_THREADS = 1024;
+constexpr int OPT_WAVES = OPT_THREADS / 64;
+constexpr int OPT_MAX_WG = 1024;                // workgroups (each with its own scratch) at most
+
+struct OptParams {
+    const u64 *keys;     // sorted keys, m per row
+    int m, bmin, bmax;
+    long long n;
+    double *E;           // n x (bmax - bmin + 1)
+    double *scratch;     // per workgroup: 5 arrays of mp doubles (A, B, C, D, D') and mp ints (opt)
+    long long mp;        // m + 2 rounded up to a multiple of 32
+    int opt_in_lds;
+};
+
+__device__ __forceinline__ bool opt_less(double a, int ia, double b, int ib) { return a < b || (a == b && ia < ib); }
+
+// min over [lo, hi] of D[i] + cost(i, j) for the candidates of lane r of a team of G lanes (i = lo + r,
+// lo + r + G, ...), smallest i among equals.  Four candidates are in flight at once (the loop is bound by the
+// latency of its loads); an index past hi is clamped to hi, which only repeats a valid candidate.
+__device__ __forceinline__ void opt_scan(const double *__restrict__ A, const double *__restrict__ B,
+                                         const double *__restrict__ C, const double *__restrict__ Dp, int j, int lo,
+                                         int hi, int r, int G, double &best, int &arg) {
+    constexpr int U = 4;
+    const double Aj = A[j], Bj = B[j], Cj = C[j];
+    best = INFINITY;
+    arg = 0x7fffffff;
+    for (int i0 = lo + r; i0 <= hi; i0 += U * G) {
+        double a[U], b[U], c[U], d[U];
+        int idx[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            idx[u] = min(i0 + u * G, hi);
+            a[u] = A[idx[u]];
+            b[u] = B[idx[u]];
+            c[u] = C[idx[u]];
+            d[u] = Dp[idx[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const double dA = Aj - a[u], dB = Bj - b[u], dC = Cj - c[u];
+            double cost = dA > 0.0 ? dC - quick_div(dB * dB, dA) : 0.0;
+            cost = cost > 0.0 ? cost : 0.0;
+            const double v = d[u] + cost;
+            if (v < best) { best = v; arg = idx[u]; }
+        }
+    }
+}
+
+__device__ __forceinline__ void opt_bounds(const int *opt, int j, int h, int m, int &lo, int &hi) {
+    lo = opt[j - h];                          // opt[0] = 0
+    hi = (j + h <= m) ? min(opt[j + h], j) : j;
+    hi = max(hi, lo);
+}
+
+// One position by a team of G lanes (a power of two, at most 64; all lanes of the wave call this together,
+// `valid` says whether the team has a position): scan, reduce over the team, lane 0 of the team writes.
+__device__ __forceinline__ void opt_team(const double *A, const double *B, const double *C, const double *Dp,
+                                         double *Dn, int *opt, int h, int m, bool valid, int q, int r, int G) {
+    const int j = valid ? h * (2 * q + 1) : 0;
+    double best = INFINITY;
+    int arg = 0x7fffffff;
+    if (valid) {
+        int lo, hi;
+        opt_bounds(opt, j, h, m, lo, hi);
+        opt_scan(A, B, C, Dp, j, lo, hi, r, G, best, arg);
+    }
+    for (int o = G >> 1; o >= 1; o >>= 1) {
+        const double ob = __shfl_xor(best, o, 64);
+        const int oa = __shfl_xor(arg, o, 64);
+        if (opt_less(ob, oa, best, arg)) { best = ob; arg = oa; }
+    }
+    if (valid && r == 0) { Dn[j] = best; opt[j] = arg; }
+}
+
+// Ranges of one level differ wildly in length (where the best cut jumps, one position inherits the whole
+// jump as its range, on every level), so positions are sorted into four classes by the number of
+// candidates: up to OPT_S by one thread, up to OPT_M by 16 lanes, up to OPT_L by a wavefront, longer ones
+// by the whole workgroup.
+constexpr int OPT_S = 16, OPT_M = 256, OPT_L = 4096;
+constexpr int OPT_MCAP = 4096, OPT_LCAP = 256, OPT_XCAP = 16;
+
+__global__ void __launch_bounds__(OPT_THREADS) kmeans_optimal_kernel(OptParams prm) {
+    __shared__ double sc[3][OPT_WAVES];
+    __shared__ double wb[OPT_XCAP][OPT_WAVES];
+    __shared__ int wa[OPT_XCAP][OPT_WAVES];
+    __shared__ unsigned short listM[OPT_MCAP], listL[OPT_LCAP], listX[OPT_XCAP];
+    __shared__ int cntM[2], cntL[2], cntX[2];
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = prm.m;
+    double *A = prm.scratch + (long long)blockIdx.x * (5 * prm.mp + prm.mp / 2);
+    double *B = A + prm.mp, *C = B + prm.mp, *D0 = C + prm.mp, *D1 = D0 + prm.mp;
+    // the cuts of the current layer: in LDS when the row fits (every level starts by reading two of them)
+    int *opt = prm.opt_in_lds ? (int *)smem : (int *)(D1 + prm.mp);
+    int L = 1;
+    while ((1 << L) < m + 1) ++L;             // positions 1..m < 2^L
+    const int chunk = (m + OPT_THREADS - 1) / OPT_THREADS;
+    const int Kmax = 1 << prm.bmax;
+    const int nb = prm.bmax - prm.bmin + 1;
+
+    if (tid == 0) { cntM[0] = cntM[1] = 0; cntL[0] = cntL[1] = 0; cntX[0] = cntX[1] = 0; }
+    int lists = 0;                            // levels done so far, over all layers and rows
+    for (long long row = blockIdx.x; row < prm.n; row += gridDim.x) {
+        const u64 *keys = prm.keys + row * (long long)m;
+        // ---- prefix sums over the sorted keys
+        const int j0 = min(m, tid * chunk), j1 = min(m, j0 + chunk);
+        double a = 0.0, b = 0.0, c = 0.0;
+        for (int j = j0; j < j1; ++j) {
+            const u64 el = keys[j];
+            const double s = (double)elem_s(el), w = (double)elem_w(el);
+            a += s;
+            b = fma(s, w, b);
+            c = fma(s * w, w, c);
+        }
+        double ia = a, ib = b, ic = c;        // inclusive scan over the wave, then over the waves
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const double ta = __shfl_up(ia, o, 64), tb = __shfl_up(ib, o, 64), tc = __shfl_up(ic, o, 64);
+            if (lane >= o) { ia += ta; ib += tb; ic += tc; }
+        }
+        if (lane == 63) { sc[0][wave] = ia; sc[1][wave] = ib; sc[2][wave] = ic; }
+        __syncthreads();
+        double pa = ia - a, pb = ib - b, pc = ic - c;     // exclusive within the wave
+        for (int w = 0; w < wave; ++w) { pa += sc[0][w]; pb += sc[1][w]; pc += sc[2][w]; }
+        if (tid == 0) { A[0] = 0.0; B[0] = 0.0; C[0] = 0.0; D0[0] = 0.0; D1[0] = 0.0; opt[0] = 0; }
+        for (int j = j0; j < j1; ++j) {
+            const u64 el = keys[j];
+            const double s = (double)elem_s(el), w = (double)elem_w(el);
+            pa += s;
+            pb = fma(s, w, pb);
+            pc = fma(s * w, w, pc);
+            A[j + 1] = pa; B[j + 1] = pb; C[j + 1] = pc;
+            double c1 = pa > 0.0 ? pc - quick_div(pb * pb, pa) : 0.0;
+            D0[j + 1] = c1 > 0.0 ? c1 : 0.0;            // one cluster
+        }
+        __syncthreads();
+
+        double *Dp = D0, *Dn = D1;
+        for (int k = 2; k <= Kmax; ++k) {
+            for (int lev = 0; lev < L; ++lev) {
+                const int h = 1 << (L - 1 - lev);
+                const int cnt = (m / h + 1) >> 1;         // odd multiples of h that are <= m
+                const int cb = lists & 1;                 // this level's list counters (zeroed a level ago)
+                ++lists;
+                // short ranges at once, the others onto the lists
+                for (int q = tid; q < cnt; q += OPT_THREADS) {
+                    const int j = h * (2 * q + 1);
+                    int lo, hi;
+                    opt_bounds(opt, j, h, m, lo, hi);
+                    const int len = hi - lo + 1;
+                    int slot = -1;
+                    if (len > OPT_L) {
+                        slot = atomicAdd(&cntX[cb], 1);
+                        if (slot < OPT_XCAP) listX[slot] = (unsigned short)q;
+                        else slot = -1;
+                    }
+                    if (slot < 0 && len > OPT_M) {
+                        slot = atomicAdd(&cntL[cb], 1);
+                        if (slot < OPT_LCAP) listL[slot] = (unsigned short)q;
+                        else slot = -1;
+                    }
+                    if (slot < 0 && len > OPT_S) {
+                        slot = atomicAdd(&cntM[cb], 1);
+                        if (slot < OPT_MCAP) listM[slot] = (unsigned short)q;
+                        else slot = -1;
+                    }
+                    if (slot < 0) {                       // short, or a list is full: this thread alone
+                        double best;
+                        int arg;
+                        opt_scan(A, B, C, Dp, j, lo, hi, 0, 1, best, arg);
+                        Dn[j] = best;
+                        opt[j] = arg;
+                    }
+                }
+                __syncthreads();
+                const int nM = min(cntM[cb], OPT_MCAP), nL = min(cntL[cb], OPT_LCAP), nX = min(cntX[cb], OPT_XCAP);
+                if (tid == 0) { cntM[cb ^ 1] = 0; cntL[cb ^ 1] = 0; cntX[cb ^ 1] = 0; }
+                for (int i0 = 0; i0 < nM; i0 += OPT_THREADS / 16) {
+                    const int idx = i0 + (tid >> 4);
+                    const bool valid = idx < nM;
+                    opt_team(A, B, C, Dp, Dn, opt, h, m, valid, valid ? listM[idx] : 0, tid & 15, 16);
+                }
+                for (int i0 = 0; i0 < nL; i0 += OPT_WAVES) {
+                    const int idx = i0 + wave;
+                    const bool valid = idx < nL;
+                    opt_team(A, B, C, Dp, Dn, opt, h, m, valid, valid ? listL[idx] : 0, lane, 64);
+                }
+                if (nX > 0) {
+                    for (int x = 0; x < nX; ++x) {
+                        const int j = h * (2 * (int)listX[x] + 1);
+                        int lo, hi;
+                        opt_bounds(opt, j, h, m, lo, hi);
+                        double best;
+                        int arg;
+                        opt_scan(A, B, C, Dp, j, lo, hi, tid, OPT_THREADS, best, arg);
+#pragma unroll
+                        for (int o = 32; o >= 1; o >>= 1) {
+                            const double ob = __shfl_xor(best, o, 64);
+                            const int oa = __shfl_xor(arg, o, 64);
+                            if (opt_less(ob, oa, best, arg)) { best = ob; arg = oa; }
+                        }
+                        if (lane == 0) { wb[x][wave] = best; wa[x][wave] = arg; }
+                    }
+                    __syncthreads();
+                    if (tid < nX) {
+                        double best = wb[tid][0];
+                        int arg = wa[tid][0];
+                        for (int w = 1; w < OPT_WAVES; ++w)
+                            if (opt_less(wb[tid][w], wa[tid][w], best, arg)) { best = wb[tid][w]; arg = wa[tid][w]; }
+                        const int j = h * (2 * (int)listX[tid] + 1);
+                        Dn[j] = best;
+                        opt[j] = arg;
+                    }
+                }
+                __syncthreads();                           // the level's opt and D are read by the next
+            }
+            if (tid == 0 && (k & (k - 1)) == 0) {
+                int bb = 0;
+                while ((1 << bb) < k) ++bb;
+                if (bb >= prm.bmin) prm.E[row * nb + (bb - prm.bmin)] = Dn[m];
+            }
+            double *t = Dp; Dp = Dn; Dn = t;
+            __syncthreads();
+        }
+    }
+}
+
 size_t sort_lds_bytes(int P) { return (size_t)(P + P / 16) * 8; }
 
 size_t lloyd_lds_bytes(int m) { return 2 * (size_t)level_map((m + 15) >> 4).bytes + 128 * sizeof(double); }
@@ -1355,7 +1596,8 @@ skim_status carve_cluster_ws(skim_ctx *ctx, ClusterParams &prm, int64_t n, doubl
     return SKIM_OK;
 }
 
-skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n) {
+// sort_only: stop once the sorted keys (unit weights already put in for rows without mass) are in prm.keys
+skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n, bool sort_only = false) {
     int threads = prm.P / EPT;
     if (threads < MIN_THREADS) threads = MIN_THREADS;
     const size_t lds = sort_lds_bytes(prm.P);
@@ -1381,6 +1623,10 @@ skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n) {
     if (prm.nseg > 1) {
         hipLaunchKernelGGL(merge_kernel, dim3((unsigned)n), dim3(MERGE_THREADS), 0, ctx->stream, prm);
         hipLaunchKernelGGL(sums_kernel, dim3((unsigned)n), dim3(1024), 0, ctx->stream, prm);
+    }
+    if (sort_only) {
+        SKIM_HIP(ctx, hipGetLastError());
+        return SKIM_OK;
     }
     if (ctx->profiling) SKIM_HIP(ctx, hipEventRecord(ctx->ev[1], ctx->stream));
     if (prm.m & 15)
@@ -1440,6 +1686,47 @@ extern "C" skim_status skim_cluster_rows(skim_ctx *ctx, const float *W, const fl
     prm.labels = labels; prm.stride = 16;
     if ((st = carve_cluster_ws(ctx, prm, n, nullptr)) != SKIM_OK) return st;
     return launch_cluster(ctx, prm, n);
+}
+
+extern "C" size_t skim_kmeans_optimal_scratch_bytes(int64_t n, int64_t m) {
+    if (n < 1 || m < 1 || m > SKIM_MAX_M) return 0;
+    const size_t mp = ((size_t)m + 2 + 31) & ~(size_t)31;
+    const size_t wgs = n < OPT_MAX_WG ? (size_t)n : (size_t)OPT_MAX_WG;
+    return wgs * mp * 44 + 256;
+}
+
+extern "C" skim_status skim_kmeans_optimal(skim_ctx *ctx, const float *W, const float *S, const float *alpha,
+                                           int64_t n, int64_t m, int64_t ld, int bmin, int bmax, double *E_opt,
+                                           void *scratch, size_t scratch_bytes) {
+    skim_status st = skim_enter(ctx);
+    if (st != SKIM_OK) return st;
+    if (!W || !S || !E_opt || !scratch) SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_kmeans_optimal: NULL argument");
+    if (bmin < 1 || bmax > SKIM_MAX_BITS || bmin > bmax) SKIM_FAIL(ctx, SKIM_ERR_ARG, "bit range [%d,%d] outside 1..4", bmin, bmax);
+    if (n < 1 || n > 0x7fffffff) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "n = %lld out of range", (long long)n);
+    if (m < (1 << bmax) || m > SKIM_MAX_M || ld < m)
+        SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "need 2^bmax <= m <= %d and ld >= m (m=%lld, ld=%lld)", SKIM_MAX_M, (long long)m, (long long)ld);
+    if (((uintptr_t)scratch & 255) != 0) SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_kmeans_optimal: scratch not 256-byte aligned");
+    const size_t need = skim_kmeans_optimal_scratch_bytes(n, m);
+    if (scratch_bytes < need)
+        SKIM_FAIL(ctx, SKIM_ERR_WORKSPACE, "skim_kmeans_optimal: scratch of %zu bytes, %zu needed", scratch_bytes, need);
+    ClusterParams prm{};
+    prm.W = W; prm.S = S; prm.alpha = alpha; prm.ld = ld; prm.m = (int)m; prm.iters = 1;
+    prm.bmin = bmin; prm.bmax = bmax; prm.stride = (2 << bmax) - (1 << bmin);
+    if ((st = carve_cluster_ws(ctx, prm, n, nullptr)) != SKIM_OK) return st;
+    if ((st = launch_cluster(ctx, prm, n, true)) != SKIM_OK) return st;
+    OptParams op{};
+    op.keys = prm.keys; op.m = (int)m; op.bmin = bmin; op.bmax = bmax; op.n = n; op.E = E_opt;
+    op.scratch = (double *)scratch;
+    op.mp = ((long long)m + 2 + 31) & ~31ll;
+    long long grid = 2ll * ctx->num_cu;
+    if (grid > OPT_MAX_WG) grid = OPT_MAX_WG;
+    if (grid > n) grid = n;
+    const size_t opt_lds = (size_t)op.mp * sizeof(int);
+    op.opt_in_lds = opt_lds <= 65536 - 16384;     // no more than the default limit, with the static arrays
+    hipLaunchKernelGGL(kmeans_optimal_kernel, dim3((unsigned)grid), dim3(OPT_THREADS), op.opt_in_lds ? opt_lds : 0,
+                       ctx->stream, op);
+    SKIM_HIP(ctx, hipGetLastError());
+    return SKIM_OK;
 }
 
 extern "C" skim_status skim_select_allocated(skim_ctx *ctx, int64_t n, int bmin, int bmax, const uint8_t *bits,

@@ -324,3 +324,44 @@ def test_dp_allocation_rejects_bad_arguments(ctx):
     out = ctx.dp_allocate(E, 2.0)
     torch.cuda.synchronize()
     assert np.all(out["bits"].cpu().numpy() == 1) and out["info"][0].item() == 0.0   # nothing to gain: no bit spent
+
+
+def _optimal_close(got, ref, W, S, alpha=None):
+    """An entry is a difference of float64 prefix sums of s w^2: absolute error of a few ulps of the row's whole
+    second moment, on top of the relative tolerance of the other floating-point outputs."""
+    scale = np.empty(W.shape[0])
+    for i in range(W.shape[0]):
+        w, s = (W[i], S[i]) if alpha is None else oracle.scale_row(W[i], S[i], alpha)
+        s = s.astype(np.float64) if np.any(s > 0) else np.ones(len(s))
+        scale[i] = np.sum(s * w.astype(np.float64) ** 2)
+    return np.abs(got - ref) <= RTOL * np.abs(ref) + 1e-12 * scale[:, None], scale[:, None]
+
+
+@pytest.mark.parametrize("n,m,dup,zs", [(24, 16, 0.0, 0.0), (24, 100, 0.2, 0.3), (20, 257, 0.0, 0.0), (12, 1000, 0.05, 0.1),
+                                        (6, 2049, 0.0, 0.0)])
+def test_optimal_clustering_error_matches_oracle(ctx, n, m, dup, zs):
+    """The exact floor of the clustering error against the oracle's O(K m^2) programme (the GPU fills each layer
+    by halving with the monotone-cut bounds): same values, and never above what the Lloyd iterations reach."""
+    W, S = skim_synth.make_ws_small(m + n, n, m, dup_frac=dup, zero_s_frac=zs)
+    S[1] = 0.0                                   # no mass: unit weights
+    W[2] = np.float32(0.5)                       # one value: nothing to lose
+    W[3] = np.round(W[3] * 50) / 50              # few distinct values
+    got = ctx.kmeans_optimal(dev(W), dev(S))
+    table = ctx.error_table(dev(W), dev(S))["E"]
+    torch.cuda.synchronize()
+    got, table = got.cpu().numpy(), table.cpu().numpy()
+    ref = oracle.kmeans_optimal_table(W, S)
+    close, scale = _optimal_close(got, ref, W, S)
+    assert np.all(close)
+    assert np.all(got[2] <= 1e-12 * scale[2]) and np.all(np.diff(got, axis=1) <= 1e-12 * scale)
+    assert np.all(got <= table * (1 + 1e-9) + 1e-12 * scale)
+
+
+def test_optimal_clustering_error_scaled_inputs_and_bit_subset(ctx):
+    W, S = skim_synth.make_ws_small(77, 16, 300)
+    rng = np.random.default_rng(5)
+    alpha = rng.uniform(0.5, 2.0, 300).astype(np.float32)
+    got = ctx.kmeans_optimal(dev(W), dev(S), alpha=dev(alpha), bmin=2, bmax=3)
+    torch.cuda.synchronize()
+    ref = oracle.kmeans_optimal_table(W, S, alpha=alpha, bmin=2, bmax=3)
+    assert got.shape == (16, 2) and np.all(_optimal_close(got.cpu().numpy(), ref, W, S, alpha)[0])

@@ -110,6 +110,35 @@ def test_config2_metric_layer_down_projection(ctx, gpu_lib):
     check_alloc_labels_pack(ctx, gpu_lib, W, S, ref, out, clean, Wd, Sd, 3.2, want_dW=True)
 
 
+def test_config2_metric_layer_exact_bounds(ctx, gpu_lib):
+    """The two yardsticks at the size bench.py reports them: the least clustering error of every row (sampled
+    rows against the oracle's O(K m^2) programme, every row against the error table it must not exceed), and the
+    knapsack optimum of the allocation on the device's own table (all rows against the oracle's recurrence)."""
+    W, S = skim_synth.make_ws(2, 2)
+    Wd, Sd = dev(W), dev(S)
+    E = ctx.error_table(Wd, Sd)["E"]
+    got = ctx.kmeans_optimal(Wd, Sd)
+    dp = ctx.dp_allocate(E, 3.2)
+    torch.cuda.synchronize()
+    E, got = E.cpu().numpy(), got.cpu().numpy()
+    scale = np.sum(S.astype(np.float64) * W.astype(np.float64) ** 2, axis=1, keepdims=True)
+    assert np.isfinite(got).all() and (got >= 0).all()
+    assert np.all(got <= E * (1 + 1e-9) + 1e-12 * scale)
+    assert np.all(np.diff(got, axis=1) <= 1e-12 * scale)
+    for i in (0, 1777, 4095):
+        ref = oracle.kmeans_optimal_row(W[i], S[i])
+        assert np.all(np.abs(got[i] - ref) <= RTOL * ref + 1e-12 * scale[i]), (i, got[i], ref)
+    ref = oracle.dp_allocate(E, 3.2)
+    info = dp["info"].cpu().numpy()
+    assert np.array_equal(dp["bits"].cpu().numpy(), ref["bits"])
+    assert info[0] == ref["total"] and info[1] == ref["spent"] and info[2] == ref["budget"] == 13107
+    g = ctx.greedy_allocate_device(dev(E), 3.2)["bits"].cpu().numpy()
+    gt = E[np.arange(4096), g - 1].sum()
+    assert ref["total"] <= gt
+    print(f"\n[4096x11008] Lloyd / least possible error per bit width = {(E.sum(0) / got.sum(0)).round(3).tolist()}, "
+          f"greedy / optimal allocation = {gt / ref['total']:.5f}")
+
+
 def test_config2_joint_allocation_over_three_matrices(ctx, gpu_lib):
     tables, costs = [], []
     for mi in range(3):
