@@ -58,6 +58,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-scale-loop", action="store_true")
+    ap.add_argument("--no-yardsticks", action="store_true", help="skip the exact-optimum yardsticks (extra figures only)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain elementwise copy of the W matrix (reads and writes n*m*4 bytes): "
                          "the known-size kernel that calibrates the HBM byte counters of a rocprofv3 --pmc run")
@@ -203,6 +204,26 @@ def main():
     out["dequant_matvec"] = {"ms": round(mv_ms, 4), "packed_bytes": int(packed_bytes),
                              "GBps": round(packed_bytes / (mv_ms * 1e-3) / 1e9, 1),
                              "frac_of_hbm_peak": round(packed_bytes / (mv_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    # yardsticks (not steps of the path): the least error any clustering / any allocation could reach
+    E_d = table["E"]
+    if not args.no_yardsticks:
+        y0, y1, y2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        ctx.kmeans_optimal(W, S)
+        ctx.dp_allocate(E_d, AVG_BITS)
+        torch.cuda.synchronize()
+        y0.record(stream)
+        opt_d = ctx.kmeans_optimal(W, S)
+        y1.record(stream)
+        dp = ctx.dp_allocate(E_d, AVG_BITS)
+        y2.record(stream)
+        torch.cuda.synchronize()
+        E_h = E_d.cpu().numpy()
+        out["yardsticks"] = {
+            "kmeans_optimal_ms": round(y0.elapsed_time(y1), 3),
+            "lloyd_error_over_least_possible_per_bit_width": (E_h.sum(0) / opt_d.cpu().numpy().sum(0)).round(4).tolist(),
+            "dp_allocate_ms": round(y1.elapsed_time(y2), 3),
+            "greedy_error_over_optimal_allocation": round(float(E_h[np.arange(n), bits - 1].sum() / dp["info"][0].item()), 6),
+        }
     if not args.no_scale_loop:
         out["scale_loop"] = bench_scale_loop(ctx, torch, np, skim_synth)
     if not args.no_cpu_baseline:
