@@ -92,6 +92,116 @@ __global__ void __launch_bounds__(UNPACK_THREADS) packed_rows_kernel(const uint3
     }
 }
 
+// The matrix-vector product proper: a workgroup takes MV_ROWS packed rows at once so that x and alpha are read
+// once for all of them (one row per workgroup re-reads 8 bytes of x and alpha per weight from L2, far more
+// than the 0.4 bytes of codes the weight costs in HBM).  A lane owns 32 consecutive columns = B whole code
+// words of every row; all its loads of an iteration (8 + 8 float4 of x and alpha, MV_ROWS * B code words) are
+// independent and in flight together.  Rows of different widths may share a workgroup (at the group borders).
+constexpr int MV_THREADS = 256;
+constexpr int MV_ROWS = 8;
+
+template <int B>
+__device__ __forceinline__ double mv_chunk(const uint32_t *__restrict__ rw, uint32_t w0, uint32_t wpr, const float *cbf,
+                                           const float (&al)[32], const double (&xd)[32], bool scaled) {
+    uint32_t wd[B + 1];
+#pragma unroll
+    for (int k = 0; k < B; ++k) wd[k] = (w0 + k < wpr) ? rw[w0 + k] : 0u;
+    wd[B] = 0u;
+    double acc = 0.0;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+        constexpr uint32_t mask = (1u << B) - 1u;
+        const int bit = e * B, wi = bit >> 5, sh = bit & 31;
+        uint32_t v = wd[wi] >> sh;
+        if (sh + B > 32) v |= wd[wi + 1] << (32 - sh);
+        const float c = cbf[v & mask];
+        const float q = scaled ? __fmul_rn(al[e], c) : c;
+        acc = fma((double)q, xd[e], acc);
+    }
+    return acc;
+}
+
+__global__ void __launch_bounds__(MV_THREADS) matvec_rows_kernel(const uint32_t *codes, const long long *gwo,
+                                                                const int *row_perm, const uint16_t *codebooks,
+                                                                const float *alpha, long long n, long long m,
+                                                                const float *x, double *y) {
+    __shared__ float cbf[MV_ROWS][16];
+    __shared__ double red[MV_ROWS][MV_THREADS / 64];
+    __shared__ RowPlace places[MV_ROWS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long long p0 = (long long)blockIdx.x * MV_ROWS;
+    if (tid < MV_ROWS) {
+        RowPlace pl{0, 0, 0};
+        if (p0 + tid < n) pl = place_row(gwo, m, p0 + tid);
+        places[tid] = pl;
+    }
+    __syncthreads();
+    if (tid < MV_ROWS * 16) {
+        const int r = tid >> 4, k = tid & 15;
+        const RowPlace pl = places[r];
+        cbf[r][k] = (pl.b > 0 && k < (1 << pl.b)) ? __half2float(__ushort_as_half(codebooks[pl.cb0 + k])) : 0.0f;
+    }
+    __syncthreads();
+    double acc[MV_ROWS];
+#pragma unroll
+    for (int r = 0; r < MV_ROWS; ++r) acc[r] = 0.0;
+    const uint32_t mm = (uint32_t)m;
+    const uint32_t nchunk = (mm + 31) >> 5;
+    for (uint32_t ch = tid; ch < nchunk; ch += MV_THREADS) {
+        const uint32_t j0 = ch << 5;
+        float al[32];
+        double xd[32];
+        if (j0 + 32 <= mm) {
+            const float4 *x4 = (const float4 *)(x + j0);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const float4 v = x4[k];
+                xd[4 * k] = v.x; xd[4 * k + 1] = v.y; xd[4 * k + 2] = v.z; xd[4 * k + 3] = v.w;
+            }
+            if (alpha) {
+                const float4 *a4 = (const float4 *)(alpha + j0);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const float4 v = a4[k];
+                    al[4 * k] = v.x; al[4 * k + 1] = v.y; al[4 * k + 2] = v.z; al[4 * k + 3] = v.w;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 32; ++e) {
+                const bool in = j0 + e < mm;
+                xd[e] = in ? (double)x[j0 + e] : 0.0;     // columns past the row: code 0 times 0
+                al[e] = (in && alpha) ? alpha[j0 + e] : 1.0f;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < MV_ROWS; ++r) {
+            const RowPlace pl = places[r];
+            const uint32_t *rw = codes + pl.word0;
+            const uint32_t wpr = (uint32_t)((m * pl.b + 31) / 32);
+            switch (pl.b) {
+                case 1: acc[r] += mv_chunk<1>(rw, ch * 1u, wpr, cbf[r], al, xd, alpha != nullptr); break;
+                case 2: acc[r] += mv_chunk<2>(rw, ch * 2u, wpr, cbf[r], al, xd, alpha != nullptr); break;
+                case 3: acc[r] += mv_chunk<3>(rw, ch * 3u, wpr, cbf[r], al, xd, alpha != nullptr); break;
+                case 4: acc[r] += mv_chunk<4>(rw, ch * 4u, wpr, cbf[r], al, xd, alpha != nullptr); break;
+                default: break;
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < MV_ROWS; ++r) {
+        double a = acc[r];
+        for (int d = 32; d >= 1; d >>= 1) a += __shfl_down(a, d, 64);
+        if (lane == 0) red[r][wave] = a;
+    }
+    __syncthreads();
+    if (tid < MV_ROWS && places[tid].b > 0) {
+        double s2 = 0.0;
+        for (int w2 = 0; w2 < MV_THREADS / 64; ++w2) s2 += red[tid][w2];
+        y[row_perm[p0 + tid]] = s2;
+    }
+}
+
 skim_status check_packed(skim_ctx *ctx, const void *codes, const void *gwo, const void *perm, const void *cbs, int64_t n,
                          int64_t m, const char *who) {
     if (!codes || !gwo || !perm || !cbs) SKIM_FAIL(ctx, SKIM_ERR_ARG, "%s: NULL argument", who);
@@ -124,9 +234,14 @@ extern "C" skim_status skim_dequant_matvec(skim_ctx *ctx, const uint32_t *codes,
     if ((st = check_packed(ctx, codes, group_word_offset, row_perm, codebooks_fp16, n, m, "skim_dequant_matvec")) != SKIM_OK)
         return st;
     if (!x || !y) SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_dequant_matvec: x and y must not be NULL");
-    hipLaunchKernelGGL(packed_rows_kernel<true>, dim3((unsigned)n), dim3(UNPACK_THREADS), 0, ctx->stream, codes,
-                       (const long long *)group_word_offset, row_perm, codebooks_fp16, alpha, (long long)m, x, y,
-                       (float *)nullptr);
+    if ((((uintptr_t)x | (uintptr_t)alpha) & 15) == 0)
+        hipLaunchKernelGGL(matvec_rows_kernel, dim3((unsigned)((n + MV_ROWS - 1) / MV_ROWS)), dim3(MV_THREADS), 0,
+                           ctx->stream, codes, (const long long *)group_word_offset, row_perm, codebooks_fp16, alpha,
+                           (long long)n, (long long)m, x, y);
+    else   // x or alpha not aligned for 16-byte loads: one row per workgroup, 4-byte loads
+        hipLaunchKernelGGL(packed_rows_kernel<true>, dim3((unsigned)n), dim3(UNPACK_THREADS), 0, ctx->stream, codes,
+                           (const long long *)group_word_offset, row_perm, codebooks_fp16, alpha, (long long)m, x, y,
+                           (float *)nullptr);
     SKIM_HIP(ctx, hipGetLastError());
     return SKIM_OK;
 }

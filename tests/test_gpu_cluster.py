@@ -230,7 +230,8 @@ def test_argument_errors(ctx, gpu_lib):
         gpu_lib.greedy_allocate(np.zeros((4, 4)), 5.0)
 
 
-@pytest.mark.parametrize("n,m,with_alpha", [(37, 100, False), (64, 257, True), (130, 1500, True), (16, 11008, False)])
+@pytest.mark.parametrize("n,m,with_alpha", [(37, 100, False), (64, 257, True), (130, 1500, True), (16, 11008, False),
+                                            (3, 16, True), (9, 4096, True)])
 def test_unpack_and_dequant_matvec_match_oracle(ctx, gpu_lib, n, m, with_alpha):
     """The packed model read back on the GPU: dense weights bit-exact, matrix-vector product (float64
     accumulation, different summation order) to 1e-12 of the sum of magnitudes."""
@@ -253,6 +254,12 @@ def test_unpack_and_dequant_matvec_match_oracle(ctx, gpu_lib, n, m, with_alpha):
     yref = oracle.dequant_matvec(*args, x, alpha=al)
     scale = np.abs(ref.astype(np.float64)) @ np.abs(x.astype(np.float64))
     assert np.all(np.abs(y.cpu().numpy() - yref) <= 1e-12 * scale)
+    # x at an address that is no multiple of 16: the kernel with 4-byte loads
+    xo = torch.zeros(m + 1, dtype=torch.float32, device="cuda")
+    xo[1:] = dev(x)
+    y2 = ctx.dequant_matvec(pk, m, xo[1:], alpha=ald)
+    torch.cuda.synchronize()
+    assert np.all(np.abs(y2.cpu().numpy() - yref) <= 1e-12 * scale)
 
 
 def _tables(rng, n, kind):
