@@ -92,7 +92,7 @@ extern "C" const char *skim_last_error(const skim_ctx *ctx) { return ctx ? ctx->
 extern "C" size_t skim_workspace_bytes(int64_t n, int64_t m) {
     if (n < 0 || m < 0) return 0;
     const size_t N = (size_t)n, M = (size_t)m;
-    const size_t ntile = (M + 127) / 128, nstrip = (N + 15) / 16;
+    const size_t ntile = (M + 127) / 128, nstrip = (N + 7) / 8;
     size_t b = 0;
     b += 2 * N * M * sizeof(float);      // scale step: dW and P
     b += 2 * N * 16 * sizeof(double);    // centroids and masses from fixed labels

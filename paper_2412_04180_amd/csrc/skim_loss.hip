@@ -21,7 +21,7 @@ constexpr int PREP_THREADS = 256;
 constexpr int BM = 128, BN = 128, BK = 16;
 constexpr int A_STRIDE = BM + 4;   // k-major A tile, padded against bank conflicts of the transposing store
 constexpr int GEMM_THREADS = 256;
-constexpr int STRIP = 16;          // rows per workgroup in the gradient kernel
+constexpr int STRIP = 8;           // rows per workgroup in the gradient kernel
 
 __device__ __forceinline__ double block_sum_256(double x, double *scratch /* >= 4 doubles */) {
     for (int d = 32; d >= 1; d >>= 1) x += __shfl_down(x, d, 64);
@@ -32,20 +32,36 @@ __device__ __forceinline__ double block_sum_256(double x, double *scratch /* >= 
     return scratch[0] + scratch[1] + scratch[2] + scratch[3];
 }
 
+// Per-cluster sums of a row with fixed labels: every wavefront adds into bins of its own in LDS (float64
+// atomic adds), four copies per wavefront picked by the lane so that lanes with the same label seldom meet
+// on one address; the copies are then added in a fixed order.
+constexpr int BIN_COPIES = 4;
+constexpr int BIN_SETS = (PREP_THREADS / 64) * BIN_COPIES;
+
+__device__ __forceinline__ double bin_total(const double (*bins)[16], int k) {
+    double t = 0.0;
+#pragma unroll
+    for (int b = 0; b < BIN_SETS; ++b) t += bins[b][k];
+    return t;
+}
+
 // Per row: weighted cluster sums with fixed labels -> centroids c (n x 16 float64),
 // masses Den (n x 16 float64), and the row of dW (float32).
 __global__ void __launch_bounds__(PREP_THREADS) row_prep_kernel(const float *W, const float *S, const float *alpha,
                                                                 long long m, long long ld, const uint8_t *labels,
                                                                 double *cent, double *Den, float *dW) {
-    __shared__ double red[2][16][4];
+    __shared__ double binD[BIN_SETS][16], binN[BIN_SETS][16];
     __shared__ double csh[16];
     const long long row = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *Wr = W + row * ld, *Sr = S + row * ld;
     const uint8_t *Lr = labels + row * m;
-    double accD[16], accN[16];
-#pragma unroll
-    for (int k = 0; k < 16; ++k) accD[k] = accN[k] = 0.0;
+    static_assert(BIN_SETS * 16 == PREP_THREADS, "one bin per thread to clear");
+    (&binD[0][0])[tid] = 0.0;
+    (&binN[0][0])[tid] = 0.0;
+    __syncthreads();
+    double *myD = binD[wave * BIN_COPIES + (lane & (BIN_COPIES - 1))];
+    double *myN = binN[wave * BIN_COPIES + (lane & (BIN_COPIES - 1))];
     for (long long j = tid; j < m; j += PREP_THREADS) {
         float wt = Wr[j], st = Sr[j];
         if (alpha) {
@@ -54,29 +70,12 @@ __global__ void __launch_bounds__(PREP_THREADS) row_prep_kernel(const float *W, 
             st = __fmul_rn(__fmul_rn(st, a), a);
         }
         const int l = Lr[j] & 15;
-        const double s = (double)st, sw = (double)st * (double)wt;
-#pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            accD[k] += (l == k) ? s : 0.0;
-            accN[k] += (l == k) ? sw : 0.0;
-        }
-    }
-#pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        double d = accD[k], nn = accN[k];
-        for (int o = 32; o >= 1; o >>= 1) {
-            d += __shfl_down(d, o, 64);
-            nn += __shfl_down(nn, o, 64);
-        }
-        if (lane == 0) {
-            red[0][k][wave] = d;
-            red[1][k][wave] = nn;
-        }
+        atomicAdd(&myD[l], (double)st);
+        atomicAdd(&myN[l], (double)st * (double)wt);
     }
     __syncthreads();
     if (tid < 16) {
-        const double d = red[0][tid][0] + red[0][tid][1] + red[0][tid][2] + red[0][tid][3];
-        const double nn = red[1][tid][0] + red[1][tid][1] + red[1][tid][2] + red[1][tid][3];
+        const double d = bin_total(binD, tid), nn = bin_total(binN, tid);
         const double c = d > 0.0 ? nn / d : 0.0;
         csh[tid] = c;
         cent[row * 16 + tid] = c;
@@ -219,52 +218,90 @@ __global__ void __launch_bounds__(1024) loss_finish_kernel(const double *partial
 }
 
 // Gradient terms.  One workgroup walks STRIP consecutive rows; per row it forms
-// Q_ik = sum_{j in k} P_ij alpha_j, then adds each column's term to the thread's
-// private column sums.  gpart[strip][l] is reduced over the strips afterwards.
+// Q_ik = sum_{j in k} P_ij alpha_j (LDS bins as in row_prep_kernel), then adds each column's term to the
+// thread's private column sums.  A thread owns the columns tid, tid + 256, ...: with REG (m <= 16 * 256)
+// their sums, alpha and the row's P and labels stay in registers, so a row is read from HBM once;
+// otherwise the sums live in gpart and the row is read twice.  gpart[strip][l] is reduced over the strips
+// afterwards.
+constexpr int GRAD_NC = 16;
+
+template <bool REG>
 __global__ void __launch_bounds__(PREP_THREADS) grad_rows_kernel(const float *W, const float *S, const float *alpha,
                                                                  long long n, long long m, long long ld,
                                                                  const uint8_t *labels, const float *P,
                                                                  const double *cent, const double *Den,
                                                                  double *gpart) {
-    __shared__ double red[16][4];
-    __shared__ double qsh[16], csh[16], dsh[16];
+    __shared__ double binQ[BIN_SETS][16];
+    __shared__ double rsh[16], csh[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const long long r0 = (long long)blockIdx.x * STRIP;
     double *gp = gpart + (long long)blockIdx.x * m;
-    for (long long l = tid; l < m; l += PREP_THREADS) gp[l] = 0.0;
+    double gacc[GRAD_NC];
+    float al[GRAD_NC];
+    if (REG) {
+#pragma unroll
+        for (int c = 0; c < GRAD_NC; ++c) {
+            const long long l = tid + (long long)c * PREP_THREADS;
+            gacc[c] = 0.0;
+            al[c] = l < m ? alpha[l] : 0.0f;
+        }
+    } else {
+        for (long long l = tid; l < m; l += PREP_THREADS) gp[l] = 0.0;
+    }
+    double *myQ = binQ[wave * BIN_COPIES + (lane & (BIN_COPIES - 1))];
     for (long long row = r0; row < min(n, r0 + STRIP); ++row) {
         const float *Pr = P + row * m;
         const uint8_t *Lr = labels + row * m;
-        double q[16];
+        const float *Wr = W + row * ld, *Sr = S + row * ld;
+        (&binQ[0][0])[tid] = 0.0;
+        __syncthreads();      // bins cleared; the previous row's rsh/csh are no longer read
+        float pv[GRAD_NC], wv[GRAD_NC], sv[GRAD_NC];
+        int lv[GRAD_NC];
+        if (REG) {
 #pragma unroll
-        for (int k = 0; k < 16; ++k) q[k] = 0.0;
-        for (long long j = tid; j < m; j += PREP_THREADS) {
-            const double pa = (double)Pr[j] * (double)alpha[j];
-            const int l = Lr[j] & 15;
+            for (int c = 0; c < GRAD_NC; ++c) {
+                const long long l = tid + (long long)c * PREP_THREADS;
+                const bool in = l < m;
+                pv[c] = in ? Pr[l] : 0.0f;
+                lv[c] = in ? (Lr[l] & 15) : 0;
+                wv[c] = in ? Wr[l] : 0.0f;
+                sv[c] = in ? Sr[l] : 0.0f;
+            }
 #pragma unroll
-            for (int k = 0; k < 16; ++k) q[k] += (l == k) ? pa : 0.0;
-        }
-        __syncthreads();  // previous row's qsh/csh/dsh are no longer read
-#pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            double x = q[k];
-            for (int o = 32; o >= 1; o >>= 1) x += __shfl_down(x, o, 64);
-            if (lane == 0) red[k][wave] = x;
+            for (int c = 0; c < GRAD_NC; ++c)
+                if (tid + (long long)c * PREP_THREADS < m) atomicAdd(&myQ[lv[c]], (double)pv[c] * (double)al[c]);
+        } else {
+            for (long long j = tid; j < m; j += PREP_THREADS)
+                atomicAdd(&myQ[Lr[j] & 15], (double)Pr[j] * (double)alpha[j]);
         }
         __syncthreads();
         if (tid < 16) {
-            qsh[tid] = red[tid][0] + red[tid][1] + red[tid][2] + red[tid][3];
+            const double q = bin_total(binQ, tid), d = Den[row * 16 + tid];
+            rsh[tid] = d > 0.0 ? q / d : 0.0;
             csh[tid] = cent[row * 16 + tid];
-            dsh[tid] = Den[row * 16 + tid];
         }
         __syncthreads();
-        const float *Wr = W + row * ld, *Sr = S + row * ld;
-        for (long long l = tid; l < m; l += PREP_THREADS) {
-            const int k = Lr[l] & 15;
-            const double a = (double)alpha[l], c = csh[k], d = dsh[k];
-            double term = (double)Pr[l] * c;
-            if (d > 0.0) term += qsh[k] * (double)Sr[l] * ((double)Wr[l] - 2.0 * a * c) / d;
-            gp[l] += -2.0 * term;   // the same thread owns column l for every row of the strip
+        if (REG) {
+#pragma unroll
+            for (int c = 0; c < GRAD_NC; ++c) {
+                const double a = (double)al[c], cc = csh[lv[c]];
+                const double term = (double)pv[c] * cc + rsh[lv[c]] * (double)sv[c] * ((double)wv[c] - 2.0 * a * cc);
+                gacc[c] += -2.0 * term;
+            }
+        } else {
+            for (long long l = tid; l < m; l += PREP_THREADS) {
+                const int k = Lr[l] & 15;
+                const double a = (double)alpha[l], cc = csh[k];
+                const double term = (double)Pr[l] * cc + rsh[k] * (double)Sr[l] * ((double)Wr[l] - 2.0 * a * cc);
+                gp[l] += -2.0 * term;   // the same thread owns column l for every row of the strip
+            }
+        }
+    }
+    if (REG) {
+#pragma unroll
+        for (int c = 0; c < GRAD_NC; ++c) {
+            const long long l = tid + (long long)c * PREP_THREADS;
+            if (l < m) gp[l] = gacc[c];
         }
     }
 }
@@ -365,8 +402,14 @@ extern "C" skim_status skim_scale_step(skim_ctx *ctx, const float *W, const floa
                        ctx->stream, w.dW, H, (int)n, (int)m, w.P, w.partial);
     hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(1024), 0, ctx->stream, w.partial, w.ntile, (long long)n,
                        loss_before, (double *)nullptr, 1ll);
-    hipLaunchKernelGGL(grad_rows_kernel, dim3(w.nstrip), dim3(PREP_THREADS), 0, ctx->stream, W, S, (const float *)alpha,
-                       (long long)n, (long long)m, (long long)ld, labels, w.P, w.cent, w.Den, w.gpart);
+    if (m <= (int64_t)GRAD_NC * PREP_THREADS)
+        hipLaunchKernelGGL(grad_rows_kernel<true>, dim3(w.nstrip), dim3(PREP_THREADS), 0, ctx->stream, W, S,
+                           (const float *)alpha, (long long)n, (long long)m, (long long)ld, labels, w.P, w.cent, w.Den,
+                           w.gpart);
+    else
+        hipLaunchKernelGGL(grad_rows_kernel<false>, dim3(w.nstrip), dim3(PREP_THREADS), 0, ctx->stream, W, S,
+                           (const float *)alpha, (long long)n, (long long)m, (long long)ld, labels, w.P, w.cent, w.Den,
+                           w.gpart);
     const double lr = (double)opts->lr0 * pow((double)opts->decay, (double)((t - 1) / opts->decay_every));
     const double bc1 = 1.0 - pow((double)opts->beta1, (double)t), bc2 = 1.0 - pow((double)opts->beta2, (double)t);
     hipLaunchKernelGGL(adam_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, ctx->stream, w.gpart, w.nstrip,
