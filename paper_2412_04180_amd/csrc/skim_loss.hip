@@ -196,16 +196,26 @@ __global__ void __launch_bounds__(GEMM_THREADS) __attribute__((amdgpu_waves_per_
     if (tid < BM && row0 + tid < n) partial[(long long)blockIdx.x * n + row0 + tid] = rsum[0][tid] + rsum[1][tid];
 }
 
-// row_loss[i] = sum over column tiles; loss = sum_i row_loss[i] (single workgroup, fixed order).
+// row_loss[i] = sum over column tiles; loss = sum_i row_loss[i] (single workgroup, fixed order).  Four
+// neighbouring lanes share a row's tiles (t = q, q + 4, ...) and add their partial sums in the order q = 0..3.
 __global__ void __launch_bounds__(1024) loss_finish_kernel(const double *partial, int ntile, long long n, double *loss,
                                                            double *row_loss, long long row_stride) {
     __shared__ double sh[16];
+    const int q = threadIdx.x & 3;
     double acc = 0.0;
-    for (long long i = threadIdx.x; i < n; i += 1024) {
+    for (long long i0 = 0; i0 < n; i0 += 256) {
+        const long long i = i0 + (threadIdx.x >> 2);
         double r = 0.0;
-        for (int t = 0; t < ntile; ++t) r += partial[(long long)t * n + i];
-        if (row_loss) row_loss[i * row_stride] = r;
-        acc += r;
+        if (i < n)
+            for (int t = q; t < ntile; t += 4) r += partial[(long long)t * n + i];
+        const double r1 = __shfl_xor(r, 1, 64);
+        const double r01 = (q & 1) ? r1 + r : r + r1;          // (q0 + q1) or (q2 + q3), lower lane first
+        const double r23 = __shfl_xor(r01, 2, 64);
+        const double tot = (q & 2) ? r23 + r01 : r01 + r23;     // (q0 + q1) + (q2 + q3) in every lane
+        if (q == 0 && i < n) {
+            if (row_loss) row_loss[i * row_stride] = tot;
+            acc += tot;
+        }
     }
     for (int d = 32; d >= 1; d >>= 1) acc += __shfl_down(acc, d, 64);
     if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = acc;
@@ -306,16 +316,30 @@ __global__ void __launch_bounds__(PREP_THREADS) grad_rows_kernel(const float *W,
     }
 }
 
-__global__ void adam_kernel(const double *gpart, int nstrip, long long m, float *alpha, float *am, float *av,
-                            float lr, float beta1, float beta2, float eps, float bc1, float bc2, float *grad_out) {
-    const long long l = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (l >= m) return;
+// Column sums of the per-strip gradient terms, then the Adam update.  32 columns per workgroup; the strips
+// are shared out to 8 groups of threads (a column's 8 partial sums are added in a fixed order).
+constexpr int ADAM_COLS = 32, ADAM_GROUPS = 8;
+
+__global__ void __launch_bounds__(ADAM_COLS * ADAM_GROUPS) adam_kernel(const double *gpart, int nstrip, long long m,
+                                                                      float *alpha, float *am, float *av, float lr,
+                                                                      float beta1, float beta2, float eps, float bc1,
+                                                                      float bc2, float *grad_out) {
+    __shared__ double part[ADAM_GROUPS][ADAM_COLS];
+    const int c = threadIdx.x % ADAM_COLS, g = threadIdx.x / ADAM_COLS;
+    const long long l = (long long)blockIdx.x * ADAM_COLS + c;
+    double acc = 0.0;
+    if (l < m)
+        for (int st = g; st < nstrip; st += ADAM_GROUPS) acc += gpart[(long long)st * m + l];
+    part[g][c] = acc;
+    __syncthreads();
+    if (g != 0 || l >= m) return;
     double g64 = 0.0;
-    for (int s = 0; s < nstrip; ++s) g64 += gpart[(long long)s * m + l];
-    const float g = (float)g64;
-    if (grad_out) grad_out[l] = g;
-    const float m1 = beta1 * am[l] + (1.0f - beta1) * g;
-    const float v1 = beta2 * av[l] + (1.0f - beta2) * g * g;
+#pragma unroll
+    for (int k = 0; k < ADAM_GROUPS; ++k) g64 += part[k][c];
+    const float gr = (float)g64;
+    if (grad_out) grad_out[l] = gr;
+    const float m1 = beta1 * am[l] + (1.0f - beta1) * gr;
+    const float v1 = beta2 * av[l] + (1.0f - beta2) * gr * gr;
     am[l] = m1;
     av[l] = v1;
     const float mh = m1 / bc1, vh = v1 / bc2;
@@ -412,7 +436,7 @@ extern "C" skim_status skim_scale_step(skim_ctx *ctx, const float *W, const floa
                            w.gpart);
     const double lr = (double)opts->lr0 * pow((double)opts->decay, (double)((t - 1) / opts->decay_every));
     const double bc1 = 1.0 - pow((double)opts->beta1, (double)t), bc2 = 1.0 - pow((double)opts->beta2, (double)t);
-    hipLaunchKernelGGL(adam_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, ctx->stream, w.gpart, w.nstrip,
+    hipLaunchKernelGGL(adam_kernel, dim3((unsigned)((m + ADAM_COLS - 1) / ADAM_COLS)), dim3(ADAM_COLS * ADAM_GROUPS), 0, ctx->stream, w.gpart, w.nstrip,
                        (long long)m, alpha, adam_m, adam_v, (float)lr, opts->beta1, opts->beta2, opts->eps, (float)bc1,
                        (float)bc2, grad_out);
     SKIM_HIP(ctx, hipGetLastError());
