@@ -372,3 +372,14 @@ def test_optimal_clustering_error_scaled_inputs_and_bit_subset(ctx):
     torch.cuda.synchronize()
     ref = oracle.kmeans_optimal_table(W, S, alpha=alpha, bmin=2, bmax=3)
     assert got.shape == (16, 2) and np.all(_optimal_close(got.cpu().numpy(), ref, W, S, alpha)[0])
+
+
+@pytest.mark.parametrize("m,bmax", [(14000, 1), (16400, 2)])
+def test_optimal_clustering_error_long_rows(ctx, m, bmax):
+    """Rows too long for the cuts to sit in LDS (they move to the caller's scratch), and rows sorted in two halves."""
+    W, S = skim_synth.make_ws_small(m, 2, m, dup_frac=0.02)
+    got = ctx.kmeans_optimal(dev(W), dev(S), bmin=1, bmax=bmax)
+    torch.cuda.synchronize()
+    ref = oracle.kmeans_optimal_table(W, S, bmin=1, bmax=bmax)
+    close, _ = _optimal_close(got.cpu().numpy(), ref, W, S)
+    assert np.all(close)
