@@ -60,6 +60,7 @@ struct ClusterParams {
     // merged into keys, and their sums are taken by a separate kernel
     int nseg, seglen;
     u64 *keys_seg;
+    int *segmass;         // per segment of a long row: nonzero when it holds sensitivity mass
     long long nwork;      // rows x segments: the units of work sort_kernel's workgroups share out
 };
 
@@ -338,8 +339,10 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
         }
         sorted[swz((uint32_t)j)] = key;
     }
-    // (segments of a long row cannot tell on their own: sums_kernel sees the whole row)
-    if (!__syncthreads_or((int)mass) && prm.nseg == 1) {
+    // (a segment of a long row cannot tell on its own: it records what it saw for merge_tile_kernel)
+    const int anymass = __syncthreads_or((int)mass);
+    if (prm.nseg > 1 && tid == 0) prm.segmass[work] = anymass;
+    if (!anymass && prm.nseg == 1) {
         // no sensitivity mass in this row: cluster with unit weights
 #pragma unroll
         for (int k = 0; k < EPT; ++k) {
@@ -362,7 +365,7 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     if (work + gridDim.x < prm.nwork) fetch_unit(prm, work + gridDim.x, tid, nth, pw, ps);
 
     if (prm.nseg > 1) {
-        // one segment of a long row: sorted keys only; merge_kernel and sums_kernel do the rest
+        // one segment of a long row: sorted keys only; merge_tile_kernel does the rest
         u64 *kseg = prm.keys_seg + row * (long long)prm.m + col0;
         for (int j = tid; j < m; j += nth) kseg[j] = sorted[swz((uint32_t)j)];
         __syncthreads();   // the LDS is refilled for the next unit
@@ -403,94 +406,121 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Rows longer than one LDS sort (m > 16384): two sorted segments are merged in global memory and
-// the sums are taken afterwards.
+// Rows longer than one LDS sort (m > 16384): the two sorted segments A, B of a row are merged tile by tile.
+// A workgroup produces MG_TILE consecutive keys of the merged row: two wavefronts find, by a 64-way
+// search in global memory, how many keys of A lie ahead of the tile's first and last output (merge path,
+// equal keys from A first); the keys in between, MG_TILE in all, are staged in LDS; every thread then
+// finds the split for its own 16 outputs by binary search in LDS, loads its share of A ascending and of B
+// descending (a bitonic sequence) and sorts it with the 4-stage merge network in registers.  The 16 outputs
+// are one chunk: its sums, and with the neighbours' the sums of 4 chunks, are written with the keys (the
+// quantities sort_kernel produces for short rows).  A row without sensitivity mass in either segment gets
+// unit weights here.
 // ---------------------------------------------------------------------------------------------
-constexpr int MERGE_THREADS = 256;
+constexpr int MG_THREADS = 256;
+constexpr int MG_TILE = MG_THREADS * EPT;
 
-// One workgroup per row.  Each thread finds its share of the output by merge-path search and
-// merges it sequentially (keys are compared through their float64 view; ties take the first run).
-__global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(ClusterParams prm) {
-    const long long row = blockIdx.x;
+// Number of keys of A among the first o keys of merge(A, B), equal keys from A first.  The predicate
+// p(x) = A[x] <= B[o-1-x] holds exactly for x below the answer; 64 lanes probe 64 positions per round.
+__device__ __forceinline__ int merge_split_wave(const double *__restrict__ A, int la, const double *__restrict__ B,
+                                                int lb, int o, int lane) {
+    int lo = max(0, o - lb), hi = min(o, la);
+    while (hi > lo) {
+        const int step = (hi - lo + 63) >> 6;
+        const int x = lo + lane * step;
+        const bool p = (x < hi) && (A[x] <= B[o - 1 - x]);
+        const int nt = __popcll(__ballot(p));          // probes 0 .. nt-1 are true
+        const int nlo = nt > 0 ? lo + (nt - 1) * step + 1 : lo;
+        hi = min(hi, lo + nt * step);
+        lo = nlo;
+    }
+    return lo;
+}
+
+__global__ void __launch_bounds__(MG_THREADS) merge_tile_kernel(ClusterParams prm, int tiles_per_row) {
+    __shared__ double buf[MG_TILE + MG_TILE / 16];
+    __shared__ int part[MG_THREADS + 1];
+    __shared__ int split[2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long long row = blockIdx.x / tiles_per_row;
+    const int tile = (int)(blockIdx.x % tiles_per_row);
     const int m = prm.m;
     const int la = min(prm.seglen, m), lb = m - la;
     const double *__restrict__ A = (const double *)(prm.keys_seg + row * (long long)m);
     const double *__restrict__ B = A + la;
-    double *__restrict__ out = (double *)(prm.keys + row * (long long)m);
-    const int q = (m + MERGE_THREADS - 1) / MERGE_THREADS;
-    const int o0 = min(m, (int)threadIdx.x * q), o1 = min(m, o0 + q);
-    if (o0 >= o1) return;
-    int lo = max(0, o0 - lb), hi = min(o0, la);
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (A[mid] <= B[o0 - 1 - mid]) lo = mid + 1; else hi = mid;
+    const int o0 = tile * MG_TILE, o1 = min(m, o0 + MG_TILE);
+    const int T = o1 - o0;
+    if (wave < 2) {
+        const int sp = merge_split_wave(A, la, B, lb, wave == 0 ? o0 : o1, lane);
+        if (lane == 0) split[wave] = sp;
     }
-    int i = lo, j = o0 - lo;
+    __syncthreads();
+    const int ia0 = split[0], ia1 = split[1];
+    const int ib0 = o0 - ia0;
+    const int lat = ia1 - ia0, lbt = T - lat;            // keys of A and of B in this tile
+    for (int x = tid; x < T; x += MG_THREADS)
+        buf[swz((uint32_t)x)] = x < lat ? A[ia0 + x] : B[ib0 + (x - lat)];
+    __syncthreads();
+    // this thread's outputs: d .. d + cnt - 1 of the tile
+    const int d = tid * EPT;
+    const int cnt = max(0, min(EPT, T - d));
+    int i = lat;                                          // keys of A ahead of output d
+    if (d < T) {
+        int lo = max(0, d - lbt), hi = min(d, lat);
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (buf[swz((uint32_t)mid)] <= buf[swz((uint32_t)(lat + d - 1 - mid))]) lo = mid + 1;
+            else hi = mid;
+        }
+        i = lo;
+    }
+    part[tid] = i;
+    if (tid == 0) part[MG_THREADS] = lat;
+    __syncthreads();
+    const int acnt = (d < T) ? ((d + EPT >= T) ? lat - i : part[tid + 1] - i) : 0;
+    const int bcnt = cnt - acnt;
+    const int jb = d - i;                                 // keys of B ahead of output d
     const double inf = __longlong_as_double((long long)PAD_KEY);
-    double a = (i < la) ? A[i] : inf, b = (j < lb) ? B[j] : inf;
-    for (int o = o0; o < o1; ++o) {
-        const bool ta = a <= b;
-        out[o] = ta ? a : b;
-        if (ta) {
-            ++i;
-            a = (i < la) ? A[i] : inf;
-        } else {
-            ++j;
-            b = (j < lb) ? B[j] : inf;
-        }
+    double v[EPT];
+#pragma unroll
+    for (int r = 0; r < EPT; ++r) {
+        const bool fromA = r < acnt, fromB = r >= EPT - bcnt;
+        const int idx = fromA ? i + r : lat + jb + (EPT - 1 - r);
+        v[r] = (fromA || fromB) ? buf[swz((uint32_t)idx)] : inf;
     }
-}
-
-// One workgroup per row: chunk sums and first weights from the merged keys (the quantities
-// sort_kernel produces for short rows), and the switch to unit weights for a row without
-// sensitivity mass.  m <= 32768, two chunks per thread.
-__global__ void __launch_bounds__(1024) sums_kernel(ClusterParams prm) {
-    const long long row = blockIdx.x;
-    const int m = prm.m;
-    const int tid = threadIdx.x;
-    const int n1u = (m + 15) >> 4;
-    u64 *keys = prm.keys + row * (long long)m;
-    for (int pass = 0; pass < 2; ++pass) {
-        double cs[2] = {0.0, 0.0}, qs[2] = {0.0, 0.0}, rs[2] = {0.0, 0.0};
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int ch = 2 * tid + h;
-            for (int e = 0; e < 16; ++e) {
-                const int r = ch * 16 + e;
-                if (r < m) {
-                    u64 el = keys[r];
-                    if (pass == 1) {            // no sensitivity mass in this row: unit weights
-                        el = unit_weight_key(el);
-                        keys[r] = el;
-                    }
-                    const double s = (double)elem_s(el), w = (double)elem_w(el);
-                    cs[h] += s;
-                    qs[h] = fma(s, w, qs[h]);
-                    rs[h] = fma(s * w, w, rs[h]);
-                }
-            }
-        }
-        if (pass == 0 && !__syncthreads_or((int)(cs[0] + cs[1] != 0.0))) continue;
+    for (int rb = 3; rb >= 0; --rb) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int ch = 2 * tid + h;
-            if (ch < n1u) {
-                prm.L1[row * prm.n1 + ch] = make_double2(cs[h], qs[h]);
-                prm.R1[row * prm.n1 + ch] = rs[h];
-                prm.w16[row * prm.n1 + ch] = elem_w(keys[16 * ch]);
-            }
+        for (int r = 0; r < EPT; ++r)
+            if (!(r & (1 << rb))) ce(v[r], v[r | (1 << rb)]);
+    }
+    const bool unit = (prm.segmass[row * 2] | prm.segmass[row * 2 + 1]) == 0;
+    u64 *keys = prm.keys + row * (long long)m + o0 + d;
+    double c = 0.0, q = 0.0, r2 = 0.0;
+    float w0 = 0.0f;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+        u64 el = NEUTRAL_KEY;
+        if (e < cnt) {
+            el = (u64)__double_as_longlong(v[e]);
+            if (unit) el = unit_weight_key(el);
+            keys[e] = el;
         }
-        {   // groups of 4 chunks = 2 neighbouring threads
-            double c2 = cs[0] + cs[1], q2 = qs[0] + qs[1], r2 = rs[0] + rs[1];
-            c2 += dpp_move_d<0xB1>(c2);   // quad_perm [1,0,3,2]
-            q2 += dpp_move_d<0xB1>(q2);
-            r2 += dpp_move_d<0xB1>(r2);
-            if ((tid & 1) == 0 && 2 * tid < n1u) {
-                prm.Q[row * prm.nq + (tid >> 1)] = make_double2(c2, q2);
-                prm.RQ[row * prm.nq + (tid >> 1)] = r2;
-            }
-        }
-        break;
+        const double sv = (double)elem_s(el), wv = (double)elem_w(el);
+        if (e == 0) w0 = elem_w(el);
+        c += sv;
+        q = fma(sv, wv, q);
+        r2 = fma(sv * wv, wv, r2);
+    }
+    const long long ch = (long long)(o0 + d) >> 4;
+    if (cnt > 0) {
+        prm.L1[row * prm.n1 + ch] = make_double2(c, q);
+        prm.R1[row * prm.n1 + ch] = r2;
+        prm.w16[row * prm.n1 + ch] = w0;
+    }
+    const double c4 = quad_sum(c), q4 = quad_sum(q), r4 = quad_sum(r2);   // threads past the row add zeros
+    if (cnt > 0 && (tid & 3) == 0) {
+        prm.Q[row * prm.nq + (ch >> 2)] = make_double2(c4, q4);
+        prm.RQ[row * prm.nq + (ch >> 2)] = r4;
     }
 }
 
@@ -1584,9 +1614,11 @@ skim_status carve_cluster_ws(skim_ctx *ctx, ClusterParams &prm, int64_t n, doubl
     prm.bstate = (BitState *)cur.take((size_t)n * 4 * sizeof(BitState));
     bool ok = prm.keys && prm.L1 && prm.Q && prm.R1 && prm.RQ && prm.w16 && prm.bstate;
     prm.keys_seg = nullptr;
+    prm.segmass = nullptr;
     if (prm.nseg > 1) {
         prm.keys_seg = (u64 *)cur.take((size_t)n * prm.m * sizeof(u64));
-        ok = ok && prm.keys_seg;
+        prm.segmass = (int *)cur.take((size_t)n * prm.nseg * sizeof(int));
+        ok = ok && prm.keys_seg && prm.segmass;
     }
     if (cent_scratch) {
         *cent_scratch = (double *)cur.take((size_t)n * prm.stride * sizeof(double));
@@ -1621,8 +1653,9 @@ skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n, bool so
     if (ctx->profiling) SKIM_HIP(ctx, hipEventRecord(ctx->ev[0], ctx->stream));
     hipLaunchKernelGGL(sort_kernel, dim3((unsigned)sort_grid), dim3(threads), lds, ctx->stream, prm);
     if (prm.nseg > 1) {
-        hipLaunchKernelGGL(merge_kernel, dim3((unsigned)n), dim3(MERGE_THREADS), 0, ctx->stream, prm);
-        hipLaunchKernelGGL(sums_kernel, dim3((unsigned)n), dim3(1024), 0, ctx->stream, prm);
+        const int tiles = (prm.m + MG_TILE - 1) / MG_TILE;
+        if ((int64_t)n * tiles > 0x7fffffff) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "too many rows");
+        hipLaunchKernelGGL(merge_tile_kernel, dim3((unsigned)(n * tiles)), dim3(MG_THREADS), 0, ctx->stream, prm, tiles);
     }
     if (sort_only) {
         SKIM_HIP(ctx, hipGetLastError());

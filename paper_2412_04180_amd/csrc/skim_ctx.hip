@@ -100,7 +100,7 @@ extern "C" size_t skim_workspace_bytes(int64_t n, int64_t m) {
     b += nstrip * M * sizeof(double);    // per-strip column sums of the gradient
     b += N * 30 * sizeof(double);        // centroid scratch of skim_error_table when the caller wants none
     b += N * (14 * M + 8192);            // clustering: sorted keys (8 B per weight), per-chunk sums and Lloyd state between the kernels
-    if (M > 16384) b += N * 8 * M;       // rows sorted in two halves: the unmerged keys
+    if (M > 16384) b += N * 8 * M + N * 8 + 256;   // rows sorted in two halves: the unmerged keys, a mass flag per half
     b += N * sizeof(int) + 1024;         // pack: row positions and group table
     b += N * 4 * sizeof(double) + 1024;  // L-full error table: S-diag errors and the loss scalar at the tail
     b += N * (16 * sizeof(float) + sizeof(double)) + 1024;   // scale training: thresholds and errors of the re-clustering
