@@ -1,7 +1,7 @@
 // Layer-wise Hessian proxy from calibration activations (Sec. 3.4: H ~ X X^T in the paper's
 // column convention; here X is N x m row-major, one activation vector per row, so
 // H = X^T X / N, m x m).  bf16 inputs, bf16 MFMA (v_mfma_f32_32x32x16_bf16) with float32
-// accumulation over chunks of 512 activations, the chunks added up in float64.
+// accumulation over chunks of 2048 activations, the chunks added up in float64.
 #include "skim_common.h"
 
 namespace {
@@ -10,56 +10,74 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int HT = 128;            // output tile (rows and columns of H = columns of X)
-constexpr int HK = 32;             // activations per LDS tile
-constexpr int HK_PAD = HK + 8;     // bf16 per LDS row: 80 bytes, keeps 16-byte alignment
+constexpr int HK = 64;             // activations per LDS tile
+constexpr int HK_PAD = HK + 8;     // bf16 per LDS row: 144 bytes (16-byte aligned; operand reads and staging
+                                   // stores of a 16-lane group fall into distinct banks)
 constexpr int H_THREADS = 256;
-constexpr int FLUSH_TILES = 16;    // float32 accumulators are added into float64 every 16 tiles = 512 activations
+constexpr int FLUSH_TILES = 32;    // float32 accumulators are added into float64 every 32 tiles = 2048 activations
 
 // LDS tile T[c][k]: column c of the X tile, HK consecutive activations (k contiguous: one
 // ds_read_b128 gives a lane its 8 bf16 of an MFMA operand).
 struct XTile {
     uint16_t t[HT][HK_PAD];
 };
+constexpr size_t H_LDS_BYTES = 4 * sizeof(XTile);     // two operands, double-buffered
 
-// One thread moves 8 activations x 2 neighbouring columns: 8 coalesced 4-byte loads, two 16-byte LDS stores.
+// Half of the workgroup stages each operand tile.  One thread moves 8 activations x 8 neighbouring columns:
+// eight 16-byte loads (a wavefront covers 8 activation rows x 128 contiguous bytes per instruction), an
+// 8 x 8 transpose of 16-bit values in registers, eight 16-byte LDS stores (one per column).
 struct Staged {
-    uint32_t r[8];
+    uint32_t r[8][4];
 };
 __device__ __forceinline__ void load_task(const uint16_t *__restrict__ X, long long N, long long m, long long k0,
-                                          long long c0, int tid, Staged &s) {
-    const int kb = tid >> 6, cp = tid & 63;          // 8-activation block, column pair
-    const long long c = c0 + 2 * cp;
+                                          long long c0, int st, bool vec, Staged &s) {
+    const int ab = st & 7, cg = st >> 3;             // 8-activation block, 8-column group
+    const long long c = c0 + 8 * cg;
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
-        const long long k = k0 + 8 * kb + t;
-        uint32_t v = 0;
+        const long long k = k0 + 8 * ab + t;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
         if (k < N) {
             const uint16_t *src = X + k * m + c;
-            if (c + 1 < m) v = *(const uint32_t *)src;       // m even and c even: 4-byte aligned
-            else if (c < m) v = src[0];
+            if (vec && c + 8 <= m) {
+                v = *(const uint4 *)src;             // m % 8 == 0 and X 16-byte aligned
+            } else {
+                uint32_t e[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) e[q] = (c + q < m) ? src[q] : 0u;
+                v = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+            }
         }
-        s.r[t] = v;
+        s.r[t][0] = v.x; s.r[t][1] = v.y; s.r[t][2] = v.z; s.r[t][3] = v.w;
     }
 }
-__device__ __forceinline__ void store_task(XTile &T, int tid, const Staged &s) {
-    const int kb = tid >> 6, cp = tid & 63;
-    uint32_t lo[4], hi[4];
+__device__ __forceinline__ void store_task(XTile &T, int st, const Staged &s) {
+    const int ab = st & 7, cg = st >> 3;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        lo[t] = (s.r[2 * t] & 0xffffu) | (s.r[2 * t + 1] << 16);
-        hi[t] = (s.r[2 * t] >> 16) | (s.r[2 * t + 1] & 0xffff0000u);
+    for (int c = 0; c < 8; ++c) {
+        uint32_t o[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t a = s.r[2 * d][c >> 1], b = s.r[2 * d + 1][c >> 1];
+            o[d] = (c & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+        }
+        *(uint4 *)&T.t[8 * cg + c][8 * ab] = make_uint4(o[0], o[1], o[2], o[3]);
     }
-    *(uint4 *)&T.t[2 * cp][8 * kb] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-    *(uint4 *)&T.t[2 * cp + 1][8 * kb] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
 }
 
 __global__ void __launch_bounds__(H_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) xtx_kernel(const uint16_t *__restrict__ X, long long N, long long m,
-                                                        float *__restrict__ H) {
-    __shared__ __align__(16) XTile TI[2], TJ[2];
+                                                        float *__restrict__ H, int vec) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    XTile *TI = (XTile *)smem, *TJ = TI + 2;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave >> 1, wc = wave & 1;
     const int l32 = lane & 31, lhi = lane >> 5;
     const long long i0 = (long long)blockIdx.y * HT, j0 = (long long)blockIdx.x * HT;
+    // threads 0..127 stage the tile of columns i0.., threads 128..255 the tile of columns j0..
+    const int st = tid & 127;
+    const bool stage_j = tid >= 128;
+    const long long sc0 = stage_j ? j0 : i0;
+    XTile *const ST = stage_j ? TJ : TI;
 
     floatx16 acc[2][2];
     double acc64[2][2][16];
@@ -74,18 +92,13 @@ __global__ void __launch_bounds__(H_THREADS) __attribute__((amdgpu_waves_per_eu(
             }
 
     const long long ntile = (N + HK - 1) / HK;
-    Staged si, sj;
-    load_task(X, N, m, 0, i0, tid, si);
-    load_task(X, N, m, 0, j0, tid, sj);
-    store_task(TI[0], tid, si);
-    store_task(TJ[0], tid, sj);
+    Staged sg;
+    load_task(X, N, m, 0, sc0, st, vec != 0, sg);
+    store_task(ST[0], st, sg);
     __syncthreads();
     for (long long kt = 0; kt < ntile; ++kt) {
         const int buf = (int)(kt & 1);
-        if (kt + 1 < ntile) {
-            load_task(X, N, m, (kt + 1) * HK, i0, tid, si);
-            load_task(X, N, m, (kt + 1) * HK, j0, tid, sj);
-        }
+        if (kt + 1 < ntile) load_task(X, N, m, (kt + 1) * HK, sc0, st, vec != 0, sg);
 #pragma unroll
         for (int ks = 0; ks < HK / 16; ++ks) {
             // operand of a lane: 8 consecutive activations 16 ks + 8 (lane / 32) .. + 7 of one column
@@ -110,10 +123,7 @@ __global__ void __launch_bounds__(H_THREADS) __attribute__((amdgpu_waves_per_eu(
                         acc[a][b][e] = 0.f;
                     }
         }
-        if (kt + 1 < ntile) {
-            store_task(TI[buf ^ 1], tid, si);
-            store_task(TJ[buf ^ 1], tid, sj);
-        }
+        if (kt + 1 < ntile) store_task(ST[buf ^ 1], st, sg);
         __syncthreads();
     }
 
@@ -141,8 +151,15 @@ extern "C" skim_status skim_hessian_from_activations(skim_ctx *ctx, const uint16
     if (N < 1 || m < 2 || (m & 1) || m > 0x7fffffff || ((uintptr_t)X_bf16 & 3))
         SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "skim_hessian_from_activations: need N >= 1, m even, X 4-byte aligned (N=%lld m=%lld)",
                   (long long)N, (long long)m);
+    static bool lds_enabled = false;
+    if (!lds_enabled) {
+        SKIM_HIP(ctx, hipFuncSetAttribute((const void *)xtx_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)H_LDS_BYTES));
+        lds_enabled = true;
+    }
     const unsigned nt = (unsigned)((m + HT - 1) / HT);
-    hipLaunchKernelGGL(xtx_kernel, dim3(nt, nt), dim3(H_THREADS), 0, ctx->stream, X_bf16, (long long)N, (long long)m, H);
+    const int vec = (m % 8 == 0) && (((uintptr_t)X_bf16 & 15) == 0);     // rows of X start 16-byte aligned
+    hipLaunchKernelGGL(xtx_kernel, dim3(nt, nt), dim3(H_THREADS), H_LDS_BYTES, ctx->stream, X_bf16, (long long)N,
+                       (long long)m, H, vec);
     SKIM_HIP(ctx, hipGetLastError());
     return SKIM_OK;
 }

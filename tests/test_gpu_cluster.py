@@ -383,3 +383,32 @@ def test_optimal_clustering_error_long_rows(ctx, m, bmax):
     ref = oracle.kmeans_optimal_table(W, S, bmin=1, bmax=bmax)
     close, _ = _optimal_close(got.cpu().numpy(), ref, W, S)
     assert np.all(close)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_and_flavours(ctx, seed):
+    """Seeded sweep over combinations the targeted tests cover one at a time: row count (odd and even: two rows
+    share a wavefront), ragged length, duplicated values, zero sensitivities, heavy elements, column scaling,
+    iteration count and bit range."""
+    rng = np.random.default_rng(9000 + seed)
+    n = int(rng.integers(1, 48))
+    m = int(rng.choice([16, 31, 64, 100, 333, 1024, 1500, 3001, 5000]))
+    W, S = skim_synth.make_ws_small(500 + seed, n, m, dup_frac=float(rng.choice([0.0, 0.1, 0.5])),
+                                    zero_s_frac=float(rng.choice([0.0, 0.2, 0.9])))
+    if seed % 3 == 0:
+        S[np.arange(n), rng.integers(0, m, n)] = 1e8                 # one element carries the mass
+    if seed % 4 == 1:
+        S[rng.integers(0, n)] = 0.0                                  # a row without mass
+    alpha = rng.uniform(0.5, 2.0, m).astype(np.float32) if seed % 2 else None
+    bmin = int(rng.integers(1, 4))
+    bmax = int(rng.integers(bmin, 5))
+    iters = int(rng.choice([1, 3, 30]))
+    ref, out, excused = check_table(ctx, W, S, alpha=alpha, iters=iters, bmin=bmin, bmax=bmax)
+    assert excused <= max(2, n // 4)
+    bits = rng.integers(1, 5, n).astype(np.uint8)
+    cr = ctx.cluster_rows(dev(W), dev(S), dev(bits), alpha=None if alpha is None else dev(alpha), iters=iters)
+    torch.cuda.synchronize()
+    rr = oracle.cluster_rows(W, S, bits, alpha=alpha, T=iters, count_near=True)
+    clean = rr["near_rows"] == 0
+    assert np.array_equal(cr["labels"].cpu().numpy()[clean], rr["labels"][clean])
+    assert np.array_equal(cr["upper"].cpu().numpy().astype(np.float64)[clean], rr["upper"][clean])
