@@ -196,27 +196,29 @@ __global__ void __launch_bounds__(GEMM_THREADS) __attribute__((amdgpu_waves_per_
     if (tid < BM && row0 + tid < n) partial[(long long)blockIdx.x * n + row0 + tid] = rsum[0][tid] + rsum[1][tid];
 }
 
-// row_loss[i] = sum over column tiles; loss = sum_i row_loss[i] (single workgroup, fixed order).  Four
-// neighbouring lanes share a row's tiles (t = q, q + 4, ...) and add their partial sums in the order q = 0..3.
-__global__ void __launch_bounds__(1024) loss_finish_kernel(const double *partial, int ntile, long long n, double *loss,
-                                                           double *row_loss, long long row_stride) {
-    __shared__ double sh[16];
-    const int q = threadIdx.x & 3;
-    double acc = 0.0;
-    for (long long i0 = 0; i0 < n; i0 += 256) {
-        const long long i = i0 + (threadIdx.x >> 2);
-        double r = 0.0;
-        if (i < n)
-            for (int t = q; t < ntile; t += 4) r += partial[(long long)t * n + i];
-        const double r1 = __shfl_xor(r, 1, 64);
-        const double r01 = (q & 1) ? r1 + r : r + r1;          // (q0 + q1) or (q2 + q3), lower lane first
-        const double r23 = __shfl_xor(r01, 2, 64);
-        const double tot = (q & 2) ? r23 + r01 : r01 + r23;     // (q0 + q1) + (q2 + q3) in every lane
-        if (q == 0 && i < n) {
-            if (row_loss) row_loss[i * row_stride] = tot;
-            acc += tot;
-        }
+// row_loss[i] = sum over column tiles (one thread per row, neighbouring threads on neighbouring rows of every
+// tile's partials; four running sums keep four loads in flight), left in partial[i] for the total.
+__global__ void __launch_bounds__(256) loss_rows_kernel(double *partial, int ntile, long long n, double *row_loss,
+                                                        long long row_stride) {
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    double r[4] = {0.0, 0.0, 0.0, 0.0};
+    int t = 0;
+    for (; t + 3 < ntile; t += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) r[u] += partial[(long long)(t + u) * n + i];
     }
+    for (; t < ntile; ++t) r[t & 3] += partial[(long long)t * n + i];
+    const double tot = (r[0] + r[1]) + (r[2] + r[3]);
+    if (row_loss) row_loss[i * row_stride] = tot;
+    partial[i] = tot;
+}
+
+// loss = sum_i partial[i] (single workgroup, fixed order).
+__global__ void __launch_bounds__(1024) loss_total_kernel(const double *partial, long long n, double *loss) {
+    __shared__ double sh[16];
+    double acc = 0.0;
+    for (long long i = threadIdx.x; i < n; i += 1024) acc += partial[i];
     for (int d = 32; d >= 1; d >>= 1) acc += __shfl_down(acc, d, 64);
     if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = acc;
     __syncthreads();
@@ -225,6 +227,13 @@ __global__ void __launch_bounds__(1024) loss_finish_kernel(const double *partial
         for (int w = 0; w < 16; ++w) s += sh[w];
         *loss = s;
     }
+}
+
+static void launch_loss_finish(hipStream_t stream, double *partial, int ntile, long long n, double *loss, double *row_loss,
+                               long long row_stride) {
+    hipLaunchKernelGGL(loss_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, partial, ntile, n,
+                       row_loss, row_stride);
+    hipLaunchKernelGGL(loss_total_kernel, dim3(1), dim3(1024), 0, stream, (const double *)partial, n, loss);
 }
 
 // Gradient terms.  One workgroup walks STRIP consecutive rows; per row it forms
@@ -401,8 +410,7 @@ skim_status skim_layer_loss_strided(skim_ctx *ctx, const float *W, const float *
                        (long long)ld, labels, w.cent, w.Den, w.dW);
     hipLaunchKernelGGL(dwh_gemm_kernel<false>, dim3(w.ntile, (unsigned)((n + BM - 1) / BM)), dim3(GEMM_THREADS), 0,
                        ctx->stream, w.dW, H, (int)n, (int)m, (float *)nullptr, w.partial);
-    hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(1024), 0, ctx->stream, w.partial, w.ntile, (long long)n, loss,
-                       row_loss, (long long)row_stride);
+    launch_loss_finish(ctx->stream, w.partial, w.ntile, (long long)n, loss, row_loss, (long long)row_stride);
     SKIM_HIP(ctx, hipGetLastError());
     return SKIM_OK;
 }
@@ -424,8 +432,7 @@ extern "C" skim_status skim_scale_step(skim_ctx *ctx, const float *W, const floa
                        (long long)m, (long long)ld, labels, w.cent, w.Den, w.dW);
     hipLaunchKernelGGL(dwh_gemm_kernel<true>, dim3(w.ntile, (unsigned)((n + BM - 1) / BM)), dim3(GEMM_THREADS), 0,
                        ctx->stream, w.dW, H, (int)n, (int)m, w.P, w.partial);
-    hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(1024), 0, ctx->stream, w.partial, w.ntile, (long long)n,
-                       loss_before, (double *)nullptr, 1ll);
+    launch_loss_finish(ctx->stream, w.partial, w.ntile, (long long)n, loss_before, (double *)nullptr, 1ll);
     if (m <= (int64_t)GRAD_NC * PREP_THREADS)
         hipLaunchKernelGGL(grad_rows_kernel<true>, dim3(w.nstrip), dim3(PREP_THREADS), 0, ctx->stream, W, S,
                            (const float *)alpha, (long long)n, (long long)m, (long long)ld, labels, w.P, w.cent, w.Den,
