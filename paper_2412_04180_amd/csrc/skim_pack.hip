@@ -89,47 +89,82 @@ __global__ void __launch_bounds__(PLAN_THREADS) pack_plan_kernel(long long n, lo
 
 // One workgroup per row.  A thread takes 32 consecutive columns at a time: their B-bit labels fill
 // exactly B words, assembled in registers and stored without staging (no LDS traffic, no barriers
-// inside the row).
-template <int B>
-__device__ __forceinline__ void pack_row_body(const float *__restrict__ Wr, const float *__restrict__ alpha, long long m,
+// inside the row).  ALPHA / DW: the call scales the columns / wants the residual; a group that lies
+// wholly inside the row (all but the last one) takes the path without per-column bounds.
+template <int B, bool ALPHA, bool DW>
+__device__ __forceinline__ void pack_row_body(const float *__restrict__ Wr, const float *__restrict__ alpha, uint32_t m,
                                               const float *thr, const int *thl, const float *cbf,
-                                              uint32_t *__restrict__ out_words, long long wpr, float *__restrict__ dWr) {
-    const long long ngroups = (m + 31) / 32;
-    for (long long g = threadIdx.x; g < ngroups; g += PACK_THREADS) {
-        const long long j0 = g * 32;
-        float w[32];
-        if (j0 + 32 <= m && (((uintptr_t)(Wr + j0)) & 15) == 0) {
+                                              uint32_t *__restrict__ out_words, uint32_t wpr, float *__restrict__ dWr) {
+    const uint32_t ngroups = (m + 31u) >> 5;
+    const bool vec_ok = ((((uintptr_t)Wr) | (ALPHA ? (uintptr_t)alpha : 0) | (DW ? (uintptr_t)dWr : 0)) & 15) == 0;
+    for (uint32_t g = threadIdx.x; g < ngroups; g += PACK_THREADS) {
+        const uint32_t j0 = g << 5;
+        const uint32_t valid = min(32u, m - j0);
+        const bool full = valid == 32u && vec_ok;
+        float w[32], a[32];
+        if (full) {
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 const float4 v = *(const float4 *)(Wr + j0 + 4 * q);
                 w[4 * q] = v.x; w[4 * q + 1] = v.y; w[4 * q + 2] = v.z; w[4 * q + 3] = v.w;
+                if (ALPHA) {
+                    const float4 u = *(const float4 *)(alpha + j0 + 4 * q);
+                    a[4 * q] = u.x; a[4 * q + 1] = u.y; a[4 * q + 2] = u.z; a[4 * q + 3] = u.w;
+                }
             }
         } else {
 #pragma unroll
-            for (int jj = 0; jj < 32; ++jj) w[jj] = (j0 + jj < m) ? Wr[j0 + jj] : 0.0f;
+            for (int jj = 0; jj < 32; ++jj) {
+                w[jj] = ((uint32_t)jj < valid) ? Wr[j0 + jj] : 0.0f;
+                if (ALPHA) a[jj] = ((uint32_t)jj < valid) ? alpha[j0 + jj] : 1.0f;
+            }
         }
         uint32_t words[B + 1];
 #pragma unroll
         for (int k = 0; k <= B; ++k) words[k] = 0u;
+        float dq[32];
 #pragma unroll
         for (int jj = 0; jj < 32; ++jj) {
-            const long long j = j0 + jj;
-            const float a = alpha ? alpha[j < m ? j : 0] : 1.0f;
-            const float wt = alpha ? __fdiv_rn(w[jj], a) : w[jj];
-            // first position whose bound is >= wt (binary search over the 16 sorted bounds)
-            int pos = (thr[7] < wt) ? 8 : 0;
-            pos += (thr[pos + 3] < wt) ? 4 : 0;
-            pos += (thr[pos + 1] < wt) ? 2 : 0;
+            const float wt = ALPHA ? __fdiv_rn(w[jj], a[jj]) : w[jj];
+            // first position whose bound is >= wt (binary search over the sorted bounds, +inf beyond the 2^B-th)
+            int pos = 0;
+            if (B >= 4) pos = (thr[7] < wt) ? 8 : 0;
+            if (B >= 3) pos += (thr[pos + 3] < wt) ? 4 : 0;
+            if (B >= 2) pos += (thr[pos + 1] < wt) ? 2 : 0;
             pos += (thr[pos] < wt) ? 1 : 0;
-            const uint32_t l = (j < m) ? (uint32_t)thl[pos] : 0u;     // padding bits stay zero
+            uint32_t l = (uint32_t)thl[pos];
+            if (DW) dq[jj] = __fmaf_rn(ALPHA ? -a[jj] : -1.0f, cbf[l], w[jj]);
+            if (!full) l = ((uint32_t)jj < valid) ? l : 0u;            // padding bits stay zero
             const int bit = jj * B, wi = bit >> 5, sh = bit & 31;
             words[wi] |= l << sh;
             if (sh + B > 32) words[wi + 1] |= l >> (32 - sh);
-            if (dWr && j < m) dWr[j] = __fmaf_rn(-a, cbf[l], w[jj]);
         }
 #pragma unroll
         for (int k = 0; k < B; ++k)
             if (g * B + k < wpr) out_words[g * B + k] = words[k];
+        if (DW) {
+            if (full) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    *(float4 *)(dWr + j0 + 4 * q) = make_float4(dq[4 * q], dq[4 * q + 1], dq[4 * q + 2], dq[4 * q + 3]);
+            } else {
+#pragma unroll
+                for (int jj = 0; jj < 32; ++jj)
+                    if ((uint32_t)jj < valid) dWr[j0 + jj] = dq[jj];
+            }
+        }
+    }
+}
+
+template <int B>
+__device__ __forceinline__ void pack_row_dispatch(const float *Wr, const float *alpha, uint32_t m, const float *thr,
+                                                  const int *thl, const float *cbf, uint32_t *ow, uint32_t wpr, float *dWr) {
+    if (alpha) {
+        if (dWr) pack_row_body<B, true, true>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr);
+        else pack_row_body<B, true, false>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr);
+    } else {
+        if (dWr) pack_row_body<B, false, true>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr);
+        else pack_row_body<B, false, false>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr);
     }
 }
 
@@ -179,10 +214,10 @@ __global__ void __launch_bounds__(PACK_THREADS) pack_rows_kernel(const float *W,
     float *dWr = dW ? dW + row * m : nullptr;
     uint32_t *ow = codes + word0;
     switch (b) {
-        case 1: pack_row_body<1>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr); break;
-        case 2: pack_row_body<2>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr); break;
-        case 3: pack_row_body<3>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr); break;
-        default: pack_row_body<4>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr); break;
+        case 1: pack_row_dispatch<1>(Wr, alpha, (uint32_t)m, thr, thl, cbf, ow, (uint32_t)wpr, dWr); break;
+        case 2: pack_row_dispatch<2>(Wr, alpha, (uint32_t)m, thr, thl, cbf, ow, (uint32_t)wpr, dWr); break;
+        case 3: pack_row_dispatch<3>(Wr, alpha, (uint32_t)m, thr, thl, cbf, ow, (uint32_t)wpr, dWr); break;
+        default: pack_row_dispatch<4>(Wr, alpha, (uint32_t)m, thr, thl, cbf, ow, (uint32_t)wpr, dWr); break;
     }
 }
 
@@ -197,7 +232,7 @@ extern "C" skim_status skim_pack(skim_ctx *ctx, const float *W, const float *alp
     if (!W || !bits || !centroids || !upper || !codes || !group_word_offset || !row_perm || !codebooks_fp16)
         SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_pack: NULL argument");
     if (n < 1 || n > 0x7fffffff || m < 1 || ld < m) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "skim_pack: bad shape n=%lld m=%lld ld=%lld", (long long)n, (long long)m, (long long)ld);
-    if (m * 4 > 0x7fffffffll * 32) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "skim_pack: row too long");
+    if (m >= (1ll << 29)) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "skim_pack: row too long (m < 2^29)");
     skim_ws_cursor cur{(char *)ctx->ws, 0, ctx->ws_bytes};
     int *rowpos = (int *)cur.take((size_t)n * sizeof(int));
     PackPlan *plan = (PackPlan *)cur.take(sizeof(PackPlan));
