@@ -13,6 +13,7 @@
 namespace {
 
 constexpr int GA_THREADS = 1024;
+constexpr size_t GA_LDS_KEYS = 128 * 1024;      // keys kept in LDS up to this many bytes (16384 keys)
 typedef unsigned long long u64;
 
 // float64 -> uint64 whose unsigned order is the order of the doubles (-0 folded into +0).
@@ -36,12 +37,17 @@ __device__ __forceinline__ void hist_add(unsigned *hist, bool valid, unsigned di
 }
 
 __global__ void __launch_bounds__(GA_THREADS) greedy_select_kernel(const double *__restrict__ E, long long n, int bmin,
-                                                                  int nb, long long T, u64 *__restrict__ keys,
+                                                                  int nb, long long T, u64 *keys_global,
                                                                   uint8_t *__restrict__ bits, long long *__restrict__ info,
-                                                                  long long budget) {
+                                                                  long long budget, int keys_in_lds) {
+    // the keys are written, re-read for the ties, marked and read again for the bits: in LDS when they fit
+    // (one workgroup: every trip to global memory is pure latency), else in the caller's workspace
+    extern __shared__ __align__(16) unsigned char ga_smem[];
+    u64 *keys = keys_in_lds ? (u64 *)ga_smem : keys_global;
     __shared__ unsigned hist[256];
     __shared__ u64 sh_prefix;
     __shared__ long long sh_rank;
+    __shared__ int sh_single;
     __shared__ long long wsum[GA_THREADS / 64];
     __shared__ long long cnt[8];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -114,11 +120,33 @@ __global__ void __launch_bounds__(GA_THREADS) greedy_select_kernel(const double 
                             if ((long long)h1 < r) { r -= h1; bin = 4 * lane; } } }
                     sh_prefix = prefix | ((u64)bin << (8 * d));
                     sh_rank = r;
+                    sh_single = (hist[bin] == 1u) ? 1 : 0;   // one key left under the new prefix: it is the threshold
                 }
             }
             __syncthreads();
             prefix = sh_prefix;
             rank = sh_rank;
+            const bool single = sh_single != 0;
+            if (single && d > 0) {
+                // the remaining digits are those of that key: its owner publishes it
+                __syncthreads();   // every thread has read sh_prefix / sh_single before it is overwritten
+                const u64 lo_mask = ~0ull << (8 * d);
+                if (in_regs) {
+#pragma unroll
+                    for (int k = 0; k < KPT; ++k) {
+                        const long long q = tid + (long long)k * GA_THREADS;
+                        if (q < nk && (rk[k] & lo_mask) == prefix) sh_prefix = rk[k];
+                    }
+                } else {
+                    for (long long q = tid; q < nk; q += GA_THREADS) {
+                        const u64 key = keys[q];
+                        if ((key & lo_mask) == prefix) sh_prefix = key;
+                    }
+                }
+                __syncthreads();
+                prefix = sh_prefix;
+                break;             // rank == 1 here
+            }
         }
         thr = prefix;
         R = rank;                  // the first R keys equal to thr, in index order, are taken
@@ -188,8 +216,17 @@ extern "C" skim_status skim_greedy_allocate_device(skim_ctx *ctx, const double *
     const size_t need = (size_t)n * (nb > 1 ? nb - 1 : 1) * sizeof(u64);
     if (!ctx->ws || ctx->ws_bytes < need)
         SKIM_FAIL(ctx, SKIM_ERR_WORKSPACE, "workspace missing or smaller than skim_workspace_bytes(n, m)");
-    hipLaunchKernelGGL(greedy_select_kernel, dim3(1), dim3(GA_THREADS), 0, ctx->stream, E, (long long)n, bmin, nb,
-                       (long long)(B - (int64_t)bmin * n), (u64 *)ctx->ws, bits, (long long *)info, (long long)B);
+    const size_t key_bytes = (size_t)n * (nb > 1 ? nb - 1 : 1) * sizeof(u64);
+    const int keys_in_lds = key_bytes <= GA_LDS_KEYS;
+    static bool lds_enabled = false;
+    if (keys_in_lds && !lds_enabled) {
+        SKIM_HIP(ctx, hipFuncSetAttribute((const void *)greedy_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                          (int)GA_LDS_KEYS));
+        lds_enabled = true;
+    }
+    hipLaunchKernelGGL(greedy_select_kernel, dim3(1), dim3(GA_THREADS), keys_in_lds ? key_bytes : 0, ctx->stream, E,
+                       (long long)n, bmin, nb, (long long)(B - (int64_t)bmin * n), (u64 *)ctx->ws, bits, (long long *)info,
+                       (long long)B, keys_in_lds);
     SKIM_HIP(ctx, hipGetLastError());
     return SKIM_OK;
 }
