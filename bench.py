@@ -7,8 +7,9 @@ One step = one pass of the hot path over the metric layer (LLaMA-7B down-project
 shape, 4096 x 11008 fp32, synthetic): error table for b = 1..4 (30 Lloyd iterations)
 -> greedy allocation to 3.2 average bits (on the device) -> selection of the allocated
 clusterings -> packing (codes + fp16 codebooks).  Nothing inside a step waits for the host.
-Inputs are resident in HBM before the timed region.  Prints ONE
-JSON line ("Measurement").
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line: rows/s of the step, the
+roofline figures of the dominant kernel (algorithmic lane-operations per launch over the kernel's time
+from HIP events on its stream), the oracle's rate on the host cores, and figures of the other entry points.
 """
 from __future__ import annotations
 
