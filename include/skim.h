@@ -203,7 +203,8 @@ int64_t skim_codebook_entries(const uint8_t *bits_host, int64_t n);
  * f16(f32(centroid)) both round-to-nearest-even.  dW (optional, n x m float32,
  * stride m, original row order) = fl32(w - alpha * f32(codebook value)).
  * Labels are rebuilt from the thresholds: the cluster with the smallest upper
- * bound >= w~.  All pointers dev; group_word_offset is dev int64[6]. */
+ * bound >= w~.  All pointers dev; group_word_offset is dev int64[6].
+ * m < 2^29 (SKIM_ERR_SHAPE beyond). */
 skim_status skim_pack(skim_ctx *ctx, const float *W, const float *alpha, int64_t n, int64_t m,
                       int64_t ld, const uint8_t *bits, const double *centroids, const float *upper,
                       uint32_t *codes, int64_t *group_word_offset, int32_t *row_perm,
