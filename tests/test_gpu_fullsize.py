@@ -255,3 +255,23 @@ def test_config3_lfull_error_table_slice(ctx, gpu_lib):
     g = oracle.greedy(got, 3.0)
     assert np.array_equal(bits, g["bits"]) and spent == g["spent"] == budget
     print(f"\n[L-full table 512x4096] rows excused {int((~clean).sum())}, max rel err {rel.max():.2e}")
+
+
+def test_joint_table_size_exact_allocation(ctx):
+    """The knapsack optimum at half the rows of config 2's joint table with unit costs (13056 rows, 3.2 bits per
+    row: 28723 states in 35 workgroups, 204 launches of 64 rows; the oracle's recurrence takes 12 s there and
+    four times that at the full 26112) against the oracle, bit for bit; the table is synthetic (reductions of
+    either sign), the clustering is not what is tested here."""
+    rng = np.random.default_rng(2)
+    n = 13056
+    g = rng.standard_normal((n, 3)) * 0.3 + 0.5
+    E = np.empty((n, 4))
+    E[:, 3] = rng.random(n)
+    for j in (2, 1, 0):
+        E[:, j] = E[:, j + 1] + g[:, j]
+    out = ctx.dp_allocate(dev(E), 3.2)
+    torch.cuda.synchronize()
+    ref = oracle.dp_allocate(E, 3.2)
+    info = out["info"].cpu().numpy()
+    assert np.array_equal(out["bits"].cpu().numpy(), ref["bits"])
+    assert info[0] == ref["total"] and info[1] == ref["spent"] and info[2] == ref["budget"] == 41779
