@@ -209,16 +209,26 @@ __device__ __forceinline__ void wave_tail(double *lds, uint32_t tid, int m) {
     sort_pass<0, -1, 3, 0>(lds, tid, m);
 }
 
-// Merges of 2^KLOG > 1024 keys: one pass over the top window [LOGP-4, LOGP) between two
-// workgroup barriers (flip stage on index bit KLOG-1, then the bits down to 10), then wave_tail.
+// Merges of 2^KLOG > 1024 keys.  KLOG = 11, 12 (11 and 12 stages) take three passes: the window
+// [KLOG-4, KLOG) between two workgroup barriers (flip stage on index bit KLOG-1 and the three bits below
+// it), then the windows [4,8) and [0,4) inside the wavefront's own 1024 keys.  KLOG = 13, 14 need four:
+// the top window [LOGP-4, LOGP) between barriers (flip stage, then the bits down to 10), then wave_tail.
 template <int LOGP, int KLOG>
 __device__ __forceinline__ void cross_merges(double *lds, uint32_t tid, int m) {
     if constexpr (KLOG <= LOGP) {
-        constexpr int WBX = LOGP - 4;
-        __syncthreads();
-        sort_pass<WBX, KLOG - 1 - WBX, KLOG - 2 - WBX, 10 - WBX>(lds, tid, m);
-        __syncthreads();
-        wave_tail(lds, tid, m);
+        if constexpr (KLOG <= 12) {
+            __syncthreads();
+            sort_pass<KLOG - 4, 3, 2, 0>(lds, tid, m);          // index bits KLOG-1 .. KLOG-4
+            __syncthreads();
+            sort_pass<4, -1, KLOG - 9, 0>(lds, tid, m);         // index bits KLOG-5 .. 4
+            sort_pass<0, -1, 3, 0>(lds, tid, m);
+        } else {
+            constexpr int WBX = LOGP - 4;
+            __syncthreads();
+            sort_pass<WBX, KLOG - 1 - WBX, KLOG - 2 - WBX, 10 - WBX>(lds, tid, m);
+            __syncthreads();
+            wave_tail(lds, tid, m);
+        }
         cross_merges<LOGP, KLOG + 1>(lds, tid, m);
     }
 }
