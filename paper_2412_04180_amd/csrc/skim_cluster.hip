@@ -814,6 +814,10 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
     bool emptyk = false;             // ... in which it owned nothing (its value repeated the one below)
     bool done = !on;
 
+    // the boundary chunk of the previous iteration stays in registers: late iterations move a boundary by a few
+    // ranks, inside the same 16 keys, and then the lane asks the memory system for nothing
+    u64 el[16];
+    int cl_held = -2;
     for (int it = 0; it < prm.iters; ++it) {
         if (__ballot(!done) == 0) break;
         const bool live = !done;     // this lane's bit width still iterates
@@ -936,16 +940,18 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
 
         // ---- one round of global loads: the boundary chunk's keys and the level-0 pieces ----------
         // (lanes without a boundary chunk read the row's first chunk and ignore it)
-        u64 el[16];
         const int rbase = cl * 16;
-        {
-            const u64x2_a8 *kv = (const u64x2_a8 *)(keys + (cl >= 0 ? rbase : 0));
+        const int cl_want = cl >= 0 ? cl : 0;
+        const bool reload = cl_want != cl_held;
+        if (reload) {
+            const u64x2_a8 *kv = (const u64x2_a8 *)(keys + cl_want * 16);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const u64x2 t2 = kv[j];
                 el[2 * j] = t2.x;
                 el[2 * j + 1] = t2.y;
             }
+            cl_held = cl_want;
         }
         const int la0 = min(b0, (a0 + 3) & ~3), rb0 = max(la0, b0 & ~3);
         double2 pc[6];
