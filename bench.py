@@ -59,6 +59,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-scale-loop", action="store_true")
+    ap.add_argument("--no-other-shapes", action="store_true", help="skip the error-table timings on the other matrix shapes")
     ap.add_argument("--no-yardsticks", action="store_true", help="skip the exact-optimum yardsticks (extra figures only)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain elementwise copy of the W matrix (reads and writes n*m*4 bytes): "
@@ -225,11 +226,35 @@ def main():
             "dp_allocate_ms": round(y1.elapsed_time(y2), 3),
             "greedy_error_over_optimal_allocation": round(float(E_h[np.arange(n), bits - 1].sum() / dp["info"][0].item()), 6),
         }
+    if not args.no_other_shapes:
+        out["error_table_other_shapes"] = bench_other_shapes(ctx, torch)
     if not args.no_scale_loop:
         out["scale_loop"] = bench_scale_loop(ctx, torch, np, skim_synth)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(W_h, S_h, np)
     print(json.dumps(out))
+
+
+def bench_other_shapes(ctx, torch, reps=3):
+    """The error-table call on the other matrix shapes of the workload configs (values drawn on the device: normal
+    weights, squared-normal sensitivities; timing only)."""
+    res = []
+    gen = torch.Generator(device="cuda").manual_seed(1)
+    for n, m in ((4096, 4096), (11008, 4096), (22016, 8192), (8192, 22016)):
+        W = torch.randn(n, m, device="cuda", generator=gen) * 0.02
+        S = torch.randn(n, m, device="cuda", generator=gen) ** 2
+        out = ctx.error_table(W, S, iters=ITERS)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            ctx.error_table(W, S, iters=ITERS, out=out)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / reps * 1e3
+        so, ll = ctx.profile_last()
+        res.append({"rows": n, "cols": m, "table_ms": round(ms, 4), "sort_ms": round(so, 4),
+                    "iterations_ms": round(ll, 4), "Gweights_per_s": round(n * m / ms / 1e6, 1)})
+        del W, S, out
+    return res
 
 
 def bench_scale_loop(ctx, torch, np, skim_synth, iters=3):
