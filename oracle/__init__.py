@@ -97,7 +97,8 @@ def cluster_row(w, s, K, T=30, count_near=False):
 
 
 def error_table(W, S, alpha=None, bmin=1, bmax=4, T=30, count_near=False):
-    """Returns dict(E n x nb, centroids_all n x sum 2^b, upper_all, near[2])."""
+    """Returns dict(E n x nb, centroids_all n x sum 2^b, upper_all, near[2], near_rows n, near_rb n x nb):
+    near_rb[i, b] counts the decisions of row i at bit width b whose margin was below 1e-9."""
     W, S, alpha = _f32(W), _f32(S), _f32(alpha)
     n, m = W.shape
     nb = bmax - bmin + 1
@@ -107,11 +108,12 @@ def error_table(W, S, alpha=None, bmin=1, bmax=4, T=30, count_near=False):
     ua = np.empty((n, stride), np.float64)
     near = np.zeros(2, np.int64)
     near_rows = np.zeros(n, np.int64) if count_near else None
+    near_rb = np.zeros((n, nb), np.int64) if count_near else None
     _check(lib().oracle_error_table(_p(W), _p(S), _p(alpha), C.c_int64(n), C.c_int64(m),
                                     C.c_int64(m), C.c_int(bmin), C.c_int(bmax), C.c_int(T), _p(E),
-                                    _p(ca), _p(ua), _p(near) if count_near else None, _p(near_rows)),
-           "error_table")
-    return dict(E=E, centroids_all=ca, upper_all=ua, near=near, near_rows=near_rows)
+                                    _p(ca), _p(ua), _p(near) if count_near else None, _p(near_rows),
+                                    _p(near_rb)), "error_table")
+    return dict(E=E, centroids_all=ca, upper_all=ua, near=near, near_rows=near_rows, near_rb=near_rb)
 
 
 def cluster_rows(W, S, bits, alpha=None, T=30, count_near=False, want_labels=True):

@@ -265,10 +265,11 @@ int oracle_cluster_row(const float *w, const float *s, int64_t m, int K, int T, 
  * L-full error of the same clustering is what oracle_layer_loss returns per
  * row.  centroids_all / upper_all hold, per row, the blocks for b = bmin..bmax
  * back to back (2^bmin + ... + 2^bmax entries).  near: [0] init, [1] assign;
- * near_rows (optional, n entries): near-tie count of each row over all b.     */
+ * near_rows (optional, n entries): near-tie count of each row over all b;
+ * near_rb (optional, n x nb): the same count per row and bit width.           */
 int oracle_error_table(const float *W, const float *S, const float *alpha, int64_t n, int64_t m,
                        int64_t ld, int bmin, int bmax, int T, double *E, double *centroids_all,
-                       double *upper_all, int64_t *near, int64_t *near_rows) {
+                       double *upper_all, int64_t *near, int64_t *near_rows, int64_t *near_rb) {
     if (bmin < 1 || bmax > 8 || bmin > bmax) return ORACLE_ERR_ARG;
     if (m < (1 << bmax) || ld < m) return ORACLE_ERR_SHAPE;
     const int nb = bmax - bmin + 1;
@@ -287,12 +288,13 @@ int oracle_error_table(const float *W, const float *S, const float *alpha, int64
             double cbuf[KMAX], ubuf[KMAX], e;
             int64_t nt[2] = {0, 0};
             int r = oracle_cluster_row(wt, st, m, K, T, NULL, cbuf, ubuf, &e, NULL,
-                                       (near || near_rows) ? nt : NULL);
+                                       (near || near_rows || near_rb) ? nt : NULL);
             if (r != ORACLE_OK) {
 #pragma omp critical
                 rc = r;
             }
             if (near_rows) near_rows[i] = (b == bmin ? 0 : near_rows[i]) + nt[0] + nt[1];
+            if (near_rb) near_rb[i * nb + (b - bmin)] = nt[0] + nt[1];
             E[i * nb + (b - bmin)] = e;
             if (centroids_all) memcpy(centroids_all + i * stride + off, cbuf, sizeof(double) * K);
             if (upper_all) memcpy(upper_all + i * stride + off, ubuf, sizeof(double) * K);
