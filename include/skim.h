@@ -210,6 +210,23 @@ skim_status skim_pack(skim_ctx *ctx, const float *W, const float *alpha, int64_t
                       uint32_t *codes, int64_t *group_word_offset, int32_t *row_perm,
                       uint16_t *codebooks_fp16, float *dW);
 
+/* skim_pack for callers that cannot allocate device memory or hand over a
+ * workspace (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): same arguments, same results, but the scratch of the call
+ * (one int per row and a small group table) lives in a device array inside the
+ * library instead of the workspace, so the call allocates nothing and needs no
+ * skim_set_workspace.  n <= SKIM_PACK_STATIC_MAX_ROWS (SKIM_ERR_SHAPE beyond;
+ * use skim_pack then).  Every GPU the library runs on holds its own copy of the
+ * array (256 KiB) until the process ends; all calls on one GPU share it, so
+ * calls that overlap on one GPU (different streams or threads) race -- issue
+ * them on one stream.  Nothing in the array has to survive or be cleared
+ * between calls: every call writes what it reads. */
+#define SKIM_PACK_STATIC_MAX_ROWS 65536
+skim_status skim_pack_static(skim_ctx *ctx, const float *W, const float *alpha, int64_t n, int64_t m,
+                             int64_t ld, const uint8_t *bits, const double *centroids,
+                             const float *upper, uint32_t *codes, int64_t *group_word_offset,
+                             int32_t *row_perm, uint16_t *codebooks_fp16, float *dW);
+
 /* ---- readers of the packed model ------------------------------------------ */
 
 /* Dequantisation of what skim_pack wrote (same layout, dev pointers):

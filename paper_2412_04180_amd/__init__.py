@@ -19,12 +19,13 @@ SKIM_OK = 0
 STATUS_NAMES = {0: "SKIM_OK", -1: "SKIM_ERR_ARG", -2: "SKIM_ERR_SHAPE", -3: "SKIM_ERR_BUDGET",
                 -4: "SKIM_ERR_WORKSPACE", -5: "SKIM_ERR_HIP", -6: "SKIM_ERR_NONFINITE"}
 MAX_M = 32768
+PACK_STATIC_MAX_ROWS = 65536
 
 EXPORTS = ["skim_create", "skim_destroy", "skim_last_error", "skim_workspace_bytes", "skim_set_workspace",
            "skim_profile_enable", "skim_profile_last",
            "skim_error_table", "skim_error_table_lfull", "skim_cluster_rows", "skim_select_allocated", "skim_greedy_allocate", "skim_greedy_allocate_device",
            "skim_dp_allocate_scratch_bytes", "skim_dp_allocate", "skim_kmeans_optimal_scratch_bytes", "skim_kmeans_optimal",
-           "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_layer_loss", "skim_scale_step", "skim_train_scale", "skim_unpack", "skim_dequant_matvec", "skim_hessian_from_activations"]
+           "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_pack_static", "skim_layer_loss", "skim_scale_step", "skim_train_scale", "skim_unpack", "skim_dequant_matvec", "skim_hessian_from_activations"]
 
 
 class SkimError(RuntimeError):
@@ -80,6 +81,7 @@ def load_library():
         lib.skim_codebook_entries.argtypes = [vp, i64]
         lib.skim_codebook_entries.restype = i64
         lib.skim_pack.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.skim_pack_static.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.skim_layer_loss.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp]
         lib.skim_scale_step.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, i64, C.POINTER(AdamOpts), vp, vp]
         lib.skim_hessian_from_activations.argtypes = [vp, vp, i64, i64, vp]
@@ -321,6 +323,16 @@ class Context:
         self._check(self.lib.skim_pack(self.h, _dp(W), _dp(alpha), n, m, W.stride(0), _dp(bits), _dp(centroids),
                                        _dp(upper), _dp(codes), _dp(gwo), _dp(perm), _dp(cbs), _dp(dW)))
         return dict(codes=codes, group_word_offset=gwo, row_perm=perm, codebooks=cbs, dW=dW)
+
+    def pack_static(self, W, alpha, bits, centroids, upper, out):
+        """skim_pack_static: the variant of pack that neither allocates nor uses the workspace.  Every output is
+        the caller's: out = dict(codes, group_word_offset, row_perm, codebooks[, dW]) of device tensors."""
+        n, m = W.shape
+        self._check(self.lib.skim_pack_static(self.h, _dp(W), _dp(alpha), n, m, W.stride(0), _dp(bits),
+                                              _dp(centroids), _dp(upper), _dp(out["codes"]),
+                                              _dp(out["group_word_offset"]), _dp(out["row_perm"]),
+                                              _dp(out["codebooks"]), _dp(out.get("dW"))))
+        return out
 
     # -- scaling vector -------------------------------------------------------
     def layer_loss(self, W, S, H, labels, alpha=None, want_row_loss=True):

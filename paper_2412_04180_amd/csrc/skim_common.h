@@ -20,6 +20,7 @@ struct skim_ctx {
     int profiling;
     hipEvent_t ev[3];    // before sort, between sort and Lloyd, after Lloyd
     int ev_valid;
+    void *pack_scratch;  // this device's address of the static scratch of skim_pack_static
 };
 
 #define SKIM_FAIL(ctx, code, ...)                                   \
@@ -59,6 +60,9 @@ struct skim_ws_cursor {
 static inline int skim_block_offset(int bmin, int b) {  // start of block b inside a row of the *_all arrays
     return (1 << b) - (1 << bmin);
 }
+
+// Looks up this device's address of the static scratch of skim_pack_static (the device must be current).
+skim_status skim_pack_static_setup(skim_ctx *ctx);
 
 // skim_layer_loss with the per-row losses written at a stride (row i at row_loss[i * row_stride]).
 skim_status skim_layer_loss_strided(skim_ctx *ctx, const float *W, const float *S, const float *alpha, const float *H,

@@ -51,6 +51,12 @@ extern "C" skim_status skim_create(skim_ctx **out, int device, void *hip_stream)
     c->ev_valid = 0;
     for (int i = 0; i < 3; ++i) c->ev[i] = nullptr;
     c->err[0] = 0;
+    c->pack_scratch = nullptr;
+    if (skim_pack_static_setup(c) != SKIM_OK) {
+        snprintf(g_create_err, sizeof(g_create_err), "skim_create: %s", c->err);
+        delete c;
+        return SKIM_ERR_HIP;
+    }
     *out = c;
     return SKIM_OK;
 }

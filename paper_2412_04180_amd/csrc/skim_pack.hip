@@ -9,8 +9,11 @@
 #include <hip/hip_fp16.h>
 #include <math.h>
 
+#include <mutex>
+
 namespace {
 
+constexpr int SKIM_PACK_STATIC_MAX_DEVICES = 64;
 constexpr int PLAN_THREADS = 1024;
 constexpr int PACK_THREADS = 256;
 
@@ -223,20 +226,11 @@ __global__ void __launch_bounds__(PACK_THREADS) pack_rows_kernel(const float *W,
 
 }  // namespace
 
-extern "C" skim_status skim_pack(skim_ctx *ctx, const float *W, const float *alpha, int64_t n, int64_t m,
-                                 int64_t ld, const uint8_t *bits, const double *centroids, const float *upper,
-                                 uint32_t *codes, int64_t *group_word_offset, int32_t *row_perm,
-                                 uint16_t *codebooks_fp16, float *dW) {
-    skim_status st = skim_enter(ctx);
-    if (st != SKIM_OK) return st;
-    if (!W || !bits || !centroids || !upper || !codes || !group_word_offset || !row_perm || !codebooks_fp16)
-        SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_pack: NULL argument");
-    if (n < 1 || n > 0x7fffffff || m < 1 || ld < m) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "skim_pack: bad shape n=%lld m=%lld ld=%lld", (long long)n, (long long)m, (long long)ld);
-    if (m >= (1ll << 29)) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "skim_pack: row too long (m < 2^29)");
-    skim_ws_cursor cur{(char *)ctx->ws, 0, ctx->ws_bytes};
-    int *rowpos = (int *)cur.take((size_t)n * sizeof(int));
-    PackPlan *plan = (PackPlan *)cur.take(sizeof(PackPlan));
-    if (!rowpos || !plan) SKIM_FAIL(ctx, SKIM_ERR_WORKSPACE, "skim_pack: workspace missing or smaller than skim_workspace_bytes(n, m)");
+// The two launches of a pack call; rowpos (n ints) and plan are the call's scratch.
+static skim_status launch_pack(skim_ctx *ctx, const float *W, const float *alpha, int64_t n, int64_t m, int64_t ld,
+                               const uint8_t *bits, const double *centroids, const float *upper, uint32_t *codes,
+                               int64_t *group_word_offset, int32_t *row_perm, uint16_t *codebooks_fp16, float *dW,
+                               int *rowpos, PackPlan *plan) {
     hipLaunchKernelGGL(pack_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, ctx->stream, (long long)n, (long long)m, bits,
                        rowpos, row_perm, plan, (long long *)group_word_offset);
     SKIM_HIP(ctx, hipGetLastError());
@@ -244,4 +238,81 @@ extern "C" skim_status skim_pack(skim_ctx *ctx, const float *W, const float *alp
                        (long long)ld, bits, centroids, upper, rowpos, plan, codes, codebooks_fp16, dW);
     SKIM_HIP(ctx, hipGetLastError());
     return SKIM_OK;
+}
+
+static skim_status check_pack_args(skim_ctx *ctx, const float *W, int64_t n, int64_t m, int64_t ld, const uint8_t *bits,
+                                   const double *centroids, const float *upper, uint32_t *codes,
+                                   int64_t *group_word_offset, int32_t *row_perm, uint16_t *codebooks_fp16) {
+    if (!W || !bits || !centroids || !upper || !codes || !group_word_offset || !row_perm || !codebooks_fp16)
+        SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_pack: NULL argument");
+    if (n < 1 || n > 0x7fffffff || m < 1 || ld < m) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "skim_pack: bad shape n=%lld m=%lld ld=%lld", (long long)n, (long long)m, (long long)ld);
+    if (m >= (1ll << 29)) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "skim_pack: row too long (m < 2^29)");
+    return SKIM_OK;
+}
+
+extern "C" skim_status skim_pack(skim_ctx *ctx, const float *W, const float *alpha, int64_t n, int64_t m,
+                                 int64_t ld, const uint8_t *bits, const double *centroids, const float *upper,
+                                 uint32_t *codes, int64_t *group_word_offset, int32_t *row_perm,
+                                 uint16_t *codebooks_fp16, float *dW) {
+    skim_status st = skim_enter(ctx);
+    if (st != SKIM_OK) return st;
+    if ((st = check_pack_args(ctx, W, n, m, ld, bits, centroids, upper, codes, group_word_offset, row_perm,
+                              codebooks_fp16)) != SKIM_OK)
+        return st;
+    skim_ws_cursor cur{(char *)ctx->ws, 0, ctx->ws_bytes};
+    int *rowpos = (int *)cur.take((size_t)n * sizeof(int));
+    PackPlan *plan = (PackPlan *)cur.take(sizeof(PackPlan));
+    if (!rowpos || !plan) SKIM_FAIL(ctx, SKIM_ERR_WORKSPACE, "skim_pack: workspace missing or smaller than skim_workspace_bytes(n, m)");
+    return launch_pack(ctx, W, alpha, n, m, ld, bits, centroids, upper, codes, group_word_offset, row_perm,
+                       codebooks_fp16, dW, rowpos, plan);
+}
+
+// ---------------------------------------------------------------------------------------------
+// skim_pack for callers that cannot allocate device memory or register a workspace: the scratch of
+// the call (row positions and the group table) lives in a file-scope device array.  Every device the
+// library runs on holds its own copy of the array at its own address; the address is looked up once
+// per device by skim_create (through skim_pack_static_setup below, with that device current) and
+// kept in the context.  Host code never passes the array's name to a kernel: on the host the name
+// is only a handle for hipGetSymbolAddress.
+// ---------------------------------------------------------------------------------------------
+static_assert(sizeof(PackPlan) <= 256, "the group table must fit the first 256 bytes of the static scratch");
+static __device__ __align__(256) unsigned char pack_static_scratch[SKIM_PACK_STATIC_MAX_ROWS * sizeof(int) + 256];
+
+static std::mutex pack_static_mutex;
+static void *pack_static_addr[SKIM_PACK_STATIC_MAX_DEVICES];   // per device, looked up once
+
+skim_status skim_pack_static_setup(skim_ctx *ctx) {
+    if (ctx->device < 0 || ctx->device >= SKIM_PACK_STATIC_MAX_DEVICES)
+        SKIM_FAIL(ctx, SKIM_ERR_ARG, "device %d beyond the %d devices the static scratch table holds", ctx->device,
+                  SKIM_PACK_STATIC_MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(pack_static_mutex);
+    if (!pack_static_addr[ctx->device]) {
+        void *ptr = nullptr;
+        SKIM_HIP(ctx, hipGetSymbolAddress(&ptr, HIP_SYMBOL(pack_static_scratch)));
+        if (!ptr) SKIM_FAIL(ctx, SKIM_ERR_HIP, "hipGetSymbolAddress returned no address for the static pack scratch");
+        pack_static_addr[ctx->device] = ptr;
+    }
+    ctx->pack_scratch = pack_static_addr[ctx->device];
+    return SKIM_OK;
+}
+
+extern "C" skim_status skim_pack_static(skim_ctx *ctx, const float *W, const float *alpha, int64_t n, int64_t m,
+                                        int64_t ld, const uint8_t *bits, const double *centroids,
+                                        const float *upper, uint32_t *codes, int64_t *group_word_offset,
+                                        int32_t *row_perm, uint16_t *codebooks_fp16, float *dW) {
+    skim_status st = skim_enter(ctx);
+    if (st != SKIM_OK) return st;
+    if ((st = check_pack_args(ctx, W, n, m, ld, bits, centroids, upper, codes, group_word_offset, row_perm,
+                              codebooks_fp16)) != SKIM_OK)
+        return st;
+    if (n > SKIM_PACK_STATIC_MAX_ROWS)
+        SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "skim_pack_static: n = %lld rows, the static scratch holds %d at most (use skim_pack)",
+                  (long long)n, SKIM_PACK_STATIC_MAX_ROWS);
+    if (!ctx->pack_scratch) SKIM_FAIL(ctx, SKIM_ERR_HIP, "skim_pack_static: the context has no static scratch address");
+    // layout: the group table in the first 256 bytes, then one int per row.  Both are written in full by the
+    // plan kernel before the row kernel reads them, so nothing of an earlier call survives into this one.
+    PackPlan *plan = (PackPlan *)ctx->pack_scratch;
+    int *rowpos = (int *)((char *)ctx->pack_scratch + 256);
+    return launch_pack(ctx, W, alpha, n, m, ld, bits, centroids, upper, codes, group_word_offset, row_perm,
+                       codebooks_fp16, dW, rowpos, plan);
 }
