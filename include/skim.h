@@ -46,7 +46,7 @@ typedef enum {
     SKIM_ERR_BUDGET = -3,    /* average bits outside [bmin, bmax]                       */
     SKIM_ERR_WORKSPACE = -4, /* workspace missing or too small                          */
     SKIM_ERR_HIP = -5,       /* a HIP runtime call failed                               */
-    SKIM_ERR_NONFINITE = -6  /* reserved                                                */
+    SKIM_ERR_NONFINITE = -6  /* validation on: W, S or alpha holds a value the method is undefined on */
 } skim_status;
 
 /* Adam with step decay for the scaling vector (Sec. 5.1 "Settings": Adam,
@@ -79,6 +79,17 @@ const char *skim_last_error(const skim_ctx *ctx);
 size_t skim_workspace_bytes(int64_t n, int64_t m);
 skim_status skim_set_workspace(skim_ctx *ctx, void *dev_ptr, size_t bytes);
 
+/* Optional validation of the inputs of the clustering calls (skim_error_table,
+ * skim_cluster_rows and the calls built on them).  The method is undefined on
+ * weights that are not finite, sensitivities that are negative or not finite
+ * and scales that are not positive finite numbers; by default such inputs are
+ * not looked for (the result is then unspecified, every access stays in
+ * bounds).  With validation on, each such call first runs one pass over W, S
+ * and alpha, waits for it (the call synchronises with the stream), and returns
+ * SKIM_ERR_NONFINITE, with the text naming the array, before any other work.
+ * Uses 256 bytes of the registered workspace. */
+skim_status skim_validate_enable(skim_ctx *ctx, int on);
+
 /* Optional timing of the two phases of a clustering call (skim_error_table,
  * skim_cluster_rows) with HIP events on the context's stream: the sort phase
  * (load, sort, sums) and the Lloyd phase (iterations, errors, outputs).
@@ -103,7 +114,7 @@ skim_status skim_profile_last(skim_ctx *ctx, float *sort_ms, float *lloyd_ms);
  * upper_all: dev float32, same layout: largest member w~ of each cluster,
  *   -inf for an empty cluster (the thresholds skim_pack rebuilds labels from);
  *   may be NULL.
- * 1 <= bmin <= bmax <= 4, 16 <= 2^bmax <= m <= SKIM_MAX_M, iters >= 1. */
+ * 1 <= bmin <= bmax <= 4, 2^bmax <= m <= SKIM_MAX_M, iters >= 1. */
 skim_status skim_error_table(skim_ctx *ctx, const float *W, const float *S, const float *alpha,
                              int64_t n, int64_t m, int64_t ld, int bmin, int bmax, int iters,
                              double *E, double *centroids_all, float *upper_all);
@@ -269,12 +280,14 @@ skim_status skim_layer_loss(skim_ctx *ctx, const float *W, const float *S, const
                             const float *H, int64_t n, int64_t m, int64_t ld,
                             const uint8_t *labels, double *loss, double *row_loss);
 
-/* Error pre-recording with the layer-wise error (Alg. 3 lines 2-10 read with
- * "Err(.) refers to the L-full form", Sec. 4.2 and Sec. 3.4): the rows are
+/* Error pre-recording with the layer-wise error (Alg. 3 lines 2-10, with the
+ * error taken in its L-full form as Sec. 4.2 prescribes; Sec. 3.4): the rows are
  * clustered for every b in [bmin, bmax] exactly as in skim_error_table, and
  *   E_full[i][b-bmin] = dW_i H dW_i^T,  dW_i = w_i - alpha * c_{i, L_i}
  * with L the labels of that clustering and c the weighted means of its clusters
- * (one fp32-MFMA contraction dW * H per bit width, float64 reductions).
+ * (a cluster whose members carry no sensitivity mass keeps the centroid the
+ * clustering left it with, the value skim_pack stores; one fp32-MFMA
+ * contraction dW * H per bit width, float64 reductions).
  * E_full: dev float64 n x nb.  E_sdiag: dev float64 n x nb, the S-diag errors
  * of the same clusterings (what skim_error_table returns), may be NULL.
  * centroids_all, upper_all: as in skim_error_table, required.  labels_work:

@@ -22,7 +22,7 @@ MAX_M = 32768
 PACK_STATIC_MAX_ROWS = 65536
 
 EXPORTS = ["skim_create", "skim_destroy", "skim_last_error", "skim_workspace_bytes", "skim_set_workspace",
-           "skim_profile_enable", "skim_profile_last",
+           "skim_profile_enable", "skim_profile_last", "skim_validate_enable",
            "skim_error_table", "skim_error_table_lfull", "skim_cluster_rows", "skim_select_allocated", "skim_greedy_allocate", "skim_greedy_allocate_device",
            "skim_dp_allocate_scratch_bytes", "skim_dp_allocate", "skim_kmeans_optimal_scratch_bytes", "skim_kmeans_optimal",
            "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_pack_static", "skim_layer_loss", "skim_scale_step", "skim_train_scale", "skim_unpack", "skim_dequant_matvec", "skim_hessian_from_activations"]
@@ -63,6 +63,7 @@ def load_library():
         lib.skim_workspace_bytes.restype = C.c_size_t
         lib.skim_set_workspace.argtypes = [vp, vp, C.c_size_t]
         lib.skim_profile_enable.argtypes = [vp, i32]
+        lib.skim_validate_enable.argtypes = [vp, i32]
         lib.skim_profile_last.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         lib.skim_error_table.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, vp, vp]
         lib.skim_error_table_lfull.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, vp, vp, vp, vp]
@@ -167,8 +168,16 @@ class Context:
     def ensure_workspace(self, n, m):
         need = self.workspace_bytes(n, m)
         if self._ws is None or self._ws.numel() < need:
-            self._ws = self.torch.empty(need, dtype=self.torch.uint8, device=self.device)
+            # allocated on the context's stream: torch's allocator then ties the lifetime of the old block to
+            # the work already queued on that stream
+            with self.torch.cuda.stream(self.stream):
+                self._ws = self.torch.empty(need, dtype=self.torch.uint8, device=self.device)
             self._check(self.lib.skim_set_workspace(self.h, _dp(self._ws), need))
+
+    def validate_enable(self, on=True):
+        """Make the clustering calls check W, S and alpha first (they then synchronise and raise SkimError with
+        status SKIM_ERR_NONFINITE on a value the method is not defined on)."""
+        self._check(self.lib.skim_validate_enable(self.h, 1 if on else 0))
 
     def profile_enable(self, on=True):
         self._check(self.lib.skim_profile_enable(self.h, 1 if on else 0))
@@ -180,7 +189,8 @@ class Context:
         return a.value, b.value
 
     def empty(self, shape, dtype):
-        return self.torch.empty(shape, dtype=dtype, device=self.device)
+        with self.torch.cuda.stream(self.stream):     # outputs belong to the stream the kernels run on
+            return self.torch.empty(shape, dtype=dtype, device=self.device)
 
     # -- clustering -----------------------------------------------------------
     def error_table(self, W, S, alpha=None, bmin=1, bmax=4, iters=30, want_centroids=True, want_upper=True,

@@ -62,6 +62,12 @@ struct ClusterParams {
     u64 *keys_seg;
     int *segmass;         // per segment of a long row: nonzero when it holds sensitivity mass
     long long nwork;      // rows x segments: the units of work sort_kernel's workgroups share out
+    int *vflag;           // validation result (one word of scratch)
+    // bucket path of sort_kernel: value bins per thread (0: always the bitonic network) and the byte
+    // offsets of its tables inside the dynamic LDS
+    int bk_bpt;
+    int bk_pad, bk_lgbpt;   // spare words after every thread's block of counters (0 or 4); log2(bk_bpt) when padded
+    uint32_t bk_hist_off, bk_coarse_off, bk_misc_off;
 };
 
 struct BitState {  // what the Lloyd lanes of one bit width leave for the epilogue
@@ -294,37 +300,398 @@ __device__ __forceinline__ int quad_sum(int x) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Bucket path of the sort.  A full sorting network pays for the worst case; the rows here are m
+// draws from a smooth density, so a monotone map from the weight to one of about 2m value bins
+// leaves a handful of keys per bin, and a counting sort by bin puts every key within a few slots
+// of its final rank in one scatter.  What remains is order inside the bins:
+//   * every thread sorts the 16 slots [16t, 16t+16) in registers (Batcher's odd-even merge sort,
+//     63 compare-exchanges), which orders every bin that lies inside one such window;
+//   * a bin that straddles a multiple of 16 has at most 8 keys on either side when no bin holds
+//     more than 8 keys, so one 8+8 merge of the upper half of window t with the lower half of
+//     window t+1 (25 compare-exchanges) finishes the row.
+// The bin map has two levels so that it adapts to the row: a coarse histogram over nth equal
+// intervals of [min, max], then every coarse interval is cut into a number of equal bins
+// proportional to its count (a piecewise linear estimate of the distribution function).  Any
+// monotone map gives a correct sort; the map only decides how full the bins get.  A row in which
+// some bin holds more than 8 keys (heavy duplicates, wild outliers, a constant row) takes the
+// bitonic network instead: same result, key for key.
+// ---------------------------------------------------------------------------------------------
+constexpr int BIN_MAX_KEYS = 8;
+
+// position of a weight on the coarse axis; single-precision operations that the compiler may not fuse,
+// so that the two places that evaluate it agree bit for bit
+__device__ __forceinline__ float coarse_pos(float w, float lo, float scale) { return __fmul_rn(__fsub_rn(w, lo), scale); }
+
+#define SKIM_X(a, b) ce(v[a], v[b]);
+// Batcher's odd-even merge sort of 16 keys, in layers of independent comparators
+__device__ __forceinline__ void sort16(double (&v)[16]) {
+    SKIM_X(0,1) SKIM_X(2,3) SKIM_X(4,5) SKIM_X(6,7) SKIM_X(8,9) SKIM_X(10,11) SKIM_X(12,13) SKIM_X(14,15)
+    SKIM_X(0,2) SKIM_X(1,3) SKIM_X(4,6) SKIM_X(5,7) SKIM_X(8,10) SKIM_X(9,11) SKIM_X(12,14) SKIM_X(13,15)
+    SKIM_X(1,2) SKIM_X(5,6) SKIM_X(0,4) SKIM_X(3,7) SKIM_X(9,10) SKIM_X(13,14) SKIM_X(8,12) SKIM_X(11,15)
+    SKIM_X(2,6) SKIM_X(1,5) SKIM_X(10,14) SKIM_X(9,13) SKIM_X(0,8) SKIM_X(7,15)
+    SKIM_X(2,4) SKIM_X(3,5) SKIM_X(10,12) SKIM_X(11,13)
+    SKIM_X(1,2) SKIM_X(3,4) SKIM_X(5,6) SKIM_X(9,10) SKIM_X(11,12) SKIM_X(13,14)
+    SKIM_X(4,12) SKIM_X(2,10) SKIM_X(6,14) SKIM_X(1,9) SKIM_X(5,13) SKIM_X(3,11)
+    SKIM_X(4,8) SKIM_X(6,10) SKIM_X(5,9) SKIM_X(7,11)
+    SKIM_X(2,4) SKIM_X(6,8) SKIM_X(10,12) SKIM_X(3,5) SKIM_X(7,9) SKIM_X(11,13)
+    SKIM_X(1,2) SKIM_X(3,4) SKIM_X(5,6) SKIM_X(7,8) SKIM_X(9,10) SKIM_X(11,12) SKIM_X(13,14)
+}
+// odd-even merge of v[0..8) and v[8..16), each ascending
+__device__ __forceinline__ void merge8x8(double (&v)[16]) {
+    SKIM_X(0,8) SKIM_X(4,12) SKIM_X(2,10) SKIM_X(6,14) SKIM_X(1,9) SKIM_X(5,13) SKIM_X(3,11) SKIM_X(7,15)
+    SKIM_X(4,8) SKIM_X(6,10) SKIM_X(5,9) SKIM_X(7,11)
+    SKIM_X(2,4) SKIM_X(6,8) SKIM_X(10,12) SKIM_X(3,5) SKIM_X(7,9) SKIM_X(11,13)
+    SKIM_X(1,2) SKIM_X(3,4) SKIM_X(5,6) SKIM_X(7,8) SKIM_X(9,10) SKIM_X(11,12) SKIM_X(13,14)
+}
+#undef SKIM_X
+
+// Inclusive prefix sum over the 64 lanes of a wavefront inside the VALU: shifts by 1, 2, 4, 8 within each
+// row of 16 lanes (a lane without a source adds 0), then the last lane of row 0 / 2 into rows 1 / 3 and lane
+// 31 into the upper half.
+__device__ __forceinline__ uint32_t wave_scan_incl(uint32_t x) {
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xF, 0xF, false);   // row_shr:1
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xF, 0xF, false);   // row_shr:2
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xF, 0xF, false);   // row_shr:4
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xF, 0xF, false);   // row_shr:8
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1, 3
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2, 3
+    return x;
+}
+// Sum of the totals of the wavefronts below `wave` (tot: 16 entries in LDS, entries past the last wavefront 0).
+__device__ __forceinline__ uint32_t waves_below(const uint32_t *tot, int wave) {
+    const uint4 *t4 = (const uint4 *)tot;
+    uint32_t acc = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint4 t = t4[q];
+        acc += (4 * q + 0 < wave ? t.x : 0u) + (4 * q + 1 < wave ? t.y : 0u) + (4 * q + 2 < wave ? t.z : 0u) +
+               (4 * q + 3 < wave ? t.w : 0u);
+    }
+    return acc;
+}
+
+// Which of a thread's key slots hold a key of the unit, and which column a slot is.
+//   VEC == false: slot k is column tid + k * nth, so all slots below kfull = m / nth hold a key, slot kfull does in
+//                 the threads below m % nth, and none above.
+//   VEC == true:  slots 4g .. 4g+3 are the four columns from 4 (tid + g * nth) on (one 16-byte load each of W and
+//                 S); m is a multiple of 4 then and the same rule holds for g with m / 4.
+// nth is a power of two, so the first test is on uniform values only.
+template <bool VEC>
+struct Slots {
+    int kfull, tid, nth;
+    bool part;
+    __device__ __forceinline__ Slots(int m, int nth_, int tid_) : tid(tid_), nth(nth_) {
+        const int sh = 31 - __builtin_clz((unsigned)nth_);
+        const int units = VEC ? (m >> 2) : m;
+        kfull = units >> sh;
+        part = tid_ < (units & (nth_ - 1));
+    }
+    __device__ __forceinline__ bool has(int k) const {
+        const int g = VEC ? (k >> 2) : k;
+        return g < kfull || (g == kfull && part);
+    }
+    __device__ __forceinline__ int col(int k) const { return VEC ? 4 * (tid + (k >> 2) * nth) + (k & 3) : tid + k * nth; }
+};
+
+// LDS tables of the bucket path (byte offsets from ClusterParams::bk_*_off):
+//   hist     two 16-bit counters per word, one per value bin; later the first rank of every bin.  A thread
+//            scans the bk_bpt bins [tid * bk_bpt, (tid + 1) * bk_bpt) with 16-byte accesses; its block of words is
+//            followed by bk_pad spare words so that the blocks of 8 neighbouring threads start in different banks
+//   coarse   COARSE_N intervals x 4 counters (a lane adds to copy lane & 3: fewer same-address collisions),
+//            then per interval (first bin, number of bins) as two floats
+//   misc     per wavefront: least weight, largest weight, mass flag, scan total, overflow flag (16 entries each)
+constexpr int COARSE_N = 256;
+constexpr uint32_t BK_COARSE_BYTES = COARSE_N * 4 * 4 + COARSE_N * 8;
+constexpr uint32_t BK_MISC_BYTES = 512;
+constexpr uint32_t BK_WMIN = 0, BK_WMAX = 64, BK_WMASS = 128, BK_WTOT = 256, BK_WOVER = 320;
+
+// Sorts the m keys held in registers (key[k], k < NS, the slots of Slots<VEC>) into LDS, rank r at slot
+// swz(r), by the bucket path.  lo, hi: least and largest weight of the row (the same in every thread).
+// Returns false, with nothing of value in LDS, when some bin took more than BIN_MAX_KEYS keys; all threads
+// of the workgroup return the same.  Contains workgroup barriers: every thread must call it.  The coarse
+// counters must be zero on entry (and a barrier must lie between clearing them and this call).
+// prefetch(g), g = 1, 2, 3: issues part g of the loads of the next unit (spread over the phases so that the
+// memory pipeline and the LDS work side by side).
+template <int NS, bool VEC, typename Prefetch>
+__device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterParams &prm, const u64 (&key)[NS],
+                                            int tid, int nth, int m, float lo, float hi, Prefetch prefetch) {
+    const int lane = tid & 63, wave = tid >> 6;
+    const Slots<VEC> sm(m, nth, tid);
+    uint32_t *hist = (uint32_t *)(smem + prm.bk_hist_off);
+    uint32_t *coarse = (uint32_t *)(smem + prm.bk_coarse_off);
+    float2 *table = (float2 *)(coarse + COARSE_N * 4);
+    uint32_t *wtot = (uint32_t *)(smem + prm.bk_misc_off + BK_WTOT);
+    uint32_t *wover = (uint32_t *)(smem + prm.bk_misc_off + BK_WOVER);
+    const int bpt = prm.bk_bpt;
+    const int nbins = bpt * nth;
+    const int hstride = (bpt >> 1) + prm.bk_pad;    // words from one thread's block of counters to the next
+    // (1 - 2^-20): the largest weight stays below the end of the axis
+    const float scale = (float)COARSE_N / (hi - lo) * 0.99999904632568359375f;
+    // ---- coarse histogram of a sample: every fourth slot of a thread (every fourth column when VEC, else
+    // the columns [4q nth, (4q+1) nth))
+    int nsample = VEC ? (m >> 2) : 0;
+    if (!VEC) {
+#pragma unroll
+        for (int k = 0; k < NS; k += 4) nsample += max(0, min(nth, m - k * nth));
+    }
+#pragma unroll
+    for (int k = 0; k < NS; k += 4) {
+        if (sm.has(k)) {
+            const int cb = min(max((int)coarse_pos(elem_w(key[k]), lo, scale), 0), COARSE_N - 1);
+            atomicAdd(&coarse[cb * 4 + (lane & 3)], 1u);
+        }
+    }
+    // clear this thread's share of the fine counters meanwhile
+    {
+        uint4 *hz = (uint4 *)(hist + tid * hstride);
+        for (int q = 0; q < (bpt >> 3); ++q) hz[q] = make_uint4(0u, 0u, 0u, 0u);
+    }
+    prefetch(1);
+    __syncthreads();
+    // ---- bins per coarse interval and the first bin of each.  Every wavefront works the whole table out for
+    // itself (4 intervals per lane) and writes it: all write the same words, and a wavefront's own LDS accesses
+    // execute in order, so no barrier is needed before the table is used.  The sampled counts are smoothed
+    // (1 2 1) so that a sparse interval the sample missed still gets bins from its neighbours' counts, and every
+    // interval gets one bin on top of its share.
+    {
+        const uint4 *cc4 = (const uint4 *)coarse;
+        float c[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint4 t = cc4[4 * lane + q];
+            c[q] = (float)(t.x + t.y + t.z + t.w);
+        }
+        float below = __int_as_float(lane_below(__float_as_int(c[3])));
+        float above = __int_as_float(lane_above(__float_as_int(c[0])));
+        if (lane == 0) below = c[0];
+        if (lane == 63) above = c[3];
+        const float ratio4 = (float)(nbins - COARSE_N - 16) / (4.0f * (float)nsample);
+        uint32_t ns[4];
+        ns[0] = (uint32_t)((below + 2.0f * c[0] + c[1]) * ratio4) + 1u;
+        ns[1] = (uint32_t)((c[0] + 2.0f * c[1] + c[2]) * ratio4) + 1u;
+        ns[2] = (uint32_t)((c[1] + 2.0f * c[2] + c[3]) * ratio4) + 1u;
+        ns[3] = (uint32_t)((c[2] + 2.0f * c[3] + above) * ratio4) + 1u;
+        const uint32_t tot = ns[0] + ns[1] + ns[2] + ns[3];
+        uint32_t base = wave_scan_incl(tot) - tot;
+        float4 e0, e1;          // integers below 2^16: exact as floats
+        e0.x = (float)base;
+        e0.y = (float)ns[0];
+        base += ns[0];
+        e0.z = (float)base;
+        e0.w = (float)ns[1];
+        base += ns[1];
+        e1.x = (float)base;
+        e1.y = (float)ns[2];
+        base += ns[2];
+        e1.z = (float)base;
+        e1.w = (float)ns[3];
+        ((float4 *)table)[2 * lane] = e0;
+        ((float4 *)table)[2 * lane + 1] = e1;
+    }
+    prefetch(2);
+    // ---- fine bin of every key; the counter's old value is the key's slot inside its bin
+    uint32_t fbs[NS];
+    bool over = false;
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+        fbs[k] = 0u;
+        if (sm.has(k)) {
+            // bin = first bin of the interval + fraction of the interval x bins of the interval, in one fused
+            // multiply-add: monotone in w, and at most the first bin of the next interval (the clamps cannot
+            // bind while the table is consistent and the weights are finite; they keep the indices in range)
+            const float x = coarse_pos(elem_w(key[k]), lo, scale);
+            const uint32_t cb = min((uint32_t)(int)x, (uint32_t)(COARSE_N - 1));
+            const float fr = __builtin_amdgcn_fractf(x);
+            const float2 tb = table[cb];
+            const uint32_t fb = min((uint32_t)fmaf(fr, tb.y, tb.x), (uint32_t)(nbins - 1));
+            const uint32_t sh = (fb & 1u) << 4;
+            const uint32_t wd = (fb >> 1) + (prm.bk_pad ? (fb >> prm.bk_lgbpt) << 2 : 0u);   // word of the bin's counter
+            const uint32_t old = atomicAdd(&hist[wd], 1u << sh);
+            const uint32_t slot = (old >> sh) & 0xFFFFu;
+            over = over || (slot >= (uint32_t)BIN_MAX_KEYS);
+            fbs[k] = (wd << 1) | (fb & 1u) | (slot << 16);     // half-word of the counter, slot
+        }
+    }
+    prefetch(3);
+    __syncthreads();
+    // ---- first rank of every bin: exclusive scan of the counters, written over them (16 bits each)
+    {
+        const int nq = bpt >> 3;                       // 16-byte pieces of this thread's block
+        uint4 *mine = (uint4 *)(hist + tid * hstride);
+        uint32_t run = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (q < nq) {
+                const uint4 c = mine[q];
+                run += (c.x & 0xFFFFu) + (c.x >> 16) + (c.y & 0xFFFFu) + (c.y >> 16) + (c.z & 0xFFFFu) + (c.z >> 16) +
+                       (c.w & 0xFFFFu) + (c.w >> 16);
+            }
+        }
+        const uint32_t inc = wave_scan_incl(run);
+        const bool wave_over = __ballot(over) != 0;
+        if (lane == 63) {
+            wtot[wave] = inc;
+            wover[wave] = wave_over ? 1u : 0u;
+        }
+        __syncthreads();
+        // a bin with more than BIN_MAX_KEYS keys anywhere in the row: the caller sorts by the network instead
+        {
+            const uint4 *o4 = (const uint4 *)wover;
+            uint32_t any = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint4 t = o4[q];
+                any |= (4 * q + 0 < (nth >> 6) ? t.x : 0u) | (4 * q + 1 < (nth >> 6) ? t.y : 0u) |
+                       (4 * q + 2 < (nth >> 6) ? t.z : 0u) | (4 * q + 3 < (nth >> 6) ? t.w : 0u);
+            }
+            if (any) return false;
+        }
+        // the counters are read once more (cheaper than carrying them in registers across the barrier)
+        uint32_t at = (inc - run + waves_below(wtot, wave));
+        auto step = [&](uint32_t c) -> uint32_t {
+            const uint32_t s0 = at;
+            at += c & 0xFFFFu;
+            const uint32_t s1 = at;
+            at += c >> 16;
+            return s0 | (s1 << 16);
+        };
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (q < nq) {
+                uint4 c = mine[q];
+                c.x = step(c.x);
+                c.y = step(c.y);
+                c.z = step(c.z);
+                c.w = step(c.w);
+                mine[q] = c;
+            }
+        }
+    }
+    __syncthreads();
+    // ---- scatter: rank = first rank of the bin + slot in the bin
+    double *lds = (double *)smem;
+    const unsigned short *first = (const unsigned short *)hist;
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+        if (sm.has(k)) {
+            // (the clamp cannot bind when the counts are right; it keeps the store inside the row regardless)
+            const uint32_t pos = min((uint32_t)first[fbs[k] & 0xFFFFu] + (fbs[k] >> 16), (uint32_t)(m - 1));
+            lds[swz(pos)] = __longlong_as_double((long long)key[k]);
+        }
+    }
+    __syncthreads();
+    // ---- order inside the bins
+    const int p0 = tid * EPT;
+    const double pad = __longlong_as_double((long long)PAD_KEY);
+    double v[EPT];
+    if (p0 < m) {
+        const double *src = lds + swz((uint32_t)p0);
+#pragma unroll
+        for (int r = 0; r < EPT; ++r) v[r] = (p0 + r < m) ? src[r] : pad;
+        sort16(v);
+        double *dst = lds + swz((uint32_t)p0);
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+            if (p0 + r < m) dst[r] = v[r];
+    }
+    __syncthreads();
+    if (p0 + 8 < m) {
+        // upper half of this window (still in registers) with the lower half of the next one
+        const double *nxt = lds + swz((uint32_t)(p0 + EPT));
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            v[r] = v[8 + r];
+            v[8 + r] = (p0 + EPT + r < m) ? nxt[r] : pad;
+        }
+        merge8x8(v);
+        double *dst = lds + swz((uint32_t)p0);
+        double *dn = lds + swz((uint32_t)(p0 + EPT));
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            if (p0 + 8 + r < m) dst[8 + r] = v[r];
+            if (p0 + EPT + r < m) dn[r] = v[8 + r];
+        }
+    }
+    __syncthreads();
+    return true;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Kernel 1: load + scale + encode, bitonic sort in LDS, sums, write-out.
 // ---------------------------------------------------------------------------------------------
 // The 16 W and 16 S values a thread contributes to one unit of work (a row, or one segment of a long row).
-__device__ __forceinline__ void fetch_unit(const ClusterParams &prm, long long work, int tid, int nth, float (&pw)[EPT],
-                                           float (&ps)[EPT]) {
+// live == false: nothing is read and every slot becomes 0 (the caller has no further unit; assigning all
+// slots either way keeps the registers from being carried around the caller's loop).
+// part: -1 = all of the unit; 0..3 = the 16-byte loads g with g % 4 == part (VEC), or everything in part 0 (!VEC).
+template <int NS, bool VEC>
+__device__ __forceinline__ void fetch_unit(const ClusterParams &prm, long long work, int tid, int nth, float (&pw)[NS],
+                                           float (&ps)[NS], bool live = true, int part = -1) {
     const long long frow = work / prm.nseg;
     const int fcol0 = (int)(work % prm.nseg) * prm.seglen;
-    const int fm = min(prm.m - fcol0, prm.seglen);
-    const float *Wr = prm.W + frow * prm.ld + fcol0;
-    const float *Sr = prm.S + frow * prm.ld + fcol0;
+    const int fm = live ? min(prm.m - fcol0, prm.seglen) : 0;
+    const Slots<VEC> sm(fm, nth, tid);
+    if constexpr (VEC) {
+        static_assert(NS % 4 == 0, "16-byte loads fill four slots at a time");
+        const float4 *W4 = (const float4 *)(prm.W + frow * prm.ld + fcol0) + tid;
+        const float4 *S4 = (const float4 *)(prm.S + frow * prm.ld + fcol0) + tid;
 #pragma unroll
-    for (int k = 0; k < EPT; ++k) {
-        const uint32_t j = (uint32_t)tid + (uint32_t)k * (uint32_t)nth;   // 32-bit offset from a uniform base
-        pw[k] = (j < (uint32_t)fm) ? Wr[j] : 0.0f;
-        ps[k] = (j < (uint32_t)fm) ? Sr[j] : 0.0f;
+        for (int g = 0; g < NS / 4; ++g) {
+            if (part >= 0 && (g & 3) != part) continue;
+            const bool h = sm.has(4 * g);
+            const float4 a = h ? W4[g * nth] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            const float4 b = h ? S4[g * nth] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            pw[4 * g] = a.x; pw[4 * g + 1] = a.y; pw[4 * g + 2] = a.z; pw[4 * g + 3] = a.w;
+            ps[4 * g] = b.x; ps[4 * g + 1] = b.y; ps[4 * g + 2] = b.z; ps[4 * g + 3] = b.w;
+        }
+    } else {
+        if (part > 0) return;
+        const float *Wr = prm.W + frow * prm.ld + fcol0 + tid;
+        const float *Sr = prm.S + frow * prm.ld + fcol0 + tid;
+#pragma unroll
+        for (int k = 0; k < NS; ++k) {
+            const bool h = sm.has(k);
+            pw[k] = h ? Wr[k * nth] : 0.0f;
+            ps[k] = h ? Sr[k * nth] : 0.0f;
+        }
     }
 }
 
+// Scaling and key encoding of the values a thread fetched (column tid + k * nth in slot k; padding beyond m).
+template <int NS, bool VEC>
+__device__ __forceinline__ void build_keys(const float (&pw)[NS], const float (&ps)[NS], const float *alpha, int tid,
+                                           int nth, int m, u64 (&key)[NS], bool &mass, float &wlo, float &whi) {
+    wlo = INFINITY;
+    whi = -INFINITY;
+    const Slots<VEC> sm(m, nth, tid);
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+        key[k] = PAD_KEY;
+        if (sm.has(k)) {
+            float wt, st;
+            scaled_pair(pw[k], ps[k], alpha, sm.col(k), wt, st);
+            key[k] = make_key(wt, st);
+            mass = mass || (st != 0.0f);
+            wlo = fminf(wlo, wt);
+            whi = fmaxf(whi, wt);
+        }
+    }
+}
+
+// NS: key slots per thread, at least ceil(seglen / blockDim.x).  VEC: 16-byte loads of W and S (rows and units
+// start at multiples of 16 bytes, lengths are multiples of 4); see Slots for the slot <-> column map.
+template <int NS, bool VEC>
 __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     extern __shared__ __align__(16) unsigned char smem[];
     u64 *sorted = (u64 *)smem;
 
-    const int tid0 = threadIdx.x, nth = blockDim.x;      // nth == P / 16
+    const int tid0 = threadIdx.x, nth = blockDim.x;      // a power of two, at least P / 16
 
     // A workgroup takes the units of work blockIdx.x, blockIdx.x + gridDim.x, ...  The W and S values
-    // of the next unit are fetched into registers (all loads in flight at once) while the sums of
-    // the current one are taken and its keys written out, which hides most of their HBM latency
-    // (a 16384-key row fills the LDS of a compute unit: no second workgroup is resident to overlap
-    // with, and the sort itself leaves no registers to hold the values any earlier).
-    float pw[EPT], ps[EPT];
-    if ((long long)blockIdx.x < prm.nwork) fetch_unit(prm, blockIdx.x, tid0, nth, pw, ps);
+    // of the next unit are fetched into registers (all loads in flight at once) as soon as those of
+    // the current unit have been encoded, so that the whole sort of the current unit hides their HBM
+    // latency (a long row fills the LDS of a compute unit: no second workgroup is resident to overlap with).
+    float pw[NS], ps[NS];
+    if ((long long)blockIdx.x < prm.nwork) fetch_unit<NS, VEC>(prm, blockIdx.x, tid0, nth, pw, ps);
 
     for (long long work = blockIdx.x; work < prm.nwork; work += gridDim.x) {
     // the thread index is made opaque per unit: per-thread addresses are recomputed where they are
@@ -335,50 +702,102 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     const int col0 = (int)(work % prm.nseg) * prm.seglen;            // first column of this segment
     const int m = min(prm.m - col0, prm.seglen);                     // keys sorted by this workgroup
     const float *alpha = prm.alpha ? prm.alpha + col0 : nullptr;
+    const bool more = work + gridDim.x < prm.nwork;
+    const bool buckets = prm.bk_bpt > 0;
+    const Slots<VEC> sm(m, nth, tid);
 
+    // keys in registers; least and largest weight, and whether the unit holds any sensitivity mass
+    u64 key[NS];
     bool mass = false;
+    float wlo = INFINITY, whi = -INFINITY;
+    build_keys<NS, VEC>(pw, ps, alpha, tid, nth, m, key, mass, wlo, whi);
+    // (the bitonic network needs the registers: without the bucket path the next unit is fetched after the sort)
+    auto prefetch = [&](int part) { fetch_unit<NS, VEC>(prm, more ? work + gridDim.x : work, tid, nth, pw, ps, more, part); };
+    if (buckets) prefetch(0);
+    int anymass;
+    float lo = 0.0f, hi = 0.0f;
+    if (buckets) {
+        // per wavefront: least and largest weight and the mass flag; every thread combines the 16 entries
+        float *wmin = (float *)(smem + prm.bk_misc_off + BK_WMIN), *wmax = (float *)(smem + prm.bk_misc_off + BK_WMAX);
+        uint32_t *wmass = (uint32_t *)(smem + prm.bk_misc_off + BK_WMASS);
 #pragma unroll
-    for (int k = 0; k < EPT; ++k) {
-        const int j = tid + k * nth;
-        u64 key = PAD_KEY;
-        if (j < m) {
-            float wt, st;
-            scaled_pair(pw[k], ps[k], alpha, j, wt, st);
-            key = make_key(wt, st);
-            mass = mass || (st != 0.0f);
+        for (int o = 32; o >= 1; o >>= 1) {
+            wlo = fminf(wlo, __shfl_xor(wlo, o, 64));
+            whi = fmaxf(whi, __shfl_xor(whi, o, 64));
         }
-        sorted[swz((uint32_t)j)] = key;
+        const bool wave_mass = __ballot(mass) != 0;
+        if ((tid & 63) == 0) {
+            wmin[tid >> 6] = wlo;
+            wmax[tid >> 6] = whi;
+            wmass[tid >> 6] = wave_mass ? 1u : 0u;
+        }
+        uint32_t *cc = (uint32_t *)(smem + prm.bk_coarse_off);
+        for (int i = tid; i < COARSE_N * 4; i += nth) cc[i] = 0u;
+        __syncthreads();
+        const int nw = nth >> 6;
+        lo = INFINITY;
+        hi = -INFINITY;
+        uint32_t any = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 a = ((const float4 *)wmin)[q], b4 = ((const float4 *)wmax)[q];
+            const uint4 c = ((const uint4 *)wmass)[q];
+            if (4 * q + 0 < nw) { lo = fminf(lo, a.x); hi = fmaxf(hi, b4.x); any |= c.x; }
+            if (4 * q + 1 < nw) { lo = fminf(lo, a.y); hi = fmaxf(hi, b4.y); any |= c.y; }
+            if (4 * q + 2 < nw) { lo = fminf(lo, a.z); hi = fmaxf(hi, b4.z); any |= c.z; }
+            if (4 * q + 3 < nw) { lo = fminf(lo, a.w); hi = fmaxf(hi, b4.w); any |= c.w; }
+        }
+        anymass = (int)any;
+    } else {
+        anymass = __syncthreads_or((int)mass);
     }
     // (a segment of a long row cannot tell on its own: it records what it saw for merge_tile_kernel)
-    const int anymass = __syncthreads_or((int)mass);
     if (prm.nseg > 1 && tid == 0) prm.segmass[work] = anymass;
     if (!anymass && prm.nseg == 1) {
         // no sensitivity mass in this row: cluster with unit weights
 #pragma unroll
-        for (int k = 0; k < EPT; ++k) {
-            const int j = tid + k * nth;
-            if (j < m) {
-                const uint32_t a = swz((uint32_t)j);
-                sorted[a] = unit_weight_key(sorted[a]);
+        for (int k = 0; k < NS; ++k)
+            if (sm.has(k)) key[k] = unit_weight_key(key[k]);
+    }
+    bool sorted_ok = false;
+    // a usable axis needs two distinct finite ends (a constant row has none)
+    if (buckets && hi > lo && (hi - lo) < INFINITY) sorted_ok = bucket_sort<NS, VEC>(smem, prm, key, tid, nth, m, lo, hi, prefetch);
+    if (!sorted_ok) {
+        // The bitonic network over the whole padded row.  Its keys overlay the bucket path's tables: wait
+        // until every thread is done with them.  The bucket path gave its key registers away, so the
+        // unit is read and encoded once more, and the next unit fetched again after it (rare).
+        if (buckets) {
+            __syncthreads();
+            fetch_unit<NS, VEC>(prm, work, tid, nth, pw, ps);
+            bool mass2 = false;
+            float lo2, hi2;
+            build_keys<NS, VEC>(pw, ps, alpha, tid, nth, m, key, mass2, lo2, hi2);
+            if (!anymass && prm.nseg == 1) {
+#pragma unroll
+                for (int k = 0; k < NS; ++k)
+                    if (sm.has(k)) key[k] = unit_weight_key(key[k]);
             }
         }
+#pragma unroll
+        for (int k = 0; k < NS; ++k)
+            if (sm.col(k) < prm.P) sorted[swz((uint32_t)sm.col(k))] = key[k];
+        for (int j = tid + NS * nth; j < prm.P; j += nth) sorted[swz((uint32_t)j)] = PAD_KEY;   // padding no slot covers
         __syncthreads();
+        switch (prm.logP) {
+            case 10: sort_row<10>((double *)sorted, (uint32_t)tid, m); break;
+            case 11: sort_row<11>((double *)sorted, (uint32_t)tid, m); break;
+            case 12: sort_row<12>((double *)sorted, (uint32_t)tid, m); break;
+            case 13: sort_row<13>((double *)sorted, (uint32_t)tid, m); break;
+            default: sort_row<14>((double *)sorted, (uint32_t)tid, m); break;
+        }
+        fetch_unit<NS, VEC>(prm, more ? work + gridDim.x : work, tid, nth, pw, ps, more);
     }
-
-    switch (prm.logP) {
-        case 10: sort_row<10>((double *)sorted, (uint32_t)tid, m); break;
-        case 11: sort_row<11>((double *)sorted, (uint32_t)tid, m); break;
-        case 12: sort_row<12>((double *)sorted, (uint32_t)tid, m); break;
-        case 13: sort_row<13>((double *)sorted, (uint32_t)tid, m); break;
-        default: sort_row<14>((double *)sorted, (uint32_t)tid, m); break;
-    }
-    if (work + gridDim.x < prm.nwork) fetch_unit(prm, work + gridDim.x, tid, nth, pw, ps);
 
     if (prm.nseg > 1) {
         // one segment of a long row: sorted keys only; merge_tile_kernel does the rest
         u64 *kseg = prm.keys_seg + row * (long long)prm.m + col0;
         for (int j = tid; j < m; j += nth) kseg[j] = sorted[swz((uint32_t)j)];
-        __syncthreads();   // the LDS is refilled for the next unit
+        if (!buckets) __syncthreads();   // the LDS is refilled for the next unit (see the end of the loop)
         continue;
     }
     // sums of s and s*w over each 16-key chunk (s*w of two floats is exact in float64), the weight
@@ -411,7 +830,10 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     // sorted keys, compact and in rank order
     u64 *keys = prm.keys + row * (long long)m;
     for (int j = tid; j < m; j += nth) keys[j] = sorted[swz((uint32_t)j)];
-    __syncthreads();       // the LDS is refilled for the next unit
+    // The next unit refills the key region of the LDS.  On the bucket path it first works on its tables, which
+    // lie beyond that region, and passes several barriers before its scatter; its bitonic branch has a barrier
+    // of its own.  Without the bucket path the refill is immediate.
+    if (!buckets) __syncthreads();
     }
 }
 
@@ -1601,6 +2023,48 @@ __global__ void __launch_bounds__(OPT_THREADS) kmeans_optimal_kernel(OptParams p
     }
 }
 
+// Input validation (off unless the caller asks for it): bit 0 a non-finite weight, bit 1 a sensitivity that is
+// negative or not finite, bit 2 a scale that is not a positive finite number.
+__global__ void validate_clear_kernel(int *flag) { *flag = 0; }
+__global__ void __launch_bounds__(256) validate_kernel(const float *W, const float *S, const float *alpha, long long n,
+                                                      int m, long long ld, int *flag) {
+    int bad = 0;
+    for (long long row = blockIdx.x; row < n; row += gridDim.x) {
+        const float *Wr = W + row * ld, *Sr = S + row * ld;
+        for (int j = threadIdx.x; j < m; j += 256) {
+            const float w = Wr[j], sv = Sr[j];
+            if (!(fabsf(w) < INFINITY)) bad |= 1;
+            if (!(sv >= 0.0f && sv < INFINITY)) bad |= 2;
+        }
+    }
+    if (alpha && blockIdx.x == 0) {
+        for (int j = threadIdx.x; j < m; j += 256) {
+            const float a = alpha[j];
+            if (!(a > 0.0f && a < INFINITY)) bad |= 4;
+        }
+    }
+    if (__ballot(bad != 0) && bad) atomicOr(flag, bad);
+}
+
+// With validation on: checks W, S and alpha on the device and waits for the answer.
+skim_status validate_inputs(skim_ctx *ctx, const ClusterParams &prm, int64_t n) {
+    if (!ctx->validate || n == 0) return SKIM_OK;
+    hipLaunchKernelGGL(validate_clear_kernel, dim3(1), dim3(1), 0, ctx->stream, prm.vflag);
+    long long grid = 8ll * ctx->num_cu;
+    if (grid > n) grid = n;
+    hipLaunchKernelGGL(validate_kernel, dim3((unsigned)grid), dim3(256), 0, ctx->stream, prm.W, prm.S, prm.alpha,
+                       (long long)n, prm.m, prm.ld, prm.vflag);
+    SKIM_HIP(ctx, hipGetLastError());
+    int flag = 0;
+    SKIM_HIP(ctx, hipMemcpyAsync(&flag, prm.vflag, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+    SKIM_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (flag)
+        SKIM_FAIL(ctx, SKIM_ERR_NONFINITE, "input validation:%s%s%s", (flag & 1) ? " W holds a value that is not finite;" : "",
+                  (flag & 2) ? " S holds a value that is negative or not finite;" : "",
+                  (flag & 4) ? " alpha holds a value that is not a positive finite number;" : "");
+    return SKIM_OK;
+}
+
 size_t sort_lds_bytes(int P) { return (size_t)(P + P / 16) * 8; }
 
 size_t lloyd_lds_bytes(int m) { return 2 * (size_t)level_map((m + 15) >> 4).bytes + 128 * sizeof(double); }
@@ -1628,7 +2092,8 @@ skim_status carve_cluster_ws(skim_ctx *ctx, ClusterParams &prm, int64_t n, doubl
     prm.RQ = (double *)cur.take((size_t)n * prm.nq * sizeof(double));
     prm.w16 = (float *)cur.take((size_t)n * prm.n1 * sizeof(float));
     prm.bstate = (BitState *)cur.take((size_t)n * 4 * sizeof(BitState));
-    bool ok = prm.keys && prm.L1 && prm.Q && prm.R1 && prm.RQ && prm.w16 && prm.bstate;
+    prm.vflag = (int *)cur.take(256);
+    bool ok = prm.keys && prm.L1 && prm.Q && prm.R1 && prm.RQ && prm.w16 && prm.bstate && prm.vflag;
     prm.keys_seg = nullptr;
     prm.segmass = nullptr;
     if (prm.nseg > 1) {
@@ -1646,28 +2111,78 @@ skim_status carve_cluster_ws(skim_ctx *ctx, ClusterParams &prm, int64_t n, doubl
 
 // sort_only: stop once the sorted keys (unit weights already put in for rows without mass) are in prm.keys
 skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n, bool sort_only = false) {
-    int threads = prm.P / EPT;
+    {
+        const skim_status vs = validate_inputs(ctx, prm, n);
+        if (vs != SKIM_OK) return vs;
+    }
+    // Threads: one per 8 slots of the padded unit, 1024 at most (and one wavefront at least); fewer key slots per
+    // thread leave the compiler more registers.
+    int threads = prm.P / 8;
+    if (threads > 1024) threads = 1024;
     if (threads < MIN_THREADS) threads = MIN_THREADS;
-    const size_t lds = sort_lds_bytes(prm.P);
+    // 16-byte loads when every unit starts at a multiple of 16 bytes and has a multiple of 4 columns; then
+    // 8, 12 or 16 slots per thread, the least that covers the unit.  Otherwise 4-byte loads and 16 slots.
+    const bool vec = ((uintptr_t)prm.W % 16 == 0) && ((uintptr_t)prm.S % 16 == 0) && (prm.ld % 4 == 0) && (prm.m % 4 == 0) &&
+                     (prm.seglen % 4 == 0);
+    const int per_thread = (prm.seglen + threads - 1) / threads;
+    const int variant = !vec ? 3 : (per_thread <= 8 ? 0 : (per_thread <= 12 ? 1 : 2));
+    size_t lds = sort_lds_bytes(prm.P);
     if ((int64_t)lds > ctx->lds_limit)
         SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "row length %d needs %zu bytes of LDS, device allows %d", prm.m, lds, ctx->lds_limit);
-    static size_t lds_enabled = 0;
-    if (lds > 65536 && lds > lds_enabled) {
-        SKIM_HIP(ctx, hipFuncSetAttribute((const void *)sort_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        lds_enabled = lds;
+    // bucket path: the keys of one unit (seglen at most), two bytes per value bin, the coarse tables.
+    // As many bins per thread as the LDS holds (at most 32768 bins: a bin index takes 15 bits), and at least
+    // about 1.1 bins per key: with fewer, too many rows would find a bin of more than BIN_MAX_KEYS keys and
+    // sort twice.
+    prm.bk_bpt = 0;
+    {
+        const size_t key_bytes = (((size_t)prm.seglen + prm.seglen / 16 + 1) * 8 + 15) & ~(size_t)15;
+        const size_t base_lds = lds;
+        int best_per_cu = 0;
+        for (int bpt = 32; bpt >= 8; bpt -= 8) {
+            // a thread's block of counters is bpt / 2 words; blocks of 8, 16 or 32 words get 4 spare words each,
+            // so that 8 neighbouring threads' 16-byte accesses fall into different banks (24 words do already)
+            const int pad = (bpt == 24) ? 0 : 4;
+            const size_t hist_bytes = (size_t)(bpt / 2 + pad) * threads * 4;
+            const size_t need = key_bytes + hist_bytes + BK_COARSE_BYTES + BK_MISC_BYTES;
+            const long long bins = (long long)bpt * threads - COARSE_N - 16;
+            if (need + 1024 > (size_t)ctx->lds_limit || 10ll * prm.seglen > 9ll * bins || bpt * threads > 32768) continue;
+            // workgroups a compute unit holds with this choice (threads and LDS); more of them beats more bins
+            const size_t total = need > base_lds ? need : base_lds;
+            int per_cu = (int)((size_t)ctx->lds_limit / (total + 256));
+            if (per_cu > 2048 / threads) per_cu = 2048 / threads;
+            if (per_cu <= best_per_cu) continue;
+            best_per_cu = per_cu;
+            prm.bk_bpt = bpt;
+            prm.bk_pad = pad;
+            prm.bk_lgbpt = bpt == 8 ? 3 : (bpt == 16 ? 4 : 5);
+            prm.bk_hist_off = (uint32_t)key_bytes;
+            prm.bk_coarse_off = (uint32_t)(key_bytes + hist_bytes);
+            prm.bk_misc_off = prm.bk_coarse_off + BK_COARSE_BYTES;
+            lds = total;
+        }
+    }
+    const void *kern = variant == 0 ? (const void *)sort_kernel<8, true>
+                     : variant == 1 ? (const void *)sort_kernel<12, true>
+                     : variant == 2 ? (const void *)sort_kernel<16, true> : (const void *)sort_kernel<16, false>;
+    if (lds > 65536 && lds > ctx->sort_lds_enabled[variant]) {
+        SKIM_HIP(ctx, hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        ctx->sort_lds_enabled[variant] = lds;
     }
     if (n == 0) return SKIM_OK;
     if ((int64_t)n * prm.nseg > 0x7fffffff) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "too many rows");
     prm.nwork = (long long)n * prm.nseg;
     // as many workgroups as the device holds at once (LDS and thread limits), each looping over its units
-    int per_cu = (int)(ctx->lds_limit / (int64_t)lds);
+    int per_cu = (int)(ctx->lds_limit / (int64_t)(lds + 256));   // (+ the kernel's small static LDS)
     if (per_cu > 2048 / threads) per_cu = 2048 / threads;
     if (per_cu < 1) per_cu = 1;
     if (per_cu > 8) per_cu = 8;
     long long sort_grid = (long long)ctx->num_cu * per_cu;
     if (sort_grid > prm.nwork) sort_grid = prm.nwork;
     if (ctx->profiling) SKIM_HIP(ctx, hipEventRecord(ctx->ev[0], ctx->stream));
-    hipLaunchKernelGGL(sort_kernel, dim3((unsigned)sort_grid), dim3(threads), lds, ctx->stream, prm);
+    if (variant == 0) hipLaunchKernelGGL((sort_kernel<8, true>), dim3((unsigned)sort_grid), dim3(threads), lds, ctx->stream, prm);
+    else if (variant == 1) hipLaunchKernelGGL((sort_kernel<12, true>), dim3((unsigned)sort_grid), dim3(threads), lds, ctx->stream, prm);
+    else if (variant == 2) hipLaunchKernelGGL((sort_kernel<16, true>), dim3((unsigned)sort_grid), dim3(threads), lds, ctx->stream, prm);
+    else hipLaunchKernelGGL((sort_kernel<16, false>), dim3((unsigned)sort_grid), dim3(threads), lds, ctx->stream, prm);
     if (prm.nseg > 1) {
         const int tiles = (prm.m + MG_TILE - 1) / MG_TILE;
         if ((int64_t)n * tiles > 0x7fffffff) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "too many rows");

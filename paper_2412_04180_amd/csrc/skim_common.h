@@ -20,6 +20,8 @@ struct skim_ctx {
     int profiling;
     hipEvent_t ev[3];    // before sort, between sort and Lloyd, after Lloyd
     int ev_valid;
+    size_t sort_lds_enabled[4];   // dynamic LDS size each variant of the sort kernel has been allowed so far (through this context)
+    int validate;        // check W, S, alpha of the clustering calls for values the method is not defined on
     void *pack_scratch;  // this device's address of the static scratch of skim_pack_static
 };
 
@@ -64,7 +66,9 @@ static inline int skim_block_offset(int bmin, int b) {  // start of block b insi
 // Looks up this device's address of the static scratch of skim_pack_static (the device must be current).
 skim_status skim_pack_static_setup(skim_ctx *ctx);
 
-// skim_layer_loss with the per-row losses written at a stride (row i at row_loss[i * row_stride]).
+// skim_layer_loss with the per-row losses written at a stride (row i at row_loss[i * row_stride]).  kept (may be
+// NULL): kept_n centroids per row at kept + i * kept_stride, used for clusters whose members carry no mass.
 skim_status skim_layer_loss_strided(skim_ctx *ctx, const float *W, const float *S, const float *alpha, const float *H,
                                     int64_t n, int64_t m, int64_t ld, const uint8_t *labels, double *loss,
-                                    double *row_loss, int64_t row_stride);
+                                    double *row_loss, int64_t row_stride, const double *kept, int64_t kept_stride,
+                                    int kept_n);

@@ -45,12 +45,20 @@ extern "C" skim_status skim_create(skim_ctx **out, int device, void *hip_stream)
     int optin = 0;
     if (hipDeviceGetAttribute(&optin, hipDeviceAttributeMaxSharedMemoryPerBlock, device) == hipSuccess && optin > c->lds_limit)
         c->lds_limit = optin;
-    if (c->lds_limit < 160 * 1024) c->lds_limit = 160 * 1024;  // gfx950: 160 KB of LDS per compute unit
+    if (c->lds_limit < 160 * 1024) {   // gfx950 has 160 KB per compute unit; the row sort is laid out for it
+        snprintf(g_create_err, sizeof(g_create_err),
+                 "skim_create: device %d reports %d bytes of LDS per workgroup, the row sort needs %d", device,
+                 c->lds_limit, 160 * 1024);
+        delete c;
+        return SKIM_ERR_HIP;
+    }
     c->num_cu = prop.multiProcessorCount;
     c->profiling = 0;
     c->ev_valid = 0;
     for (int i = 0; i < 3; ++i) c->ev[i] = nullptr;
     c->err[0] = 0;
+    for (int i = 0; i < 4; ++i) c->sort_lds_enabled[i] = 0;
+    c->validate = 0;
     c->pack_scratch = nullptr;
     if (skim_pack_static_setup(c) != SKIM_OK) {
         snprintf(g_create_err, sizeof(g_create_err), "skim_create: %s", c->err);
@@ -66,6 +74,12 @@ extern "C" skim_status skim_destroy(skim_ctx *ctx) {
     for (int i = 0; i < 3; ++i)
         if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
     delete ctx;
+    return SKIM_OK;
+}
+
+extern "C" skim_status skim_validate_enable(skim_ctx *ctx, int on) {
+    if (!ctx) return SKIM_ERR_ARG;
+    ctx->validate = on ? 1 : 0;
     return SKIM_OK;
 }
 

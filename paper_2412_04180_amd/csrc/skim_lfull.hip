@@ -80,8 +80,10 @@ extern "C" skim_status skim_error_table_lfull(skim_ctx *ctx, const float *W, con
         hipLaunchKernelGGL(labels_from_bounds_kernel, dim3((unsigned)n), dim3(LAB_THREADS), 0, ctx->stream, W, alpha,
                            (long long)m, (long long)ld, 1 << b, upper_all, stride, (1 << b) - (1 << bmin), labels_work);
         SKIM_HIP(ctx, hipGetLastError());
+        // a cluster whose members carry no sensitivity mass keeps the centroid the clustering left it with
+        // (the value the packed codebook holds), not the 0 a weighted mean over no mass would give
         if ((st = skim_layer_loss_strided(ctx, W, S, alpha, H, n, m, ld, labels_work, loss_scalar, E_full + (b - bmin),
-                                          nb)) != SKIM_OK)
+                                          nb, centroids_all + ((1 << b) - (1 << bmin)), stride, 1 << b)) != SKIM_OK)
             return st;
     }
     return SKIM_OK;

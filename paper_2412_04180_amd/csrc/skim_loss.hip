@@ -47,9 +47,12 @@ __device__ __forceinline__ double bin_total(const double (*bins)[16], int k) {
 
 // Per row: weighted cluster sums with fixed labels -> centroids c (n x 16 float64),
 // masses Den (n x 16 float64), and the row of dW (float32).
+// kept (optional): per row, at kept + row * kept_stride, the centroid a cluster keeps when its members carry no
+// sensitivity mass (what the clustering that produced the labels left there); without it such a centroid is 0.
 __global__ void __launch_bounds__(PREP_THREADS) row_prep_kernel(const float *W, const float *S, const float *alpha,
                                                                 long long m, long long ld, const uint8_t *labels,
-                                                                double *cent, double *Den, float *dW) {
+                                                                double *cent, double *Den, float *dW,
+                                                                const double *kept, long long kept_stride, int kept_n) {
     __shared__ double binD[BIN_SETS][16], binN[BIN_SETS][16];
     __shared__ double csh[16];
     const long long row = blockIdx.x;
@@ -76,7 +79,7 @@ __global__ void __launch_bounds__(PREP_THREADS) row_prep_kernel(const float *W, 
     __syncthreads();
     if (tid < 16) {
         const double d = bin_total(binD, tid), nn = bin_total(binN, tid);
-        const double c = d > 0.0 ? nn / d : 0.0;
+        const double c = d > 0.0 ? nn / d : ((kept && tid < kept_n) ? kept[row * kept_stride + tid] : 0.0);
         csh[tid] = c;
         cent[row * 16 + tid] = c;
         Den[row * 16 + tid] = d;
@@ -393,12 +396,13 @@ skim_status check_shape(skim_ctx *ctx, int64_t n, int64_t m, int64_t ld) {
 extern "C" skim_status skim_layer_loss(skim_ctx *ctx, const float *W, const float *S, const float *alpha,
                                        const float *H, int64_t n, int64_t m, int64_t ld, const uint8_t *labels,
                                        double *loss, double *row_loss) {
-    return skim_layer_loss_strided(ctx, W, S, alpha, H, n, m, ld, labels, loss, row_loss, 1);
+    return skim_layer_loss_strided(ctx, W, S, alpha, H, n, m, ld, labels, loss, row_loss, 1, nullptr, 0, 0);
 }
 
 skim_status skim_layer_loss_strided(skim_ctx *ctx, const float *W, const float *S, const float *alpha, const float *H,
                                     int64_t n, int64_t m, int64_t ld, const uint8_t *labels, double *loss,
-                                    double *row_loss, int64_t row_stride) {
+                                    double *row_loss, int64_t row_stride, const double *kept, int64_t kept_stride,
+                                    int kept_n) {
     skim_status st = skim_enter(ctx);
     if (st != SKIM_OK) return st;
     if (!W || !S || !H || !labels || !loss) SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_layer_loss: NULL argument");
@@ -407,7 +411,7 @@ skim_status skim_layer_loss_strided(skim_ctx *ctx, const float *W, const float *
     LossWs w;
     if ((st = carve(ctx, n, m, false, w)) != SKIM_OK) return st;
     hipLaunchKernelGGL(row_prep_kernel, dim3((unsigned)n), dim3(PREP_THREADS), 0, ctx->stream, W, S, alpha, (long long)m,
-                       (long long)ld, labels, w.cent, w.Den, w.dW);
+                       (long long)ld, labels, w.cent, w.Den, w.dW, kept, (long long)kept_stride, kept_n);
     hipLaunchKernelGGL(dwh_gemm_kernel<false>, dim3(w.ntile, (unsigned)((n + BM - 1) / BM)), dim3(GEMM_THREADS), 0,
                        ctx->stream, w.dW, H, (int)n, (int)m, (float *)nullptr, w.partial);
     launch_loss_finish(ctx->stream, w.partial, w.ntile, (long long)n, loss, row_loss, (long long)row_stride);
@@ -429,7 +433,7 @@ extern "C" skim_status skim_scale_step(skim_ctx *ctx, const float *W, const floa
     LossWs w;
     if ((st = carve(ctx, n, m, true, w)) != SKIM_OK) return st;
     hipLaunchKernelGGL(row_prep_kernel, dim3((unsigned)n), dim3(PREP_THREADS), 0, ctx->stream, W, S, (const float *)alpha,
-                       (long long)m, (long long)ld, labels, w.cent, w.Den, w.dW);
+                       (long long)m, (long long)ld, labels, w.cent, w.Den, w.dW, (const double *)nullptr, 0ll, 0);
     hipLaunchKernelGGL(dwh_gemm_kernel<true>, dim3(w.ntile, (unsigned)((n + BM - 1) / BM)), dim3(GEMM_THREADS), 0,
                        ctx->stream, w.dW, H, (int)n, (int)m, w.P, w.partial);
     launch_loss_finish(ctx->stream, w.partial, w.ntile, (long long)n, loss_before, (double *)nullptr, 1ll);

@@ -207,6 +207,33 @@ def test_pack_mixed_bits_matches_oracle_layout(ctx):
     assert np.array_equal(cr["labels"].cpu().numpy()[clean], rr["labels"][clean])
 
 
+def test_validation_mode_reports_values_the_method_is_undefined_on(gpu_lib):
+    W, S = skim_synth.make_ws_small(91, 6, 200)
+    al = skim_synth.make_alpha(2, 200)
+    c = gpu_lib.Context(0)
+    try:
+        c.validate_enable(True)
+        c.error_table(dev(W), dev(S), dev(al))                      # clean inputs pass
+        for arr, name, val in [("W", "W", np.nan), ("W", "W", np.inf), ("S", "S", -1.0), ("S", "S", np.nan),
+                               ("alpha", "alpha", 0.0), ("alpha", "alpha", -np.inf)]:
+            Wb, Sb, ab = W.copy(), S.copy(), al.copy()
+            {"W": Wb, "S": Sb, "alpha": ab}[arr].flat[137] = val
+            with pytest.raises(gpu_lib.SkimError, match=name) as ei:
+                c.error_table(dev(Wb), dev(Sb), dev(ab))
+            assert ei.value.status == -6
+        with pytest.raises(gpu_lib.SkimError):
+            Sb = S.copy()
+            Sb[5, 199] = -0.5                                       # the last element of the last row
+            c.cluster_rows(dev(W), dev(Sb), dev(np.full(6, 2, np.uint8)))
+        c.validate_enable(False)
+        Sb = S.copy()
+        Sb[0, 0] = -1.0
+        c.error_table(dev(W), dev(Sb))                              # off (the default): not looked for, no error
+        torch.cuda.synchronize()
+    finally:
+        c.close()
+
+
 def test_argument_errors(ctx, gpu_lib):
     W, S = skim_synth.make_ws_small(90, 4, 64)
     with pytest.raises(gpu_lib.SkimError):
