@@ -405,55 +405,103 @@ constexpr uint32_t BK_COARSE_BYTES = COARSE_N * 4 * 4 + COARSE_N * 8;
 constexpr uint32_t BK_MISC_BYTES = 512;
 constexpr uint32_t BK_WMIN = 0, BK_WMAX = 64, BK_WMASS = 128, BK_WTOT = 256, BK_WOVER = 320;
 
+// The bin map a workgroup carries from one unit to the next: the axis of the coarse intervals and whether the
+// table in LDS (bins per interval) is valid and the fine counters are zero.  The first unit of a workgroup
+// builds the map from a sample of its own keys; every later unit is binned with the map the unit before it
+// left behind, whose table was re-derived from that unit's exact counts -- rows of one matrix resemble each
+// other, and any monotone map sorts correctly.  A unit that overflows a bin (it then sorts by the network)
+// drops the map, and the next unit builds its own.
+struct BinMap {
+    bool have;
+    float lo, scale;
+};
+
+// Bins per coarse interval from the counts c[0..3] of this lane's 4 intervals (lane l: intervals 4l .. 4l+3;
+// all 64 lanes call): counts smoothed (1 2 1) so that a sparse interval still gets bins from its neighbours'
+// counts, one bin on top of every interval's share, running sum over the intervals = first bin.
+// ratio4 = (bins to hand out) / (4 x sum of the counts).
+__device__ __forceinline__ void write_bin_table(float2 *table, int lane, const float (&c)[4], float ratio4) {
+    float below = __int_as_float(lane_below(__float_as_int(c[3])));
+    float above = __int_as_float(lane_above(__float_as_int(c[0])));
+    if (lane == 0) below = c[0];
+    if (lane == 63) above = c[3];
+    uint32_t ns[4];
+    ns[0] = (uint32_t)((below + 2.0f * c[0] + c[1]) * ratio4) + 1u;
+    ns[1] = (uint32_t)((c[0] + 2.0f * c[1] + c[2]) * ratio4) + 1u;
+    ns[2] = (uint32_t)((c[1] + 2.0f * c[2] + c[3]) * ratio4) + 1u;
+    ns[3] = (uint32_t)((c[2] + 2.0f * c[3] + above) * ratio4) + 1u;
+    const uint32_t tot = ns[0] + ns[1] + ns[2] + ns[3];
+    uint32_t base = wave_scan_incl(tot) - tot;
+    float4 e0, e1;          // integers below 2^16: exact as floats
+    e0.x = (float)base;
+    e0.y = (float)ns[0];
+    base += ns[0];
+    e0.z = (float)base;
+    e0.w = (float)ns[1];
+    base += ns[1];
+    e1.x = (float)base;
+    e1.y = (float)ns[2];
+    base += ns[2];
+    e1.z = (float)base;
+    e1.w = (float)ns[3];
+    ((float4 *)table)[2 * lane] = e0;
+    ((float4 *)table)[2 * lane + 1] = e1;
+}
+
 // Sorts the m keys held in registers (key[k], k < NS, the slots of Slots<VEC>) into LDS, rank r at slot
-// swz(r), by the bucket path.  lo, hi: least and largest weight of the row (the same in every thread).
-// Returns false, with nothing of value in LDS, when some bin took more than BIN_MAX_KEYS keys; all threads
-// of the workgroup return the same.  Contains workgroup barriers: every thread must call it.  The coarse
-// counters must be zero on entry (and a barrier must lie between clearing them and this call).
-// prefetch(g), g = 1, 2, 3: issues part g of the loads of the next unit (spread over the phases so that the
-// memory pipeline and the LDS work side by side).
+// swz(r), by the bucket path.  map: see BinMap; when map.have is false, map.lo / map.scale must hold the axis of
+// this unit (least weight, COARSE_N / range) and the coarse counters must be zero (with a barrier between
+// clearing them and this call).  Returns false, with nothing of value in LDS and map.have false, when some bin
+// took more than BIN_MAX_KEYS keys; all threads of the workgroup return the same.  Contains workgroup
+// barriers: every thread must call it.  anymass: whether any key of the unit carries sensitivity mass (from the
+// per-wavefront flags the caller left in LDS); a unit without mass is scattered with unit weights (single
+// segment rows only).  prefetch(g), g = 1, 2, 3: issues part g of the loads of the next unit.  The parts are
+// spread over the phases: all compute units run these phases nearly in step, and loads issued together by all
+// of them queue up behind the memory's peak rate.
 template <int NS, bool VEC, typename Prefetch>
 __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterParams &prm, const u64 (&key)[NS],
-                                            int tid, int nth, int m, float lo, float hi, Prefetch prefetch) {
-    const int lane = tid & 63, wave = tid >> 6;
+                                            int tid, int nth, int m, BinMap &map, int &anymass, Prefetch prefetch) {
+    const int lane = tid & 63, wave = tid >> 6, nw = nth >> 6;
     const Slots<VEC> sm(m, nth, tid);
     uint32_t *hist = (uint32_t *)(smem + prm.bk_hist_off);
     uint32_t *coarse = (uint32_t *)(smem + prm.bk_coarse_off);
     float2 *table = (float2 *)(coarse + COARSE_N * 4);
     uint32_t *wtot = (uint32_t *)(smem + prm.bk_misc_off + BK_WTOT);
     uint32_t *wover = (uint32_t *)(smem + prm.bk_misc_off + BK_WOVER);
+    const uint32_t *wmass = (const uint32_t *)(smem + prm.bk_misc_off + BK_WMASS);
     const int bpt = prm.bk_bpt;
     const int nbins = bpt * nth;
     const int hstride = (bpt >> 1) + prm.bk_pad;    // words from one thread's block of counters to the next
-    // (1 - 2^-20): the largest weight stays below the end of the axis
-    const float scale = (float)COARSE_N / (hi - lo) * 0.99999904632568359375f;
-    // ---- coarse histogram of a sample: every fourth slot of a thread (every fourth column when VEC, else
-    // the columns [4q nth, (4q+1) nth))
-    int nsample = VEC ? (m >> 2) : 0;
-    if (!VEC) {
+    const float lo = map.lo, scale = map.scale;
+    // half-word (16-bit counter, later first rank) of a bin inside hist
+    auto bin_halfword = [&](uint32_t fb) -> uint32_t {
+        const uint32_t wd = (fb >> 1) + (prm.bk_pad ? (fb >> prm.bk_lgbpt) << 2 : 0u);
+        return (wd << 1) | (fb & 1u);
+    };
+    if (!map.have) {
+        // ---- coarse histogram of a sample: every fourth slot of a thread (every fourth column when VEC, else
+        // the columns [4q nth, (4q+1) nth))
+        int nsample = VEC ? (m >> 2) : 0;
+        if (!VEC) {
 #pragma unroll
-        for (int k = 0; k < NS; k += 4) nsample += max(0, min(nth, m - k * nth));
-    }
-#pragma unroll
-    for (int k = 0; k < NS; k += 4) {
-        if (sm.has(k)) {
-            const int cb = min(max((int)coarse_pos(elem_w(key[k]), lo, scale), 0), COARSE_N - 1);
-            atomicAdd(&coarse[cb * 4 + (lane & 3)], 1u);
+            for (int k = 0; k < NS; k += 4) nsample += max(0, min(nth, m - k * nth));
         }
-    }
-    // clear this thread's share of the fine counters meanwhile
-    {
-        uint4 *hz = (uint4 *)(hist + tid * hstride);
-        for (int q = 0; q < (bpt >> 3); ++q) hz[q] = make_uint4(0u, 0u, 0u, 0u);
-    }
-    prefetch(1);
-    __syncthreads();
-    // ---- bins per coarse interval and the first bin of each.  Every wavefront works the whole table out for
-    // itself (4 intervals per lane) and writes it: all write the same words, and a wavefront's own LDS accesses
-    // execute in order, so no barrier is needed before the table is used.  The sampled counts are smoothed
-    // (1 2 1) so that a sparse interval the sample missed still gets bins from its neighbours' counts, and every
-    // interval gets one bin on top of its share.
-    {
+#pragma unroll
+        for (int k = 0; k < NS; k += 4) {
+            if (sm.has(k)) {
+                const int cb = min(max((int)coarse_pos(elem_w(key[k]), lo, scale), 0), COARSE_N - 1);
+                atomicAdd(&coarse[cb * 4 + (lane & 3)], 1u);
+            }
+        }
+        // clear this thread's share of the fine counters meanwhile
+        {
+            uint4 *hz = (uint4 *)(hist + tid * hstride);
+            for (int q = 0; q < (bpt >> 3); ++q) hz[q] = make_uint4(0u, 0u, 0u, 0u);
+        }
+        __syncthreads();
+        // ---- the table.  Every wavefront works the whole table out for itself (4 intervals per lane) and writes
+        // it: all write the same words, and a wavefront's own LDS accesses execute in order, so no barrier is
+        // needed before the table is used.
         const uint4 *cc4 = (const uint4 *)coarse;
         float c[4];
 #pragma unroll
@@ -461,34 +509,8 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
             const uint4 t = cc4[4 * lane + q];
             c[q] = (float)(t.x + t.y + t.z + t.w);
         }
-        float below = __int_as_float(lane_below(__float_as_int(c[3])));
-        float above = __int_as_float(lane_above(__float_as_int(c[0])));
-        if (lane == 0) below = c[0];
-        if (lane == 63) above = c[3];
-        const float ratio4 = (float)(nbins - COARSE_N - 16) / (4.0f * (float)nsample);
-        uint32_t ns[4];
-        ns[0] = (uint32_t)((below + 2.0f * c[0] + c[1]) * ratio4) + 1u;
-        ns[1] = (uint32_t)((c[0] + 2.0f * c[1] + c[2]) * ratio4) + 1u;
-        ns[2] = (uint32_t)((c[1] + 2.0f * c[2] + c[3]) * ratio4) + 1u;
-        ns[3] = (uint32_t)((c[2] + 2.0f * c[3] + above) * ratio4) + 1u;
-        const uint32_t tot = ns[0] + ns[1] + ns[2] + ns[3];
-        uint32_t base = wave_scan_incl(tot) - tot;
-        float4 e0, e1;          // integers below 2^16: exact as floats
-        e0.x = (float)base;
-        e0.y = (float)ns[0];
-        base += ns[0];
-        e0.z = (float)base;
-        e0.w = (float)ns[1];
-        base += ns[1];
-        e1.x = (float)base;
-        e1.y = (float)ns[2];
-        base += ns[2];
-        e1.z = (float)base;
-        e1.w = (float)ns[3];
-        ((float4 *)table)[2 * lane] = e0;
-        ((float4 *)table)[2 * lane + 1] = e1;
+        write_bin_table(table, lane, c, (float)(nbins - COARSE_N - 16) / (4.0f * (float)nsample));
     }
-    prefetch(2);
     // ---- fine bin of every key; the counter's old value is the key's slot inside its bin
     uint32_t fbs[NS];
     bool over = false;
@@ -496,23 +518,25 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
     for (int k = 0; k < NS; ++k) {
         fbs[k] = 0u;
         if (sm.has(k)) {
+            // Position on the coarse axis, held inside the axis (a carried map may not cover this unit's extremes:
+            // weights beyond either end all go to the first / last bin, which keeps the map monotone).
             // bin = first bin of the interval + fraction of the interval x bins of the interval, in one fused
-            // multiply-add: monotone in w, and at most the first bin of the next interval (the clamps cannot
-            // bind while the table is consistent and the weights are finite; they keep the indices in range)
-            const float x = coarse_pos(elem_w(key[k]), lo, scale);
-            const uint32_t cb = min((uint32_t)(int)x, (uint32_t)(COARSE_N - 1));
+            // multiply-add: monotone in w, and at most the first bin of the next interval (the last clamp cannot
+            // bind while the table is consistent; it keeps the index inside the counters)
+            const float x = fminf(fmaxf(coarse_pos(elem_w(key[k]), lo, scale), 0.0f), (float)COARSE_N - 0.0001f);
+            const uint32_t cb = (uint32_t)(int)x;
             const float fr = __builtin_amdgcn_fractf(x);
             const float2 tb = table[cb];
             const uint32_t fb = min((uint32_t)fmaf(fr, tb.y, tb.x), (uint32_t)(nbins - 1));
-            const uint32_t sh = (fb & 1u) << 4;
-            const uint32_t wd = (fb >> 1) + (prm.bk_pad ? (fb >> prm.bk_lgbpt) << 2 : 0u);   // word of the bin's counter
-            const uint32_t old = atomicAdd(&hist[wd], 1u << sh);
+            const uint32_t hw = bin_halfword(fb);
+            const uint32_t sh = (hw & 1u) << 4;
+            const uint32_t old = atomicAdd(&hist[hw >> 1], 1u << sh);
             const uint32_t slot = (old >> sh) & 0xFFFFu;
             over = over || (slot >= (uint32_t)BIN_MAX_KEYS);
-            fbs[k] = (wd << 1) | (fb & 1u) | (slot << 16);     // half-word of the counter, slot
+            fbs[k] = hw | (slot << 16);
         }
     }
-    prefetch(3);
+    prefetch(1);
     __syncthreads();
     // ---- first rank of every bin: exclusive scan of the counters, written over them (16 bits each)
     {
@@ -534,17 +558,24 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
             wover[wave] = wave_over ? 1u : 0u;
         }
         __syncthreads();
-        // a bin with more than BIN_MAX_KEYS keys anywhere in the row: the caller sorts by the network instead
+        // the per-wavefront flags: a bin with more than BIN_MAX_KEYS keys anywhere in the unit (the caller then
+        // sorts by the network instead), and whether the unit holds sensitivity mass
         {
-            const uint4 *o4 = (const uint4 *)wover;
-            uint32_t any = 0;
+            const uint4 *o4 = (const uint4 *)wover, *m4 = (const uint4 *)wmass;
+            uint32_t any = 0, mass = 0;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const uint4 t = o4[q];
-                any |= (4 * q + 0 < (nth >> 6) ? t.x : 0u) | (4 * q + 1 < (nth >> 6) ? t.y : 0u) |
-                       (4 * q + 2 < (nth >> 6) ? t.z : 0u) | (4 * q + 3 < (nth >> 6) ? t.w : 0u);
+                const uint4 t = o4[q], u = m4[q];
+                any |= (4 * q + 0 < nw ? t.x : 0u) | (4 * q + 1 < nw ? t.y : 0u) | (4 * q + 2 < nw ? t.z : 0u) |
+                       (4 * q + 3 < nw ? t.w : 0u);
+                mass |= (4 * q + 0 < nw ? u.x : 0u) | (4 * q + 1 < nw ? u.y : 0u) | (4 * q + 2 < nw ? u.z : 0u) |
+                        (4 * q + 3 < nw ? u.w : 0u);
             }
-            if (any) return false;
+            anymass = (int)mass;
+            if (any) {
+                map.have = false;
+                return false;
+            }
         }
         // the counters are read once more (cheaper than carrying them in registers across the barrier)
         uint32_t at = (inc - run + waves_below(wtot, wave));
@@ -567,18 +598,22 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
             }
         }
     }
+    prefetch(2);
     __syncthreads();
     // ---- scatter: rank = first rank of the bin + slot in the bin
     double *lds = (double *)smem;
     const unsigned short *first = (const unsigned short *)hist;
+    const bool unit_weights = !anymass && prm.nseg == 1;
 #pragma unroll
     for (int k = 0; k < NS; ++k) {
         if (sm.has(k)) {
             // (the clamp cannot bind when the counts are right; it keeps the store inside the row regardless)
             const uint32_t pos = min((uint32_t)first[fbs[k] & 0xFFFFu] + (fbs[k] >> 16), (uint32_t)(m - 1));
-            lds[swz(pos)] = __longlong_as_double((long long)key[k]);
+            const u64 kk = unit_weights ? unit_weight_key(key[k]) : key[k];
+            lds[swz(pos)] = __longlong_as_double((long long)kk);
         }
     }
+    prefetch(3);
     __syncthreads();
     // ---- order inside the bins
     const int p0 = tid * EPT;
@@ -594,7 +629,30 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
         for (int r = 0; r < 8; ++r)
             if (p0 + r < m) dst[r] = v[r];
     }
+    // ---- the table for the next unit, from this unit's exact counts: the keys of a coarse interval are the
+    // difference of the first ranks of its first bin and of the next interval's first bin.  One wavefront (the
+    // last: it has the least to do in the passes) writes it; nothing reads the table before the next unit.
+    if (wave == nw - 1) {
+        const float4 e0 = ((const float4 *)table)[2 * lane], e1 = ((const float4 *)table)[2 * lane + 1];
+        const uint32_t f0 = first[bin_halfword(min((uint32_t)e0.x, (uint32_t)(nbins - 1)))];
+        const uint32_t f1 = first[bin_halfword(min((uint32_t)e0.z, (uint32_t)(nbins - 1)))];
+        const uint32_t f2 = first[bin_halfword(min((uint32_t)e1.x, (uint32_t)(nbins - 1)))];
+        const uint32_t f3 = first[bin_halfword(min((uint32_t)e1.z, (uint32_t)(nbins - 1)))];
+        uint32_t f4 = (uint32_t)lane_above((int)f0);
+        if (lane == 63) f4 = (uint32_t)m;
+        float c[4];
+        c[0] = (float)(int)(f1 - f0);
+        c[1] = (float)(int)(f2 - f1);
+        c[2] = (float)(int)(f3 - f2);
+        c[3] = (float)(int)(f4 - f3);
+        write_bin_table(table, lane, c, (float)(nbins - COARSE_N - 16) / (4.0f * (float)m));
+    }
     __syncthreads();
+    // the fine counters start the next unit at zero
+    {
+        uint4 *hz = (uint4 *)(hist + tid * hstride);
+        for (int q = 0; q < (bpt >> 3); ++q) hz[q] = make_uint4(0u, 0u, 0u, 0u);
+    }
     if (p0 + 8 < m) {
         // upper half of this window (still in registers) with the lower half of the next one
         const double *nxt = lds + swz((uint32_t)(p0 + EPT));
@@ -613,6 +671,7 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
         }
     }
     __syncthreads();
+    map.have = true;
     return true;
 }
 
@@ -693,6 +752,10 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     float pw[NS], ps[NS];
     if ((long long)blockIdx.x < prm.nwork) fetch_unit<NS, VEC>(prm, blockIdx.x, tid0, nth, pw, ps);
 
+    BinMap map;
+    map.have = false;
+    map.lo = 0.0f;
+    map.scale = 0.0f;
     for (long long work = blockIdx.x; work < prm.nwork; work += gridDim.x) {
     // the thread index is made opaque per unit: per-thread addresses are recomputed where they are
     // used instead of being hoisted out of this loop and held in registers through the sort
@@ -714,10 +777,10 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     // (the bitonic network needs the registers: without the bucket path the next unit is fetched after the sort)
     auto prefetch = [&](int part) { fetch_unit<NS, VEC>(prm, more ? work + gridDim.x : work, tid, nth, pw, ps, more, part); };
     if (buckets) prefetch(0);
-    int anymass;
-    float lo = 0.0f, hi = 0.0f;
+    int anymass = 1;
+    bool sorted_ok = false;
     if (buckets) {
-        // per wavefront: least and largest weight and the mass flag; every thread combines the 16 entries
+        // per wavefront: least and largest weight and the mass flag, for whoever needs them after a barrier
         float *wmin = (float *)(smem + prm.bk_misc_off + BK_WMIN), *wmax = (float *)(smem + prm.bk_misc_off + BK_WMAX);
         uint32_t *wmass = (uint32_t *)(smem + prm.bk_misc_off + BK_WMASS);
 #pragma unroll
@@ -731,37 +794,37 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
             wmax[tid >> 6] = whi;
             wmass[tid >> 6] = wave_mass ? 1u : 0u;
         }
-        uint32_t *cc = (uint32_t *)(smem + prm.bk_coarse_off);
-        for (int i = tid; i < COARSE_N * 4; i += nth) cc[i] = 0u;
-        __syncthreads();
-        const int nw = nth >> 6;
-        lo = INFINITY;
-        hi = -INFINITY;
-        uint32_t any = 0;
+        bool usable = true;
+        if (!map.have) {
+            // no map carried over: the axis is this unit's own range
+            uint32_t *cc = (uint32_t *)(smem + prm.bk_coarse_off);
+            for (int i = tid; i < COARSE_N * 4; i += nth) cc[i] = 0u;
+            __syncthreads();
+            const int nw = nth >> 6;
+            float lo = INFINITY, hi = -INFINITY;
+            uint32_t any = 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const float4 a = ((const float4 *)wmin)[q], b4 = ((const float4 *)wmax)[q];
-            const uint4 c = ((const uint4 *)wmass)[q];
-            if (4 * q + 0 < nw) { lo = fminf(lo, a.x); hi = fmaxf(hi, b4.x); any |= c.x; }
-            if (4 * q + 1 < nw) { lo = fminf(lo, a.y); hi = fmaxf(hi, b4.y); any |= c.y; }
-            if (4 * q + 2 < nw) { lo = fminf(lo, a.z); hi = fmaxf(hi, b4.z); any |= c.z; }
-            if (4 * q + 3 < nw) { lo = fminf(lo, a.w); hi = fmaxf(hi, b4.w); any |= c.w; }
+            for (int q = 0; q < 4; ++q) {
+                const float4 a = ((const float4 *)wmin)[q], b4 = ((const float4 *)wmax)[q];
+                const uint4 c = ((const uint4 *)wmass)[q];
+                if (4 * q + 0 < nw) { lo = fminf(lo, a.x); hi = fmaxf(hi, b4.x); any |= c.x; }
+                if (4 * q + 1 < nw) { lo = fminf(lo, a.y); hi = fmaxf(hi, b4.y); any |= c.y; }
+                if (4 * q + 2 < nw) { lo = fminf(lo, a.z); hi = fmaxf(hi, b4.z); any |= c.z; }
+                if (4 * q + 3 < nw) { lo = fminf(lo, a.w); hi = fmaxf(hi, b4.w); any |= c.w; }
+            }
+            anymass = (int)any;
+            // a usable axis needs two distinct finite ends (a constant row has none);
+            // (1 - 2^-20): the largest weight stays below the end of the axis
+            usable = hi > lo && (hi - lo) < INFINITY;
+            map.lo = lo;
+            map.scale = (float)COARSE_N / (hi - lo) * 0.99999904632568359375f;
         }
-        anymass = (int)any;
+        if (usable) sorted_ok = bucket_sort<NS, VEC>(smem, prm, key, tid, nth, m, map, anymass, prefetch);
     } else {
         anymass = __syncthreads_or((int)mass);
     }
     // (a segment of a long row cannot tell on its own: it records what it saw for merge_tile_kernel)
     if (prm.nseg > 1 && tid == 0) prm.segmass[work] = anymass;
-    if (!anymass && prm.nseg == 1) {
-        // no sensitivity mass in this row: cluster with unit weights
-#pragma unroll
-        for (int k = 0; k < NS; ++k)
-            if (sm.has(k)) key[k] = unit_weight_key(key[k]);
-    }
-    bool sorted_ok = false;
-    // a usable axis needs two distinct finite ends (a constant row has none)
-    if (buckets && hi > lo && (hi - lo) < INFINITY) sorted_ok = bucket_sort<NS, VEC>(smem, prm, key, tid, nth, m, lo, hi, prefetch);
     if (!sorted_ok) {
         // The bitonic network over the whole padded row.  Its keys overlay the bucket path's tables: wait
         // until every thread is done with them.  The bucket path gave its key registers away, so the
@@ -772,11 +835,12 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
             bool mass2 = false;
             float lo2, hi2;
             build_keys<NS, VEC>(pw, ps, alpha, tid, nth, m, key, mass2, lo2, hi2);
-            if (!anymass && prm.nseg == 1) {
+        }
+        if (!anymass && prm.nseg == 1) {
+            // no sensitivity mass in this row: cluster with unit weights
 #pragma unroll
-                for (int k = 0; k < NS; ++k)
-                    if (sm.has(k)) key[k] = unit_weight_key(key[k]);
-            }
+            for (int k = 0; k < NS; ++k)
+                if (sm.has(k)) key[k] = unit_weight_key(key[k]);
         }
 #pragma unroll
         for (int k = 0; k < NS; ++k)
