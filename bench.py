@@ -42,7 +42,7 @@ def alg_lane_ops_per_row(m: int) -> float:
 
 def read_traffic():
     """HBM bytes per launch of the clustering kernel from the committed rocprofv3 counter summary."""
-    p = os.path.join(ROOT, "profiles", "sort_kernel_4096x11008_hbm_traffic.txt")
+    p = os.path.join(ROOT, "profiles", "error_table_4096x11008_hbm_traffic.txt")
     try:
         for line in open(p):
             if line.startswith("traffic_bytes_per_launch"):
@@ -50,6 +50,94 @@ def read_traffic():
     except OSError:
         pass
     return None
+
+
+COUNTER_PASSES = (("FETCH_SIZE",), ("WRITE_SIZE",),
+                  ("SQ_BUSY_CYCLES", "SQ_INSTS_VALU", "SQ_ACTIVE_INST_VALU", "SQ_INSTS_LDS", "SQ_ACTIVE_INST_LDS"))
+
+
+def counter_child():
+    """What a rocprofv3 counter pass runs: the plain copy of known size that calibrates the byte counters, then
+    the error-table call on the metric layer a few times.  Prints nothing."""
+    import torch
+
+    import paper_2412_04180_amd as skim
+    import skim_synth
+
+    ctx = skim.Context(0)
+    W_h, S_h = skim_synth.make_ws(2, 2)
+    W, S = torch.from_numpy(W_h).cuda(), torch.from_numpy(S_h).cuda()
+    dst = torch.empty_like(W)
+    for _ in range(3):
+        torch.mul(W, 1.0, out=dst)
+    out = None
+    for _ in range(3):
+        out = ctx.error_table(W, S, iters=ITERS, out=out)
+    torch.cuda.synchronize()
+
+
+def collect_counters(timeout_s=150):
+    """rocprofv3 --pmc over `bench.py --counter-child`, one run per counter group.  Returns
+    {kernel: {counter: median value per dispatch}} with kernels 'copy', 'sort', 'lloyd', 'finish', or raises."""
+    import csv
+    import glob
+    import shutil
+    import statistics
+    import subprocess
+    import tempfile
+
+    if shutil.which("rocprofv3") is None:
+        raise RuntimeError("rocprofv3 not on PATH")
+    res = {}
+    for group in COUNTER_PASSES:
+        d = tempfile.mkdtemp(prefix="skim_pmc_", dir="/tmp")
+        try:
+            cmd = ["timeout", "-s", "KILL", str(timeout_s), "rocprofv3", "--pmc", *group, "--kernel-trace",
+                   "--output-format", "csv", "-d", d, "--", sys.executable, os.path.join(ROOT, "bench.py"),
+                   "--counter-child"]
+            r = subprocess.run(cmd, cwd="/tmp", env=dict(os.environ, TMPDIR="/tmp"), stdout=subprocess.PIPE,
+                               stderr=subprocess.STDOUT, text=True)
+            files = glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True)
+            if r.returncode != 0 or not files:
+                raise RuntimeError(f"rocprofv3 --pmc {' '.join(group)} failed (rc {r.returncode}): {r.stdout[-300:]}")
+            vals = {}
+            for row in csv.DictReader(open(files[0])):
+                name = row["Kernel_Name"]
+                kern = ("sort" if "sort_kernel" in name else "lloyd" if "lloyd_iter_kernel" in name else
+                        "finish" if "finish_kernel" in name else "copy" if "elementwise" in name else None)
+                if kern:
+                    vals.setdefault((kern, row["Counter_Name"]), []).append(float(row["Counter_Value"]))
+            for (kern, cname), v in vals.items():
+                res.setdefault(kern, {})[cname] = statistics.median(v)
+        finally:
+            shutil.rmtree(d, ignore_errors=True)
+    for k in ("copy", "sort", "lloyd", "finish"):
+        if k not in res:
+            raise RuntimeError(f"no dispatch of the {k} kernel in the counter output")
+    return res
+
+
+def host_cpus():
+    """(logical CPUs this process may use, physical cores of the machine) from the OS."""
+    try:
+        logical = len(os.sched_getaffinity(0))
+    except AttributeError:
+        logical = os.cpu_count() or 1
+    cores = set()
+    try:
+        phys = core = None
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("physical id"):
+                phys = line.split(":")[1].strip()
+            elif line.startswith("core id"):
+                core = line.split(":")[1].strip()
+            elif not line.strip():
+                if phys is not None and core is not None:
+                    cores.add((phys, core))
+                phys = core = None
+    except OSError:
+        pass
+    return logical, (len(cores) or None)
 
 
 def main():
@@ -64,7 +152,14 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain elementwise copy of the W matrix (reads and writes n*m*4 bytes): "
                          "the known-size kernel that calibrates the HBM byte counters of a rocprofv3 --pmc run")
+    ap.add_argument("--no-counters", action="store_true",
+                    help="skip the rocprofv3 counter passes (HBM traffic, executed VALU instructions); the figures "
+                         "are then taken from the committed summary under profiles/")
+    ap.add_argument("--counter-child", action="store_true", help=argparse.SUPPRESS)
     args = ap.parse_args()
+    if args.counter_child:
+        counter_child()
+        return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
               "(no sharding or collectives are part of it)", file=sys.stderr)
@@ -101,7 +196,6 @@ def main():
     ev_c = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     ev_d = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     t_sort, t_lloyd = [0.0], [0.0]
-    ctx.profile_enable(True)     # HIP events around the kernels of the clustering call, on its stream
 
     def step(i=None):
         if i is not None:
@@ -132,6 +226,7 @@ def main():
     # per-kernel times of the clustering call (the library keeps the events of its last call): a few
     # more calls, each read back before the next
     prof_calls = min(args.steps, 10)
+    ctx.profile_enable(True)     # HIP events around the kernels of the clustering call, on its stream (after the timed region)
     for _ in range(prof_calls):
         ctx.error_table(W, S, iters=ITERS, out=table)
         stream.synchronize()
@@ -160,16 +255,27 @@ def main():
     achieved_alu = alg_ops / (ms_sort * 1e-3) / 1e12
     alg_bytes = 8.0 * n * m
     hbm_gbs = alg_bytes / (ms_sort * 1e-3) / 1e9
+    # the same bound counted with what this kernel's compare-exchange costs (two instructions: fp64 min and max):
+    # the comparison work then needs less time than reading W and S once, and HBM is the limiting roofline
+    own_alu_us = 2.0 / 5.0 * alg_ops / (ALU_PEAK_TLANEOPS * 1e12) * 1e6
+    hbm_floor_us = alg_bytes / (HBM_PEAK_GBS * 1e9) * 1e6
     roofline = {
         "bound": "alu", "kernel": "sort_kernel (dominant kernel of skim_error_table)",
         "achieved": round(achieved_alu, 4), "peak": round(ALU_PEAK_TLANEOPS, 2), "unit": "Tlaneop/s",
         "frac": round(achieved_alu / ALU_PEAK_TLANEOPS, 5),
-        "traffic": read_traffic(),
+        "traffic": None,
         "kernel_ms": round(ms_sort, 4),
         "algorithmic_lane_ops_per_launch": alg_ops,
+        "algorithmic_lane_ops_basis": "m*log2(m) compare-exchanges per row at 5 lane-operations each (64-bit compare + 4 selects)",
         "hbm_algorithmic_bytes_per_launch": alg_bytes,
         "hbm_achieved_GBps": round(hbm_gbs, 1), "hbm_frac": round(hbm_gbs / HBM_PEAK_GBS, 5),
         "whole_table_frac": round(alg_ops / (ms_table * 1e-3) / 1e12 / ALU_PEAK_TLANEOPS, 5),
+        "whole_table_hbm_frac": round(alg_bytes / (ms_table * 1e-3) / 1e9 / HBM_PEAK_GBS, 5),
+        "counted_with_this_kernels_own_compare_exchange": {
+            "lane_ops_per_compare_exchange": 2, "alu_floor_us": round(own_alu_us, 1), "hbm_floor_us": round(hbm_floor_us, 1),
+            "limiting": "hbm" if hbm_floor_us > own_alu_us else "alu",
+            "frac": round(max(hbm_floor_us, own_alu_us) / (ms_sort * 1e3), 5),
+            "whole_table_frac": round(max(hbm_floor_us, own_alu_us) / (ms_table * 1e3), 5)},
     }
 
     out = {
@@ -206,6 +312,18 @@ def main():
     out["dequant_matvec"] = {"ms": round(mv_ms, 4), "packed_bytes": int(packed_bytes),
                              "GBps": round(packed_bytes / (mv_ms * 1e-3) / 1e9, 1),
                              "frac_of_hbm_peak": round(packed_bytes / (mv_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    yf = ctx.dequant_matvec_f32(pk, m, xv)
+    torch.cuda.synchronize()
+    mv0.record(stream)
+    for _ in range(10):
+        ctx.dequant_matvec_f32(pk, m, xv, out=yf)
+    mv1.record(stream)
+    torch.cuda.synchronize()
+    mvf_ms = mv0.elapsed_time(mv1) / 10
+    out["dequant_matvec_f32"] = {"ms": round(mvf_ms, 4), "packed_bytes": int(packed_bytes),
+                                 "GBps": round(packed_bytes / (mvf_ms * 1e-3) / 1e9, 1),
+                                 "frac_of_hbm_peak": round(packed_bytes / (mvf_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                 "max_abs_diff_to_float64_reader": float((yf.double() - yv).abs().max().item())}
     # yardsticks (not steps of the path): the least error any clustering / any allocation could reach
     E_d = table["E"]
     if not args.no_yardsticks:
@@ -232,6 +350,40 @@ def main():
         out["scale_loop"] = bench_scale_loop(ctx, torch, np, skim_synth)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(W_h, S_h, np)
+    # hardware counters of the clustering kernels, from rocprofv3 passes over a child process of this script
+    counters, note = None, None
+    if not args.no_counters:
+        try:
+            counters = collect_counters()
+        except Exception as e:   # the bench line must not depend on the profiler
+            note = f"live counter passes failed ({str(e)[:200]})"
+    rf = out["roofline"]
+    if counters is not None:
+        copy_bytes = float(n) * m * 4
+        ff = copy_bytes / counters["copy"]["FETCH_SIZE"]      # bytes per counter unit, from the copy of known size
+        wf = copy_bytes / counters["copy"]["WRITE_SIZE"]
+        byt = {k: counters[k]["FETCH_SIZE"] * ff + counters[k]["WRITE_SIZE"] * wf for k in ("sort", "lloyd", "finish")}
+        c = counters["sort"]
+        rf["traffic"] = round(byt["sort"])
+        rf["traffic_source"] = ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes of this run (median per dispatch), "
+                                "scaled by a plain copy of n*m*4 bytes")
+        rf["traffic_read_write"] = [round(c["FETCH_SIZE"] * ff), round(c["WRITE_SIZE"] * wf)]
+        rf["traffic_over_algorithmic"] = round(byt["sort"] / alg_bytes, 3)
+        rf["whole_table_traffic"] = round(sum(byt.values()))
+        rf["whole_table_traffic_over_algorithmic"] = round(sum(byt.values()) / alg_bytes, 3)
+        rf["executed_lane_ops"] = round(c["SQ_INSTS_VALU"] * 64)
+        rf["algorithmic_efficiency"] = round(alg_ops / (c["SQ_INSTS_VALU"] * 64), 4)
+        # SQ_BUSY_CYCLES counts per shader engine (32); SQ_ACTIVE_INST_* in units of 4 clocks of one of 1024 SIMDs
+        clocks = c["SQ_BUSY_CYCLES"] / 32.0
+        rf["valu_busy"] = round(c["SQ_ACTIVE_INST_VALU"] * 4 / (clocks * 1024), 4)
+        rf["lds_busy"] = round(c["SQ_ACTIVE_INST_LDS"] * 4 / (clocks * 1024), 4)
+        cl = counters["lloyd"]
+        rf["lloyd_kernel"] = {"executed_lane_ops": round(cl["SQ_INSTS_VALU"] * 64),
+                              "valu_busy": round(cl["SQ_ACTIVE_INST_VALU"] * 4 / (cl["SQ_BUSY_CYCLES"] / 32.0 * 1024), 4),
+                              "traffic": round(byt["lloyd"])}
+    else:
+        rf["traffic"] = read_traffic()
+        rf["traffic_source"] = "profiles/error_table_4096x11008_hbm_traffic.txt (committed summary)" + (f"; {note}" if note else "")
     print(json.dumps(out))
 
 
@@ -355,7 +507,9 @@ def cpu_baseline(W_h, S_h, np, target_s=12.0):
     cr = oracle.cluster_rows(Ws, Ss, g["bits"])
     oracle.pack(Ws, g["bits"], cr["labels"], cr["centroids"])
     t_all = time.perf_counter() - t0
+    logical, physical = host_cpus()
     return {"value": round(R / t_all, 2), "unit": "rows/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "host_logical_cpus_available": logical, "host_physical_cores": physical,
             "sample": f"first {R} of {n} rows of the same 4096x11008 matrix: error table b=1..4 (30 iterations), "
                       f"greedy 3.2 bits, labels at the allocated widths, pack",
             "error_table_only_rows_per_s": round(R / t_tab, 2), "seconds": round(t_all, 2)}

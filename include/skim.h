@@ -258,6 +258,16 @@ skim_status skim_dequant_matvec(skim_ctx *ctx, const uint32_t *codes, const int6
                                 const int32_t *row_perm, const uint16_t *codebooks_fp16,
                                 const float *alpha, int64_t n, int64_t m, const float *x, double *y);
 
+/* The same product in float32, for a reader bound by the packed bytes it
+ * streams rather than by float64 arithmetic (the memory footprint argument of
+ * Sec. 5.4 and the packed layout of App. D.2 are about this reader):
+ *   y[i] = sum_j f32(codebook_i[code_ij]) * (alpha_j * x_j),  fused multiply-adds
+ * in float32, a summation order of its own; it agrees with skim_dequant_matvec
+ * to about 1e-6 of sum_j |Wq_ij x_j|.  y: dev float32, indexed by original row. */
+skim_status skim_dequant_matvec_f32(skim_ctx *ctx, const uint32_t *codes, const int64_t *group_word_offset,
+                                    const int32_t *row_perm, const uint16_t *codebooks_fp16,
+                                    const float *alpha, int64_t n, int64_t m, const float *x, float *y);
+
 /* ---- scaling vector ----------------------------------------------------- */
 
 /* Layer-wise Hessian proxy from calibration activations (Sec. 3.4):

@@ -25,7 +25,7 @@ EXPORTS = ["skim_create", "skim_destroy", "skim_last_error", "skim_workspace_byt
            "skim_profile_enable", "skim_profile_last", "skim_validate_enable",
            "skim_error_table", "skim_error_table_lfull", "skim_cluster_rows", "skim_select_allocated", "skim_greedy_allocate", "skim_greedy_allocate_device",
            "skim_dp_allocate_scratch_bytes", "skim_dp_allocate", "skim_kmeans_optimal_scratch_bytes", "skim_kmeans_optimal",
-           "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_pack_static", "skim_layer_loss", "skim_scale_step", "skim_train_scale", "skim_unpack", "skim_dequant_matvec", "skim_hessian_from_activations"]
+           "skim_packed_words", "skim_codebook_entries", "skim_pack", "skim_pack_static", "skim_layer_loss", "skim_scale_step", "skim_train_scale", "skim_unpack", "skim_dequant_matvec", "skim_dequant_matvec_f32", "skim_hessian_from_activations"]
 
 
 class SkimError(RuntimeError):
@@ -88,6 +88,7 @@ def load_library():
         lib.skim_hessian_from_activations.argtypes = [vp, vp, i64, i64, vp]
         lib.skim_unpack.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, vp]
         lib.skim_dequant_matvec.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, vp, vp]
+        lib.skim_dequant_matvec_f32.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, vp, vp]
         lib.skim_train_scale.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i32, i32, i32, i64, C.POINTER(AdamOpts),
                                          vp, vp, vp, vp, vp, vp]
         _lib = lib
@@ -378,6 +379,15 @@ class Context:
         self._check(self.lib.skim_dequant_matvec(self.h, _dp(pk["codes"]), _dp(pk["group_word_offset"]),
                                                  _dp(pk["row_perm"]), _dp(pk["codebooks"]), _dp(alpha), n, m,
                                                  _dp(x), _dp(y)))
+        return y
+
+    def dequant_matvec_f32(self, pk, m, x, alpha=None, out=None):
+        """y = Wq x for the packed model `pk` in float32 arithmetic; y float32[n] in original row order."""
+        n = pk["row_perm"].numel()
+        y = out if out is not None else self.empty((n,), self.torch.float32)
+        self._check(self.lib.skim_dequant_matvec_f32(self.h, _dp(pk["codes"]), _dp(pk["group_word_offset"]),
+                                                     _dp(pk["row_perm"]), _dp(pk["codebooks"]), _dp(alpha), n, m,
+                                                     _dp(x), _dp(y)))
         return y
 
     def train_scale(self, W, S, H, bits, alpha, adam_m, adam_v, steps=120, outer=1, t0=1, kmeans_iters=30, opts=None):

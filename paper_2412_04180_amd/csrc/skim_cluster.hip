@@ -92,8 +92,8 @@ __device__ __forceinline__ uint32_t swz(uint32_t i) { return i + (i >> 4); }
 // grow with (high, low); negative keys fall with their magnitude, i.e. with |w| and, for equal
 // w, with the complemented s.  Two keys are equal only when w and s are.
 __device__ __forceinline__ u64 make_key(float w, float s) {
-    if (w == 0.0f) w = 0.0f;
-    if (s == 0.0f) s = 0.0f;
+    w = __fadd_rn(w, 0.0f);   // -0 + 0 = +0 under round-to-nearest; every other value is unchanged
+    s = __fadd_rn(s, 0.0f);
     const uint32_t hi = __float_as_uint(w);
     uint32_t lo = __float_as_uint(s);
     if (hi >> 31) lo = ~lo;
@@ -357,19 +357,6 @@ __device__ __forceinline__ uint32_t wave_scan_incl(uint32_t x) {
     x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2, 3
     return x;
 }
-// Sum of the totals of the wavefronts below `wave` (tot: 16 entries in LDS, entries past the last wavefront 0).
-__device__ __forceinline__ uint32_t waves_below(const uint32_t *tot, int wave) {
-    const uint4 *t4 = (const uint4 *)tot;
-    uint32_t acc = 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const uint4 t = t4[q];
-        acc += (4 * q + 0 < wave ? t.x : 0u) + (4 * q + 1 < wave ? t.y : 0u) + (4 * q + 2 < wave ? t.z : 0u) +
-               (4 * q + 3 < wave ? t.w : 0u);
-    }
-    return acc;
-}
-
 // Which of a thread's key slots hold a key of the unit, and which column a slot is.
 //   VEC == false: slot k is column tid + k * nth, so all slots below kfull = m / nth hold a key, slot kfull does in
 //                 the threads below m % nth, and none above.
@@ -399,11 +386,11 @@ struct Slots {
 //            followed by bk_pad spare words so that the blocks of 8 neighbouring threads start in different banks
 //   coarse   COARSE_N intervals x 4 counters (a lane adds to copy lane & 3: fewer same-address collisions),
 //            then per interval (first bin, number of bins) as two floats
-//   misc     per wavefront: least weight, largest weight, mass flag, scan total, overflow flag (16 entries each)
+//   misc     per wavefront: least weight, largest weight, mass flag, scan total with its flags (16 entries each)
 constexpr int COARSE_N = 256;
 constexpr uint32_t BK_COARSE_BYTES = COARSE_N * 4 * 4 + COARSE_N * 8;
 constexpr uint32_t BK_MISC_BYTES = 512;
-constexpr uint32_t BK_WMIN = 0, BK_WMAX = 64, BK_WMASS = 128, BK_WTOT = 256, BK_WOVER = 320;
+constexpr uint32_t BK_WMIN = 0, BK_WMAX = 64, BK_WMASS = 128, BK_WTOT = 256;
 
 // The bin map a workgroup carries from one unit to the next: the axis of the coarse intervals and whether the
 // table in LDS (bins per interval) is valid and the fine counters are zero.  The first unit of a workgroup
@@ -453,22 +440,21 @@ __device__ __forceinline__ void write_bin_table(float2 *table, int lane, const f
 // this unit (least weight, COARSE_N / range) and the coarse counters must be zero (with a barrier between
 // clearing them and this call).  Returns false, with nothing of value in LDS and map.have false, when some bin
 // took more than BIN_MAX_KEYS keys; all threads of the workgroup return the same.  Contains workgroup
-// barriers: every thread must call it.  anymass: whether any key of the unit carries sensitivity mass (from the
-// per-wavefront flags the caller left in LDS); a unit without mass is scattered with unit weights (single
+// barriers: every thread must call it.  wave_mass: whether a key of this wavefront carries sensitivity mass;
+// anymass (out): whether any key of the unit does; a unit without mass is scattered with unit weights (single
 // segment rows only).  prefetch(g), g = 1, 2, 3: issues part g of the loads of the next unit.  The parts are
 // spread over the phases: all compute units run these phases nearly in step, and loads issued together by all
 // of them queue up behind the memory's peak rate.
 template <int NS, bool VEC, typename Prefetch>
 __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterParams &prm, const u64 (&key)[NS],
-                                            int tid, int nth, int m, BinMap &map, int &anymass, Prefetch prefetch) {
+                                            int tid, int nth, int m, BinMap &map, bool wave_mass, int &anymass,
+                                            Prefetch prefetch) {
     const int lane = tid & 63, wave = tid >> 6, nw = nth >> 6;
     const Slots<VEC> sm(m, nth, tid);
     uint32_t *hist = (uint32_t *)(smem + prm.bk_hist_off);
     uint32_t *coarse = (uint32_t *)(smem + prm.bk_coarse_off);
     float2 *table = (float2 *)(coarse + COARSE_N * 4);
     uint32_t *wtot = (uint32_t *)(smem + prm.bk_misc_off + BK_WTOT);
-    uint32_t *wover = (uint32_t *)(smem + prm.bk_misc_off + BK_WOVER);
-    const uint32_t *wmass = (const uint32_t *)(smem + prm.bk_misc_off + BK_WMASS);
     const int bpt = prm.bk_bpt;
     const int nbins = bpt * nth;
     const int hstride = (bpt >> 1) + prm.bk_pad;    // words from one thread's block of counters to the next
@@ -513,7 +499,8 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
     }
     // ---- fine bin of every key; the counter's old value is the key's slot inside its bin
     uint32_t fbs[NS];
-    bool over = false;
+    uint32_t smax = 0;          // largest slot any of this thread's keys got
+    const bool padded = prm.bk_pad != 0;
 #pragma unroll
     for (int k = 0; k < NS; ++k) {
         fbs[k] = 0u;
@@ -528,11 +515,11 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
             const float fr = __builtin_amdgcn_fractf(x);
             const float2 tb = table[cb];
             const uint32_t fb = min((uint32_t)fmaf(fr, tb.y, tb.x), (uint32_t)(nbins - 1));
-            const uint32_t hw = bin_halfword(fb);
+            const uint32_t hw = padded ? bin_halfword(fb) : fb;
             const uint32_t sh = (hw & 1u) << 4;
             const uint32_t old = atomicAdd(&hist[hw >> 1], 1u << sh);
             const uint32_t slot = (old >> sh) & 0xFFFFu;
-            over = over || (slot >= (uint32_t)BIN_MAX_KEYS);
+            smax = max(smax, slot);
             fbs[k] = hw | (slot << 16);
         }
     }
@@ -552,33 +539,32 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
             }
         }
         const uint32_t inc = wave_scan_incl(run);
-        const bool wave_over = __ballot(over) != 0;
-        if (lane == 63) {
-            wtot[wave] = inc;
-            wover[wave] = wave_over ? 1u : 0u;
-        }
+        const bool wave_over = __ballot(smax >= (uint32_t)BIN_MAX_KEYS) != 0;
+        // one word per wavefront: keys up to and including this wavefront's bins << 2 | overflow << 1 | mass
+        if (lane == 63) wtot[wave] = (inc << 2) | (wave_over ? 2u : 0u) | (wave_mass ? 1u : 0u);
         __syncthreads();
-        // the per-wavefront flags: a bin with more than BIN_MAX_KEYS keys anywhere in the unit (the caller then
-        // sorts by the network instead), and whether the unit holds sensitivity mass
+        uint32_t below = 0, flags = 0;
         {
-            const uint4 *o4 = (const uint4 *)wover, *m4 = (const uint4 *)wmass;
-            uint32_t any = 0, mass = 0;
+            const uint4 *t4 = (const uint4 *)wtot;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const uint4 t = o4[q], u = m4[q];
-                any |= (4 * q + 0 < nw ? t.x : 0u) | (4 * q + 1 < nw ? t.y : 0u) | (4 * q + 2 < nw ? t.z : 0u) |
-                       (4 * q + 3 < nw ? t.w : 0u);
-                mass |= (4 * q + 0 < nw ? u.x : 0u) | (4 * q + 1 < nw ? u.y : 0u) | (4 * q + 2 < nw ? u.z : 0u) |
-                        (4 * q + 3 < nw ? u.w : 0u);
-            }
-            anymass = (int)mass;
-            if (any) {
-                map.have = false;
-                return false;
+                const uint4 t = t4[q];
+                const uint32_t e[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (4 * q + i < nw) flags |= e[i];
+                    if (4 * q + i < wave) below += e[i] >> 2;
+                }
             }
         }
+        anymass = (int)(flags & 1u);
+        // a bin with more than BIN_MAX_KEYS keys anywhere in the unit: the caller sorts by the network instead
+        if (flags & 2u) {
+            map.have = false;
+            return false;
+        }
         // the counters are read once more (cheaper than carrying them in registers across the barrier)
-        uint32_t at = (inc - run + waves_below(wtot, wave));
+        uint32_t at = inc - run + below;
         auto step = [&](uint32_t c) -> uint32_t {
             const uint32_t s0 = at;
             at += c & 0xFFFFu;
@@ -604,13 +590,22 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
     double *lds = (double *)smem;
     const unsigned short *first = (const unsigned short *)hist;
     const bool unit_weights = !anymass && prm.nseg == 1;
+    if (!unit_weights) {
 #pragma unroll
-    for (int k = 0; k < NS; ++k) {
-        if (sm.has(k)) {
-            // (the clamp cannot bind when the counts are right; it keeps the store inside the row regardless)
-            const uint32_t pos = min((uint32_t)first[fbs[k] & 0xFFFFu] + (fbs[k] >> 16), (uint32_t)(m - 1));
-            const u64 kk = unit_weights ? unit_weight_key(key[k]) : key[k];
-            lds[swz(pos)] = __longlong_as_double((long long)kk);
+        for (int k = 0; k < NS; ++k) {
+            if (sm.has(k)) {
+                // (the clamp cannot bind when the counts are right; it keeps the store inside the row regardless)
+                const uint32_t pos = min((uint32_t)first[fbs[k] & 0xFFFFu] + (fbs[k] >> 16), (uint32_t)(m - 1));
+                lds[swz(pos)] = __longlong_as_double((long long)key[k]);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < NS; ++k) {
+            if (sm.has(k)) {
+                const uint32_t pos = min((uint32_t)first[fbs[k] & 0xFFFFu] + (fbs[k] >> 16), (uint32_t)(m - 1));
+                lds[swz(pos)] = __longlong_as_double((long long)unit_weight_key(key[k]));
+            }
         }
     }
     prefetch(3);
@@ -619,7 +614,14 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
     const int p0 = tid * EPT;
     const double pad = __longlong_as_double((long long)PAD_KEY);
     double v[EPT];
-    if (p0 < m) {
+    if (p0 + EPT <= m) {                 // a whole window: no tests per key
+        double *win = lds + swz((uint32_t)p0);
+#pragma unroll
+        for (int r = 0; r < EPT; ++r) v[r] = win[r];
+        sort16(v);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) win[r] = v[r];
+    } else if (p0 < m) {
         const double *src = lds + swz((uint32_t)p0);
 #pragma unroll
         for (int r = 0; r < EPT; ++r) v[r] = (p0 + r < m) ? src[r] : pad;
@@ -653,8 +655,22 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
         uint4 *hz = (uint4 *)(hist + tid * hstride);
         for (int q = 0; q < (bpt >> 3); ++q) hz[q] = make_uint4(0u, 0u, 0u, 0u);
     }
-    if (p0 + 8 < m) {
-        // upper half of this window (still in registers) with the lower half of the next one
+    if (p0 + EPT + 8 <= m) {
+        // upper half of this window (still in registers) with the lower half of the next one, all inside the unit
+        double *dst = lds + swz((uint32_t)p0);
+        double *dn = lds + swz((uint32_t)(p0 + EPT));
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            v[r] = v[8 + r];
+            v[8 + r] = dn[r];
+        }
+        merge8x8(v);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            dst[8 + r] = v[r];
+            dn[r] = v[8 + r];
+        }
+    } else if (p0 + 8 < m) {
         const double *nxt = lds + swz((uint32_t)(p0 + EPT));
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
@@ -819,7 +835,7 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
             map.lo = lo;
             map.scale = (float)COARSE_N / (hi - lo) * 0.99999904632568359375f;
         }
-        if (usable) sorted_ok = bucket_sort<NS, VEC>(smem, prm, key, tid, nth, m, map, anymass, prefetch);
+        if (usable) sorted_ok = bucket_sort<NS, VEC>(smem, prm, key, tid, nth, m, map, wave_mass, anymass, prefetch);
     } else {
         anymass = __syncthreads_or((int)mass);
     }
@@ -871,14 +887,19 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
         const u64 *mine = sorted + swz((uint32_t)(mine_ok ? tid * EPT : 0));
         double c = 0.0, q = 0.0, r2 = 0.0;
         float w0 = 0.0f;
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            const u64 el = (tid * EPT + e < m) ? mine[e] : NEUTRAL_KEY;
+        auto add_key = [&](u64 el, int e) {
             const double sv = (double)elem_s(el), wv = (double)elem_w(el);
             if (e == 0) w0 = elem_w(el);
             c += sv;
             q = fma(sv, wv, q);
             r2 = fma(sv * wv, wv, r2);     // second moment, for the row errors
+        };
+        if (tid * EPT + EPT <= m) {        // a whole chunk: no tests per key
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) add_key(mine[e], e);
+        } else {
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) add_key((tid * EPT + e < m) ? mine[e] : NEUTRAL_KEY, e);
         }
         if (mine_ok) {
             prm.L1[row * prm.n1 + tid] = make_double2(c, q);
@@ -2194,22 +2215,22 @@ skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n, bool so
     if ((int64_t)lds > ctx->lds_limit)
         SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "row length %d needs %zu bytes of LDS, device allows %d", prm.m, lds, ctx->lds_limit);
     // bucket path: the keys of one unit (seglen at most), two bytes per value bin, the coarse tables.
-    // As many bins per thread as the LDS holds (at most 32768 bins: a bin index takes 15 bits), and at least
-    // about 1.1 bins per key: with fewer, too many rows would find a bin of more than BIN_MAX_KEYS keys and
-    // sort twice.
+    // About 1.4 bins per key or more (at most 32768 bins: a bin index takes 15 bits): with fewer, too many rows
+    // would find a bin of more than BIN_MAX_KEYS keys and sort twice; with many more, clearing and scanning the
+    // counters costs more than the rare second sort.
     prm.bk_bpt = 0;
     {
         const size_t key_bytes = (((size_t)prm.seglen + prm.seglen / 16 + 1) * 8 + 15) & ~(size_t)15;
         const size_t base_lds = lds;
         int best_per_cu = 0;
-        for (int bpt = 32; bpt >= 8; bpt -= 8) {
+        for (int bpt = 8; bpt <= 32; bpt += 8) {
             // a thread's block of counters is bpt / 2 words; blocks of 8, 16 or 32 words get 4 spare words each,
             // so that 8 neighbouring threads' 16-byte accesses fall into different banks (24 words do already)
             const int pad = (bpt == 24) ? 0 : 4;
             const size_t hist_bytes = (size_t)(bpt / 2 + pad) * threads * 4;
             const size_t need = key_bytes + hist_bytes + BK_COARSE_BYTES + BK_MISC_BYTES;
             const long long bins = (long long)bpt * threads - COARSE_N - 16;
-            if (need + 1024 > (size_t)ctx->lds_limit || 10ll * prm.seglen > 9ll * bins || bpt * threads > 32768) continue;
+            if (need + 1024 > (size_t)ctx->lds_limit || 10ll * prm.seglen > 7ll * bins || bpt * threads > 32768) continue;
             // workgroups a compute unit holds with this choice (threads and LDS); more of them beats more bins
             const size_t total = need > base_lds ? need : base_lds;
             int per_cu = (int)((size_t)ctx->lds_limit / (total + 256));

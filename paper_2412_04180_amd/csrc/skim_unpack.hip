@@ -202,6 +202,123 @@ __global__ void __launch_bounds__(MV_THREADS) matvec_rows_kernel(const uint32_t 
     }
 }
 
+// The same product with float32 arithmetic, for a reader that is limited by the packed bytes it streams rather
+// than by float64 issue: y_i = sum_j c_ij * (alpha_j x_j), c_ij = f32(codebook_i[code_ij]), fused multiply-adds in
+// float32.  A workgroup takes MVF_ROWS rows; a lane owns 32 consecutive columns = B whole code words of every
+// row and forms alpha_j x_j once for all rows.  Per weight: one shift, one mask (the code, already scaled to a
+// byte offset), one LDS read of the codebook entry (row base in the instruction's offset field), one FMA.
+constexpr int MVF_THREADS = 256;
+constexpr int MVF_ROWS = 8;
+
+template <int B, int R>
+__device__ __forceinline__ float mvf_chunk(const uint32_t *__restrict__ rw, uint32_t w0, uint32_t wpr,
+                                           const float (*cbf)[16], const float (&xs)[32]) {
+    uint32_t wd[B + 1];
+#pragma unroll
+    for (int k = 0; k < B; ++k) wd[k] = (w0 + k < wpr) ? rw[w0 + k] : 0u;
+    wd[B] = 0u;
+    float acc0 = 0.0f, acc1 = 0.0f;
+    const char *base = (const char *)cbf[R];
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+        constexpr uint32_t mask4 = ((1u << B) - 1u) << 2;       // the code times 4: byte offset of a float
+        const int bit = e * B, wi = bit >> 5, sh = bit & 31;
+        // (code << 2) = bits [sh, sh + B) of the stream moved to bits [2, 2 + B)
+        uint32_t v = sh >= 2 ? (wd[wi] >> (sh - 2)) : (wd[wi] << (2 - sh));
+        if (sh + B > 32) v |= wd[wi + 1] << (34 - sh);
+        const float c = *(const float *)(base + (v & mask4));
+        if (e & 1) acc1 = fmaf(c, xs[e], acc1);
+        else acc0 = fmaf(c, xs[e], acc0);
+    }
+    return acc0 + acc1;
+}
+
+template <int R>
+__device__ __forceinline__ void mvf_rows(const uint32_t *codes, const RowPlace *places, long long m, uint32_t ch,
+                                         const float (*cbf)[16], const float (&xs)[32], float (&acc)[MVF_ROWS]) {
+    if constexpr (R < MVF_ROWS) {
+        const RowPlace pl = places[R];
+        const uint32_t *rw = codes + pl.word0;
+        const uint32_t wpr = (uint32_t)((m * pl.b + 31) / 32);
+        switch (pl.b) {
+            case 1: acc[R] += mvf_chunk<1, R>(rw, ch * 1u, wpr, cbf, xs); break;
+            case 2: acc[R] += mvf_chunk<2, R>(rw, ch * 2u, wpr, cbf, xs); break;
+            case 3: acc[R] += mvf_chunk<3, R>(rw, ch * 3u, wpr, cbf, xs); break;
+            case 4: acc[R] += mvf_chunk<4, R>(rw, ch * 4u, wpr, cbf, xs); break;
+            default: break;
+        }
+        mvf_rows<R + 1>(codes, places, m, ch, cbf, xs, acc);
+    }
+}
+
+template <bool ALIGNED>
+__global__ void __launch_bounds__(MVF_THREADS) matvec_f32_kernel(const uint32_t *codes, const long long *gwo,
+                                                                 const int *row_perm, const uint16_t *codebooks,
+                                                                 const float *alpha, long long n, long long m,
+                                                                 const float *x, float *y) {
+    __shared__ float cbf[MVF_ROWS][16];
+    __shared__ float red[MVF_ROWS][MVF_THREADS / 64];
+    __shared__ RowPlace places[MVF_ROWS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long long p0 = (long long)blockIdx.x * MVF_ROWS;
+    if (tid < MVF_ROWS) {
+        RowPlace pl{0, 0, 0};
+        if (p0 + tid < n) pl = place_row(gwo, m, p0 + tid);
+        places[tid] = pl;
+    }
+    __syncthreads();
+    if (tid < MVF_ROWS * 16) {
+        const int r = tid >> 4, k = tid & 15;
+        const RowPlace pl = places[r];
+        cbf[r][k] = (pl.b > 0 && k < (1 << pl.b)) ? __half2float(__ushort_as_half(codebooks[pl.cb0 + k])) : 0.0f;
+    }
+    __syncthreads();
+    float acc[MVF_ROWS];
+#pragma unroll
+    for (int r = 0; r < MVF_ROWS; ++r) acc[r] = 0.0f;
+    const uint32_t mm = (uint32_t)m;
+    const uint32_t nchunk = (mm + 31) >> 5;
+    for (uint32_t ch = tid; ch < nchunk; ch += MVF_THREADS) {
+        const uint32_t j0 = ch << 5;
+        float xs[32];                                  // alpha_j * x_j (columns past the row: 0)
+        if (ALIGNED && j0 + 32 <= mm) {
+            const float4 *x4 = (const float4 *)(x + j0);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const float4 v = x4[k];
+                xs[4 * k] = v.x; xs[4 * k + 1] = v.y; xs[4 * k + 2] = v.z; xs[4 * k + 3] = v.w;
+            }
+            if (alpha) {
+                const float4 *a4 = (const float4 *)(alpha + j0);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const float4 v = a4[k];
+                    xs[4 * k] *= v.x; xs[4 * k + 1] *= v.y; xs[4 * k + 2] *= v.z; xs[4 * k + 3] *= v.w;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 32; ++e) {
+                const bool in = j0 + e < mm;
+                xs[e] = in ? (alpha ? alpha[j0 + e] * x[j0 + e] : x[j0 + e]) : 0.0f;
+            }
+        }
+        mvf_rows<0>(codes, places, m, ch, cbf, xs, acc);
+    }
+#pragma unroll
+    for (int r = 0; r < MVF_ROWS; ++r) {
+        float a = acc[r];
+        for (int d = 32; d >= 1; d >>= 1) a += __shfl_down(a, d, 64);
+        if (lane == 0) red[r][wave] = a;
+    }
+    __syncthreads();
+    if (tid < MVF_ROWS && places[tid].b > 0) {
+        float s2 = 0.0f;
+        for (int w2 = 0; w2 < MVF_THREADS / 64; ++w2) s2 += red[tid][w2];
+        y[row_perm[p0 + tid]] = s2;
+    }
+}
+
 skim_status check_packed(skim_ctx *ctx, const void *codes, const void *gwo, const void *perm, const void *cbs, int64_t n,
                          int64_t m, const char *who) {
     if (!codes || !gwo || !perm || !cbs) SKIM_FAIL(ctx, SKIM_ERR_ARG, "%s: NULL argument", who);
@@ -242,6 +359,27 @@ extern "C" skim_status skim_dequant_matvec(skim_ctx *ctx, const uint32_t *codes,
         hipLaunchKernelGGL(packed_rows_kernel<true>, dim3((unsigned)n), dim3(UNPACK_THREADS), 0, ctx->stream, codes,
                            (const long long *)group_word_offset, row_perm, codebooks_fp16, alpha, (long long)m, x, y,
                            (float *)nullptr);
+    SKIM_HIP(ctx, hipGetLastError());
+    return SKIM_OK;
+}
+
+extern "C" skim_status skim_dequant_matvec_f32(skim_ctx *ctx, const uint32_t *codes, const int64_t *group_word_offset,
+                                               const int32_t *row_perm, const uint16_t *codebooks_fp16,
+                                               const float *alpha, int64_t n, int64_t m, const float *x, float *y) {
+    skim_status st = skim_enter(ctx);
+    if (st != SKIM_OK) return st;
+    if ((st = check_packed(ctx, codes, group_word_offset, row_perm, codebooks_fp16, n, m, "skim_dequant_matvec_f32")) != SKIM_OK)
+        return st;
+    if (!x || !y) SKIM_FAIL(ctx, SKIM_ERR_ARG, "skim_dequant_matvec_f32: x and y must not be NULL");
+    const dim3 grid((unsigned)((n + MVF_ROWS - 1) / MVF_ROWS));
+    if ((((uintptr_t)x | (uintptr_t)alpha) & 15) == 0)
+        hipLaunchKernelGGL(matvec_f32_kernel<true>, grid, dim3(MVF_THREADS), 0, ctx->stream, codes,
+                           (const long long *)group_word_offset, row_perm, codebooks_fp16, alpha, (long long)n,
+                           (long long)m, x, y);
+    else
+        hipLaunchKernelGGL(matvec_f32_kernel<false>, grid, dim3(MVF_THREADS), 0, ctx->stream, codes,
+                           (const long long *)group_word_offset, row_perm, codebooks_fp16, alpha, (long long)n,
+                           (long long)m, x, y);
     SKIM_HIP(ctx, hipGetLastError());
     return SKIM_OK;
 }

@@ -24,7 +24,7 @@ def lib():
 def declared_symbols():
     text = open(os.path.join(ROOT, "include", "skim.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(skim_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(skim_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(lib):

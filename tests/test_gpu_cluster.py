@@ -273,12 +273,18 @@ def test_unpack_and_dequant_matvec_match_oracle(ctx, gpu_lib, n, m, with_alpha):
     yref = oracle.dequant_matvec(*args, x, alpha=al)
     scale = np.abs(ref.astype(np.float64)) @ np.abs(x.astype(np.float64))
     assert np.all(np.abs(y.cpu().numpy() - yref) <= 1e-12 * scale)
+    # the float32 reader: same product, float32 fused multiply-adds in its own order
+    yf = ctx.dequant_matvec_f32(pk, m, dev(x), alpha=ald)
+    torch.cuda.synchronize()
+    assert np.all(np.abs(yf.cpu().numpy().astype(np.float64) - yref) <= 1e-5 * scale)
     # x at an address that is no multiple of 16: the kernel with 4-byte loads
     xo = torch.zeros(m + 1, dtype=torch.float32, device="cuda")
     xo[1:] = dev(x)
     y2 = ctx.dequant_matvec(pk, m, xo[1:], alpha=ald)
+    yf2 = ctx.dequant_matvec_f32(pk, m, xo[1:], alpha=ald)
     torch.cuda.synchronize()
     assert np.all(np.abs(y2.cpu().numpy() - yref) <= 1e-12 * scale)
+    assert np.all(np.abs(yf2.cpu().numpy().astype(np.float64) - yref) <= 1e-5 * scale)
 
 
 def _tables(rng, n, kind):
