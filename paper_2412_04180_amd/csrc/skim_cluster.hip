@@ -1114,11 +1114,10 @@ __device__ __forceinline__ double quick_div(double n, double d) {
 
 // RAGGED: the row length is not a multiple of 16, so the last chunk holds fewer than 16 keys.
 template <bool RAGGED>
-__global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams prm, long long nrows) {
+__global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams prm, long long nrows, LevelMap LM) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int m = prm.m;
-    const int n1u = (m + 15) >> 4;
-    const LevelMap LM = level_map(n1u);
+    const int n1u = (m + 15) >> 4;   // LM = level_map(n1u), worked out by the host
     const int lane = threadIdx.x;
     const int h = lane >> 5, l5 = lane & 31;
 
@@ -2278,12 +2277,13 @@ skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n, bool so
         return SKIM_OK;
     }
     if (ctx->profiling) SKIM_HIP(ctx, hipEventRecord(ctx->ev[1], ctx->stream));
+    const LevelMap lm = level_map((prm.m + 15) >> 4);
     if (prm.m & 15)
         hipLaunchKernelGGL(lloyd_iter_kernel<true>, dim3((unsigned)((n + 1) / 2)), dim3(ITER_THREADS),
-                           lloyd_lds_bytes(prm.m), ctx->stream, prm, (long long)n);
+                           lloyd_lds_bytes(prm.m), ctx->stream, prm, (long long)n, lm);
     else
         hipLaunchKernelGGL(lloyd_iter_kernel<false>, dim3((unsigned)((n + 1) / 2)), dim3(ITER_THREADS),
-                           lloyd_lds_bytes(prm.m), ctx->stream, prm, (long long)n);
+                           lloyd_lds_bytes(prm.m), ctx->stream, prm, (long long)n, lm);
     hipLaunchKernelGGL(finish_kernel, dim3((unsigned)n), dim3(FIN_THREADS), 0, ctx->stream, prm);
     if (ctx->profiling) {
         SKIM_HIP(ctx, hipEventRecord(ctx->ev[2], ctx->stream));
