@@ -218,11 +218,10 @@ extern "C" skim_status skim_greedy_allocate_device(skim_ctx *ctx, const double *
         SKIM_FAIL(ctx, SKIM_ERR_WORKSPACE, "workspace missing or smaller than skim_workspace_bytes(n, m)");
     const size_t key_bytes = (size_t)n * (nb > 1 ? nb - 1 : 1) * sizeof(u64);
     const int keys_in_lds = key_bytes <= GA_LDS_KEYS;
-    static bool lds_enabled = false;
-    if (keys_in_lds && !lds_enabled) {
+    if (keys_in_lds && !ctx->greedy_lds_enabled) {
         SKIM_HIP(ctx, hipFuncSetAttribute((const void *)greedy_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                           (int)GA_LDS_KEYS));
-        lds_enabled = true;
+        ctx->greedy_lds_enabled = 1;
     }
     hipLaunchKernelGGL(greedy_select_kernel, dim3(1), dim3(GA_THREADS), keys_in_lds ? key_bytes : 0, ctx->stream, E,
                        (long long)n, bmin, nb, (long long)(B - (int64_t)bmin * n), (u64 *)ctx->ws, bits, (long long *)info,

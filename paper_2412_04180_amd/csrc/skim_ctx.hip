@@ -58,6 +58,8 @@ extern "C" skim_status skim_create(skim_ctx **out, int device, void *hip_stream)
     for (int i = 0; i < 3; ++i) c->ev[i] = nullptr;
     c->err[0] = 0;
     for (int i = 0; i < 4; ++i) c->sort_lds_enabled[i] = 0;
+    c->greedy_lds_enabled = 0;
+    c->xtx_lds_enabled = 0;
     c->validate = 0;
     c->pack_scratch = nullptr;
     if (skim_pack_static_setup(c) != SKIM_OK) {

@@ -151,10 +151,9 @@ extern "C" skim_status skim_hessian_from_activations(skim_ctx *ctx, const uint16
     if (N < 1 || m < 2 || (m & 1) || m > 0x7fffffff || ((uintptr_t)X_bf16 & 3))
         SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "skim_hessian_from_activations: need N >= 1, m even, X 4-byte aligned (N=%lld m=%lld)",
                   (long long)N, (long long)m);
-    static bool lds_enabled = false;
-    if (!lds_enabled) {
+    if (!ctx->xtx_lds_enabled) {
         SKIM_HIP(ctx, hipFuncSetAttribute((const void *)xtx_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)H_LDS_BYTES));
-        lds_enabled = true;
+        ctx->xtx_lds_enabled = 1;
     }
     const unsigned nt = (unsigned)((m + HT - 1) / HT);
     const int vec = (m % 8 == 0) && (((uintptr_t)X_bf16 & 15) == 0);     // rows of X start 16-byte aligned
