@@ -1045,45 +1045,84 @@ __global__ void __launch_bounds__(MG_THREADS) merge_tile_kernel(ClusterParams pr
 // Kernel 2: Lloyd iterations.
 // ---------------------------------------------------------------------------------------------
 
-// Sums above the 16-key chunks form a radix-4 tree: level 0 = chunk sums (global memory),
-// level l = sums of 4 entries of level l-1, up to a single root.  A workgroup keeps, per row, the
-// levels >= 1, the first weight of every chunk and the running sum of s ahead of every level-1
-// group in LDS.
+// Sums over whole 16-key chunks.  Level 0 = chunk sums (global memory, written by the sort); level 1 = groups of
+// 4 chunks (64 keys).  For sum s and sum s*w a workgroup keeps, per row, the running sums ahead of every group in
+// LDS as double-double numbers (an unevaluated pair hi + lo, about 106 bits): the sum over a range of groups is the
+// difference of two of them, exact to about 2^-104 of the row total, so a cluster of tiny mass next to a heavy
+// element keeps full relative precision (a difference of plain float64 running sums would not).  The second
+// moments (sum s*w*w), needed once at the end, form a radix-4 tree: level 1 in global memory, levels >= 2 in LDS.
 struct LevelMap {
-    int nlev;        // levels 0 .. nlev-1
+    int nlev;        // levels 0 .. nlev-1 of the second-moment tree
     int n[8];        // entries per level
-    int off[8];      // byte offset of level >= 1 inside the row's LDS block
-    int roff[8];     // byte offset of the second-moment sums of level >= 1 (one double per entry)
-    int w16_off, pre_off, zero_off, bytes;   // zero_off: an entry (0, 0) for the slots a lane does not need
+    int roff[8];     // byte offset of the second-moment sums of level >= 2 inside the row's LDS block
+    int w16_off, ppd_off, ppn_off, bytes;   // first weights; running sums of s and of s*w (n[1] + 1 double2 each)
 };
 __host__ __device__ inline LevelMap level_map(int n1u) {
     LevelMap L;
     L.w16_off = 0;
     int o = (n1u * 4 + 15) & ~15;
     L.n[0] = n1u;
-    L.off[0] = 0;
     int lv = 0, n = n1u;
     do {
         n = (n + 3) >> 2;
         ++lv;
         L.n[lv] = n;
-        L.off[lv] = o;
-        o += n * 16;
     } while (n > 1);
-    for (int k = lv + 1; k < 8; ++k) { L.n[k] = 0; L.off[k] = 0; }
+    for (int k = lv + 1; k < 8; ++k) L.n[k] = 0;
     L.nlev = lv + 1;
+    L.ppd_off = o;
+    o += (L.n[1] + 1) * 16;
+    L.ppn_off = o;
+    o += (L.n[1] + 1) * 16;
     L.roff[0] = 0;
-    for (int k = 1; k < 8; ++k) {
+    L.roff[1] = 0;
+    for (int k = 2; k < 8; ++k) {
         L.roff[k] = o;
         o += ((L.n[k] * 8) + 15) & ~15;
     }
-    L.pre_off = o;
-    o += (L.n[1] + 1) * 8;
-    o = (o + 15) & ~15;
-    L.zero_off = o;
-    o += 16;
     L.bytes = o;
     return L;
+}
+
+// Double-double arithmetic on (hi, lo) pairs held in a double2 (x = hi, y = lo).
+__device__ __forceinline__ double2 dd_add(double2 a, double2 b) {
+    const double s = a.x + b.x;
+    const double bb = s - a.x;
+    double e = (a.x - (s - bb)) + (b.x - bb);     // a.x + b.x = s + e exactly
+    e += a.y + b.y;
+    const double h = s + e;
+    return make_double2(h, e - (h - s));
+}
+// b - a rounded to one double
+__device__ __forceinline__ double dd_diff(double2 b, double2 a) {
+    const double s = b.x - a.x;
+    const double bb = s - b.x;
+    const double e = (b.x - (s - bb)) + (-a.x - bb);   // b.x - a.x = s + e exactly
+    return s + (e + (b.y - a.y));
+}
+// x of the lane selected by a DPP control word in the lanes of the enabled rows, 0 elsewhere and where the
+// pattern has no source lane
+template <int CTRL, int ROWS>
+__device__ __forceinline__ double dpp_or_zero(double x) {
+    const long long b = __double_as_longlong(x);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)b, CTRL, ROWS, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, ROWS, 0xF, false);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+template <int CTRL, int ROWS>
+__device__ __forceinline__ double2 dd_scan_step(double2 x) {
+    const double2 t = make_double2(dpp_or_zero<CTRL, ROWS>(x.x), dpp_or_zero<CTRL, ROWS>(x.y));
+    return dd_add(x, t);
+}
+// inclusive double-double prefix sum over the 64 lanes (the pattern of wave_scan_incl)
+__device__ __forceinline__ double2 dd_wave_scan_incl(double2 x) {
+    x = dd_scan_step<0x111, 0xF>(x);
+    x = dd_scan_step<0x112, 0xF>(x);
+    x = dd_scan_step<0x114, 0xF>(x);
+    x = dd_scan_step<0x118, 0xF>(x);
+    x = dd_scan_step<0x142, 0xA>(x);
+    x = dd_scan_step<0x143, 0xC>(x);
+    return x;
 }
 
 constexpr int ITER_THREADS = 64;   // one wavefront serves two rows
@@ -1095,9 +1134,8 @@ constexpr int MAX_LEVELS = 8;
 // holds it, by a search over the chunks' first weights in LDS, then the rank inside that chunk
 // from its 16 keys (one round of global loads) -- and adds up its range from: the keys of its own
 // boundary chunk, the lower part of the next cluster's boundary chunk (handed over by that lane),
-// and the whole chunks in between as aligned pieces of the radix-4 tree.  Nothing outside the
-// range enters a sum, so a cluster of tiny weight mass next to a heavy element keeps full
-// relative precision (a difference of running prefix sums would not).
+// and the whole chunks in between: up to 3 chunk sums at either end (global memory) and the whole groups
+// of 4 chunks as a difference of two double-double running sums (LDS).
 typedef u64 u64x2 __attribute__((ext_vector_type(2)));
 typedef u64x2 __attribute__((aligned(8))) u64x2_a8;
 
@@ -1121,9 +1159,9 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
     const int lane = threadIdx.x;
     const int h = lane >> 5, l5 = lane & 31;
 
-    // ---- prologue: both rows' trees, first weights and running sums into LDS -------------------
-    // (all global loads of a batch are in flight together; level 1 comes ready-made from the sort)
+    // ---- prologue: both rows' first weights, running sums and second-moment levels into LDS -------
     const int nhalf = (2ll * blockIdx.x + 1 < nrows) ? 2 : 1;
+    const int ng = LM.n[1];
     for (int hh = 0; hh < nhalf; ++hh) {
         const long long rr = 2ll * blockIdx.x + hh;
         unsigned char *blkw = smem + (size_t)hh * LM.bytes;
@@ -1142,46 +1180,66 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
                 if (j < n1u) w16w[j] = t8[u];
             }
         }
-        const double2 *gq = prm.Q + rr * prm.nq;
-        double2 *l1 = (double2 *)(blkw + LM.off[1]);
-        for (int q0 = 0; q0 < LM.n[1]; q0 += 4 * ITER_THREADS) {
-            double2 t4[4];
+        // running sums ahead of every group of 4 chunks, pp[ng] = row total.  A lane takes `per` consecutive
+        // groups; one double-double scan over the lanes per quantity.
+        {
+            const double2 *gq = prm.Q + rr * prm.nq;
+            double2 *ppd = (double2 *)(blkw + LM.ppd_off), *ppn = (double2 *)(blkw + LM.ppn_off);
+            const int per = (ng + ITER_THREADS - 1) / ITER_THREADS;     // at most 8 (rows of up to 32768 keys)
+            double2 qv[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int q = q0 + u * ITER_THREADS + lane;
-                t4[u] = (q < LM.n[1]) ? gq[q] : make_double2(0.0, 0.0);
+            for (int k = 0; k < 8; ++k) {
+                const int q = lane * per + k;
+                qv[k] = (k < per && q < ng) ? gq[q] : make_double2(0.0, 0.0);
+            }
+            double2 md = make_double2(0.0, 0.0), mn = make_double2(0.0, 0.0);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                md = dd_add(md, make_double2(qv[k].x, 0.0));
+                mn = dd_add(mn, make_double2(qv[k].y, 0.0));
+            }
+            const double2 id = dd_wave_scan_incl(md), in = dd_wave_scan_incl(mn);
+            // sums of the lanes below: the inclusive sums shifted up by one lane
+            double2 rd = make_double2(lane_below(id.x), lane_below(id.y));
+            double2 rn = make_double2(lane_below(in.x), lane_below(in.y));
+            if (lane == 0) {
+                rd = make_double2(0.0, 0.0);
+                rn = make_double2(0.0, 0.0);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int q = q0 + u * ITER_THREADS + lane;
-                if (q < LM.n[1]) l1[q] = t4[u];
+            for (int k = 0; k < 8; ++k) {
+                const int q = lane * per + k;
+                if (k < per && q < ng) {
+                    ppd[q] = rd;
+                    ppn[q] = rn;
+                    rd = dd_add(rd, make_double2(qv[k].x, 0.0));
+                    rn = dd_add(rn, make_double2(qv[k].y, 0.0));
+                    if (q == ng - 1) {
+                        ppd[ng] = rd;
+                        ppn[ng] = rn;
+                    }
+                }
             }
         }
-        const double *grq = prm.RQ + rr * prm.nq;
-        double *r1 = (double *)(blkw + LM.roff[1]);
-        for (int q = lane; q < LM.n[1]; q += ITER_THREADS) r1[q] = grq[q];
-        if (lane == 0) *(double2 *)(blkw + LM.zero_off) = make_double2(0.0, 0.0);
+        // second moments: level 2 from the groups' sums in global memory
+        if (LM.nlev > 2) {
+            const double *grq = prm.RQ + rr * prm.nq;
+            double *r2 = (double *)(blkw + LM.roff[2]);
+            for (int q = lane; q < LM.n[2]; q += ITER_THREADS) {
+                double acc = 0.0;
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (4 * q + k < ng) acc += grq[4 * q + k];
+                r2[q] = acc;
+            }
+        }
     }
     __syncthreads();
 #pragma unroll
-    for (int lv = 2; lv < MAX_LEVELS; ++lv) {
+    for (int lv = 3; lv < MAX_LEVELS; ++lv) {
         if (lv < LM.nlev) {
             for (int hh = 0; hh < nhalf; ++hh) {
                 unsigned char *blkw = smem + (size_t)hh * LM.bytes;
-                const double2 *src = (const double2 *)(blkw + LM.off[lv - 1]);
-                double2 *dst = (double2 *)(blkw + LM.off[lv]);
-                for (int q = lane; q < LM.n[lv]; q += ITER_THREADS) {
-                    double d = 0.0, nn = 0.0;
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        if (4 * q + k < LM.n[lv - 1]) {
-                            const double2 x = src[4 * q + k];
-                            d += x.x;
-                            nn += x.y;
-                        }
-                    }
-                    dst[q] = make_double2(d, nn);
-                }
                 const double *rsrc = (const double *)(blkw + LM.roff[lv - 1]);
                 double *rdst = (double *)(blkw + LM.roff[lv]);
                 for (int q = lane; q < LM.n[lv]; q += ITER_THREADS) {
@@ -1195,36 +1253,6 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
             __syncthreads();
         }
     }
-    {   // running sum of s ahead of each level-1 group (64 keys); pre[n[1]] = total.  A lane takes
-        // `per` consecutive groups; one scan over the lanes per row.
-        const int ng = LM.n[1];
-        const int per = (ng + ITER_THREADS - 1) / ITER_THREADS;
-        for (int hh = 0; hh < nhalf; ++hh) {
-            unsigned char *blkw = smem + (size_t)hh * LM.bytes;
-            const double2 *l1 = (const double2 *)(blkw + LM.off[1]);
-            double *prew = (double *)(blkw + LM.pre_off);
-            double mine = 0.0;
-            for (int k = 0; k < per; ++k) {
-                const int q = lane * per + k;
-                if (q < ng) mine += l1[q].x;
-            }
-            double inc = mine;
-            for (int d = 1; d < 64; d <<= 1) {
-                const double u = __shfl_up(inc, d, 64);
-                if (lane >= d) inc += u;
-            }
-            double run = inc - mine;
-            for (int k = 0; k < per; ++k) {
-                const int q = lane * per + k;
-                if (q < ng) {
-                    prew[q] = run;
-                    run += l1[q].x;
-                }
-            }
-            if (lane == 63) prew[ng] = inc;
-        }
-    }
-    __syncthreads();
 
     // ---- lane -> (row, bit width, position) ------------------------------------------------------
     const long long row = 2ll * blockIdx.x + h;
@@ -1245,28 +1273,27 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
 
     const unsigned char *blk = smem + (size_t)h * LM.bytes;
     const float *w16 = (const float *)(blk + LM.w16_off);
-    const double *pre = (const double *)(blk + LM.pre_off);
+    const double2 *ppd = (const double2 *)(blk + LM.ppd_off), *ppn = (const double2 *)(blk + LM.ppn_off);
     const u64 *__restrict__ keys = prm.keys + rowc * (long long)m;
     const double2 *__restrict__ L1 = prm.L1 + rowc * prm.n1;
 
     // ---- weighted-quantile start with strictly increasing ranks ---------------------------------
     int r = 0;
     {
-        const int ng = LM.n[1];
-        const double total = pre[ng];
+        const double total = ppd[ng].x;
         const double tau = total * (double)(2 * p + 1) / (double)(2 * K);
         // largest group g with pre[g] < tau (pre[0] = 0 < tau)
         int lo = 0, hi = on ? ng - 1 : 0;
         while (__ballot(lo < hi)) {
             const int mid = (lo + hi + 1) >> 1;
-            const double x = pre[min(mid, ng)];
+            const double x = ppd[min(mid, ng)].x;
             if (lo < hi) {
                 if (x < tau) lo = mid; else hi = mid - 1;
             }
         }
         // chunk inside the group: largest chunk whose running sum ahead of it is < tau
         int chunk = 4 * lo;
-        double acc = pre[lo];
+        double acc = ppd[lo].x;
         if (on) {
             double dch[3];
 #pragma unroll
@@ -1314,8 +1341,6 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
     double v = on ? (double)elem_w(keys[r]) : 0.0;
     int idx = p;
     int Bcur = 0, Bold = -1, idxold = -1, cold = 0;
-    int ca3 = -1, cb3 = -1;          // range at the 1024-key level whose sums cD3, cN3 hold
-    double cD3 = 0.0, cN3 = 0.0;
     double Dk = 0.0, Nk = 0.0;       // sums of this lane's cluster under the last assignment it took part in
     bool emptyk = false;             // ... in which it owned nothing (its value repeated the one below)
     bool done = !on;
@@ -1538,56 +1563,18 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
         if (p == K - 1 || cl_next <= cl) { nD = 0.0; nN = 0.0; }
         D += nD;
         N += nN;
-        // level-0 pieces, then the levels in LDS
+        // level-0 pieces, then the whole groups of 4 chunks in between from the running sums in LDS
 #pragma unroll
         for (int k = 0; k < 6; ++k) {
             D += pc[k].x;
             N += pc[k].y;
         }
-        int a = la0 >> 2, bq = rb0 >> 2;
-        if (la0 >= rb0) { a = 0; bq = 0; }
-        // one level of the tree: up to 3 entries at either end of [a, bq), then the range one level up
-        auto level_step = [&](int off, int &ra, int &rb_, double &sd, double &sn) {
-            const int la = min(rb_, (ra + 3) & ~3), rb = max(la, rb_ & ~3);
-#pragma unroll
-            for (int k2 = 0; k2 < 3; ++k2) {
-                // a slot that is not needed reads the zero entry instead
-                const int o1 = (ra + k2 < la) ? off + (ra + k2) * 16 : LM.zero_off;
-                const int o2 = (rb + k2 < rb_) ? off + (rb + k2) * 16 : LM.zero_off;
-                const double2 x1 = *(const double2 *)(blk + o1);
-                const double2 x2 = *(const double2 *)(blk + o2);
-                sd += x1.x;
-                sn += x1.y;
-                sd += x2.x;
-                sn += x2.y;
-            }
-            if (la < rb) { ra = la >> 2; rb_ = rb >> 2; } else { ra = 0; rb_ = 0; }
-        };
-#pragma unroll
-        for (int lv = 1; lv < 3; ++lv) {
-            if (lv < LM.nlev && __ballot(a < bq) != 0) level_step(LM.off[lv], a, bq, D, N);
-        }
-        if (LM.nlev > 3) {
-            // levels from 1024 keys up change rarely from one iteration to the next: their part of
-            // the sum is kept per lane together with the range it belongs to
-            const bool need = a < bq;
-            const bool miss = need && (a != ca3 || bq != cb3);
-            if (__ballot(miss) != 0) {
-                double tD = 0.0, tN = 0.0;
-                int a3 = a, b3 = bq;
-#pragma unroll
-                for (int lv = 3; lv < MAX_LEVELS; ++lv) {
-                    if (lv < LM.nlev && __ballot(a3 < b3) != 0) level_step(LM.off[lv], a3, b3, tD, tN);
-                }
-                ca3 = a;
-                cb3 = bq;
-                cD3 = tD;
-                cN3 = tN;
-            }
-            if (need) {
-                D += cD3;
-                N += cN3;
-            }
+        {
+            int ga = la0 >> 2, gb = rb0 >> 2;
+            if (la0 >= rb0) { ga = 0; gb = 0; }
+            const double2 da = ppd[ga], db = ppd[gb], na = ppn[ga], nb = ppn[gb];
+            D += dd_diff(db, da);
+            N += dd_diff(nb, na);
         }
         if (summing) {
             Dk = D;
@@ -1645,7 +1632,7 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
 #pragma unroll
         for (int lv = 1; lv < MAX_LEVELS; ++lv) {
             if (lv < LM.nlev && __ballot(ra < rb) != 0) {
-                const double *L = (const double *)(blk + LM.roff[lv]);
+                const double *L = (lv == 1) ? prm.RQ + rowc * prm.nq : (const double *)(blk + LM.roff[lv]);
                 const int la = min(rb, (ra + 3) & ~3), rbb = max(la, rb & ~3);
 #pragma unroll
                 for (int k = 0; k < 3; ++k) {
