@@ -3,7 +3,7 @@
 // stored in lower precision).  Two kernels: a one-workgroup plan that orders the
 // rows by (bits, row index) and lays out the groups, and a row kernel that
 // rebuilds each label from the cluster thresholds and emits the bit stream
-// (32 columns = b whole words per thread, assembled in registers).
+// (32 columns = b whole words per four lanes, assembled in registers).
 #include "skim_common.h"
 
 #include <hip/hip_fp16.h>
@@ -16,6 +16,9 @@ namespace {
 constexpr int SKIM_PACK_STATIC_MAX_DEVICES = 64;
 constexpr int PLAN_THREADS = 1024;
 constexpr int PACK_THREADS = 256;
+constexpr int PACK_UNROLL = 1;   // groups of 32 columns a quad of lanes has in flight at a time; more of them cost
+                                 // registers, and resident wavefronts hide the load latency better (measured: 48, 57,
+                                 // 67 us per call on 4096 x 11008 with 1, 2, 3)
 
 struct PackPlan {         // lives in the workspace
     long long row_start[6];   // first packed position of the b-bit group
@@ -90,84 +93,141 @@ __global__ void __launch_bounds__(PLAN_THREADS) pack_plan_kernel(long long n, lo
     }
 }
 
-// One workgroup per row.  A thread takes 32 consecutive columns at a time: their B-bit labels fill
-// exactly B words, assembled in registers and stored without staging (no LDS traffic, no barriers
-// inside the row).  ALPHA / DW: the call scales the columns / wants the residual; a group that lies
-// wholly inside the row (all but the last one) takes the path without per-column bounds.
-template <int B, bool ALPHA, bool DW>
-__device__ __forceinline__ void pack_row_body(const float *__restrict__ Wr, const float *__restrict__ alpha, uint32_t m,
-                                              const float *thr, const int *thl, const float *cbf,
-                                              uint32_t *__restrict__ out_words, uint32_t wpr, float *__restrict__ dWr) {
+// One workgroup per row.  Four neighbouring lanes take 32 consecutive columns, 8 each (two 16-byte loads per
+// lane, a quad reads one 128-byte line): the B-bit labels of the 32 columns fill exactly B words.  A lane packs
+// its 8 labels into 8 B bits and shifts them to their place in the B words; the four lanes OR their words
+// together (DPP inside the quad) and lanes 0 .. B-1 of the quad store one word each, so a wavefront's stores are
+// consecutive words.
+// Label of a weight = cluster at position (number of the row's sorted cluster bounds below the weight).  The
+// bounds are the same for the whole workgroup: they are read once into scalar registers and every weight is
+// compared against them there (no dependent LDS lookups per weight); for 16 clusters, three scalar bounds pick a
+// quarter and one 16-byte LDS read brings that quarter's bounds.  ident: positions and cluster indices coincide
+// (centroids ascending in the cluster index, the usual case), so no position -> cluster lookup is needed.
+// A lane works on PACK_UNROLL groups at a time (a "round": all their loads are in flight together); the loads of
+// the first round are issued by the kernel before it sorts the bounds.  ALPHA / DW: the call scales the columns / wants the residual.
+struct PackRound {
+    float w[PACK_UNROLL][8], a[PACK_UNROLL][8];
+};
+
+template <bool ALPHA>
+__device__ __forceinline__ void pack_load_round(PackRound &r, const float *__restrict__ Wr, const float *__restrict__ alpha,
+                                                uint32_t m, uint32_t g0, bool vec_ok) {
     const uint32_t ngroups = (m + 31u) >> 5;
-    const bool vec_ok = ((((uintptr_t)Wr) | (ALPHA ? (uintptr_t)alpha : 0) | (DW ? (uintptr_t)dWr : 0)) & 15) == 0;
-    for (uint32_t g = threadIdx.x; g < ngroups; g += PACK_THREADS) {
-        const uint32_t j0 = g << 5;
-        const uint32_t valid = min(32u, m - j0);
-        const bool full = valid == 32u && vec_ok;
-        float w[32], a[32];
-        if (full) {
+    const uint32_t t = threadIdx.x & 3u;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
+    for (int u = 0; u < PACK_UNROLL; ++u) {
+        const uint32_t g = g0 + u * (PACK_THREADS / 4);
+        const uint32_t j0 = (g << 5) + 8u * t;
+        if (g >= ngroups) continue;
+        if (vec_ok && j0 + 8u <= m) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
                 const float4 v = *(const float4 *)(Wr + j0 + 4 * q);
-                w[4 * q] = v.x; w[4 * q + 1] = v.y; w[4 * q + 2] = v.z; w[4 * q + 3] = v.w;
+                r.w[u][4 * q] = v.x; r.w[u][4 * q + 1] = v.y; r.w[u][4 * q + 2] = v.z; r.w[u][4 * q + 3] = v.w;
                 if (ALPHA) {
-                    const float4 u = *(const float4 *)(alpha + j0 + 4 * q);
-                    a[4 * q] = u.x; a[4 * q + 1] = u.y; a[4 * q + 2] = u.z; a[4 * q + 3] = u.w;
+                    const float4 x = *(const float4 *)(alpha + j0 + 4 * q);
+                    r.a[u][4 * q] = x.x; r.a[u][4 * q + 1] = x.y; r.a[u][4 * q + 2] = x.z; r.a[u][4 * q + 3] = x.w;
                 }
             }
         } else {
 #pragma unroll
-            for (int jj = 0; jj < 32; ++jj) {
-                w[jj] = ((uint32_t)jj < valid) ? Wr[j0 + jj] : 0.0f;
-                if (ALPHA) a[jj] = ((uint32_t)jj < valid) ? alpha[j0 + jj] : 1.0f;
+            for (int i = 0; i < 8; ++i) {
+                r.w[u][i] = (j0 + i < m) ? Wr[j0 + i] : 0.0f;
+                if (ALPHA) r.a[u][i] = (j0 + i < m) ? alpha[j0 + i] : 1.0f;
             }
         }
-        uint32_t words[B + 1];
+    }
+}
+
+// cur: the first round, already loaded (pack_load_round at g0 = threadIdx.x / 4)
+template <int B, bool ALPHA, bool DW>
+__device__ __forceinline__ void pack_row_body(PackRound &cur, const float *__restrict__ Wr, const float *__restrict__ alpha,
+                                              uint32_t m, bool vec_ok, const float *thr, const int *thl, const float *cbf,
+                                              uint32_t *__restrict__ out_words, uint32_t wpr, float *__restrict__ dWr) {
+    constexpr int K = 1 << B;
+    constexpr int NSC = (B == 4) ? 3 : K - 1;      // bounds held in scalar registers
+    float ts[NSC];
 #pragma unroll
-        for (int k = 0; k <= B; ++k) words[k] = 0u;
-        float dq[32];
+    for (int k = 0; k < NSC; ++k) {
+        const float x = (B == 4) ? thr[4 * k + 3] : thr[k];
+        ts[k] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x)));
+    }
+    int same = 1;
 #pragma unroll
-        for (int jj = 0; jj < 32; ++jj) {
-            const float wt = ALPHA ? __fdiv_rn(w[jj], a[jj]) : w[jj];
-            // first position whose bound is >= wt (binary search over the sorted bounds, +inf beyond the 2^B-th)
-            int pos = 0;
-            if (B >= 4) pos = (thr[7] < wt) ? 8 : 0;
-            if (B >= 3) pos += (thr[pos + 3] < wt) ? 4 : 0;
-            if (B >= 2) pos += (thr[pos + 1] < wt) ? 2 : 0;
-            pos += (thr[pos] < wt) ? 1 : 0;
-            uint32_t l = (uint32_t)thl[pos];
-            if (DW) dq[jj] = __fmaf_rn(ALPHA ? -a[jj] : -1.0f, cbf[l], w[jj]);
-            if (!full) l = ((uint32_t)jj < valid) ? l : 0u;            // padding bits stay zero
-            const int bit = jj * B, wi = bit >> 5, sh = bit & 31;
-            words[wi] |= l << sh;
-            if (sh + B > 32) words[wi + 1] |= l >> (32 - sh);
-        }
+    for (int k = 0; k < K; ++k) same &= (thl[k] == k) ? 1 : 0;
+    const bool ident = __builtin_amdgcn_readfirstlane(same) != 0;
+
+    const uint32_t ngroups = (m + 31u) >> 5;
+    const uint32_t t = threadIdx.x & 3u;
+    // place of this lane's 8 B bits inside the B words of its group
+    const uint32_t o = 8u * B * t, wi = o >> 5, sh = o & 31u;
+    constexpr uint32_t GSTEP = PACK_THREADS / 4, RSTEP = PACK_UNROLL * GSTEP;
+    for (uint32_t g0 = threadIdx.x >> 2; g0 < ngroups; g0 += RSTEP) {
+        if (g0 != (threadIdx.x >> 2)) pack_load_round<ALPHA>(cur, Wr, alpha, m, g0, vec_ok);
 #pragma unroll
-        for (int k = 0; k < B; ++k)
-            if (g * B + k < wpr) out_words[g * B + k] = words[k];
-        if (DW) {
-            if (full) {
+        for (int u = 0; u < PACK_UNROLL; ++u) {
+            const uint32_t g = g0 + u * GSTEP;
+            const uint32_t j0 = (g << 5) + 8u * t;
+            if (g >= ngroups) continue;          // (the same for the four lanes of a quad)
+            const bool full = vec_ok && j0 + 8u <= m;
+            uint32_t p = 0u;
+            float dq[8];
 #pragma unroll
-                for (int q = 0; q < 8; ++q)
-                    *(float4 *)(dWr + j0 + 4 * q) = make_float4(dq[4 * q], dq[4 * q + 1], dq[4 * q + 2], dq[4 * q + 3]);
-            } else {
+            for (int i = 0; i < 8; ++i) {
+                const float wt = ALPHA ? __fdiv_rn(cur.w[u][i], cur.a[u][i]) : cur.w[u][i];
+                // first position whose bound is >= wt = number of bounds below wt (bounds ascending, +inf beyond the 2^B-th)
+                uint32_t pos = 0u;
+                if (B == 4) {
+                    uint32_t q = 0u;
 #pragma unroll
-                for (int jj = 0; jj < 32; ++jj)
-                    if ((uint32_t)jj < valid) dWr[j0 + jj] = dq[jj];
+                    for (int k = 0; k < 3; ++k) q += (ts[k] < wt) ? 1u : 0u;
+                    const float4 t4 = *(const float4 *)(thr + 4u * q);
+                    pos = 4u * q + ((t4.x < wt) ? 1u : 0u) + ((t4.y < wt) ? 1u : 0u) + ((t4.z < wt) ? 1u : 0u);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < NSC; ++k) pos += (ts[k] < wt) ? 1u : 0u;
+                }
+                uint32_t l = ident ? pos : (uint32_t)thl[pos];
+                if (DW) dq[i] = __fmaf_rn(ALPHA ? -cur.a[u][i] : -1.0f, cbf[l], cur.w[u][i]);
+                if (!full) l = (j0 + i < m) ? l : 0u;            // padding bits stay zero
+                p |= l << (i * B);
+            }
+            const uint32_t lowpart = p << sh;
+            const uint32_t highpart = sh ? (p >> (32u - sh)) : 0u;      // zero unless the 8 B bits cross a word
+            uint32_t mine = 0u;
+#pragma unroll
+            for (int k = 0; k < B; ++k) {
+                uint32_t c = ((wi == (uint32_t)k) ? lowpart : 0u) | ((wi + 1u == (uint32_t)k) ? highpart : 0u);
+                c |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)c, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+                c |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)c, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+                if (t == (uint32_t)k) mine = c;
+            }
+            if (t < (uint32_t)B && g * B + t < wpr) out_words[g * B + t] = mine;
+            if (DW) {
+                if (full) {
+#pragma unroll
+                    for (int q = 0; q < 2; ++q)
+                        *(float4 *)(dWr + j0 + 4 * q) = make_float4(dq[4 * q], dq[4 * q + 1], dq[4 * q + 2], dq[4 * q + 3]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        if (j0 + i < m) dWr[j0 + i] = dq[i];
+                }
             }
         }
     }
 }
 
 template <int B>
-__device__ __forceinline__ void pack_row_dispatch(const float *Wr, const float *alpha, uint32_t m, const float *thr,
-                                                  const int *thl, const float *cbf, uint32_t *ow, uint32_t wpr, float *dWr) {
+__device__ __forceinline__ void pack_row_dispatch(PackRound &cur, const float *Wr, const float *alpha, uint32_t m, bool vec_ok,
+                                                  const float *thr, const int *thl, const float *cbf, uint32_t *ow,
+                                                  uint32_t wpr, float *dWr) {
     if (alpha) {
-        if (dWr) pack_row_body<B, true, true>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr);
-        else pack_row_body<B, true, false>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr);
+        if (dWr) pack_row_body<B, true, true>(cur, Wr, alpha, m, vec_ok, thr, thl, cbf, ow, wpr, dWr);
+        else pack_row_body<B, true, false>(cur, Wr, alpha, m, vec_ok, thr, thl, cbf, ow, wpr, dWr);
     } else {
-        if (dWr) pack_row_body<B, false, true>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr);
-        else pack_row_body<B, false, false>(Wr, alpha, m, thr, thl, cbf, ow, wpr, dWr);
+        if (dWr) pack_row_body<B, false, true>(cur, Wr, alpha, m, vec_ok, thr, thl, cbf, ow, wpr, dWr);
+        else pack_row_body<B, false, false>(cur, Wr, alpha, m, vec_ok, thr, thl, cbf, ow, wpr, dWr);
     }
 }
 
@@ -176,11 +236,19 @@ __global__ void __launch_bounds__(PACK_THREADS) pack_rows_kernel(const float *W,
                                                                  const double *cent, const float *upper,
                                                                  const int *rowpos, const PackPlan *plan,
                                                                  uint32_t *codes, uint16_t *codebooks, float *dW) {
-    __shared__ float thr[16];
+    __shared__ __align__(16) float thr[16];
     __shared__ int thl[16];
     __shared__ float cbf[16];
     const long long row = blockIdx.x;
     const int tid = threadIdx.x;
+    // the first round of weights is on its way while the row's bounds are put in order
+    const float *Wr = W + row * ld;
+    float *dWr = dW ? dW + row * m : nullptr;
+    const bool vec_ok = ((((uintptr_t)Wr) | (uintptr_t)alpha | (uintptr_t)dWr) & 15) == 0;
+    PackRound first;
+    if (alpha) pack_load_round<true>(first, Wr, alpha, (uint32_t)m, (uint32_t)tid >> 2, vec_ok);
+    else pack_load_round<false>(first, Wr, alpha, (uint32_t)m, (uint32_t)tid >> 2, vec_ok);
+
     const int p = rowpos[row];
     if (p < 0) return;  // bits outside 1..4: row is not part of the packed model
     const int b = bits[row];
@@ -213,14 +281,12 @@ __global__ void __launch_bounds__(PACK_THREADS) pack_rows_kernel(const float *W,
     // (cannot happen for thresholds taken from this row) falls to the cluster of the largest bound
     if (tid >= K && tid < 16) thl[tid] = thl[K - 1];
     __syncthreads();
-    const float *Wr = W + row * ld;
-    float *dWr = dW ? dW + row * m : nullptr;
     uint32_t *ow = codes + word0;
     switch (b) {
-        case 1: pack_row_dispatch<1>(Wr, alpha, (uint32_t)m, thr, thl, cbf, ow, (uint32_t)wpr, dWr); break;
-        case 2: pack_row_dispatch<2>(Wr, alpha, (uint32_t)m, thr, thl, cbf, ow, (uint32_t)wpr, dWr); break;
-        case 3: pack_row_dispatch<3>(Wr, alpha, (uint32_t)m, thr, thl, cbf, ow, (uint32_t)wpr, dWr); break;
-        default: pack_row_dispatch<4>(Wr, alpha, (uint32_t)m, thr, thl, cbf, ow, (uint32_t)wpr, dWr); break;
+        case 1: pack_row_dispatch<1>(first, Wr, alpha, (uint32_t)m, vec_ok, thr, thl, cbf, ow, (uint32_t)wpr, dWr); break;
+        case 2: pack_row_dispatch<2>(first, Wr, alpha, (uint32_t)m, vec_ok, thr, thl, cbf, ow, (uint32_t)wpr, dWr); break;
+        case 3: pack_row_dispatch<3>(first, Wr, alpha, (uint32_t)m, vec_ok, thr, thl, cbf, ow, (uint32_t)wpr, dWr); break;
+        default: pack_row_dispatch<4>(first, Wr, alpha, (uint32_t)m, vec_ok, thr, thl, cbf, ow, (uint32_t)wpr, dWr); break;
     }
 }
 
