@@ -1676,6 +1676,18 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
             o->exact = exact_b ? 1 : 0;
         }
     }
+    // table mode: centroids, bounds and errors go out from here; finish_kernel only has the flagged errors left
+    {
+        int b1 = lane_above(Bold);
+        if (p == K - 1) b1 = m;
+        if (on && !prm.bits) {
+            const long long obase = row * prm.stride + ((1 << b) - (1 << prm.bmin));
+            const float up = (b1 > Bold) ? elem_w(keys[b1 - 1]) : -INFINITY;
+            prm.cent[obase + idx] = v;
+            if (prm.upper) prm.upper[obase + idx] = up;
+            if (p == 0 && !exact_b) prm.E[row * (prm.bmax - prm.bmin + 1) + (b - prm.bmin)] = err_b;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1694,6 +1706,13 @@ __global__ void __launch_bounds__(FIN_THREADS) finish_kernel(ClusterParams prm) 
     const long long row = blockIdx.x;
     const u64 *__restrict__ keys = prm.keys + row * (long long)m;
     const int rowbits = prm.bits ? (int)prm.bits[row] : 0;
+    if (!prm.bits) {
+        // table mode: lloyd_iter_kernel has written everything except the errors it flagged for evaluation key by key
+        const BitState *st = prm.bstate + row * 4;
+        int todo = 0;
+        for (int bi = prm.bmin - 1; bi < prm.bmax; ++bi) todo |= st[bi].exact;
+        if (!todo) return;      // (the same for the whole workgroup)
+    }
     {
         const int *src = (const int *)(prm.bstate + row * 4);
         int *dst = (int *)bs;
@@ -1780,8 +1799,8 @@ __global__ void __launch_bounds__(FIN_THREADS) finish_kernel(ClusterParams prm) 
                 if (lane == 0) prm.E[row] = err;
                 obase = row * 16;
             } else {
-                if (lane == 0) prm.E[row * nb + (bb - prm.bmin)] = err;
-                obase = row * prm.stride + ((1 << bb) - (1 << prm.bmin));
+                if (lane == 0 && bs[bi].exact) prm.E[row * nb + (bb - prm.bmin)] = err;
+                continue;       // centroids and bounds were written by lloyd_iter_kernel
             }
             if (lane < Kb) {
                 const int k = bs[bi].idx[lane];
