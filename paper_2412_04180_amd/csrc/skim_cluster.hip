@@ -104,6 +104,10 @@ __device__ __forceinline__ float elem_s(u64 e) {
     const uint32_t lo = (uint32_t)e;
     return __uint_as_float((e >> 63) ? ~lo : lo);
 }
+// The sorted keys in global memory (ClusterParams::keys) carry s as it is: the complement only serves the order
+// inside the sort, and the kernels that read the sorted rows would undo it for every key they touch.
+__device__ __forceinline__ u64 plain_key(u64 e) { return (e >> 63) ? (e ^ 0xFFFFFFFFull) : e; }
+__device__ __forceinline__ float plain_s(u64 e) { return __uint_as_float((uint32_t)e); }
 // same key with s replaced by 1 (unit weights)
 __device__ __forceinline__ u64 unit_weight_key(u64 e) {
     const uint32_t one = 0x3F800000u;
@@ -914,7 +918,7 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     }
     // sorted keys, compact and in rank order
     u64 *keys = prm.keys + row * (long long)m;
-    for (int j = tid; j < m; j += nth) keys[j] = sorted[swz((uint32_t)j)];
+    for (int j = tid; j < m; j += nth) keys[j] = plain_key(sorted[swz((uint32_t)j)]);
     // The next unit refills the key region of the LDS.  On the bucket path it first works on its tables, which
     // lie beyond that region, and passes several barriers before its scatter; its bitonic branch has a barrier
     // of its own.  Without the bucket path the refill is immediate.
@@ -1020,7 +1024,7 @@ __global__ void __launch_bounds__(MG_THREADS) merge_tile_kernel(ClusterParams pr
         if (e < cnt) {
             el = (u64)__double_as_longlong(v[e]);
             if (unit) el = unit_weight_key(el);
-            keys[e] = el;
+            keys[e] = plain_key(el);
         }
         const double sv = (double)elem_s(el), wv = (double)elem_w(el);
         if (e == 0) w0 = elem_w(el);
@@ -1160,43 +1164,67 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
     const int h = lane >> 5, l5 = lane & 31;
 
     // ---- prologue: both rows' first weights, running sums and second-moment levels into LDS -------
+    // All that the two rows need first is requested in one go (one trip to global memory instead of one per
+    // array and row): the groups' sums, the first 512 first weights, the first 64 level-2 second moments.
     const int nhalf = (2ll * blockIdx.x + 1 < nrows) ? 2 : 1;
     const int ng = LM.n[1];
-    for (int hh = 0; hh < nhalf; ++hh) {
+    const int per = (ng + ITER_THREADS - 1) / ITER_THREADS;     // groups per lane: at most 8 (rows of up to 32768 keys)
+    double2 qv[2][8];
+    float t8[2][8];
+    double rq4[2][4];
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+        const long long rr = 2ll * blockIdx.x + (hh < nhalf ? hh : 0);
+        const double2 *gq = prm.Q + rr * prm.nq;
+        const float *gw = prm.w16 + rr * prm.n1;
+        const double *grq = prm.RQ + rr * prm.nq;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int q = lane * per + k;
+            qv[hh][k] = (k < per && q < ng) ? gq[q] : make_double2(0.0, 0.0);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int j = u * ITER_THREADS + lane;
+            t8[hh][u] = (j < n1u) ? gw[j] : 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) rq4[hh][k] = (LM.nlev > 2 && 4 * lane + k < ng) ? grq[4 * lane + k] : 0.0;
+    }
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+        if (hh >= nhalf) break;
         const long long rr = 2ll * blockIdx.x + hh;
         unsigned char *blkw = smem + (size_t)hh * LM.bytes;
         float *w16w = (float *)(blkw + LM.w16_off);
         const float *gw = prm.w16 + rr * prm.n1;
-        for (int j0 = 0; j0 < n1u; j0 += 8 * ITER_THREADS) {
-            float t8[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int j = u * ITER_THREADS + lane;
+            if (j < n1u) w16w[j] = t8[hh][u];
+        }
+        for (int j0 = 8 * ITER_THREADS; j0 < n1u; j0 += 8 * ITER_THREADS) {
+            float t[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int j = j0 + u * ITER_THREADS + lane;
-                t8[u] = (j < n1u) ? gw[j] : 0.0f;
+                t[u] = (j < n1u) ? gw[j] : 0.0f;
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int j = j0 + u * ITER_THREADS + lane;
-                if (j < n1u) w16w[j] = t8[u];
+                if (j < n1u) w16w[j] = t[u];
             }
         }
         // running sums ahead of every group of 4 chunks, pp[ng] = row total.  A lane takes `per` consecutive
         // groups; one double-double scan over the lanes per quantity.
         {
-            const double2 *gq = prm.Q + rr * prm.nq;
             double2 *ppd = (double2 *)(blkw + LM.ppd_off), *ppn = (double2 *)(blkw + LM.ppn_off);
-            const int per = (ng + ITER_THREADS - 1) / ITER_THREADS;     // at most 8 (rows of up to 32768 keys)
-            double2 qv[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int q = lane * per + k;
-                qv[k] = (k < per && q < ng) ? gq[q] : make_double2(0.0, 0.0);
-            }
             double2 md = make_double2(0.0, 0.0), mn = make_double2(0.0, 0.0);
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
-                md = dd_add(md, make_double2(qv[k].x, 0.0));
-                mn = dd_add(mn, make_double2(qv[k].y, 0.0));
+                md = dd_add(md, make_double2(qv[hh][k].x, 0.0));
+                mn = dd_add(mn, make_double2(qv[hh][k].y, 0.0));
             }
             const double2 id = dd_wave_scan_incl(md), in = dd_wave_scan_incl(mn);
             // sums of the lanes below: the inclusive sums shifted up by one lane
@@ -1212,8 +1240,8 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
                 if (k < per && q < ng) {
                     ppd[q] = rd;
                     ppn[q] = rn;
-                    rd = dd_add(rd, make_double2(qv[k].x, 0.0));
-                    rn = dd_add(rn, make_double2(qv[k].y, 0.0));
+                    rd = dd_add(rd, make_double2(qv[hh][k].x, 0.0));
+                    rn = dd_add(rn, make_double2(qv[hh][k].y, 0.0));
                     if (q == ng - 1) {
                         ppd[ng] = rd;
                         ppn[ng] = rn;
@@ -1225,7 +1253,8 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
         if (LM.nlev > 2) {
             const double *grq = prm.RQ + rr * prm.nq;
             double *r2 = (double *)(blkw + LM.roff[2]);
-            for (int q = lane; q < LM.n[2]; q += ITER_THREADS) {
+            if (lane < LM.n[2]) r2[lane] = ((rq4[hh][0] + rq4[hh][1]) + rq4[hh][2]) + rq4[hh][3];
+            for (int q = lane + ITER_THREADS; q < LM.n[2]; q += ITER_THREADS) {
                 double acc = 0.0;
 #pragma unroll
                 for (int k = 0; k < 4; ++k)
@@ -1279,6 +1308,8 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
 
     // ---- weighted-quantile start with strictly increasing ranks ---------------------------------
     int r = 0;
+    float wstart = 0.0f;     // weight of the key at rank r, when r ends up inside the chunk read below
+    bool wstart_ok = false;
     {
         const double total = ppd[ng].x;
         const double tau = total * (double)(2 * p + 1) / (double)(2 * K);
@@ -1294,6 +1325,9 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
         // chunk inside the group: largest chunk whose running sum ahead of it is < tau
         int chunk = 4 * lo;
         double acc = ppd[lo].x;
+        u64 el[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) el[j] = NEUTRAL_KEY;
         if (on) {
             double dch[3];
 #pragma unroll
@@ -1312,14 +1346,13 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
                 }
             }
             const int r0 = chunk * 16;
-            u64 el[16];
 #pragma unroll
             for (int j = 0; j < 16; ++j) el[j] = (r0 + j < m) ? keys[r0 + j] : NEUTRAL_KEY;
             int found = min(r0 + 15, m - 1);
             bool hit = false;
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
-                acc += (double)elem_s(el[j]);
+                acc += (double)plain_s(el[j]);
                 if (!hit && r0 + j < m && acc >= tau) {
                     found = r0 + j;
                     hit = true;
@@ -1337,8 +1370,18 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
                 prev = rk;
             }
         }
+        if (on) {
+            // the repair seldom moves a rank out of the 16 keys already in registers
+            const int off = r - chunk * 16;
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (off == j) { wstart = elem_w(el[j]); wstart_ok = true; }
+        }
     }
-    double v = on ? (double)elem_w(keys[r]) : 0.0;
+    if (__ballot(on && !wstart_ok) != 0) {
+        if (on && !wstart_ok) wstart = elem_w(keys[r]);
+    }
+    double v = on ? (double)wstart : 0.0;
     int idx = p;
     int Bcur = 0, Bold = -1, idxold = -1, cold = 0;
     double Dk = 0.0, Nk = 0.0;       // sums of this lane's cluster under the last assignment it took part in
@@ -1536,10 +1579,12 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
         double lowD = 0.0, lowN = 0.0, D = 0.0, N = 0.0;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            const float sf = elem_s(el[j]);
+            const float sf = plain_s(el[j]);
             const double wd = (double)elem_w(el[j]);
+            // tl <= th: the keys below th minus those below tl are the cluster's own (the difference is s or 0, exactly)
             const float sl = (j < tl) ? sf : 0.0f;
-            const float sh = (j >= tl && j < th) ? sf : 0.0f;
+            const float su = (j < th) ? sf : 0.0f;
+            const float sh = __fsub_rn(su, sl);
             const double sld = (double)sl, shd = (double)sh;
             lowD += sld;
             lowN = fma(sld, wd, lowN);     // s * w of two floats is exact
@@ -1615,24 +1660,41 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
             pr[k] = (c0 + k < la0) ? R1[c0 + k] : 0.0;
             pr[3 + k] = (rb0 + k < c3) ? R1[rb0 + k] : 0.0;
         }
+        // level 1 (groups of 4 chunks) lives in global memory too: its pieces are requested with the rest
+        int ra = la0 >> 2, rb = rb0 >> 2;
+        if (la0 >= rb0) { ra = 0; rb = 0; }
+        double pq[6];
+        {
+            const double *RQg = prm.RQ + rowc * prm.nq;
+            const int la = min(rb, (ra + 3) & ~3), rbb = max(la, rb & ~3);
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                pq[k] = (ra + k < la) ? RQg[ra + k] : 0.0;
+                pq[3 + k] = (rbb + k < rb) ? RQg[rbb + k] : 0.0;
+            }
+            if (la < rbb) { ra = la >> 2; rb = rbb >> 2; } else { ra = 0; rb = 0; }
+        }
         const int abase = a & ~15;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const bool ina = (abase + j >= a) && (abase + j < e0);
             const bool inb = (e1 + j < bnd);
-            const double sa = ina ? (double)elem_s(ea[j]) : 0.0, wa = ina ? (double)elem_w(ea[j]) : 0.0;
-            const double sb = inb ? (double)elem_s(eb[j]) : 0.0, wb = inb ? (double)elem_w(eb[j]) : 0.0;
+            const double sa = ina ? (double)plain_s(ea[j]) : 0.0, wa = ina ? (double)elem_w(ea[j]) : 0.0;
+            const double sb = inb ? (double)plain_s(eb[j]) : 0.0, wb = inb ? (double)elem_w(eb[j]) : 0.0;
             Rp = fma(sa * wa, wa, Rp);
             Rp = fma(sb * wb, wb, Rp);
         }
 #pragma unroll
         for (int k = 0; k < 6; ++k) Rp += pr[k];
-        int ra = la0 >> 2, rb = rb0 >> 2;
-        if (la0 >= rb0) { ra = 0; rb = 0; }
 #pragma unroll
-        for (int lv = 1; lv < MAX_LEVELS; ++lv) {
+        for (int k = 0; k < 3; ++k) {      // (the order the level loop below adds in: low end, high end, alternating)
+            Rp += pq[k];
+            Rp += pq[3 + k];
+        }
+#pragma unroll
+        for (int lv = 2; lv < MAX_LEVELS; ++lv) {
             if (lv < LM.nlev && __ballot(ra < rb) != 0) {
-                const double *L = (lv == 1) ? prm.RQ + rowc * prm.nq : (const double *)(blk + LM.roff[lv]);
+                const double *L = (const double *)(blk + LM.roff[lv]);
                 const int la = min(rb, (ra + 3) & ~3), rbb = max(la, rb & ~3);
 #pragma unroll
                 for (int k = 0; k < 3; ++k) {
@@ -1752,7 +1814,7 @@ __global__ void __launch_bounds__(FIN_THREADS) finish_kernel(ClusterParams prm) 
             const int base = base0 + u * FIN_THREADS;
             if (base >= m) break;
             const int rk = base + lane;
-            const double w = (double)elem_w(els[u]), s = (double)elem_s(els[u]);
+            const double w = (double)elem_w(els[u]), s = (double)plain_s(els[u]);
 #pragma unroll
             for (int bi = 0; bi < 4; ++bi) {
                 if (!act[bi]) continue;
@@ -1995,7 +2057,7 @@ __global__ void __launch_bounds__(OPT_THREADS) kmeans_optimal_kernel(OptParams p
         double a = 0.0, b = 0.0, c = 0.0;
         for (int j = j0; j < j1; ++j) {
             const u64 el = keys[j];
-            const double s = (double)elem_s(el), w = (double)elem_w(el);
+            const double s = (double)plain_s(el), w = (double)elem_w(el);
             a += s;
             b = fma(s, w, b);
             c = fma(s * w, w, c);
@@ -2013,7 +2075,7 @@ __global__ void __launch_bounds__(OPT_THREADS) kmeans_optimal_kernel(OptParams p
         if (tid == 0) { A[0] = 0.0; B[0] = 0.0; C[0] = 0.0; D0[0] = 0.0; D1[0] = 0.0; opt[0] = 0; }
         for (int j = j0; j < j1; ++j) {
             const u64 el = keys[j];
-            const double s = (double)elem_s(el), w = (double)elem_w(el);
+            const double s = (double)plain_s(el), w = (double)elem_w(el);
             pa += s;
             pb = fma(s, w, pb);
             pc = fma(s * w, w, pc);
