@@ -30,7 +30,7 @@ __device__ __forceinline__ void hist_add(unsigned *hist, bool valid, unsigned di
     const u64 act = __ballot(valid);
     if (act == 0) return;
     const int leader = __ffsll((long long)act) - 1;
-    const unsigned first = (unsigned)__shfl((int)dig, leader, 64);
+    const unsigned first = (unsigned)__builtin_amdgcn_readlane((int)dig, leader);   // leader is the same in every lane
     const u64 same = __ballot(valid && dig == first);
     if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[first], (unsigned)__popcll(same));
     else if (valid && dig != first) atomicAdd(&hist[dig], 1u);
@@ -84,6 +84,7 @@ __global__ void __launch_bounds__(GA_THREADS) greedy_select_kernel(const double 
     long long rank = T;            // rank among the keys that share the prefix fixed so far
     u64 thr = 0;
     long long R = 0;               // keys equal to the threshold that are still taken
+    bool lone = false;             // exactly one key equals the threshold and it is taken: taken <=> key >= thr
     if (T > 0 && T < nk) {
         for (int d = 7; d >= 0; --d) {
             if (tid < 256) hist[tid] = 0;
@@ -145,6 +146,7 @@ __global__ void __launch_bounds__(GA_THREADS) greedy_select_kernel(const double 
                 }
                 __syncthreads();
                 prefix = sh_prefix;
+                lone = true;
                 break;             // rank == 1 here
             }
         }
@@ -156,7 +158,7 @@ __global__ void __launch_bounds__(GA_THREADS) greedy_select_kernel(const double 
     const long long per = (nk + GA_THREADS - 1) / GA_THREADS;
     const long long q0 = min(nk, per * tid), q1 = min(nk, q0 + per);
     long long eq_before = 0;
-    if (T > 0 && T < nk) {
+    if (T > 0 && T < nk && !lone) {
         long long mine = 0;
         for (long long q = q0; q < q1; ++q) mine += (keys[q] == thr) ? 1 : 0;
         long long inc = mine;
@@ -172,8 +174,9 @@ __global__ void __launch_bounds__(GA_THREADS) greedy_select_kernel(const double 
     }
     __syncthreads();
     // taken: key > thr, or key == thr among the first R equal ones; T >= nk takes everything.
-    // Mark by overwriting the key with 1 / 0 (each thread owns its index range).
-    for (long long q = q0; q < q1; ++q) {
+    // Mark by overwriting the key with 1 / 0 (each thread owns its index range).  With a lone key at the threshold
+    // the comparison key >= thr says it all and the rows are counted from the keys themselves.
+    for (long long q = q0; q < q1 && !lone; ++q) {
         const u64 key = keys[q];
         bool take;
         if (T <= 0) take = false;
@@ -184,11 +187,27 @@ __global__ void __launch_bounds__(GA_THREADS) greedy_select_kernel(const double 
         keys[q] = take ? 1ull : 0ull;
     }
     __syncthreads();
-    for (long long i = tid; i < n; i += GA_THREADS) {
-        int b = bmin;
-        for (int j = 0; j < nu; ++j) b += (int)keys[i * nu + j];
-        bits[i] = (uint8_t)b;
-        atomicAdd((unsigned long long *)&cnt[b & 7], 1ull);
+    // rows per bit width: counted per wavefront with ballots (one LDS atomic per wavefront and width instead of
+    // one per row on a handful of addresses)
+    long long wcnt[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (long long i0 = 0; i0 < n; i0 += GA_THREADS) {
+        const long long i = i0 + tid;
+        int b = -1;
+        if (i < n) {
+            b = bmin;
+            for (int j = 0; j < nu; ++j) {
+                const u64 key = keys[i * nu + j];
+                b += lone ? (key >= thr ? 1 : 0) : (int)key;
+            }
+            bits[i] = (uint8_t)b;
+        }
+#pragma unroll
+        for (int v = 0; v < 8; ++v) wcnt[v] += __popcll(__ballot(b == v));
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int v = 0; v < 8; ++v)
+            if (wcnt[v]) atomicAdd((unsigned long long *)&cnt[v], (unsigned long long)wcnt[v]);
     }
     __syncthreads();
     if (tid < 8) info[tid] = cnt[tid];
