@@ -41,21 +41,32 @@ __global__ void __launch_bounds__(PLAN_THREADS) pack_plan_kernel(long long n, lo
     }
     for (int b = 0; b < 4; ++b) cnt[b][t] = c[b];
     __syncthreads();
-    // exclusive scan of each bit width's counts over the threads (one wavefront per bit width)
+    // exclusive scan of each bit width's counts over the threads: one wavefront per bit width, a lane takes
+    // PLAN_THREADS / 64 consecutive entries and the lanes' totals are scanned inside the VALU (DPP)
     const int wave = t >> 6, lane = t & 63;
     if (wave < 4) {
-        int run = 0;
-        for (int base = 0; base < PLAN_THREADS; base += 64) {
-            const int v = cnt[wave][base + lane];
-            int inc = v;
-            for (int d = 1; d < 64; d <<= 1) {
-                const int u = __shfl_up(inc, d, 64);
-                if (lane >= d) inc += u;
-            }
-            cnt[wave][base + lane] = run + inc - v;
-            run += __shfl(inc, 63, 64);
+        constexpr int PER = PLAN_THREADS / 64;
+        int v[PER];
+        int tot = 0;
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            v[k] = cnt[wave][lane * PER + k];
+            tot += v[k];
         }
-        if (lane == 0) gstart[wave + 1] = run;  // group sizes for now
+        int inc = tot;
+        inc += __builtin_amdgcn_update_dpp(0, inc, 0x111, 0xF, 0xF, false);   // row_shr:1
+        inc += __builtin_amdgcn_update_dpp(0, inc, 0x112, 0xF, 0xF, false);   // row_shr:2
+        inc += __builtin_amdgcn_update_dpp(0, inc, 0x114, 0xF, 0xF, false);   // row_shr:4
+        inc += __builtin_amdgcn_update_dpp(0, inc, 0x118, 0xF, 0xF, false);   // row_shr:8
+        inc += __builtin_amdgcn_update_dpp(0, inc, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1, 3
+        inc += __builtin_amdgcn_update_dpp(0, inc, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2, 3
+        int run = inc - tot;
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            cnt[wave][lane * PER + k] = run;
+            run += v[k];
+        }
+        if (lane == 63) gstart[wave + 1] = inc;  // group sizes for now
     }
     __syncthreads();
     if (t == 0) {
