@@ -4,17 +4,20 @@
 // Three kernels per call.
 //  sort_kernel       one workgroup per row at a time: the row's (w~, s~) pairs become 64-bit keys
 //                    whose bit pattern, read as a float64, orders like (w~, s~); they are sorted
-//                    once in LDS (bitonic network, compare-exchange = v_min_f64 + v_max_f64) and
-//                    written to scratch together with float64 sums of s~ and s~ w~ per aligned
-//                    16-key chunk and the weight of every chunk's first key.
+//                    once in LDS (counting sort by value bin + two register passes; a bitonic
+//                    network for the rows that overflow a bin; compare-exchange = v_min_f64 +
+//                    v_max_f64) and written to scratch together with float64 sums of s~, s~ w~ and
+//                    s~ w~^2 per aligned 16-key chunk and the weight of every chunk's first key.
 //  lloyd_iter_kernel one lane per cluster, two rows per wavefront, all four bit widths at once.
 //                    In sorted order every cluster of a 1-D K-means is a contiguous rank range,
 //                    so one Lloyd iteration is: per pair of neighbouring centroids a search for
 //                    the rank where the nearer centroid changes (chunk by a search in LDS, rank
 //                    inside the chunk from its keys), then centroid = (sum of s~ w~) / (sum of
-//                    s~) over the range, assembled from aligned pieces of a radix-4 sum tree.
-//  finish_kernel     one workgroup per row: errors by direct evaluation over the sorted keys,
-//                    centroids, thresholds, labels.
+//                    s~) over the range, assembled from the keys of the boundary chunks, a few
+//                    chunk sums and a difference of double-double running sums.  In table mode it
+//                    also writes centroids, bounds and errors.
+//  finish_kernel     one workgroup per row: errors the iteration kernel flagged (direct evaluation
+//                    over the sorted keys); for skim_cluster_rows centroids, thresholds, labels.
 //
 // Arithmetic on every decision path is float64 and uses the same predicates as the
 // definition: |w - c_lo| versus |w - c_hi| with the lower cluster index winning equal
