@@ -210,13 +210,9 @@ __global__ void __launch_bounds__(MV_THREADS) matvec_rows_kernel(const uint32_t 
 constexpr int MVF_THREADS = 256;
 constexpr int MVF_ROWS = 8;
 
+// the 32 weights of one row whose B code words are in wd[0..B) (wd[B] = 0)
 template <int B, int R>
-__device__ __forceinline__ float mvf_chunk(const uint32_t *__restrict__ rw, uint32_t w0, uint32_t wpr,
-                                           const float (*cbf)[16], const float (&xs)[32]) {
-    uint32_t wd[B + 1];
-#pragma unroll
-    for (int k = 0; k < B; ++k) wd[k] = (w0 + k < wpr) ? rw[w0 + k] : 0u;
-    wd[B] = 0u;
+__device__ __forceinline__ float mvf_words(const uint32_t (&wd)[B + 1], const float (*cbf)[16], const float (&xs)[32]) {
     float acc0 = 0.0f, acc1 = 0.0f;
     const char *base = (const char *)cbf[R];
 #pragma unroll
@@ -231,6 +227,41 @@ __device__ __forceinline__ float mvf_chunk(const uint32_t *__restrict__ rw, uint
         else acc0 = fmaf(c, xs[e], acc0);
     }
     return acc0 + acc1;
+}
+
+template <int B, int R>
+__device__ __forceinline__ float mvf_chunk(const uint32_t *__restrict__ rw, uint32_t w0, uint32_t wpr,
+                                           const float (*cbf)[16], const float (&xs)[32]) {
+    uint32_t wd[B + 1];
+#pragma unroll
+    for (int k = 0; k < B; ++k) wd[k] = (w0 + k < wpr) ? rw[w0 + k] : 0u;
+    wd[B] = 0u;
+    return mvf_words<B, R>(wd, cbf, xs);
+}
+
+// All MVF_ROWS rows of the workgroup have B bits (rows are packed by bit width, so this is every workgroup but
+// the few that straddle two groups): the code words of all rows are requested before the first is used.
+template <int B, int R>
+__device__ __forceinline__ void mvf_same_rows(const uint32_t (&wd)[MVF_ROWS][B + 1], const float (*cbf)[16],
+                                              const float (&xs)[32], float (&acc)[MVF_ROWS]) {
+    if constexpr (R < MVF_ROWS) {
+        acc[R] += mvf_words<B, R>(wd[R], cbf, xs);
+        mvf_same_rows<B, R + 1>(wd, cbf, xs, acc);
+    }
+}
+template <int B>
+__device__ __forceinline__ void mvf_same(const uint32_t *codes, const RowPlace *places, long long m, uint32_t ch,
+                                         const float (*cbf)[16], const float (&xs)[32], float (&acc)[MVF_ROWS]) {
+    const uint32_t wpr = (uint32_t)((m * B + 31) / 32);
+    uint32_t wd[MVF_ROWS][B + 1];
+#pragma unroll
+    for (int r = 0; r < MVF_ROWS; ++r) {
+        const uint32_t *rw = codes + places[r].word0;
+#pragma unroll
+        for (int k = 0; k < B; ++k) wd[r][k] = (ch * B + k < wpr) ? rw[ch * B + k] : 0u;
+        wd[r][B] = 0u;
+    }
+    mvf_same_rows<B, 0>(wd, cbf, xs, acc);
 }
 
 template <int R>
@@ -276,6 +307,11 @@ __global__ void __launch_bounds__(MVF_THREADS) matvec_f32_kernel(const uint32_t 
     float acc[MVF_ROWS];
 #pragma unroll
     for (int r = 0; r < MVF_ROWS; ++r) acc[r] = 0.0f;
+    // the bit width all rows of this workgroup share, 0 when they differ (or some are past the end)
+    int same_b = places[0].b;
+#pragma unroll
+    for (int r = 1; r < MVF_ROWS; ++r) same_b = (places[r].b == same_b) ? same_b : 0;
+    same_b = __builtin_amdgcn_readfirstlane(same_b);
     const uint32_t mm = (uint32_t)m;
     const uint32_t nchunk = (mm + 31) >> 5;
     for (uint32_t ch = tid; ch < nchunk; ch += MVF_THREADS) {
@@ -303,7 +339,13 @@ __global__ void __launch_bounds__(MVF_THREADS) matvec_f32_kernel(const uint32_t 
                 xs[e] = in ? (alpha ? alpha[j0 + e] * x[j0 + e] : x[j0 + e]) : 0.0f;
             }
         }
-        mvf_rows<0>(codes, places, m, ch, cbf, xs, acc);
+        switch (same_b) {
+            case 1: mvf_same<1>(codes, places, m, ch, cbf, xs, acc); break;
+            case 2: mvf_same<2>(codes, places, m, ch, cbf, xs, acc); break;
+            case 3: mvf_same<3>(codes, places, m, ch, cbf, xs, acc); break;
+            case 4: mvf_same<4>(codes, places, m, ch, cbf, xs, acc); break;
+            default: mvf_rows<0>(codes, places, m, ch, cbf, xs, acc); break;
+        }
     }
 #pragma unroll
     for (int r = 0; r < MVF_ROWS; ++r) {
