@@ -708,8 +708,9 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
 template <int NS, bool VEC>
 __device__ __forceinline__ void fetch_unit(const ClusterParams &prm, long long work, int tid, int nth, float (&pw)[NS],
                                            float (&ps)[NS], bool live = true, int part = -1) {
-    const long long frow = work / prm.nseg;
-    const int fcol0 = (int)(work % prm.nseg) * prm.seglen;
+    // (a row has one segment or two: no 64-bit division)
+    const long long frow = prm.nseg > 1 ? (work >> 1) : work;
+    const int fcol0 = prm.nseg > 1 ? (int)(work & 1) * prm.seglen : 0;
     const int fm = live ? min(prm.m - fcol0, prm.seglen) : 0;
     const Slots<VEC> sm(fm, nth, tid);
     if constexpr (VEC) {
@@ -784,8 +785,8 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     // used instead of being hoisted out of this loop and held in registers through the sort
     int tid = tid0;
     asm volatile("" : "+v"(tid));
-    const long long row = work / prm.nseg;
-    const int col0 = (int)(work % prm.nseg) * prm.seglen;            // first column of this segment
+    const long long row = prm.nseg > 1 ? (work >> 1) : work;
+    const int col0 = prm.nseg > 1 ? (int)(work & 1) * prm.seglen : 0;   // first column of this segment
     const int m = min(prm.m - col0, prm.seglen);                     // keys sorted by this workgroup
     const float *alpha = prm.alpha ? prm.alpha + col0 : nullptr;
     const bool more = work + gridDim.x < prm.nwork;
