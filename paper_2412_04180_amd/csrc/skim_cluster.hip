@@ -26,6 +26,8 @@
 
 #include <math.h>
 
+#include <type_traits>
+
 typedef unsigned long long u64;
 
 namespace {
@@ -393,11 +395,13 @@ struct Slots {
 //            followed by bk_pad spare words so that the blocks of 8 neighbouring threads start in different banks
 //   coarse   COARSE_N intervals x 4 counters (a lane adds to copy lane & 3: fewer same-address collisions),
 //            then per interval (first bin, number of bins) as two floats
-//   misc     per wavefront: least weight, largest weight, mass flag, scan total with its flags (16 entries each)
+//   misc     per wavefront: least weight, largest weight, mass flag, OR of the weights' bits, scan total with its
+//            flags, sum and count of the exponents of s (16 entries each); the fill table of BinMap (65 words)
 constexpr int COARSE_N = 256;
 constexpr uint32_t BK_COARSE_BYTES = COARSE_N * 4 * 4 + COARSE_N * 8;
-constexpr uint32_t BK_MISC_BYTES = 512;
-constexpr uint32_t BK_WMIN = 0, BK_WMAX = 64, BK_WMASS = 128, BK_WTOT = 256;
+constexpr uint32_t BK_MISC_BYTES = 1024;
+constexpr uint32_t BK_WMIN = 0, BK_WMAX = 64, BK_WMASS = 128, BK_WOR = 192, BK_WTOT = 256, BK_SMIN = 320, BK_SMAX = 384, BK_STAB = 512;
+constexpr int STAB_N = 64;        // pieces of the fill table: a quarter octave of s each, 8 octaves to either side of sbm
 
 // The bin map a workgroup carries from one unit to the next: the axis of the coarse intervals and whether the
 // table in LDS (bins per interval) is valid and the fine counters are zero.  The first unit of a workgroup
@@ -408,7 +412,42 @@ constexpr uint32_t BK_WMIN = 0, BK_WMAX = 64, BK_WMASS = 128, BK_WTOT = 256;
 struct BinMap {
     bool have;
     float lo, scale;
+    // Rows whose weights all have their low bits clear (values converted from a 16-bit format) hold every value
+    // many times over, and equal weights would share one bin.  The bin is then taken from the weight with those
+    // bits filled in from s: a value between this weight and the next one the format has, rising with s -- so the
+    // map stays monotone in the key and equal weights spread over the bins up to the next value.  The fill is a
+    // piecewise linear function of the bit pattern of s (about its logarithm): STAB_N pieces of a quarter octave
+    // around sbm, the pattern in the middle of the row's mean octave; the table in LDS holds, per piece, the
+    // share of the row's s below it, scaled to the 2^kz fill values (so equal weights spread evenly whatever the
+    // distribution of s); s beyond the table takes the nearest end.  Integer arithmetic on a nondecreasing table:
+    // monotone by construction.  lowmask = 2^kz - 1 (the clear bits, 8 to 16 of them); 0: off.
+    uint32_t lowmask, sbm;
 };
+
+// The weight a key is binned by (see BinMap).  A negative weight gets the complement of the fill: its value
+// must rise with s too, i.e. its magnitude fall.
+// piece of the fill table a pattern of s falls into, and its position inside the piece in 2^-16ths
+__device__ __forceinline__ void fill_piece(uint32_t sb, uint32_t sbm, int &idx, uint32_t &f16) {
+    const int z = (int)(sb - sbm);                            // (patterns of s >= 0 are below 2^31: no wrap)
+    const int q = (z >> 21) + STAB_N / 2;                     // quarter octaves; floor for negative z
+    idx = min(max(q, 0), STAB_N - 1);
+    f16 = q < 0 ? 0u : (q >= STAB_N ? 0xFFFFu : ((uint32_t)z & 0x1FFFFFu) >> 5);
+}
+
+template <bool SPREAD>
+__device__ __forceinline__ float bin_weight(u64 key, const BinMap &map, const uint32_t *stab) {
+    const uint32_t hi = (uint32_t)(key >> 32);
+    if (!SPREAD) return __uint_as_float(hi);
+    const uint32_t lo = (uint32_t)key;
+    const bool neg = (hi >> 31) != 0u;
+    const uint32_t sb = neg ? ~lo : lo;                       // the bits of s
+    int idx;
+    uint32_t f16;
+    fill_piece(sb, map.sbm, idx, f16);
+    const uint32_t t0 = stab[idx], t1 = stab[idx + 1];
+    const uint32_t u = min(t0 + (((t1 - t0) * f16) >> 16), map.lowmask);
+    return __uint_as_float(hi | (neg ? map.lowmask - u : u));
+}
 
 // Bins per coarse interval from the counts c[0..3] of this lane's 4 intervals (lane l: intervals 4l .. 4l+3;
 // all 64 lanes call): counts smoothed (1 2 1) so that a sparse interval still gets bins from its neighbours'
@@ -462,6 +501,7 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
     uint32_t *coarse = (uint32_t *)(smem + prm.bk_coarse_off);
     float2 *table = (float2 *)(coarse + COARSE_N * 4);
     uint32_t *wtot = (uint32_t *)(smem + prm.bk_misc_off + BK_WTOT);
+    const uint32_t *stab = (const uint32_t *)(smem + prm.bk_misc_off + BK_STAB);
     const int bpt = prm.bk_bpt;
     const int nbins = bpt * nth;
     const int hstride = (bpt >> 1) + prm.bk_pad;    // words from one thread's block of counters to the next
@@ -471,18 +511,15 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
         const uint32_t wd = (fb >> 1) + (prm.bk_pad ? (fb >> prm.bk_lgbpt) << 2 : 0u);
         return (wd << 1) | (fb & 1u);
     };
-    if (!map.have) {
-        // ---- coarse histogram of a sample: every fourth slot of a thread (every fourth column when VEC, else
-        // the columns [4q nth, (4q+1) nth))
-        int nsample = VEC ? (m >> 2) : 0;
-        if (!VEC) {
+    if (__builtin_expect(!map.have, 0)) {
+        // ---- coarse histogram of the unit's keys (a sample of every fourth key was tried: its table overflowed a
+        // bin several times as often, and a unit that takes the network leaves the next without a map again)
+        const int nsample = m;
 #pragma unroll
-            for (int k = 0; k < NS; k += 4) nsample += max(0, min(nth, m - k * nth));
-        }
-#pragma unroll
-        for (int k = 0; k < NS; k += 4) {
+        for (int k = 0; k < NS; ++k) {
             if (sm.has(k)) {
-                const int cb = min(max((int)coarse_pos(elem_w(key[k]), lo, scale), 0), COARSE_N - 1);
+                const float wb = map.lowmask ? bin_weight<true>(key[k], map, stab) : bin_weight<false>(key[k], map, stab);
+                const int cb = min(max((int)coarse_pos(wb, lo, scale), 0), COARSE_N - 1);
                 atomicAdd(&coarse[cb * 4 + (lane & 3)], 1u);
             }
         }
@@ -508,28 +545,35 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
     uint32_t fbs[NS];
     uint32_t smax = 0;          // largest slot any of this thread's keys got
     const bool padded = prm.bk_pad != 0;
+    auto count_keys = [&](auto spread) {
+        constexpr bool SPREAD = decltype(spread)::value;
 #pragma unroll
-    for (int k = 0; k < NS; ++k) {
-        fbs[k] = 0u;
-        if (sm.has(k)) {
-            // Position on the coarse axis, held inside the axis (a carried map may not cover this unit's extremes:
-            // weights beyond either end all go to the first / last bin, which keeps the map monotone).
-            // bin = first bin of the interval + fraction of the interval x bins of the interval, in one fused
-            // multiply-add: monotone in w, and at most the first bin of the next interval (the last clamp cannot
-            // bind while the table is consistent; it keeps the index inside the counters)
-            const float x = fminf(fmaxf(coarse_pos(elem_w(key[k]), lo, scale), 0.0f), (float)COARSE_N - 0.0001f);
-            const uint32_t cb = (uint32_t)(int)x;
-            const float fr = __builtin_amdgcn_fractf(x);
-            const float2 tb = table[cb];
-            const uint32_t fb = min((uint32_t)fmaf(fr, tb.y, tb.x), (uint32_t)(nbins - 1));
-            const uint32_t hw = padded ? bin_halfword(fb) : fb;
-            const uint32_t sh = (hw & 1u) << 4;
-            const uint32_t old = atomicAdd(&hist[hw >> 1], 1u << sh);
-            const uint32_t slot = (old >> sh) & 0xFFFFu;
-            smax = max(smax, slot);
-            fbs[k] = hw | (slot << 16);
+        for (int k = 0; k < NS; ++k) {
+            fbs[k] = 0u;
+            if (sm.has(k)) {
+                // Position on the coarse axis, held inside the axis (a carried map may not cover this unit's extremes:
+                // weights beyond either end all go to the first / last bin, which keeps the map monotone).
+                // bin = first bin of the interval + fraction of the interval x bins of the interval, in one fused
+                // multiply-add: monotone in w, and at most the first bin of the next interval (the last clamp cannot
+                // bind while the table is consistent; it keeps the index inside the counters)
+                const float x = fminf(fmaxf(coarse_pos(bin_weight<SPREAD>(key[k], map, stab), lo, scale), 0.0f), (float)COARSE_N - 0.0001f);
+                // (a carried map may promise clear low bits that this unit does not have: it then sorts by the network)
+                if (SPREAD && ((uint32_t)(key[k] >> 32) & map.lowmask)) smax = (uint32_t)BIN_MAX_KEYS;
+                const uint32_t cb = (uint32_t)(int)x;
+                const float fr = __builtin_amdgcn_fractf(x);
+                const float2 tb = table[cb];
+                const uint32_t fb = min((uint32_t)fmaf(fr, tb.y, tb.x), (uint32_t)(nbins - 1));
+                const uint32_t hw = padded ? bin_halfword(fb) : fb;
+                const uint32_t sh = (hw & 1u) << 4;
+                const uint32_t old = atomicAdd(&hist[hw >> 1], 1u << sh);
+                const uint32_t slot = (old >> sh) & 0xFFFFu;
+                smax = max(smax, slot);
+                fbs[k] = hw | (slot << 16);
+            }
         }
-    }
+    };
+    if (__builtin_expect(map.lowmask != 0u, 0)) count_keys(std::true_type{});
+    else count_keys(std::false_type{});
     prefetch(1);
     __syncthreads();
     // ---- first rank of every bin: exclusive scan of the counters, written over them (16 bits each)
@@ -780,6 +824,8 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     map.have = false;
     map.lo = 0.0f;
     map.scale = 0.0f;
+    map.lowmask = 0u;
+    map.sbm = 0u;
     for (long long work = blockIdx.x; work < prm.nwork; work += gridDim.x) {
     // the thread index is made opaque per unit: per-thread addresses are recomputed where they are
     // used instead of being hoisted out of this loop and held in registers through the sort
@@ -819,14 +865,86 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
             wmass[tid >> 6] = wave_mass ? 1u : 0u;
         }
         bool usable = true;
-        if (!map.have) {
+        if (__builtin_expect(!map.have, 0)) {
             // no map carried over: the axis is this unit's own range
             uint32_t *cc = (uint32_t *)(smem + prm.bk_coarse_off);
             for (int i = tid; i < COARSE_N * 4; i += nth) cc[i] = 0u;
+            // which bits any weight of the unit has set, and the typical exponent of s (sum and count of the
+            // exponent fields of the positive s)
+            uint32_t *wor = (uint32_t *)(smem + prm.bk_misc_off + BK_WOR);
+            uint32_t *sex = (uint32_t *)(smem + prm.bk_misc_off + BK_SMIN), *scn = (uint32_t *)(smem + prm.bk_misc_off + BK_SMAX);
+            {
+                uint32_t orb = 0u, esum = 0u, ecnt = 0u;
+#pragma unroll
+                for (int k = 0; k < NS; ++k) {
+                    if (sm.has(k)) {
+                        const uint32_t h = (uint32_t)(key[k] >> 32), l = (uint32_t)key[k];
+                        const uint32_t sb = (h >> 31) ? ~l : l;
+                        orb |= h;
+                        esum += sb >> 23;
+                        ecnt += sb ? 1u : 0u;
+                    }
+                }
+#pragma unroll
+                for (int o = 32; o >= 1; o >>= 1) {
+                    orb |= (uint32_t)__shfl_xor((int)orb, o, 64);
+                    esum += (uint32_t)__shfl_xor((int)esum, o, 64);
+                    ecnt += (uint32_t)__shfl_xor((int)ecnt, o, 64);
+                }
+                if ((tid & 63) == 0) {
+                    wor[tid >> 6] = orb;
+                    sex[tid >> 6] = esum;
+                    scn[tid >> 6] = ecnt;
+                }
+            }
             __syncthreads();
             const int nw = nth >> 6;
             float lo = INFINITY, hi = -INFINITY;
             uint32_t any = 0;
+            {
+                uint32_t orb = 0u, esum = 0u, ecnt = 0u;
+                for (int w2 = 0; w2 < nw; ++w2) {
+                    orb |= wor[w2];
+                    esum += sex[w2];
+                    ecnt += scn[w2];
+                }
+                // clear low bits of the mantissa only (a row of zeros and powers of two would clear more), 16 at
+                // most; fewer than 8 leave the values distinct enough
+                int kz = orb ? min(__builtin_ctz(orb), 16) : 0;
+                if (kz < 8) kz = 0;
+                const int emean = ecnt ? (int)(esum / ecnt) : 127;
+                // (the same in every lane: kept in scalar registers)
+                map.lowmask = (uint32_t)__builtin_amdgcn_readfirstlane((int)((1u << kz) - 1u));
+                map.sbm = (uint32_t)__builtin_amdgcn_readfirstlane((int)(((uint32_t)emean << 23) + (1u << 22)));
+            }
+            if (map.lowmask) {
+                // the fill table: counts of s per piece (16 copies of the counters, in the space of the value
+                // bins' counters, which are cleared again below), running sums scaled to the fill values
+                uint32_t *sh = (uint32_t *)(smem + prm.bk_hist_off);
+                uint32_t *stabw = (uint32_t *)(smem + prm.bk_misc_off + BK_STAB);
+                for (int i = tid; i < STAB_N * 16; i += nth) sh[i] = 0u;
+                __syncthreads();
+#pragma unroll
+                for (int k = 0; k < NS; ++k) {
+                    if (sm.has(k)) {
+                        const uint32_t h = (uint32_t)(key[k] >> 32), l = (uint32_t)key[k];
+                        int idx;
+                        uint32_t f16;
+                        fill_piece((h >> 31) ? ~l : l, map.sbm, idx, f16);
+                        atomicAdd(&sh[idx * 16 + (tid & 15)], 1u);
+                    }
+                }
+                __syncthreads();
+                if (tid < 64) {
+                    uint32_t c = 0u;
+                    for (int q = 0; q < 16; ++q) c += sh[tid * 16 + q];
+                    const uint32_t inc = wave_scan_incl(c);
+                    // share of the keys below piece tid, in fill values (m <= 32768, the mask <= 65535: no overflow)
+                    stabw[tid] = (uint32_t)(((unsigned long long)(inc - c) * (map.lowmask + 1u)) / (uint32_t)m);
+                    if (tid == 63) stabw[64] = map.lowmask + 1u;
+                }
+                __syncthreads();
+            }
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const float4 a = ((const float4 *)wmin)[q], b4 = ((const float4 *)wmax)[q];
@@ -849,7 +967,7 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     }
     // (a segment of a long row cannot tell on its own: it records what it saw for merge_tile_kernel)
     if (prm.nseg > 1 && tid == 0) prm.segmass[work] = anymass;
-    if (!sorted_ok) {
+    if (!sorted_ok) {      // (no branch hint here: with one the compiler runs the 12-slot variant out of registers)
         // The bitonic network over the whole padded row.  Its keys overlay the bucket path's tables: wait
         // until every thread is done with them.  The bucket path gave its key registers away, so the
         // unit is read and encoded once more, and the next unit fetched again after it (rare).

@@ -188,6 +188,64 @@ def test_row_stride(ctx):
     assert rel_close(out["E"].cpu().numpy()[clean], ref["E"][clean]).all()
 
 
+def test_many_rows_of_repeated_values_take_the_network_row_after_row(ctx):
+    """Every row holds 24 distinct weights, each about ten times over: the value bins of the sort overflow in
+    every row, so every row of a workgroup is attempted by the bucket path, dropped, and sorted by the network
+    (there are many more rows than resident workgroups).  Results must not depend on which path sorted a row or
+    on what the row before it left behind."""
+    n, m = 30000, 256
+    rng = np.random.default_rng(77)
+    vals = (rng.standard_normal((n, 24)) * 0.02).astype(np.float32)
+    pick = rng.integers(0, 24, (n, m))
+    W = np.take_along_axis(vals, pick, axis=1)
+    S = (rng.standard_normal((n, m)) ** 2).astype(np.float32)
+    rows = np.r_[0:64, 14000:14064, n - 64:n]      # the oracle's comparison on a sample of rows, the GPU on all
+    out = ctx.error_table(dev(W), dev(S))
+    torch.cuda.synchronize()
+    ref = oracle.error_table(W[rows], S[rows], count_near=True)
+    E = out["E"].cpu().numpy()[rows]
+    ca = out["centroids_all"].cpu().numpy()[rows]
+    ua = out["upper_all"].cpu().numpy()[rows]
+    st = parity_util.compare_table(W[rows], S[rows], None, ref, E, ca, ua)
+    assert st["clean"].mean() > 0.5, "too few entries compared exactly"
+    # the same rows on their own (one row per workgroup: the first attempt of the bucket path, then the network)
+    alone = ctx.error_table(dev(W[rows]), dev(S[rows]))
+    torch.cuda.synchronize()
+    assert np.array_equal(alone["E"].cpu().numpy(), E)
+    assert np.array_equal(alone["upper_all"].cpu().numpy(), ua)
+    assert np.array_equal(alone["centroids_all"].cpu().numpy(), ca)
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "fp16"])
+def test_weights_converted_from_a_16_bit_format(ctx, fmt):
+    """Weights that were rounded to bfloat16 / float16 and widened again: every row holds each value many times
+    over, and the sort spreads equal weights over its value bins by their sensitivity.  Rows long enough to fill
+    the bins, more rows than workgroups (so that the carried bin map is exercised), oracle on a sample of rows."""
+    n, m = 600, 11008
+    rng = np.random.default_rng(5)
+    W = (rng.standard_normal((n, m)) * 0.02).astype(np.float32)
+    mask = rng.random((n, m)) < 0.005
+    W = np.where(mask, (rng.standard_normal((n, m)) * 0.2).astype(np.float32), W)
+    if fmt == "bf16":
+        W = torch.from_numpy(W).bfloat16().float().numpy()
+    else:
+        W = W.astype(np.float16).astype(np.float32)
+    S = (rng.standard_normal((n, m)) ** 2).astype(np.float32)
+    S[5, ::3] = 0.0                                   # sensitivities with exact zeros in one row
+    W[7] = -np.abs(W[7])                              # a row of negative weights only
+    out = ctx.error_table(dev(W), dev(S))
+    torch.cuda.synchronize()
+    rows = np.r_[0:24, 300:316, n - 8:n]
+    ref = oracle.error_table(W[rows], S[rows], count_near=True)
+    st = parity_util.compare_table(W[rows], S[rows], None, ref, out["E"].cpu().numpy()[rows],
+                                   out["centroids_all"].cpu().numpy()[rows], out["upper_all"].cpu().numpy()[rows])
+    # (repeated values make exact ties common: the oracle excuses most entries above one bit, and those are held
+    # to the self-consistency checks; the one-bit entries and the rest are compared exactly)
+    assert st["clean"].mean() > 0.1, "too few entries compared exactly"
+    bits = rng.integers(1, 5, len(rows)).astype(np.uint8)
+    check_rows(ctx, W[rows], S[rows], bits)
+
+
 def test_pack_mixed_bits_matches_oracle_layout(ctx):
     n, m = 97, 1111
     W, S = skim_synth.make_ws_small(80, n, m)
