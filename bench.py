@@ -389,11 +389,15 @@ def main():
 
 def bench_other_shapes(ctx, torch, reps=3):
     """The error-table call on the other matrix shapes of the workload configs (values drawn on the device: normal
-    weights, squared-normal sensitivities; timing only)."""
+    weights, squared-normal sensitivities; timing only), and on the metric shape with weights that were rounded to
+    float16 / bfloat16 first, as the weights of a released model are (every value then occurs many times in a row)."""
     res = []
     gen = torch.Generator(device="cuda").manual_seed(1)
-    for n, m in ((4096, 4096), (11008, 4096), (22016, 8192), (8192, 22016)):
+    for n, m, fmt in ((4096, 4096, None), (11008, 4096, None), (22016, 8192, None), (8192, 22016, None),
+                      (4096, 11008, "float16"), (4096, 11008, "bfloat16")):
         W = torch.randn(n, m, device="cuda", generator=gen) * 0.02
+        if fmt is not None:
+            W = W.to(getattr(torch, fmt)).float()
         S = torch.randn(n, m, device="cuda", generator=gen) ** 2
         out = ctx.error_table(W, S, iters=ITERS)
         torch.cuda.synchronize()
@@ -403,8 +407,11 @@ def bench_other_shapes(ctx, torch, reps=3):
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) / reps * 1e3
         so, ll = ctx.profile_last()
-        res.append({"rows": n, "cols": m, "table_ms": round(ms, 4), "sort_ms": round(so, 4),
-                    "iterations_ms": round(ll, 4), "Gweights_per_s": round(n * m / ms / 1e6, 1)})
+        entry = {"rows": n, "cols": m, "table_ms": round(ms, 4), "sort_ms": round(so, 4),
+                 "iterations_ms": round(ll, 4), "Gweights_per_s": round(n * m / ms / 1e6, 1)}
+        if fmt is not None:
+            entry["weights_rounded_to"] = fmt
+        res.append(entry)
         del W, S, out
     return res
 
