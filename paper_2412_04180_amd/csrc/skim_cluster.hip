@@ -989,12 +989,20 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
             if (sm.col(k) < prm.P) sorted[swz((uint32_t)sm.col(k))] = key[k];
         for (int j = tid + NS * nth; j < prm.P; j += nth) sorted[swz((uint32_t)j)] = PAD_KEY;   // padding no slot covers
         __syncthreads();
-        switch (prm.logP) {
-            case 10: sort_row<10>((double *)sorted, (uint32_t)tid, m); break;
-            case 11: sort_row<11>((double *)sorted, (uint32_t)tid, m); break;
-            case 12: sort_row<12>((double *)sorted, (uint32_t)tid, m); break;
-            case 13: sort_row<13>((double *)sorted, (uint32_t)tid, m); break;
-            default: sort_row<14>((double *)sorted, (uint32_t)tid, m); break;
+        // (the variants with 16-byte loads serve fixed ranges of the padded length: 8 slots up to 8192 keys, 12 and
+        // 16 slots 16384; only the networks a variant can be asked for are compiled into it)
+        if constexpr (VEC && NS > 8) {
+            sort_row<14>((double *)sorted, (uint32_t)tid, m);
+        } else {
+            switch (prm.logP) {
+                case 10: sort_row<10>((double *)sorted, (uint32_t)tid, m); break;
+                case 11: sort_row<11>((double *)sorted, (uint32_t)tid, m); break;
+                case 12: sort_row<12>((double *)sorted, (uint32_t)tid, m); break;
+                case 13: sort_row<13>((double *)sorted, (uint32_t)tid, m); break;
+                default:
+                    if constexpr (!VEC) sort_row<14>((double *)sorted, (uint32_t)tid, m);
+                    break;
+            }
         }
         fetch_unit<NS, VEC>(prm, more ? work + gridDim.x : work, tid, nth, pw, ps, more);
     }
@@ -2400,6 +2408,9 @@ skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n, bool so
                      (prm.seglen % 4 == 0);
     const int per_thread = (prm.seglen + threads - 1) / threads;
     const int variant = !vec ? 3 : (per_thread <= 8 ? 0 : (per_thread <= 12 ? 1 : 2));
+    // (what the kernel variants rely on for the networks compiled into them)
+    if ((variant == 0 && prm.logP > 13) || ((variant == 1 || variant == 2) && prm.logP != 14))
+        SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "internal: sort variant %d does not serve a padded length of 2^%d", variant, prm.logP);
     size_t lds = sort_lds_bytes(prm.P);
     if ((int64_t)lds > ctx->lds_limit)
         SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "row length %d needs %zu bytes of LDS, device allows %d", prm.m, lds, ctx->lds_limit);
