@@ -1529,7 +1529,7 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
         int ilo = lane_below(idx);
         {   // keep positions ordered by (value, cluster index)
             const bool ok = done || (p == 0) || (vlo < v) || (vlo == v && ilo < idx);
-            if (__ballot(!ok)) {
+            if (__builtin_expect(__ballot(!ok) != 0, 0)) {
                 int rank = 0;
                 for (int k = 0; k < 16; ++k) {
                     const double vq = shfl_d(v, from_pos(k));
@@ -1555,7 +1555,7 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
         int rep = idx;       // lowest cluster index among the positions sharing this value
         int replo = ilo;
         const bool anydup = __ballot(dup) != 0;
-        if (anydup) {
+        if (__builtin_expect(anydup, 0)) {
             int rs = p;      // first position of this position's run of equal values
             for (int k = 1; k < 16; ++k) {
                 const int dk = __shfl((int)dup, from_pos(k), 64);
@@ -1627,7 +1627,7 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
         // keys of that chunk below the boundary; a position that repeats the value below it owns
         // nothing and passes on what the next distinct position shows
         int xcl = cl;
-        if (anydup) {
+        if (__builtin_expect(anydup, 0)) {
             if (dup) xcl = (p == K - 1) ? n1u : -2;
             for (int k = 14; k >= 1; --k) {
                 const int nx = __shfl(xcl, from_pos(k + 1), 64);
@@ -1679,7 +1679,7 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
         }
         if (cl < 0) tc = 0;
         Bcur = (searching && cl >= 0) ? rbase + tc : 0;  // p == 0 or no chunk below the boundary: 0
-        if (anydup) {
+        if (__builtin_expect(anydup, 0)) {
             // a position sharing its value with the one before it owns nothing:
             // its range starts where the next distinct value's range starts
             if (dup) Bcur = (p == K - 1) ? m : -1;
@@ -1721,7 +1721,7 @@ __global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams 
             D += shd;
             N = fma(shd, wd, N);
         }
-        if (anydup) {
+        if (__builtin_expect(anydup, 0)) {
             double xd = lowD, xn = lowN;
             int tag = dup ? ((p == K - 1) ? 1 : -2) : 0;   // -2: waiting for the next distinct position
             if (dup) { xd = 0.0; xn = 0.0; }
