@@ -1145,7 +1145,11 @@ __global__ void __launch_bounds__(MG_THREADS) merge_tile_kernel(ClusterParams pr
             if (!(r & (1 << rb))) ce(v[r], v[r | (1 << rb)]);
     }
     const bool unit = (prm.segmass[row * 2] | prm.segmass[row * 2 + 1]) == 0;
-    u64 *keys = prm.keys + row * (long long)m + o0 + d;
+    // the merged keys go back to LDS (every thread has read what it needs: barrier) and from there to global
+    // memory with consecutive lanes on consecutive keys (16 keys per thread written in place would put the 64
+    // lanes of a store on 64 different lines)
+    __syncthreads();
+    u64 *obuf = (u64 *)buf;
     double c = 0.0, q = 0.0, r2 = 0.0;
     float w0 = 0.0f;
 #pragma unroll
@@ -1154,7 +1158,7 @@ __global__ void __launch_bounds__(MG_THREADS) merge_tile_kernel(ClusterParams pr
         if (e < cnt) {
             el = (u64)__double_as_longlong(v[e]);
             if (unit) el = unit_weight_key(el);
-            keys[e] = plain_key(el);
+            obuf[swz((uint32_t)(d + e))] = plain_key(el);
         }
         const double sv = (double)elem_s(el), wv = (double)elem_w(el);
         if (e == 0) w0 = elem_w(el);
@@ -1173,6 +1177,9 @@ __global__ void __launch_bounds__(MG_THREADS) merge_tile_kernel(ClusterParams pr
         prm.Q[row * prm.nq + (ch >> 2)] = make_double2(c4, q4);
         prm.RQ[row * prm.nq + (ch >> 2)] = r4;
     }
+    __syncthreads();
+    u64 *keys = prm.keys + row * (long long)m + o0;
+    for (int x = tid; x < T; x += MG_THREADS) keys[x] = obuf[swz((uint32_t)x)];
 }
 
 // ---------------------------------------------------------------------------------------------
