@@ -310,7 +310,7 @@ __device__ __forceinline__ int quad_sum(int x) {
 
 // ---------------------------------------------------------------------------------------------
 // Bucket path of the sort.  A full sorting network pays for the worst case; the rows here are m
-// draws from a smooth density, so a monotone map from the weight to one of about 2m value bins
+// draws from a smooth density, so a monotone map from the weight to one of about 1.5 m value bins
 // leaves a handful of keys per bin, and a counting sort by bin puts every key within a few slots
 // of its final rank in one scatter.  What remains is order inside the bins:
 //   * every thread sorts the 16 slots [16t, 16t+16) in registers (Batcher's odd-even merge sort,
@@ -318,7 +318,7 @@ __device__ __forceinline__ int quad_sum(int x) {
 //   * a bin that straddles a multiple of 16 has at most 8 keys on either side when no bin holds
 //     more than 8 keys, so one 8+8 merge of the upper half of window t with the lower half of
 //     window t+1 (25 compare-exchanges) finishes the row.
-// The bin map has two levels so that it adapts to the row: a coarse histogram over nth equal
+// The bin map has two levels so that it adapts to the row: a coarse histogram over COARSE_N equal
 // intervals of [min, max], then every coarse interval is cut into a number of equal bins
 // proportional to its count (a piecewise linear estimate of the distribution function).  Any
 // monotone map gives a correct sort; the map only decides how full the bins get.  A row in which
@@ -405,7 +405,7 @@ constexpr int STAB_N = 64;        // pieces of the fill table: a quarter octave 
 
 // The bin map a workgroup carries from one unit to the next: the axis of the coarse intervals and whether the
 // table in LDS (bins per interval) is valid and the fine counters are zero.  The first unit of a workgroup
-// builds the map from a sample of its own keys; every later unit is binned with the map the unit before it
+// builds the map from its own keys; every later unit is binned with the map the unit before it
 // left behind, whose table was re-derived from that unit's exact counts -- rows of one matrix resemble each
 // other, and any monotone map sorts correctly.  A unit that overflows a bin (it then sorts by the network)
 // drops the map, and the next unit builds its own.
@@ -514,7 +514,6 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
     if (__builtin_expect(!map.have, 0)) {
         // ---- coarse histogram of the unit's keys (a sample of every fourth key was tried: its table overflowed a
         // bin several times as often, and a unit that takes the network leaves the next without a map again)
-        const int nsample = m;
 #pragma unroll
         for (int k = 0; k < NS; ++k) {
             if (sm.has(k)) {
@@ -539,7 +538,7 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
             const uint4 t = cc4[4 * lane + q];
             c[q] = (float)(t.x + t.y + t.z + t.w);
         }
-        write_bin_table(table, lane, c, (float)(nbins - COARSE_N - 16) / (4.0f * (float)nsample));
+        write_bin_table(table, lane, c, (float)(nbins - COARSE_N - 16) / (4.0f * (float)m));
     }
     // ---- fine bin of every key; the counter's old value is the key's slot inside its bin
     uint32_t fbs[NS];
