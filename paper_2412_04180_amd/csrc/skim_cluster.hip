@@ -1291,8 +1291,11 @@ __device__ __forceinline__ double quick_div(double n, double d) {
 }
 
 // RAGGED: the row length is not a multiple of 16, so the last chunk holds fewer than 16 keys.
-template <bool RAGGED>
-__global__ void __launch_bounds__(ITER_THREADS) lloyd_iter_kernel(ClusterParams prm, long long nrows, LevelMap LM) {
+// WAVES: wavefronts per SIMD the kernel is compiled for.  2 needs no spills (187 registers); when a matrix has more
+// rows than 2 per SIMD can hold at once, 3 (168 registers, about 70 of them spilled) finishes sooner all the same.
+template <bool RAGGED, int WAVES>
+__global__ void __launch_bounds__(ITER_THREADS) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))
+lloyd_iter_kernel(ClusterParams prm, long long nrows, LevelMap LM) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int m = prm.m;
     const int n1u = (m + 15) >> 4;   // LM = level_map(n1u), worked out by the host
@@ -2485,12 +2488,21 @@ skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n, bool so
     }
     if (ctx->profiling) SKIM_HIP(ctx, hipEventRecord(ctx->ev[1], ctx->stream));
     const LevelMap lm = level_map((prm.m + 15) >> 4);
-    if (prm.m & 15)
-        hipLaunchKernelGGL(lloyd_iter_kernel<true>, dim3((unsigned)((n + 1) / 2)), dim3(ITER_THREADS),
-                           lloyd_lds_bytes(prm.m), ctx->stream, prm, (long long)n, lm);
-    else
-        hipLaunchKernelGGL(lloyd_iter_kernel<false>, dim3((unsigned)((n + 1) / 2)), dim3(ITER_THREADS),
-                           lloyd_lds_bytes(prm.m), ctx->stream, prm, (long long)n, lm);
+    {
+        // two wavefronts per SIMD = 8 workgroups per compute unit; three when that cannot hold all rows at once and
+        // the LDS has room for 12 workgroups
+        const size_t llds = lloyd_lds_bytes(prm.m);
+        const long long wgs = (n + 1) / 2;
+        const bool three = wgs > 8ll * ctx->num_cu && (size_t)ctx->lds_limit / (llds + 256) >= 12;
+        const dim3 grid((unsigned)wgs), block(ITER_THREADS);
+        if (prm.m & 15) {
+            if (three) hipLaunchKernelGGL((lloyd_iter_kernel<true, 3>), grid, block, llds, ctx->stream, prm, (long long)n, lm);
+            else hipLaunchKernelGGL((lloyd_iter_kernel<true, 2>), grid, block, llds, ctx->stream, prm, (long long)n, lm);
+        } else {
+            if (three) hipLaunchKernelGGL((lloyd_iter_kernel<false, 3>), grid, block, llds, ctx->stream, prm, (long long)n, lm);
+            else hipLaunchKernelGGL((lloyd_iter_kernel<false, 2>), grid, block, llds, ctx->stream, prm, (long long)n, lm);
+        }
+    }
     hipLaunchKernelGGL(finish_kernel, dim3((unsigned)n), dim3(FIN_THREADS), 0, ctx->stream, prm);
     if (ctx->profiling) {
         SKIM_HIP(ctx, hipEventRecord(ctx->ev[2], ctx->stream));
