@@ -1667,12 +1667,17 @@ lloyd_iter_kernel(ClusterParams prm, long long nrows, LevelMap LM) {
             cl_held = cl_want;
         }
         const int la0 = min(b0, (a0 + 3) & ~3), rb0 = max(la0, b0 & ~3);
+        // (with two wavefronts per SIMD the pieces are requested here, ahead of the work on the keys; with three
+        // there are no registers to park them in, and a third wavefront to wait behind)
         double2 pc[6];
+        auto load_pieces = [&]() {
 #pragma unroll
-        for (int k = 0; k < 3; ++k) {
-            pc[k] = (a0 + k < la0) ? L1[a0 + k] : make_double2(0.0, 0.0);
-            pc[3 + k] = (rb0 + k < b0) ? L1[rb0 + k] : make_double2(0.0, 0.0);
-        }
+            for (int k = 0; k < 3; ++k) {
+                pc[k] = (a0 + k < la0) ? L1[a0 + k] : make_double2(0.0, 0.0);
+                pc[3 + k] = (rb0 + k < b0) ? L1[rb0 + k] : make_double2(0.0, 0.0);
+            }
+        };
+        if (WAVES <= 2) load_pieces();
 
         int tc = 0;
         if (RAGGED) {
@@ -1743,6 +1748,7 @@ lloyd_iter_kernel(ClusterParams prm, long long nrows, LevelMap LM) {
             lowD = xd;
             lowN = xn;
         }
+        if (WAVES > 2) load_pieces();
         double nD = lane_above(lowD), nN = lane_above(lowN);
         if (p == K - 1 || cl_next <= cl) { nD = 0.0; nN = 0.0; }
         D += nD;
