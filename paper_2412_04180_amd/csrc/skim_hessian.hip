@@ -3,6 +3,7 @@
 // H = X^T X / N, m x m).  bf16 inputs, bf16 MFMA (v_mfma_f32_32x32x16_bf16) with float32
 // accumulation over chunks of 2048 activations, the chunks added up in float64.
 #include "skim_common.h"
+#include <type_traits>
 
 namespace {
 
@@ -51,19 +52,22 @@ __device__ __forceinline__ void load_task(const uint16_t *__restrict__ X, long l
         s.r[t][0] = v.x; s.r[t][1] = v.y; s.r[t][2] = v.z; s.r[t][3] = v.w;
     }
 }
-__device__ __forceinline__ void store_task(XTile &T, int st, const Staged &s) {
+// columns [cb, ce) of the task's 8 (compile-time bounds once the caller's loop is unrolled)
+__device__ __forceinline__ void store_cols(uint16_t (*T)[HK_PAD], int st, const Staged &s, int cb, int ce) {
     const int ab = st & 7, cg = st >> 3;
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
+        if (c < cb || c >= ce) continue;
         uint32_t o[4];
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
             const uint32_t a = s.r[2 * d][c >> 1], b = s.r[2 * d + 1][c >> 1];
             o[d] = (c & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
         }
-        *(uint4 *)&T.t[8 * cg + c][8 * ab] = make_uint4(o[0], o[1], o[2], o[3]);
+        *(uint4 *)&T[8 * cg + c][8 * ab] = make_uint4(o[0], o[1], o[2], o[3]);
     }
 }
+__device__ __forceinline__ void store_task(XTile &T, int st, const Staged &s) { store_cols(T.t, st, s, 0, 8); }
 
 __global__ void __launch_bounds__(H_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) xtx_kernel(const uint16_t *__restrict__ X, long long N, long long m,
                                                         float *__restrict__ H, int vec) {
@@ -141,6 +145,173 @@ __global__ void __launch_bounds__(H_THREADS) __attribute__((amdgpu_waves_per_eu(
             }
 }
 
+// ---- the kernel for large m: 256 x 256 output tile, one workgroup per CU ---------------------------------------
+// Four wavefronts, each a 128 x 128 quarter (4 x 4 accumulator tiles of 32 x 32: 256 accumulator registers, one
+// wavefront per SIMD), so an MFMA operand read from LDS feeds four MFMAs instead of two and a byte fetched from L2
+// feeds twice the arithmetic of the 128 x 128 kernel.  Two register sets stage the X tiles: the loads of tile
+// kt + 3 are issued in step kt and stored to LDS in step kt + 2, between the MFMAs of that step, so neither the
+// memory latency nor the transposes stand between two steps.  The float32 accumulators are added into H itself
+// (float32, read-modify-write by the one thread that owns the entry) every 8192 activations: the sums over a
+// chunk carry at most 512 roundings at 1/16 or less of the total each, the 16 chunk additions of 131072
+// activations one rounding each -- a few 1e-6 of sqrt(H_jj H_ll) in the worst case.
+constexpr int BT = 256;
+constexpr int B_THREADS = 256;
+constexpr int B_FLUSH_TILES = 128;
+struct BTile {
+    uint16_t t[BT][HK_PAD];
+};
+constexpr size_t B_LDS_BYTES = 4 * sizeof(BTile);     // two operands, double-buffered: 147456 bytes
+
+// 16-byte loads of one task (8 activations x 8 columns) from rows k0 + 8 ab + t; CHECK: rows past N read as zero
+template <bool CHECK>
+__device__ __forceinline__ void load_rows(const uint16_t *__restrict__ p, long long m, long long krem, Staged &s) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (!CHECK || t < krem) v = *(const uint4 *)(p + t * m);
+        s.r[t][0] = v.x; s.r[t][1] = v.y; s.r[t][2] = v.z; s.r[t][3] = v.w;
+    }
+}
+
+// Needs m % 8 == 0 and X 16-byte aligned (every 8-column group of a row is one aligned 16-byte load).
+__global__ void __launch_bounds__(B_THREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
+xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *__restrict__ H, int nt) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    BTile *TI = (BTile *)smem, *TJ = TI + 2;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    // Workgroup -> tile.  Consecutive workgroup ids go to the 8 XCDs in turn; the ids one XCD receives are mapped
+    // to consecutive tiles of a band-by-band order (bands of 8 tile rows, column by column inside a band), so the
+    // workgroups that share an L2 at any time share operand panels: 32 of them cover 8 x 4 tiles, 12 panels for 64
+    // panel uses.
+    long long v = blockIdx.x;
+    const long long total = (long long)nt * nt;
+    if ((total & 7) == 0) v = (v & 7) * (total >> 3) + (v >> 3);
+    const int band = (int)(v / (8ll * nt));
+    const int hb = min(8, nt - 8 * band);
+    const int inb = (int)(v - 8ll * nt * band);
+    const long long i0 = (long long)(8 * band + inb % hb) * BT, j0 = (long long)(inb / hb) * BT;
+
+    floatx16 acc[4][4];
+
+    // staging: thread tid moves activations 8 ab .. + 7, columns 8 cg .. + 7 of either operand tile.  A column group
+    // past the matrix reads the tile's first group instead: its products only reach entries (i >= m or j >= m)
+    // that are never stored.  Rows past N (last tile only) read as zero.
+    const int ab = tid & 7, cg = tid >> 3;
+    const uint16_t *pi = X + (long long)(8 * ab) * m + (i0 + 8 * cg < m ? i0 + 8 * cg : i0);
+    const uint16_t *pj = X + (long long)(8 * ab) * m + (j0 + 8 * cg < m ? j0 + 8 * cg : j0);
+    // The activations are cut into 64-row tiles from the end: the first one is the short one, rows [0, r0) with
+    // r0 = N - 64 (nreal - 1) in 1 .. 64, zero-padded to 64.  An all-zero tile goes in front when that makes the
+    // count even, so the loop below runs whole pairs of steps and, from tile 2 on, loads full tiles without
+    // looking at N.
+    const long long nreal = (N + HK - 1) / HK;          // >= 2: the host sends N >= 128 here
+    const int odd = (int)(nreal & 1);
+    const long long ntile = nreal + odd;
+    const long long r0 = N - (nreal - 1) * HK;
+    Staged si[2], sj[2];         // two tiles on their way from global memory to LDS: tile t in set t & 1
+    auto load_tile = [&](long long kt, Staged &di, Staged &dj) {
+        const long long k0 = r0 + (kt - 1 - odd) * HK;
+        load_rows<false>(pi + k0 * m, m, 0, di);
+        load_rows<false>(pj + k0 * m, m, 0, dj);
+    };
+    if (odd) {
+        load_rows<true>(pi, m, 0, si[0]);                  // no rows: zeros
+        load_rows<true>(pj, m, 0, sj[0]);
+        load_rows<true>(pi, m, r0 - 8 * ab, si[1]);
+        load_rows<true>(pj, m, r0 - 8 * ab, sj[1]);
+    } else {
+        load_rows<true>(pi, m, r0 - 8 * ab, si[0]);
+        load_rows<true>(pj, m, r0 - 8 * ab, sj[0]);
+        load_tile(1, si[1], sj[1]);
+    }
+    store_cols(TI[0].t, tid, si[0], 0, 8);
+    store_cols(TJ[0].t, tid, sj[0], 0, 8);
+    __syncthreads();
+    const double inv = 1.0 / (double)N;
+
+    // one step: first the loads of tile kt + 2 are issued (into the register set tile kt left when it went to LDS
+    // in the step before), then the MFMAs of tile kt (LDS buffer PAR); during the second half tile kt + 1, requested
+    // a step and a half ago, goes from its registers into the other buffer
+    auto step = [&](auto par_c, auto fresh_c, long long kt) {
+        constexpr int PAR = decltype(par_c)::value;
+        constexpr bool FRESH = decltype(fresh_c)::value;     // first step of a chunk: the sums start from zero
+        load_tile(min(kt + 2, ntile - 1), si[PAR], sj[PAR]);     // (past the end: the last tile again, unused)
+#pragma unroll
+        for (int ks = 0; ks < HK / 16; ++ks) {
+            const int kk = 16 * ks + 8 * lhi;
+            bf16x8 a[4], b[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                a[x] = *(const bf16x8 *)&TI[PAR].t[wr * 128 + 32 * x + l32][kk];
+                b[x] = *(const bf16x8 *)&TJ[PAR].t[wc * 128 + 32 * x + l32][kk];
+            }
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+#pragma unroll
+                for (int y = 0; y < 4; ++y) {
+                    if (FRESH && ks == 0) {
+                        floatx16 zero;
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) zero[e] = 0.f;
+                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[x], b[y], zero, 0, 0, 0);
+                    } else {
+                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[x], b[y], acc[x][y], 0, 0, 0);
+                    }
+                }
+            if (ks >= 2) {      // (after the last tile this stores a repeat of the last tile: harmless, never read)
+                store_cols(TI[PAR ^ 1].t, tid, si[PAR ^ 1], 4 * (ks - 2), 4 * (ks - 2) + 4);
+                store_cols(TJ[PAR ^ 1].t, tid, sj[PAR ^ 1], 4 * (ks - 2), 4 * (ks - 2) + 4);
+            }
+            __builtin_amdgcn_sched_barrier(0);      // operands of one k-slice at a time: the scheduler would fetch all four early
+        }
+        __syncthreads();
+    };
+    for (long long c0 = 0; c0 < ntile; c0 += B_FLUSH_TILES) {
+        const long long cend = min(c0 + (long long)B_FLUSH_TILES, ntile);
+        // (c0 is even: tile kt sits in LDS buffer kt & 1)
+        // (whole pairs: a second step under a condition would have the loads of the first, which only it uses,
+        // sunk into that condition by the compiler, a whole step late)
+        step(std::integral_constant<int, 0>{}, std::true_type{}, c0);
+        step(std::integral_constant<int, 1>{}, std::false_type{}, c0 + 1);
+        for (long long kt = c0 + 2; kt < cend; kt += 2) {
+            step(std::integral_constant<int, 0>{}, std::false_type{}, kt);
+            step(std::integral_constant<int, 1>{}, std::false_type{}, kt + 1);
+        }
+        // the chunk's sums go into H.  Accumulator element e of a 32 x 32 tile: row = 8*(e/4) + 4*(lane/32) + e%4,
+        // column = lane%32.  Straight-line code, one accumulator tile at a time: an entry outside the matrix is
+        // turned into "add nothing to this thread's first entry" instead of a branch (with a branch per entry the
+        // compiler copies all 256 accumulators out at once and spills what the MFMA loop keeps in registers).
+        // (The empty asm keeps the address arithmetic of this rare block inside it.)
+        const bool first = c0 == 0, last = cend == ntile;
+        const long long ib = i0 + wr * 128 + 4 * lhi, jb = j0 + wc * 128 + l32;
+        float *hp = H + ib * m + jb;
+        long long mm = m;
+        int rlim = (int)min(m - ib, 4096ll), clim = (int)min(m - jb, 4096ll);   // valid rows / columns from (ib, jb) on
+        double scale = last ? inv : 1.0;
+        asm volatile("" : "+v"(hp), "+s"(mm), "+v"(rlim), "+v"(clim), "+v"(scale));
+        if (rlim > 0 && clim > 0) {
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+#pragma unroll
+                for (int y = 0; y < 4; ++y) {
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int r = x * 32 + 8 * (e >> 2) + (e & 3), c = y * 32;
+                        const bool valid = r < rlim && c < clim;
+                        float *q = valid ? hp + r * mm + c : hp;
+                        const float old = *q;
+                        float av;       // read here and now, not copied out ahead with the other 255
+                        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(av) : "a"(acc[x][y][e]));
+                        const float t = (first ? 0.f : old) + av;
+                        *q = valid ? (float)((double)t * scale) : old;
+                    }
+                }
+        }
+    }
+}
+
 }  // namespace
 
 extern "C" skim_status skim_hessian_from_activations(skim_ctx *ctx, const uint16_t *X_bf16, int64_t N, int64_t m,
@@ -155,8 +326,21 @@ extern "C" skim_status skim_hessian_from_activations(skim_ctx *ctx, const uint16
         SKIM_HIP(ctx, hipFuncSetAttribute((const void *)xtx_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)H_LDS_BYTES));
         ctx->xtx_lds_enabled = 1;
     }
-    const unsigned nt = (unsigned)((m + HT - 1) / HT);
     const int vec = (m % 8 == 0) && (((uintptr_t)X_bf16 & 15) == 0);     // rows of X start 16-byte aligned
+    // 256 x 256 tiles once they fill most of the chip (m >= 3584 on 256 CUs); smaller m takes the 128 x 128 kernel
+    const long long ntb = (m + BT - 1) / BT;
+    if (vec && N >= 2 * HK && ntb * ntb >= (long long)ctx->num_cu * 3 / 4) {
+        if (ctx->xtx_lds_enabled < 2) {
+            SKIM_HIP(ctx, hipFuncSetAttribute((const void *)xtx_big_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)B_LDS_BYTES));
+            SKIM_HIP(ctx, hipFuncSetAttribute((const void *)xtx_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)H_LDS_BYTES));
+            ctx->xtx_lds_enabled = 2;
+        }
+        hipLaunchKernelGGL(xtx_big_kernel, dim3((unsigned)(ntb * ntb)), dim3(B_THREADS), B_LDS_BYTES, ctx->stream, X_bf16,
+                           (long long)N, (long long)m, H, (int)ntb);
+        SKIM_HIP(ctx, hipGetLastError());
+        return SKIM_OK;
+    }
+    const unsigned nt = (unsigned)((m + HT - 1) / HT);
     hipLaunchKernelGGL(xtx_kernel, dim3(nt, nt), dim3(H_THREADS), H_LDS_BYTES, ctx->stream, X_bf16, (long long)N,
                        (long long)m, H, vec);
     SKIM_HIP(ctx, hipGetLastError());

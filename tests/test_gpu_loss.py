@@ -183,10 +183,15 @@ def test_train_scale_is_the_composition_of_its_steps_and_tracks_the_oracle(ctx, 
     assert ref["loss_trace"][-1] < ref["loss_trace"][0]
 
 
-@pytest.mark.parametrize("N,m", [(40, 12), (300, 130), (1000, 256), (4096, 640)])
+@pytest.mark.parametrize("N,m", [(40, 12), (300, 130), (1000, 256), (4096, 640),
+                                 # wide layers take the kernel with 256 x 256 tiles: a last tile of 8 columns and a
+                                 # short first slice of activations; two accumulation chunks; a tile count that is
+                                 # no multiple of 8; the fewest activations that kernel takes
+                                 (200, 3592), (8200, 3840), (128, 4096)])
 def test_hessian_from_activations_matches_oracle(ctx, N, m):
     """H = X^T X / N from bfloat16 activations against the float64 definition: every entry within 1e-5 of the
-    entry's natural scale sqrt(H_jj H_ll) (float32 accumulation over 512 activations, float64 across chunks)."""
+    entry's natural scale sqrt(H_jj H_ll) (float32 accumulation within a chunk of activations; across chunks
+    float64 in the 128 x 128 kernel, float32 -- at most a few dozen additions -- in the 256 x 256 one)."""
     X = np.concatenate(list(skim_synth.make_x(3, N, m)))        # float32 values that are exact in bfloat16
     ref = oracle.hessian_from_activations(X).astype(np.float64)
     Xb = torch.from_numpy(X).cuda().to(torch.bfloat16)
