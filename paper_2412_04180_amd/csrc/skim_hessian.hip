@@ -52,9 +52,9 @@ __device__ __forceinline__ void load_task(const uint16_t *__restrict__ X, long l
         s.r[t][0] = v.x; s.r[t][1] = v.y; s.r[t][2] = v.z; s.r[t][3] = v.w;
     }
 }
-// columns [cb, ce) of the task's 8 (compile-time bounds once the caller's loop is unrolled)
-__device__ __forceinline__ void store_cols(uint16_t (*T)[HK_PAD], int st, const Staged &s, int cb, int ce) {
-    const int ab = st & 7, cg = st >> 3;
+// columns [cb, ce) of the task's 8 (compile-time bounds once the caller's loop is unrolled): the 8 activations of
+// column 8 cg + c go to 16-byte slot `slot` of that column's LDS row
+__device__ __forceinline__ void store_cols(uint16_t (*T)[HK_PAD], int cg, int slot, const Staged &s, int cb, int ce) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
         if (c < cb || c >= ce) continue;
@@ -64,10 +64,10 @@ __device__ __forceinline__ void store_cols(uint16_t (*T)[HK_PAD], int st, const 
             const uint32_t a = s.r[2 * d][c >> 1], b = s.r[2 * d + 1][c >> 1];
             o[d] = (c & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
         }
-        *(uint4 *)&T[8 * cg + c][8 * ab] = make_uint4(o[0], o[1], o[2], o[3]);
+        *(uint4 *)&T[8 * cg + c][8 * slot] = make_uint4(o[0], o[1], o[2], o[3]);
     }
 }
-__device__ __forceinline__ void store_task(XTile &T, int st, const Staged &s) { store_cols(T.t, st, s, 0, 8); }
+__device__ __forceinline__ void store_task(XTile &T, int st, const Staged &s) { store_cols(T.t, st >> 3, st & 7, s, 0, 8); }
 
 __global__ void __launch_bounds__(H_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) xtx_kernel(const uint16_t *__restrict__ X, long long N, long long m,
                                                         float *__restrict__ H, int vec) {
@@ -195,10 +195,18 @@ xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *
 
     floatx16 acc[4][4];
 
-    // staging: thread tid moves activations 8 ab .. + 7, columns 8 cg .. + 7 of either operand tile.  A column group
+    // staging: thread tid moves activations 8 ab .. + 7, columns 8 cg .. + 7 of either operand tile, the 32 lanes of a half wavefront the 32 groups of one row:
+    // a wavefront's load instruction reads 512 contiguous bytes of each of two rows (with ab fastest it would be 128
+    // bytes of eight rows 8 m bytes apart, which the memory system serves at half the rate).  A column group
     // past the matrix reads the tile's first group instead: its products only reach entries (i >= m or j >= m)
-    // that are never stored.  Rows past N (last tile only) read as zero.
-    const int ab = tid & 7, cg = tid >> 3;
+    // that are never stored.
+    // LDS row of a column: its 64 activations as eight 16-byte slots, rotated by (column / 32) slots.  An operand
+    // read (lanes = 32 consecutive columns, one rotation) then has the plain 144-byte row stride of the unrotated
+    // layout, and a staging store (lanes = column groups, 8 x 144 bytes apart, which alone would fall into one set
+    // of banks) spreads over the banks by its rotations: within the 32 lanes of a row the groups are dealt out
+    // 0, 4, .. 28, 1, 5, .. so that any 8 consecutive lanes carry 8 different rotations.
+    const int cg = 4 * (tid & 7) + ((tid >> 3) & 3), ab = tid >> 5;
+    const int st_slot = (ab + (cg >> 2)) & 7;
     const uint16_t *pi = X + (long long)(8 * ab) * m + (i0 + 8 * cg < m ? i0 + 8 * cg : i0);
     const uint16_t *pj = X + (long long)(8 * ab) * m + (j0 + 8 * cg < m ? j0 + 8 * cg : j0);
     // The activations are cut into 64-row tiles from the end: the first one is the short one, rows [0, r0) with
@@ -225,10 +233,19 @@ xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *
         load_rows<true>(pj, m, r0 - 8 * ab, sj[0]);
         load_tile(1, si[1], sj[1]);
     }
-    store_cols(TI[0].t, tid, si[0], 0, 8);
-    store_cols(TJ[0].t, tid, sj[0], 0, 8);
+    store_cols(TI[0].t, cg, st_slot, si[0], 0, 8);
+    store_cols(TJ[0].t, cg, st_slot, sj[0], 0, 8);
     __syncthreads();
     const double inv = 1.0 / (double)N;
+    // A wavefront takes every other 32-column block of either operand: rows 32 (2 x + wr) + lane % 32 of the i tile,
+    // 32 (2 y + wc) + lane % 32 of the j tile.  Operand of a lane in k-slice ks: activations 16 ks + 8 (lane / 32)
+    // .. + 7, i.e. slot (2 ks + lane / 32 + 2 x + wr) % 8 of its row: four values per operand, by (ks + x) % 4.
+    int rslot_a[4], rslot_b[4];  // (as first activation of the slot)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        rslot_a[q] = 8 * ((2 * q + wr + lhi) & 7);
+        rslot_b[q] = 8 * ((2 * q + wc + lhi) & 7);
+    }
 
     // one step: first the loads of tile kt + 2 are issued (into the register set tile kt left when it went to LDS
     // in the step before), then the MFMAs of tile kt (LDS buffer PAR); during the second half tile kt + 1, requested
@@ -239,12 +256,11 @@ xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *
         load_tile(min(kt + 2, ntile - 1), si[PAR], sj[PAR]);     // (past the end: the last tile again, unused)
 #pragma unroll
         for (int ks = 0; ks < HK / 16; ++ks) {
-            const int kk = 16 * ks + 8 * lhi;
             bf16x8 a[4], b[4];
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
-                a[x] = *(const bf16x8 *)&TI[PAR].t[wr * 128 + 32 * x + l32][kk];
-                b[x] = *(const bf16x8 *)&TJ[PAR].t[wc * 128 + 32 * x + l32][kk];
+                a[x] = *(const bf16x8 *)&TI[PAR].t[32 * (2 * x + wr) + l32][rslot_a[(ks + x) & 3]];
+                b[x] = *(const bf16x8 *)&TJ[PAR].t[32 * (2 * x + wc) + l32][rslot_b[(ks + x) & 3]];
             }
 #pragma unroll
             for (int x = 0; x < 4; ++x)
@@ -260,10 +276,9 @@ xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *
                     }
                 }
             if (ks >= 2) {      // (after the last tile this stores a repeat of the last tile: harmless, never read)
-                store_cols(TI[PAR ^ 1].t, tid, si[PAR ^ 1], 4 * (ks - 2), 4 * (ks - 2) + 4);
-                store_cols(TJ[PAR ^ 1].t, tid, sj[PAR ^ 1], 4 * (ks - 2), 4 * (ks - 2) + 4);
+                store_cols(TI[PAR ^ 1].t, cg, st_slot, si[PAR ^ 1], 4 * (ks - 2), 4 * (ks - 2) + 4);
+                store_cols(TJ[PAR ^ 1].t, cg, st_slot, sj[PAR ^ 1], 4 * (ks - 2), 4 * (ks - 2) + 4);
             }
-            __builtin_amdgcn_sched_barrier(0);      // operands of one k-slice at a time: the scheduler would fetch all four early
         }
         __syncthreads();
     };
@@ -284,7 +299,7 @@ xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *
         // compiler copies all 256 accumulators out at once and spills what the MFMA loop keeps in registers).
         // (The empty asm keeps the address arithmetic of this rare block inside it.)
         const bool first = c0 == 0, last = cend == ntile;
-        const long long ib = i0 + wr * 128 + 4 * lhi, jb = j0 + wc * 128 + l32;
+        const long long ib = i0 + wr * 32 + 4 * lhi, jb = j0 + wc * 32 + l32;
         float *hp = H + ib * m + jb;
         long long mm = m;
         int rlim = (int)min(m - ib, 4096ll), clim = (int)min(m - jb, 4096ll);   // valid rows / columns from (ib, jb) on
@@ -298,7 +313,7 @@ xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
-                        const int r = x * 32 + 8 * (e >> 2) + (e & 3), c = y * 32;
+                        const int r = x * 64 + 8 * (e >> 2) + (e & 3), c = y * 64;
                         const bool valid = r < rlim && c < clim;
                         float *q = valid ? hp + r * mm + c : hp;
                         const float old = *q;
