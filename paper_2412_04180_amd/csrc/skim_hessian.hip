@@ -146,16 +146,17 @@ __global__ void __launch_bounds__(H_THREADS) __attribute__((amdgpu_waves_per_eu(
 }
 
 // ---- the kernel for large m: 256 x 256 output tile, one workgroup per CU ---------------------------------------
-// Four wavefronts, each a 128 x 128 quarter (4 x 4 accumulator tiles of 32 x 32: 256 accumulator registers, one
-// wavefront per SIMD), so an MFMA operand read from LDS feeds four MFMAs instead of two and a byte fetched from L2
-// feeds twice the arithmetic of the 128 x 128 kernel.  Two register sets stage the X tiles: the loads of tile
-// kt + 3 are issued in step kt and stored to LDS in step kt + 2, between the MFMAs of that step, so neither the
-// memory latency nor the transposes stand between two steps.  The float32 accumulators are added into H itself
-// (float32, read-modify-write by the one thread that owns the entry) every 8192 activations: the sums over a
-// chunk carry at most 512 roundings at 1/16 or less of the total each, the 16 chunk additions of 131072
-// activations one rounding each -- a few 1e-6 of sqrt(H_jj H_ll) in the worst case.
+// Eight wavefronts, two per SIMD, each a 128 x 64 part of the tile (4 x 2 accumulator tiles of 32 x 32), so an MFMA
+// operand read from LDS feeds 2.7 MFMAs instead of two and a byte fetched from L2 feeds twice the arithmetic of the
+// 128 x 128 kernel; while one wavefront of a SIMD waits for LDS, memory or the barrier the other one issues MFMAs.
+// Two register sets stage the X tiles: the loads of tile kt + 2 are issued at the start of step kt and stored to
+// LDS in the second half of step kt + 1, between the MFMAs of that step, so neither the memory latency nor the
+// transposes stand between two steps.  The float32 accumulators are added into H itself (float32,
+// read-modify-write by the one thread that owns the entry) every 8192 activations: the sums over a chunk carry at
+// most 512 roundings at 1/16 or less of the total each, the 16 chunk additions of 131072 activations one rounding
+// each -- a few 1e-6 of sqrt(H_jj H_ll) in the worst case.
 constexpr int BT = 256;
-constexpr int B_THREADS = 256;
+constexpr int B_THREADS = 512;
 constexpr int B_FLUSH_TILES = 128;
 struct BTile {
     uint16_t t[BT][HK_PAD];
@@ -173,13 +174,13 @@ __device__ __forceinline__ void load_rows(const uint16_t *__restrict__ p, long l
     }
 }
 
-// Needs m % 8 == 0 and X 16-byte aligned (every 8-column group of a row is one aligned 16-byte load).
-__global__ void __launch_bounds__(B_THREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
+// Needs m % 8 == 0, X 16-byte aligned (every 8-column group of a row is one aligned 16-byte load) and N >= 128.
+__global__ void __launch_bounds__(B_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *__restrict__ H, int nt) {
     extern __shared__ __align__(16) unsigned char smem[];
     BTile *TI = (BTile *)smem, *TJ = TI + 2;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wr = wave >> 1, wc = wave & 1;
+    const int wr = wave >> 2, wc = wave & 3;
     const int l32 = lane & 31, lhi = lane >> 5;
     // Workgroup -> tile.  Consecutive workgroup ids go to the 8 XCDs in turn; the ids one XCD receives are mapped
     // to consecutive tiles of a band-by-band order (bands of 8 tile rows, column by column inside a band), so the
@@ -193,22 +194,25 @@ xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *
     const int inb = (int)(v - 8ll * nt * band);
     const long long i0 = (long long)(8 * band + inb % hb) * BT, j0 = (long long)(inb / hb) * BT;
 
-    floatx16 acc[4][4];
+    floatx16 acc[4][2];
 
-    // staging: thread tid moves activations 8 ab .. + 7, columns 8 cg .. + 7 of either operand tile, the 32 lanes of a half wavefront the 32 groups of one row:
-    // a wavefront's load instruction reads 512 contiguous bytes of each of two rows (with ab fastest it would be 128
-    // bytes of eight rows 8 m bytes apart, which the memory system serves at half the rate).  A column group
-    // past the matrix reads the tile's first group instead: its products only reach entries (i >= m or j >= m)
-    // that are never stored.
+    // Staging: wavefronts 0-3 move the i tile, 4-7 the j tile; a thread moves activations 8 ab .. + 7 of columns
+    // 8 cg .. + 7, the 32 lanes of a half wavefront the 32 column groups of one row: a load instruction reads 512
+    // contiguous bytes of each of two rows (with ab fastest it would be 128 bytes of eight rows 8 m bytes apart,
+    // which the memory system serves at half the rate).  A column group past the matrix reads the tile's first
+    // group instead: its products only reach entries (i >= m or j >= m) that are never stored.
     // LDS row of a column: its 64 activations as eight 16-byte slots, rotated by (column / 32) slots.  An operand
     // read (lanes = 32 consecutive columns, one rotation) then has the plain 144-byte row stride of the unrotated
     // layout, and a staging store (lanes = column groups, 8 x 144 bytes apart, which alone would fall into one set
     // of banks) spreads over the banks by its rotations: within the 32 lanes of a row the groups are dealt out
     // 0, 4, .. 28, 1, 5, .. so that any 8 consecutive lanes carry 8 different rotations.
-    const int cg = 4 * (tid & 7) + ((tid >> 3) & 3), ab = tid >> 5;
+    const int su = tid & 255;
+    const bool stage_j = tid >= 256;
+    const int cg = 4 * (su & 7) + ((su >> 3) & 3), ab = su >> 5;
     const int st_slot = (ab + (cg >> 2)) & 7;
-    const uint16_t *pi = X + (long long)(8 * ab) * m + (i0 + 8 * cg < m ? i0 + 8 * cg : i0);
-    const uint16_t *pj = X + (long long)(8 * ab) * m + (j0 + 8 * cg < m ? j0 + 8 * cg : j0);
+    const long long sc0 = stage_j ? j0 : i0;
+    const uint16_t *px = X + (long long)(8 * ab) * m + (sc0 + 8 * cg < m ? sc0 + 8 * cg : sc0);
+    BTile *const ST = stage_j ? TJ : TI;
     // The activations are cut into 64-row tiles from the end: the first one is the short one, rows [0, r0) with
     // r0 = N - 64 (nreal - 1) in 1 .. 64, zero-padded to 64.  An all-zero tile goes in front when that makes the
     // count even, so the loop below runs whole pairs of steps and, from tile 2 on, loads full tiles without
@@ -217,29 +221,25 @@ xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *
     const int odd = (int)(nreal & 1);
     const long long ntile = nreal + odd;
     const long long r0 = N - (nreal - 1) * HK;
-    Staged si[2], sj[2];         // two tiles on their way from global memory to LDS: tile t in set t & 1
-    auto load_tile = [&](long long kt, Staged &di, Staged &dj) {
+    Staged sg[2];                // two tiles on their way from global memory to LDS: tile t in set t & 1
+    auto load_tile = [&](long long kt, Staged &d) {
         const long long k0 = r0 + (kt - 1 - odd) * HK;
-        load_rows<false>(pi + k0 * m, m, 0, di);
-        load_rows<false>(pj + k0 * m, m, 0, dj);
+        load_rows<false>(px + k0 * m, m, 0, d);
     };
     if (odd) {
-        load_rows<true>(pi, m, 0, si[0]);                  // no rows: zeros
-        load_rows<true>(pj, m, 0, sj[0]);
-        load_rows<true>(pi, m, r0 - 8 * ab, si[1]);
-        load_rows<true>(pj, m, r0 - 8 * ab, sj[1]);
+        load_rows<true>(px, m, 0, sg[0]);                  // no rows: zeros
+        load_rows<true>(px, m, r0 - 8 * ab, sg[1]);
     } else {
-        load_rows<true>(pi, m, r0 - 8 * ab, si[0]);
-        load_rows<true>(pj, m, r0 - 8 * ab, sj[0]);
-        load_tile(1, si[1], sj[1]);
+        load_rows<true>(px, m, r0 - 8 * ab, sg[0]);
+        load_tile(1, sg[1]);
     }
-    store_cols(TI[0].t, cg, st_slot, si[0], 0, 8);
-    store_cols(TJ[0].t, cg, st_slot, sj[0], 0, 8);
+    store_cols(ST[0].t, cg, st_slot, sg[0], 0, 8);
     __syncthreads();
     const double inv = 1.0 / (double)N;
-    // A wavefront takes every other 32-column block of either operand: rows 32 (2 x + wr) + lane % 32 of the i tile,
-    // 32 (2 y + wc) + lane % 32 of the j tile.  Operand of a lane in k-slice ks: activations 16 ks + 8 (lane / 32)
-    // .. + 7, i.e. slot (2 ks + lane / 32 + 2 x + wr) % 8 of its row: four values per operand, by (ks + x) % 4.
+    // A wavefront takes every other 32-column block of the i tile and every fourth of the j tile: rows
+    // 32 (2 x + wr) + lane % 32 and 32 (4 y + wc) + lane % 32.  Operand of a lane in k-slice ks: activations
+    // 16 ks + 8 (lane / 32) .. + 7, i.e. slot (2 ks + lane / 32 + block) % 8 of its row: four values per operand,
+    // by (ks + x) % 4 and (ks + 2 y) % 4.
     int rslot_a[4], rslot_b[4];  // (as first activation of the slot)
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -253,19 +253,18 @@ xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *
     auto step = [&](auto par_c, auto fresh_c, long long kt) {
         constexpr int PAR = decltype(par_c)::value;
         constexpr bool FRESH = decltype(fresh_c)::value;     // first step of a chunk: the sums start from zero
-        load_tile(min(kt + 2, ntile - 1), si[PAR], sj[PAR]);     // (past the end: the last tile again, unused)
+        load_tile(min(kt + 2, ntile - 1), sg[PAR]);          // (past the end: the last tile again, unused)
 #pragma unroll
         for (int ks = 0; ks < HK / 16; ++ks) {
-            bf16x8 a[4], b[4];
+            bf16x8 a[4], b[2];
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                a[x] = *(const bf16x8 *)&TI[PAR].t[32 * (2 * x + wr) + l32][rslot_a[(ks + x) & 3]];
-                b[x] = *(const bf16x8 *)&TJ[PAR].t[32 * (2 * x + wc) + l32][rslot_b[(ks + x) & 3]];
-            }
+            for (int x = 0; x < 4; ++x) a[x] = *(const bf16x8 *)&TI[PAR].t[32 * (2 * x + wr) + l32][rslot_a[(ks + x) & 3]];
+#pragma unroll
+            for (int y = 0; y < 2; ++y) b[y] = *(const bf16x8 *)&TJ[PAR].t[32 * (4 * y + wc) + l32][rslot_b[(ks + 2 * y) & 3]];
 #pragma unroll
             for (int x = 0; x < 4; ++x)
 #pragma unroll
-                for (int y = 0; y < 4; ++y) {
+                for (int y = 0; y < 2; ++y) {
                     if (FRESH && ks == 0) {
                         floatx16 zero;
 #pragma unroll
@@ -275,10 +274,8 @@ xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *
                         acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[x], b[y], acc[x][y], 0, 0, 0);
                     }
                 }
-            if (ks >= 2) {      // (after the last tile this stores a repeat of the last tile: harmless, never read)
-                store_cols(TI[PAR ^ 1].t, cg, st_slot, si[PAR ^ 1], 4 * (ks - 2), 4 * (ks - 2) + 4);
-                store_cols(TJ[PAR ^ 1].t, cg, st_slot, sj[PAR ^ 1], 4 * (ks - 2), 4 * (ks - 2) + 4);
-            }
+            if (ks >= 2)        // (after the last tile this stores a repeat of the last tile: harmless, never read)
+                store_cols(ST[PAR ^ 1].t, cg, st_slot, sg[PAR ^ 1], 4 * (ks - 2), 4 * (ks - 2) + 4);
         }
         __syncthreads();
     };
@@ -296,7 +293,7 @@ xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *
         // the chunk's sums go into H.  Accumulator element e of a 32 x 32 tile: row = 8*(e/4) + 4*(lane/32) + e%4,
         // column = lane%32.  Straight-line code, one accumulator tile at a time: an entry outside the matrix is
         // turned into "add nothing to this thread's first entry" instead of a branch (with a branch per entry the
-        // compiler copies all 256 accumulators out at once and spills what the MFMA loop keeps in registers).
+        // compiler copies all accumulators out at once and spills what the MFMA loop keeps in registers).
         // (The empty asm keeps the address arithmetic of this rare block inside it.)
         const bool first = c0 == 0, last = cend == ntile;
         const long long ib = i0 + wr * 32 + 4 * lhi, jb = j0 + wc * 32 + l32;
@@ -309,15 +306,15 @@ xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *
 #pragma unroll
             for (int x = 0; x < 4; ++x)
 #pragma unroll
-                for (int y = 0; y < 4; ++y) {
+                for (int y = 0; y < 2; ++y) {
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
-                        const int r = x * 64 + 8 * (e >> 2) + (e & 3), c = y * 64;
+                        const int r = x * 64 + 8 * (e >> 2) + (e & 3), c = y * 128;
                         const bool valid = r < rlim && c < clim;
                         float *q = valid ? hp + r * mm + c : hp;
                         const float old = *q;
-                        float av;       // read here and now, not copied out ahead with the other 255
+                        float av;       // read here and now, not copied out ahead with all the others
                         asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(av) : "a"(acc[x][y][e]));
                         const float t = (first ? 0.f : old) + av;
                         *q = valid ? (float)((double)t * scale) : old;
