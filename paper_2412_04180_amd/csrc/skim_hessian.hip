@@ -1,7 +1,9 @@
 // Layer-wise Hessian proxy from calibration activations (Sec. 3.4: H ~ X X^T in the paper's
 // column convention; here X is N x m row-major, one activation vector per row, so
 // H = X^T X / N, m x m).  bf16 inputs, bf16 MFMA (v_mfma_f32_32x32x16_bf16) with float32
-// accumulation over chunks of 2048 activations, the chunks added up in float64.
+// accumulation over chunks of activations.  Two kernels: 128 x 128 output tiles with the chunks
+// (2048 activations) added up in float64 registers, and, for layers wide enough to fill the chip
+// with them, 256 x 256 tiles with the chunks (8192 activations) added up in float32 in H itself.
 #include "skim_common.h"
 #include <type_traits>
 
@@ -188,7 +190,10 @@ xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *
     // panel uses.
     long long v = blockIdx.x;
     const long long total = (long long)nt * nt;
-    if ((total & 7) == 0) v = (v & 7) * (total >> 3) + (v >> 3);
+    {
+        const long long q8 = total >> 3, r8 = total & 7, xcd = v & 7;     // XCD xcd receives q8 (+ 1 if xcd < r8) ids
+        v = xcd * q8 + min(xcd, r8) + (v >> 3);
+    }
     const int band = (int)(v / (8ll * nt));
     const int hb = min(8, nt - 8 * band);
     const int inb = (int)(v - 8ll * nt * band);
