@@ -274,9 +274,11 @@ skim_status skim_dequant_matvec_f32(skim_ctx *ctx, const uint32_t *codes, const 
  *   H = X^T X / N,  X: dev N x m bfloat16 (bit patterns, row-major, one activation
  *   vector per row; 4-byte aligned, m even),  H: dev m x m float32.
  * bf16 MFMA with float32 accumulation over chunks of activations (2048; 8192 for
- * m >= 3584 with m % 8 == 0, X 16-byte aligned and N >= 128, where the chunks are
- * added up in float32 in H itself; otherwise in float64); every entry within 1e-5
- * of sqrt(H_jj H_ll) for N up to about 10^6; H comes out symmetric bit for bit. */
+ * m > 2560 with m % 8 == 0, X 16-byte aligned and N >= 128, where the chunks are
+ * added up in float32 in H itself and only the tiles on and above the diagonal are
+ * computed; otherwise in float64); every entry within 1e-5 of sqrt(H_jj H_ll) for N up
+ * to about 10^6; H comes out symmetric bit for bit.  H is written only (its
+ * previous contents do not matter). */
 skim_status skim_hessian_from_activations(skim_ctx *ctx, const uint16_t *X_bf16, int64_t N, int64_t m,
                                           float *H);
 

@@ -2,8 +2,9 @@
 // column convention; here X is N x m row-major, one activation vector per row, so
 // H = X^T X / N, m x m).  bf16 inputs, bf16 MFMA (v_mfma_f32_32x32x16_bf16) with float32
 // accumulation over chunks of activations.  Two kernels: 128 x 128 output tiles with the chunks
-// (2048 activations) added up in float64 registers, and, for layers wide enough to fill the chip
-// with them, 256 x 256 tiles with the chunks (8192 activations) added up in float32 in H itself.
+// (2048 activations) added up in float64 registers, and, for layers of more than 2560 columns,
+// 256 x 256 tiles (the symmetric half, mirrored at the end) with the chunks (8192 activations) added
+// up in float32 in H itself.
 #include "skim_common.h"
 #include <type_traits>
 
@@ -147,7 +148,7 @@ __global__ void __launch_bounds__(H_THREADS) __attribute__((amdgpu_waves_per_eu(
             }
 }
 
-// ---- the kernel for large m: 256 x 256 output tile, one workgroup per CU ---------------------------------------
+// ---- the kernel for large m: 256 x 256 output tile, one workgroup per CU, tiles on and above the diagonal only -----
 // Eight wavefronts, two per SIMD, each a 128 x 64 part of the tile (4 x 2 accumulator tiles of 32 x 32), so an MFMA
 // operand read from LDS feeds 2.7 MFMAs instead of two and a byte fetched from L2 feeds twice the arithmetic of the
 // 128 x 128 kernel; while one wavefront of a SIMD waits for LDS, memory or the barrier the other one issues MFMAs.
@@ -184,20 +185,40 @@ xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave >> 2, wc = wave & 3;
     const int l32 = lane & 31, lhi = lane >> 5;
-    // Workgroup -> tile.  Consecutive workgroup ids go to the 8 XCDs in turn; the ids one XCD receives are mapped
-    // to consecutive tiles of a band-by-band order (bands of 8 tile rows, column by column inside a band), so the
-    // workgroups that share an L2 at any time share operand panels: 32 of them cover 8 x 4 tiles, 12 panels for 64
-    // panel uses.
+    // Workgroup -> tile.  H is symmetric: only the tiles (bi, bj) with bi <= bj are computed, nt (nt + 1) / 2 of them,
+    // and a tile off the diagonal writes its transpose as well at the end.  Consecutive workgroup ids go to the 8
+    // XCDs in turn; the ids one XCD receives are mapped to consecutive tiles of a band-by-band order (bands of 8
+    // tile rows; inside a band column by column, first the columns the diagonal cuts short), so the workgroups
+    // that share an L2 at any time share operand panels: 32 of them cover about 8 x 4 tiles, 12 panels for 64 uses.
     long long v = blockIdx.x;
-    const long long total = (long long)nt * nt;
+    const long long total = (long long)nt * (nt + 1) / 2;
     {
         const long long q8 = total >> 3, r8 = total & 7, xcd = v & 7;     // XCD xcd receives q8 (+ 1 if xcd < r8) ids
         v = xcd * q8 + min(xcd, r8) + (v >> 3);
     }
-    const int band = (int)(v / (8ll * nt));
-    const int hb = min(8, nt - 8 * band);
-    const int inb = (int)(v - 8ll * nt * band);
-    const long long i0 = (long long)(8 * band + inb % hb) * BT, j0 = (long long)(inb / hb) * BT;
+    int bi = 0, bj = 0;
+    for (int rb = 0; rb < nt; rb += 8) {
+        const int hb = min(8, nt - rb);
+        const long long tri = (long long)hb * (hb + 1) / 2, cnt = tri + (long long)hb * (nt - rb - hb);
+        if (v < cnt) {
+            if (v < tri) {          // column rb + t holds the t + 1 rows rb .. rb + t
+                int t = 0;
+                while (v >= t + 1) {
+                    v -= t + 1;
+                    ++t;
+                }
+                bj = rb + t;
+                bi = rb + (int)v;
+            } else {
+                v -= tri;
+                bj = rb + hb + (int)(v / hb);
+                bi = rb + (int)(v % hb);
+            }
+            break;
+        }
+        v -= cnt;
+    }
+    const long long i0 = (long long)bi * BT, j0 = (long long)bj * BT;
 
     floatx16 acc[4][2];
 
@@ -325,6 +346,15 @@ xtx_big_kernel(const uint16_t *__restrict__ X, long long N, long long m, float *
                         *q = valid ? (float)((double)t * scale) : old;
                     }
                 }
+            // the transposed tile, once, from the finished entries (each thread reads back what it wrote itself)
+            if (last && bi != bj) {
+                float *ht = H + jb * m + ib;      // entry (jb, ib); entry (jb + c, ib + r) mirrors (ib + r, jb + c)
+                for (int idx = 0; idx < 128; ++idx) {
+                    const int x = idx >> 5, y = (idx >> 4) & 1, e = idx & 15;
+                    const int r = x * 64 + 8 * (e >> 2) + (e & 3), c = y * 128;
+                    if (r < rlim && c < clim) ht[c * mm + r] = hp[r * mm + c];
+                }
+            }
         }
     }
 }
@@ -344,15 +374,16 @@ extern "C" skim_status skim_hessian_from_activations(skim_ctx *ctx, const uint16
         ctx->xtx_lds_enabled = 1;
     }
     const int vec = (m % 8 == 0) && (((uintptr_t)X_bf16 & 15) == 0);     // rows of X start 16-byte aligned
-    // 256 x 256 tiles once they fill most of the chip (m >= 3584 on 256 CUs); smaller m takes the 128 x 128 kernel
+    // 256 x 256 tiles from 11 tiles a side (m > 2560): a single round of them on a partly filled chip already beats
+    // the 128 x 128 kernel there
     const long long ntb = (m + BT - 1) / BT;
-    if (vec && N >= 2 * HK && ntb * ntb >= (long long)ctx->num_cu * 3 / 4) {
+    if (vec && N >= 2 * HK && ntb >= 11) {
         if (ctx->xtx_lds_enabled < 2) {
             SKIM_HIP(ctx, hipFuncSetAttribute((const void *)xtx_big_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)B_LDS_BYTES));
             SKIM_HIP(ctx, hipFuncSetAttribute((const void *)xtx_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)H_LDS_BYTES));
             ctx->xtx_lds_enabled = 2;
         }
-        hipLaunchKernelGGL(xtx_big_kernel, dim3((unsigned)(ntb * ntb)), dim3(B_THREADS), B_LDS_BYTES, ctx->stream, X_bf16,
+        hipLaunchKernelGGL(xtx_big_kernel, dim3((unsigned)(ntb * (ntb + 1) / 2)), dim3(B_THREADS), B_LDS_BYTES, ctx->stream, X_bf16,
                            (long long)N, (long long)m, H, (int)ntb);
         SKIM_HIP(ctx, hipGetLastError());
         return SKIM_OK;

@@ -186,8 +186,8 @@ def test_train_scale_is_the_composition_of_its_steps_and_tracks_the_oracle(ctx, 
 @pytest.mark.parametrize("N,m", [(40, 12), (300, 130), (1000, 256), (4096, 640),
                                  # wide layers take the kernel with 256 x 256 tiles: a last tile of 8 columns and a
                                  # short first slice of activations; two accumulation chunks; a tile count that is
-                                 # no multiple of 8; the fewest activations that kernel takes
-                                 (200, 3592), (8200, 3840), (128, 4096)])
+                                 # no multiple of 8; the fewest activations and the narrowest layer that kernel takes
+                                 (200, 3592), (8200, 3840), (128, 4096), (300, 2568)])
 def test_hessian_from_activations_matches_oracle(ctx, N, m):
     """H = X^T X / N from bfloat16 activations against the float64 definition: every entry within 1e-5 of the
     entry's natural scale sqrt(H_jj H_ll) (float32 accumulation within a chunk of activations; across chunks
