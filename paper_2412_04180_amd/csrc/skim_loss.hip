@@ -328,9 +328,10 @@ __global__ void __launch_bounds__(PREP_THREADS) grad_rows_kernel(const float *W,
     }
 }
 
-// Column sums of the per-strip gradient terms, then the Adam update.  32 columns per workgroup; the strips
-// are shared out to 8 groups of threads (a column's 8 partial sums are added in a fixed order).
-constexpr int ADAM_COLS = 32, ADAM_GROUPS = 8;
+// Column sums of the per-strip gradient terms, then the Adam update.  16 columns per workgroup (m / 16 workgroups:
+// one per CU at 4096 columns); the strips are shared out to 64 groups of threads (a column's 64 partial sums are
+// added in a fixed order).
+constexpr int ADAM_COLS = 16, ADAM_GROUPS = 64;
 
 __global__ void __launch_bounds__(ADAM_COLS * ADAM_GROUPS) adam_kernel(const double *gpart, int nstrip, long long m,
                                                                       float *alpha, float *am, float *av, float lr,
