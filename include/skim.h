@@ -101,10 +101,10 @@ skim_status skim_profile_last(skim_ctx *ctx, float *sort_ms, float *lloyd_ms);
 
 /* ---- clustering --------------------------------------------------------- */
 
-/* Error pre-recording (Alg. 3 lines 2-10): for every row i and every bit
+/* Error pre-recording (Alg. 3, pre-recording loop): for every row i and every bit
  * width b in [bmin, bmax] run the weighted K-means
  *     Kmeans(W_i * alpha^-1, weights = S_i * alpha^2, n_centroids = 2^b)
- * (Alg. 3 line 5; objective: the S-diag form of Sec. 3.3) from the
+ * (the Kmeans call of Alg. 3; objective: the S-diag form of Sec. 3.3) from the
  * weighted-quantile start for `iters` Lloyd iterations and record
  *     E[i][b - bmin] = sum_j s~_ij (w~_ij - c_{a_ij})^2 .
  * W, S: dev, n x m float32, stride ld.  alpha: dev, m float32, or NULL (= 1).
@@ -119,7 +119,7 @@ skim_status skim_error_table(skim_ctx *ctx, const float *W, const float *S, cons
                              int64_t n, int64_t m, int64_t ld, int bmin, int bmax, int iters,
                              double *E, double *centroids_all, float *upper_all);
 
-/* K-means at one bit width per row (Alg. 3 lines 12-15; the re-clustering of
+/* K-means at one bit width per row (Alg. 3, clustering loop at the allocated bits; the re-clustering of
  * W * alpha^-1 in Alg. 2).  bits: dev uint8[n], each in 1..4.
  * labels: dev uint8 n x m (dense, stride m), may be NULL.
  * centroids: dev float64 n x 16 (first 2^bits[i] used, rest 0).
@@ -130,7 +130,7 @@ skim_status skim_cluster_rows(skim_ctx *ctx, const float *W, const float *S, con
 
 /* Pick, for every row, the block of its allocated bit width out of the
  * per-bit outputs of skim_error_table (clustering is deterministic, so the
- * K-means of Alg. 3 lines 12-15 need not be run again).  All pointers dev.
+ * K-means of Alg. 3, clustering loop at the allocated bits need not be run again).  All pointers dev.
  * centroids: n x 16 float64, upper: n x 16 float32 (layout of
  * skim_cluster_rows), err: float64[n], may be NULL. */
 skim_status skim_select_allocated(skim_ctx *ctx, int64_t n, int bmin, int bmax, const uint8_t *bits,
@@ -294,7 +294,7 @@ skim_status skim_layer_loss(skim_ctx *ctx, const float *W, const float *S, const
                             const float *H, int64_t n, int64_t m, int64_t ld,
                             const uint8_t *labels, double *loss, double *row_loss);
 
-/* Error pre-recording with the layer-wise error (Alg. 3 lines 2-10, with the
+/* Error pre-recording with the layer-wise error (Alg. 3, pre-recording loop, with the
  * error taken in its L-full form as Sec. 4.2 prescribes; Sec. 3.4): the rows are
  * clustered for every b in [bmin, bmax] exactly as in skim_error_table, and
  *   E_full[i][b-bmin] = dW_i H dW_i^T,  dW_i = w_i - alpha * c_{i, L_i}

@@ -339,7 +339,7 @@ def layer_loss(W, H, labels, c, alpha=None, want_P=False):
 
 
 def error_table_lfull(W, S, H, alpha=None, bmin=1, bmax=4, iters=30, count_near=False):
-    """Error pre-recording with the layer-wise error (Alg. 3 lines 2-10, Err(.) in its L-full form):
+    """Error pre-recording with the layer-wise error (Alg. 3, pre-recording loop, Err(.) in its L-full form):
     for each b the rows are clustered (K = 2^b), and E[i][b-bmin] = dW_i H dW_i^T with
     dW_i = w_i - alpha * replace(c, L)_i for the labels L and centroids c the clustering returned."""
     W = _f32(W)

@@ -87,9 +87,9 @@ static int cmp_elem(const void *pa, const void *pb) {
     return (a->j > b->j) - (a->j < b->j);
 }
 
-/* Weighted-quantile initialisation (the paper's Kmeans() call, Alg. 3 line 5,
- * does not say how centroids start; the workload definition fixes
- * "weighted-quantile init").  Reading:
+/* Weighted-quantile initialisation (the Kmeans call of Alg. 3
+ * does not say how centroids start; the workload definition fixes a
+ * weighted-quantile start).  Reading:
  *   order the row ascending by (w, s, index); C_r = running sum of s in that
  *   order; centroid k starts at the element whose rank is the first r with
  *   C_r >= total * (2k+1) / (2K).  Ranks are then forced to be strictly
@@ -160,7 +160,7 @@ int oracle_quantile_init(const float *w, const float *s, int64_t m, int K, doubl
 
 /* ------------------------------------------------------------------ */
 /* One row of sensitivity-weighted 1-D K-means: Kmeans(W_i, weights = G_i,
- * n_centroids = 2^b) of Alg. 3 line 5, minimising the S-diag objective
+ * n_centroids = 2^b) of the Kmeans call of Alg. 3, minimising the S-diag objective
  * sum_j s_j (w_j - c_{a_j})^2 (Sec. 3.3).  Plain Lloyd iteration:
  *   (A) every weight goes to its nearest centroid, |w - c_k| in double,
  *       the lowest k winning equal distances;
@@ -259,7 +259,7 @@ int oracle_cluster_row(const float *w, const float *s, int64_t m, int K, int T, 
 }
 
 /* ------------------------------------------------------------------ */
-/* Error pre-recording, Alg. 3 lines 2-10: E[i][b - bmin] for every row and
+/* Error pre-recording, Alg. 3, pre-recording loop: E[i][b - bmin] for every row and
  * every candidate bit width.  Reading: the recorded error is the S-diag
  * objective the clustering itself minimises (it needs only W and S); the
  * L-full error of the same clustering is what oracle_layer_loss returns per
@@ -312,7 +312,7 @@ int oracle_error_table(const float *W, const float *S, const float *alpha, int64
     return rc;
 }
 
-/* K-means at the allocated bit width of every row, Alg. 3 lines 12-15 and the
+/* K-means at the allocated bit width of every row, Alg. 3, clustering loop at the allocated bits and the
  * re-clustering of W * alpha^-1 in Alg. 2.  centroids / upper are n x 16 with
  * the first 2^bits[i] entries of row i used (the rest set to 0 / -inf).
  * near_rows (optional, n entries) receives each row's near-tie count.         */
@@ -357,7 +357,8 @@ int oracle_cluster_rows(const float *W, const float *S, const float *alpha, int6
  *  - the budget is B = floor(avg_bits * sum(cost) + 1e-9) bits and the loop
  *    stops when no still-upgradable row fits, so that the constraint
  *    (1/n) sum b_i <= avg_bits of Sec. 4.2 holds; with unit costs this is the
- *    printed "until sum b >= n * bit" whenever n * bit is an integer;
+ *    stop rule of the listing (the bits handed out reach n times the target)
+ *    whenever that product is an integer;
  *  - cost (optional) is the number of weights of each row, for tables that
  *    join matrices of different widths; the row maximising reduction / cost
  *    is taken.  NULL means unit cost, the algorithm as printed.
@@ -509,7 +510,7 @@ int64_t oracle_pack(const float *W, const float *alpha, int64_t n, int64_t m, in
 }
 
 /* ------------------------------------------------------------------ */
-/* calc_centroids(W * alpha^-1, L) of Alg. 2 / Alg. 3 line 17: with the labels
+/* calc_centroids(W * alpha^-1, L) of Alg. 2 / the centroid update in the training loop of Alg. 3: with the labels
  * fixed, centroid k of row i is the weighted mean of its members in the
  * scaled domain, c_ik = sum s~ w~ / sum s~ (0 when the cluster carries no
  * mass).  Den (optional) returns the denominators.  c, Den are n x 16.      */

@@ -1,4 +1,4 @@
-// Per-row sensitivity-weighted 1-D K-means (Alg. 3 lines 2-10 and 12-15; the
+// Per-row sensitivity-weighted 1-D K-means (Alg. 3, pre-recording loop and 12-15; the
 // re-clustering of W * alpha^-1 in Alg. 2) for gfx950.
 //
 // Three kernels per call.

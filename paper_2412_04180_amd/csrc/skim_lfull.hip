@@ -1,4 +1,4 @@
-// Error pre-recording with the layer-wise error (Alg. 3 lines 2-10 with Err(.) in its L-full
+// Error pre-recording with the layer-wise error (Alg. 3, pre-recording loop with Err(.) in its L-full
 // form, Sec. 3.4 and the remark under Alg. 1): for every bit width the rows are clustered as
 // in skim_error_table, each weight gets the label of its cluster, and the error of channel i
 // is dW_i H dW_i^T.  Composition of the clustering call, a label kernel and the layer-loss

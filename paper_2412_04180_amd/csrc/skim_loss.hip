@@ -1,4 +1,4 @@
-// Scaling-vector step of SKIM (Sec. 4.3, Alg. 2 inner loop; Alg. 3 lines 16-22)
+// Scaling-vector step of SKIM (Sec. 4.3, Alg. 2 inner loop; Alg. 3, training loop)
 // for gfx950: centroids from fixed labels, the layer-wise (L-full, Sec. 3.4)
 // loss tr(dW H dW^T), its gradient with respect to alpha and the Adam update.
 //
