@@ -2495,11 +2495,16 @@ skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n, bool so
     if (ctx->profiling) SKIM_HIP(ctx, hipEventRecord(ctx->ev[1], ctx->stream));
     const LevelMap lm = level_map((prm.m + 15) >> 4);
     {
-        // two wavefronts per SIMD = 8 workgroups per compute unit; three when that cannot hold all rows at once and
-        // the LDS has room for 12 workgroups
+        // Two wavefronts per SIMD = up to 8 workgroups per compute unit, three = up to 12, both as far as the LDS
+        // has room.  A workgroup's time hardly depends on how many are resident, so the kernel takes as many rounds of
+        // workgroups as it needs to seat them all; the three-wavefront variant (about an eighth slower per round)
+        // is taken when it saves more rounds than that.
         const size_t llds = lloyd_lds_bytes(prm.m);
         const long long wgs = (n + 1) / 2;
-        const bool three = wgs > 8ll * ctx->num_cu && (size_t)ctx->lds_limit / (llds + 256) >= 12;
+        const long long fit = (long long)((size_t)ctx->lds_limit / (llds + 256));
+        const long long seats2 = ctx->num_cu * max(1ll, min(8ll, fit)), seats3 = ctx->num_cu * max(1ll, min(12ll, fit));
+        const long long rounds2 = (wgs + seats2 - 1) / seats2, rounds3 = (wgs + seats3 - 1) / seats3;
+        const bool three = 9 * rounds3 < 8 * rounds2;
         const dim3 grid((unsigned)wgs), block(ITER_THREADS);
         if (prm.m & 15) {
             if (three) hipLaunchKernelGGL((lloyd_iter_kernel<true, 3>), grid, block, llds, ctx->stream, prm, (long long)n, lm);
