@@ -21,7 +21,7 @@ struct skim_ctx {
     hipEvent_t ev[3];    // before sort, between sort and Lloyd, after Lloyd
     int ev_valid;
     size_t sort_lds_enabled[4];   // dynamic LDS size each variant of the sort kernel has been allowed so far (through this context)
-    int greedy_lds_enabled, xtx_lds_enabled;   // the larger dynamic-LDS limit of these kernels has been set through this context
+    int greedy_lds_enabled, xtx_lds_enabled, gemm3_lds_enabled;   // the larger dynamic-LDS limit of these kernels has been set through this context
     int validate;        // check W, S, alpha of the clustering calls for values the method is not defined on
     void *pack_scratch;  // this device's address of the static scratch of skim_pack_static
 };

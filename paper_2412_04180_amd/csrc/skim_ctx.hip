@@ -60,6 +60,7 @@ extern "C" skim_status skim_create(skim_ctx **out, int device, void *hip_stream)
     for (int i = 0; i < 4; ++i) c->sort_lds_enabled[i] = 0;
     c->greedy_lds_enabled = 0;
     c->xtx_lds_enabled = 0;
+    c->gemm3_lds_enabled = 0;
     c->validate = 0;
     c->pack_scratch = nullptr;
     if (skim_pack_static_setup(c) != SKIM_OK) {
@@ -116,7 +117,8 @@ extern "C" size_t skim_workspace_bytes(int64_t n, int64_t m) {
     const size_t N = (size_t)n, M = (size_t)m;
     const size_t ntile = (M + 127) / 128, nstrip = (N + 7) / 8;
     size_t b = 0;
-    b += 2 * N * M * sizeof(float);      // scale step: dW and P
+    b += 3 * N * M * sizeof(uint16_t) + N * M * sizeof(float);   // scale step: dW (as three bfloat16 pieces per value, or as float32) and P
+    b += 3 * M * M * sizeof(uint16_t);   // the pieces of H
     b += 2 * N * 16 * sizeof(double);    // centroids and masses from fixed labels
     b += ntile * N * sizeof(double);     // per-tile row sums of the loss
     b += nstrip * M * sizeof(double);    // per-strip column sums of the gradient

@@ -17,6 +17,25 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
+// Pieces of a float32 value for the contraction on the bf16 matrix cores (see dwh_gemm3_kernel)
+__device__ __forceinline__ uint32_t bf16_rn(float f) {      // finite f
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ float bf16_f32(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ __forceinline__ void split3(float x, uint32_t &p1, uint32_t &p2, uint32_t &p3) {
+    p1 = bf16_rn(x);
+    float r = x - bf16_f32(p1);       // exact
+    p2 = bf16_rn(r);
+    r -= bf16_f32(p2);                // exact; at most 8 significant bits are left
+    p3 = bf16_rn(r);
+}
+__device__ __forceinline__ size_t plane_index(long long row, long long m, long long k) {
+    return (size_t)row * 3 * (size_t)m + (size_t)(k >> 5) * 96 + (size_t)(k & 31);     // piece p at + 32 p
+}
+
+
 constexpr int PREP_THREADS = 256;
 constexpr int BM = 128, BN = 128, BK = 16;
 constexpr int A_STRIDE = BM + 4;   // k-major A tile, padded against bank conflicts of the transposing store
@@ -46,12 +65,12 @@ __device__ __forceinline__ double bin_total(const double (*bins)[16], int k) {
 }
 
 // Per row: weighted cluster sums with fixed labels -> centroids c (n x 16 float64),
-// masses Den (n x 16 float64), and the row of dW (float32).
+// masses Den (n x 16 float64), and the row of dW (float32, or its three bfloat16 pieces when dWp is given).
 // kept (optional): per row, at kept + row * kept_stride, the centroid a cluster keeps when its members carry no
 // sensitivity mass (what the clustering that produced the labels left there); without it such a centroid is 0.
 __global__ void __launch_bounds__(PREP_THREADS) row_prep_kernel(const float *W, const float *S, const float *alpha,
                                                                 long long m, long long ld, const uint8_t *labels,
-                                                                double *cent, double *Den, float *dW,
+                                                                double *cent, double *Den, float *dW, uint16_t *dWp,
                                                                 const double *kept, long long kept_stride, int kept_n) {
     __shared__ double binD[BIN_SETS][16], binN[BIN_SETS][16];
     __shared__ double csh[16];
@@ -85,9 +104,20 @@ __global__ void __launch_bounds__(PREP_THREADS) row_prep_kernel(const float *W, 
         Den[row * 16 + tid] = d;
     }
     __syncthreads();
+    // dW as float32 for dwh_gemm_kernel, or as three bfloat16 pieces per value for dwh_gemm3_kernel
     for (long long j = tid; j < m; j += PREP_THREADS) {
         const double a = alpha ? (double)alpha[j] : 1.0;
-        dW[row * m + j] = (float)((double)Wr[j] - a * csh[Lr[j] & 15]);
+        const float d = (float)((double)Wr[j] - a * csh[Lr[j] & 15]);
+        if (dWp) {
+            uint32_t p1, p2, p3;
+            split3(d, p1, p2, p3);
+            uint16_t *o = dWp + plane_index(row, m, j);
+            o[0] = (uint16_t)p1;
+            o[32] = (uint16_t)p2;
+            o[64] = (uint16_t)p3;
+        } else {
+            dW[row * m + j] = d;
+        }
     }
 }
 
@@ -197,6 +227,161 @@ __global__ void __launch_bounds__(GEMM_THREADS) __attribute__((amdgpu_waves_per_
     }
     __syncthreads();
     if (tid < BM && row0 + tid < n) partial[(long long)blockIdx.x * n + row0 + tid] = rsum[0][tid] + rsum[1][tid];
+}
+
+// ---- the same contraction on the bf16 matrix cores -----------------------------------------------------------
+// A float32 value is the exact sum of three bfloat16 values (8 + 8 + 8 significant bits, each piece the rounding of
+// what the pieces before it leave), so x y = sum over the nine products of pieces, each exact in float32.  The six
+// products with piece indices i + j <= 4 carry everything down to 2^-24 of |x y| -- the size of float32's own
+// rounding -- and v_mfma_f32_32x32x16_bf16 does one of them for 16 k in half the time v_mfma_f32_32x32x2_f32
+// needs for 2 k: 6 x 32 clocks against 512 per 16 k.  Accumulation is float32 in the matrix core either way.
+// Layout of a split matrix ("planes"): row r, for every block of 32 k: [piece 1 (32) | piece 2 (32) | piece 3 (32)]
+// as 192 contiguous bytes, 3 m bfloat16 per row; a 32-k step of a row is then one contiguous read.
+// H (m x m float32, symmetric, m % 32 == 0) -> its planes, row j of the planes = row j of H = column j of H.
+__global__ void __launch_bounds__(256) split_rows_kernel(const float *__restrict__ H, long long rows, long long m,
+                                                         uint16_t *__restrict__ Hp) {
+    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;     // 8 consecutive k of one row
+    const long long per_row = m >> 3;
+    if (g >= rows * per_row) return;
+    const long long j = g / per_row, k = (g - j * per_row) << 3;
+    const float4 a = *(const float4 *)(H + j * m + k), b = *(const float4 *)(H + j * m + k + 4);
+    const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    uint32_t p[3][8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) split3(x[e], p[0][e], p[1][e], p[2][e]);
+    uint16_t *dst = Hp + plane_index(j, m, k);
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+        *(uint4 *)(dst + 32 * q) = make_uint4(p[q][0] | (p[q][1] << 16), p[q][2] | (p[q][3] << 16), p[q][4] | (p[q][5] << 16),
+                                              p[q][6] | (p[q][7] << 16));
+}
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+constexpr int G3_BM = 256, G3_BN = 128, G3_BK = 32, G3_THREADS = 512;
+constexpr int G3_PITCH = 104;                  // bfloat16 per LDS row: 3 pieces x 32 k + 8 of padding = 208 bytes
+constexpr int G3_ROWS = G3_BM + G3_BN;         // the dW rows of the tile, then the H rows
+constexpr int G3_CHUNKS = G3_ROWS * 12 / G3_THREADS;      // 16-byte pieces a thread stages per step: 9
+constexpr size_t G3_LDS_BYTES = 2 * (size_t)G3_ROWS * G3_PITCH * sizeof(uint16_t);   // double-buffered: 159744
+
+// P = dW H from the planes of dW (n rows) and of H (m rows; H symmetric: its row j stands in for its column j).
+// 256 x 128 output tile, 8 wavefronts (two per SIMD) of 64 x 64; 32 k per step, LDS double-buffered, the next
+// step's rows staged through registers while this step's MFMAs run.  Epilogue as in dwh_gemm_kernel, with dW
+// put together again from its pieces (exactly).
+template <bool STORE_P>
+__global__ void __launch_bounds__(G3_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+dwh_gemm3_kernel(const uint16_t *__restrict__ Ap, const uint16_t *__restrict__ Hp, int n, int m, float *__restrict__ P,
+                 double *__restrict__ partial) {
+    extern __shared__ __align__(16) unsigned char g3_smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int row0 = blockIdx.y * G3_BM, col0 = blockIdx.x * G3_BN;
+
+    // staging: piece c = tid + 512 q of the 384 x 12 pieces of a step; consecutive lanes read consecutive 16 bytes
+    const uint16_t *src[G3_CHUNKS];
+    uint32_t dst[G3_CHUNKS];          // byte offset inside one LDS buffer
+    bool ok[G3_CHUNKS];
+#pragma unroll
+    for (int q = 0; q < G3_CHUNKS; ++q) {
+        const int c = tid + G3_THREADS * q;
+        const int trow = c / 12, part = c - 12 * trow;
+        const bool isa = trow < G3_BM;
+        const long long grow = isa ? (long long)row0 + trow : (long long)col0 + (trow - G3_BM);
+        ok[q] = grow < (isa ? (long long)n : (long long)m);
+        src[q] = (isa ? Ap : Hp) + (size_t)(ok[q] ? grow : 0) * 3 * (size_t)m + 8 * part;
+        dst[q] = (uint32_t)(trow * G3_PITCH + 8 * part) * 2u;
+    }
+    uint4 sg[G3_CHUNKS];
+    auto load_step = [&](int kt) {
+#pragma unroll
+        for (int q = 0; q < G3_CHUNKS; ++q) {
+            const uint4 v = *(const uint4 *)(src[q] + (size_t)kt * 96);
+            sg[q] = ok[q] ? v : make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+    auto store_step = [&](int buf, int q0, int q1) {
+        unsigned char *base = g3_smem + (size_t)buf * (G3_ROWS * G3_PITCH * 2);
+#pragma unroll
+        for (int q = 0; q < G3_CHUNKS; ++q)
+            if (q >= q0 && q < q1) *(uint4 *)(base + dst[q]) = sg[q];
+    };
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const int nk = m / G3_BK;
+    load_step(0);
+    store_step(0, 0, G3_CHUNKS);
+    load_step(nk > 1 ? 1 : 0);
+    __syncthreads();
+    // operand of a lane: 8 consecutive k (16 ks + 8 (lane / 32) ..) of piece p of row (lane % 32) of a 32-row block
+    const uint32_t a_off = (uint32_t)((wr * 64 + l32) * G3_PITCH + 8 * lhi) * 2u;
+    const uint32_t b_off = (uint32_t)((G3_BM + wc * 64 + l32) * G3_PITCH + 8 * lhi) * 2u;
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        const unsigned char *tb = g3_smem + (size_t)buf * (G3_ROWS * G3_PITCH * 2);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8_t a[3][2], b[3][2];
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+#pragma unroll
+                for (int x = 0; x < 2; ++x) {
+                    a[p][x] = *(const bf16x8_t *)(tb + a_off + (uint32_t)(32 * x * G3_PITCH + 32 * p + 16 * ks) * 2u);
+                    b[p][x] = *(const bf16x8_t *)(tb + b_off + (uint32_t)(32 * x * G3_PITCH + 32 * p + 16 * ks) * 2u);
+                }
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int y = 0; y < 2; ++y) {
+                    // smallest products first
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][x], b[1][y], acc[x][y], 0, 0, 0);
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][x], b[2][y], acc[x][y], 0, 0, 0);
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2][x], b[0][y], acc[x][y], 0, 0, 0);
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][x], b[1][y], acc[x][y], 0, 0, 0);
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][x], b[0][y], acc[x][y], 0, 0, 0);
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][x], b[0][y], acc[x][y], 0, 0, 0);
+                }
+            // the next step's rows go to the other buffer between the MFMAs (past the end: a repeat, never read)
+            if (ks == 0) store_step(buf ^ 1, 0, 5);
+            else store_step(buf ^ 1, 5, G3_CHUNKS);
+        }
+        load_step(min(kt + 2, nk - 1));
+        __syncthreads();
+    }
+
+    // epilogue.  Accumulator element e of a 32 x 32 tile: row = 8*(e/4) + 4*(lane/32) + e%4, column = lane%32.
+    double *rsum = (double *)g3_smem;          // [2][G3_BM]; the tiles are no longer read
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int rl = wr * 64 + i * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
+            const int r = row0 + rl;
+            double t = 0.0;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int c = col0 + wc * 64 + j * 32 + l32;
+                if (r < n && c < m) {
+                    const float p = acc[i][j][e];
+                    if (STORE_P) P[(long long)r * m + c] = p;
+                    const uint16_t *ap = Ap + plane_index(r, m, c);
+                    const float dw = (bf16_f32(ap[0]) + bf16_f32(ap[32])) + bf16_f32(ap[64]);     // exact
+                    t += (double)p * (double)dw;
+                }
+            }
+            // sum over the 32 lanes that share this row
+            for (int o = 16; o >= 1; o >>= 1) t += __shfl_xor(t, o, 64);
+            if (l32 == 0) rsum[wc * G3_BM + rl] = t;
+        }
+    }
+    __syncthreads();
+    if (tid < G3_BM && row0 + tid < n) partial[(long long)blockIdx.x * n + row0 + tid] = rsum[tid] + rsum[G3_BM + tid];
 }
 
 // row_loss[i] = sum over column tiles (one thread per row, neighbouring threads on neighbouring rows of every
@@ -361,27 +546,71 @@ __global__ void __launch_bounds__(ADAM_COLS * ADAM_GROUPS) adam_kernel(const dou
 
 struct LossWs {
     float *dW, *P;
+    uint16_t *dWp, *Hp;      // pieces of dW and of H for dwh_gemm3_kernel (null: the float32 kernel is used)
     double *cent, *Den, *partial, *gpart;
     int ntile, nstrip;
 };
+
+// The contraction runs on the bf16 matrix cores when the rows split into whole 32-k blocks and are long enough to
+// fill a step pipeline; otherwise on the float32 ones.
+bool use_pieces(int64_t m) { return (m % G3_BK) == 0 && m >= 128; }
 
 skim_status carve(skim_ctx *ctx, int64_t n, int64_t m, bool need_grad, LossWs &w) {
     skim_ws_cursor cur{(char *)ctx->ws, 0, ctx->ws_bytes};
     w.ntile = (int)((m + BN - 1) / BN);
     w.nstrip = (int)((n + STRIP - 1) / STRIP);
-    w.dW = (float *)cur.take((size_t)n * m * sizeof(float));
+    w.dW = nullptr;
+    w.dWp = w.Hp = nullptr;
+    if (use_pieces(m)) {        // (first in the workspace: skim_train_scale keeps the pieces of H across its steps)
+        w.Hp = (uint16_t *)cur.take((size_t)m * m * 3 * sizeof(uint16_t));
+        w.dWp = (uint16_t *)cur.take((size_t)n * m * 3 * sizeof(uint16_t));
+    } else {
+        w.dW = (float *)cur.take((size_t)n * m * sizeof(float));
+    }
     w.cent = (double *)cur.take((size_t)n * 16 * sizeof(double));
     w.Den = (double *)cur.take((size_t)n * 16 * sizeof(double));
     w.partial = (double *)cur.take((size_t)w.ntile * n * sizeof(double));
     w.P = nullptr;
     w.gpart = nullptr;
-    bool ok = w.dW && w.cent && w.Den && w.partial;
+    bool ok = (w.dW || (w.dWp && w.Hp)) && w.cent && w.Den && w.partial;
     if (need_grad) {
         w.P = (float *)cur.take((size_t)n * m * sizeof(float));
         w.gpart = (double *)cur.take((size_t)w.nstrip * m * sizeof(double));
         ok = ok && w.P && w.gpart;
     }
     if (!ok) SKIM_FAIL(ctx, SKIM_ERR_WORKSPACE, "workspace missing or smaller than skim_workspace_bytes(n, m)");
+    return SKIM_OK;
+}
+
+// P = dW H (and the per-tile row sums of P o dW) by whichever kernel the workspace was carved for.  h_ready: the
+// pieces of H are already in w.Hp (skim_train_scale splits H once per round of steps).
+skim_status launch_contraction(skim_ctx *ctx, const LossWs &w, const float *H, int64_t n, int64_t m, bool store_p,
+                               bool h_ready) {
+    if (w.dWp) {
+        if (!ctx->gemm3_lds_enabled) {
+            SKIM_HIP(ctx, hipFuncSetAttribute((const void *)dwh_gemm3_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)G3_LDS_BYTES));
+            SKIM_HIP(ctx, hipFuncSetAttribute((const void *)dwh_gemm3_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)G3_LDS_BYTES));
+            ctx->gemm3_lds_enabled = 1;
+        }
+        if (!h_ready)
+            hipLaunchKernelGGL(split_rows_kernel, dim3((unsigned)((m * (m / 8) + 255) / 256)), dim3(256), 0, ctx->stream, H,
+                               (long long)m, (long long)m, w.Hp);
+        const dim3 grid((unsigned)((m + G3_BN - 1) / G3_BN), (unsigned)((n + G3_BM - 1) / G3_BM));
+        if (store_p)
+            hipLaunchKernelGGL(dwh_gemm3_kernel<true>, grid, dim3(G3_THREADS), G3_LDS_BYTES, ctx->stream, w.dWp, w.Hp, (int)n,
+                               (int)m, w.P, w.partial);
+        else
+            hipLaunchKernelGGL(dwh_gemm3_kernel<false>, grid, dim3(G3_THREADS), G3_LDS_BYTES, ctx->stream, w.dWp, w.Hp, (int)n,
+                               (int)m, (float *)nullptr, w.partial);
+    } else {
+        const dim3 grid(w.ntile, (unsigned)((n + BM - 1) / BM));
+        if (store_p)
+            hipLaunchKernelGGL(dwh_gemm_kernel<true>, grid, dim3(GEMM_THREADS), 0, ctx->stream, w.dW, H, (int)n, (int)m, w.P,
+                               w.partial);
+        else
+            hipLaunchKernelGGL(dwh_gemm_kernel<false>, grid, dim3(GEMM_THREADS), 0, ctx->stream, w.dW, H, (int)n, (int)m,
+                               (float *)nullptr, w.partial);
+    }
     return SKIM_OK;
 }
 
@@ -412,18 +641,30 @@ skim_status skim_layer_loss_strided(skim_ctx *ctx, const float *W, const float *
     LossWs w;
     if ((st = carve(ctx, n, m, false, w)) != SKIM_OK) return st;
     hipLaunchKernelGGL(row_prep_kernel, dim3((unsigned)n), dim3(PREP_THREADS), 0, ctx->stream, W, S, alpha, (long long)m,
-                       (long long)ld, labels, w.cent, w.Den, w.dW, kept, (long long)kept_stride, kept_n);
-    hipLaunchKernelGGL(dwh_gemm_kernel<false>, dim3(w.ntile, (unsigned)((n + BM - 1) / BM)), dim3(GEMM_THREADS), 0,
-                       ctx->stream, w.dW, H, (int)n, (int)m, (float *)nullptr, w.partial);
+                       (long long)ld, labels, w.cent, w.Den, w.dW, w.dWp, kept, (long long)kept_stride, kept_n);
+    if ((st = launch_contraction(ctx, w, H, n, m, false, false)) != SKIM_OK) return st;
     launch_loss_finish(ctx->stream, w.partial, w.ntile, (long long)n, loss, row_loss, (long long)row_stride);
     SKIM_HIP(ctx, hipGetLastError());
     return SKIM_OK;
+}
+
+namespace {
+skim_status scale_step_impl(skim_ctx *ctx, const float *W, const float *S, const float *H, int64_t n, int64_t m,
+                            int64_t ld, const uint8_t *labels, float *alpha, float *adam_m, float *adam_v, int64_t t,
+                            const skim_adam_opts *opts, double *loss_before, float *grad_out, bool h_ready);
 }
 
 extern "C" skim_status skim_scale_step(skim_ctx *ctx, const float *W, const float *S, const float *H, int64_t n,
                                        int64_t m, int64_t ld, const uint8_t *labels, float *alpha, float *adam_m,
                                        float *adam_v, int64_t t, const skim_adam_opts *opts, double *loss_before,
                                        float *grad_out) {
+    return scale_step_impl(ctx, W, S, H, n, m, ld, labels, alpha, adam_m, adam_v, t, opts, loss_before, grad_out, false);
+}
+
+namespace {
+skim_status scale_step_impl(skim_ctx *ctx, const float *W, const float *S, const float *H, int64_t n, int64_t m,
+                            int64_t ld, const uint8_t *labels, float *alpha, float *adam_m, float *adam_v, int64_t t,
+                            const skim_adam_opts *opts, double *loss_before, float *grad_out, bool h_ready) {
     skim_status st = skim_enter(ctx);
     if (st != SKIM_OK) return st;
     if (!W || !S || !H || !labels || !alpha || !adam_m || !adam_v || !opts || !loss_before)
@@ -434,9 +675,8 @@ extern "C" skim_status skim_scale_step(skim_ctx *ctx, const float *W, const floa
     LossWs w;
     if ((st = carve(ctx, n, m, true, w)) != SKIM_OK) return st;
     hipLaunchKernelGGL(row_prep_kernel, dim3((unsigned)n), dim3(PREP_THREADS), 0, ctx->stream, W, S, (const float *)alpha,
-                       (long long)m, (long long)ld, labels, w.cent, w.Den, w.dW, (const double *)nullptr, 0ll, 0);
-    hipLaunchKernelGGL(dwh_gemm_kernel<true>, dim3(w.ntile, (unsigned)((n + BM - 1) / BM)), dim3(GEMM_THREADS), 0,
-                       ctx->stream, w.dW, H, (int)n, (int)m, w.P, w.partial);
+                       (long long)m, (long long)ld, labels, w.cent, w.Den, w.dW, w.dWp, (const double *)nullptr, 0ll, 0);
+    if ((st = launch_contraction(ctx, w, H, n, m, true, h_ready)) != SKIM_OK) return st;
     launch_loss_finish(ctx->stream, w.partial, w.ntile, (long long)n, loss_before, (double *)nullptr, 1ll);
     if (m <= (int64_t)GRAD_NC * PREP_THREADS)
         hipLaunchKernelGGL(grad_rows_kernel<true>, dim3(w.nstrip), dim3(PREP_THREADS), 0, ctx->stream, W, S,
@@ -454,6 +694,7 @@ extern "C" skim_status skim_scale_step(skim_ctx *ctx, const float *W, const floa
     SKIM_HIP(ctx, hipGetLastError());
     return SKIM_OK;
 }
+}  // namespace
 
 // Scaling-vector training (Alg. 2): `outer` rounds of { labels = K-means of W * alpha^-1 at the given bit
 // widths; `steps` optimiser steps on alpha with the labels fixed }, then the centroids and the loss at the
@@ -484,9 +725,10 @@ extern "C" skim_status skim_train_scale(skim_ctx *ctx, const float *W, const flo
         if ((st = skim_cluster_rows(ctx, W, S, alpha, n, m, ld, bits, kmeans_iters, labels, centroids, upper, err)) !=
             SKIM_OK)
             return st;
+        // H is cut into its pieces once per round (the re-clustering has written over that part of the workspace)
         for (int k = 0; k < steps; ++k, ++t, ++slot) {
-            if ((st = skim_scale_step(ctx, W, S, H, n, m, ld, labels, alpha, adam_m, adam_v, t, opts,
-                                      loss_trace + slot, nullptr)) != SKIM_OK)
+            if ((st = scale_step_impl(ctx, W, S, H, n, m, ld, labels, alpha, adam_m, adam_v, t, opts, loss_trace + slot,
+                                      nullptr, k > 0)) != SKIM_OK)
                 return st;
         }
     }
