@@ -495,9 +495,15 @@ def bench_scale_loop(ctx, torch, np, skim_synth, iters=3):
             "lfull_error_table_ms": round(t_lfull, 4),
             "lfull_error_table_tflops": round(4 * flops / (t_lfull * 1e-3) / 1e12, 2),
             "recluster_ms": round(t_cluster / iters, 4), "layer_loss_ms": round(t_loss / iters, 4),
+            # 2 n m^2 flops of the contraction per second of the whole layer-loss call.  The contraction runs on the
+            # bf16 matrix cores with every float32 operand cut into three bfloat16 pieces (the six leading piece
+            # products per k: float32-grade result): the matrix cores execute 6 x 2 n m^2 flops
             "layer_loss_tflops": round(flops / (t_loss / iters * 1e-3) / 1e12, 2),
+            "layer_loss_executed_bf16_tflops": round(6 * flops / (t_loss / iters * 1e-3) / 1e12, 1),
+            "mfma_bf16_peak_tflops": 2500.0,
+            "layer_loss_frac_of_mfma_peak": round(6 * flops / (t_loss / iters * 1e-3) / 1e12 / 2500.0, 4),
             "mfma_f32_peak_tflops": MFMA_F32_PEAK_TFLOPS,
-            "layer_loss_frac_of_mfma_peak": round(flops / (t_loss / iters * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS, 4),
+            "layer_loss_over_f32_mfma_peak": round(flops / (t_loss / iters * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS, 4),
             "loss_after_each_iteration": losses}
 
 

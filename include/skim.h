@@ -288,8 +288,13 @@ skim_status skim_hessian_from_activations(skim_ctx *ctx, const uint16_t *X_bf16,
  *   loss = tr(dW H dW^T) = sum_i dW_i H dW_i^T  (Sec. 3.4, L-full; H ~ X X^T)
  * H: dev m x m float32 (symmetric).  labels: dev uint8 n x m.  loss: dev
  * float64 scalar.  row_loss: dev float64[n] (the L-full error of each channel),
- * may be NULL.  The contraction dW*H runs on fp32 MFMA with fp32 accumulation;
- * the final reductions are float64.  m must be a multiple of 16. */
+ * may be NULL.  The contraction dW*H accumulates in float32 on the matrix cores:
+ * for m a multiple of 32 (and >= 128) on the bf16 ones, with every float32 operand
+ * cut exactly into three bfloat16 pieces and the six leading piece products taken
+ * per k (what is dropped is below 2^-24 of each product, the size of float32's own
+ * rounding); otherwise on the fp32 ones.  The bf16 path reads row j of H for its
+ * column j: H must be symmetric, as the H of Sec. 3.4 is.  The final reductions are
+ * float64.  m must be a multiple of 16. */
 skim_status skim_layer_loss(skim_ctx *ctx, const float *W, const float *S, const float *alpha,
                             const float *H, int64_t n, int64_t m, int64_t ld,
                             const uint8_t *labels, double *loss, double *row_loss);
@@ -300,8 +305,8 @@ skim_status skim_layer_loss(skim_ctx *ctx, const float *W, const float *S, const
  *   E_full[i][b-bmin] = dW_i H dW_i^T,  dW_i = w_i - alpha * c_{i, L_i}
  * with L the labels of that clustering and c the weighted means of its clusters
  * (a cluster whose members carry no sensitivity mass keeps the centroid the
- * clustering left it with, the value skim_pack stores; one fp32-MFMA
- * contraction dW * H per bit width, float64 reductions).
+ * clustering left it with, the value skim_pack stores; one contraction
+ * dW * H per bit width as in skim_layer_loss, float64 reductions).
  * E_full: dev float64 n x nb.  E_sdiag: dev float64 n x nb, the S-diag errors
  * of the same clusterings (what skim_error_table returns), may be NULL.
  * centroids_all, upper_all: as in skim_error_table, required.  labels_work:

@@ -4,7 +4,8 @@
 //
 //   c_ik  = sum_{j in k} s~_ij w~_ij / sum_{j in k} s~_ij      (calc_centroids(W*alpha^-1, L))
 //   dW_ij = w_ij - alpha_j c_{i,L_ij}                           (W - replace(c, L) * alpha)
-//   P     = dW H            fp32 MFMA, fp32 accumulation (the path's one dense contraction)
+//   P     = dW H            matrix cores, float32 accumulation (the path's one dense contraction): bf16 MFMA on
+//                           three-piece splits of the float32 operands (dwh_gemm3_kernel), or fp32 MFMA (dwh_gemm_kernel)
 //   loss  = sum_ij P_ij dW_ij                                   float64 reduction
 //   dloss/dalpha_l = -2 sum_i [ P_il c_{i,L_il}
 //                    + Q_{i,L_il} s_il (w_il - 2 alpha_l c_{i,L_il}) / D_{i,L_il} ],
