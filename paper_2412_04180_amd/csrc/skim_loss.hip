@@ -72,7 +72,8 @@ __device__ __forceinline__ double bin_total(const double (*bins)[16], int k) {
 __global__ void __launch_bounds__(PREP_THREADS) row_prep_kernel(const float *W, const float *S, const float *alpha,
                                                                 long long m, long long ld, const uint8_t *labels,
                                                                 double *cent, double *Den, float *dW, uint16_t *dWp,
-                                                                const double *kept, long long kept_stride, int kept_n) {
+                                                                const double *kept, long long kept_stride, int kept_n,
+                                                                bool vec4) {
     __shared__ double binD[BIN_SETS][16], binN[BIN_SETS][16];
     __shared__ double csh[16];
     const long long row = blockIdx.x;
@@ -85,16 +86,28 @@ __global__ void __launch_bounds__(PREP_THREADS) row_prep_kernel(const float *W, 
     __syncthreads();
     double *myD = binD[wave * BIN_COPIES + (lane & (BIN_COPIES - 1))];
     double *myN = binN[wave * BIN_COPIES + (lane & (BIN_COPIES - 1))];
-    for (long long j = tid; j < m; j += PREP_THREADS) {
-        float wt = Wr[j], st = Sr[j];
+    auto add_element = [&](float wt, float st, float a, int l) {
         if (alpha) {
-            const float a = alpha[j];
             wt = __fdiv_rn(wt, a);
             st = __fmul_rn(__fmul_rn(st, a), a);
         }
-        const int l = Lr[j] & 15;
         atomicAdd(&myD[l], (double)st);
         atomicAdd(&myN[l], (double)st * (double)wt);
+    };
+    // vec4: rows start 16-byte aligned (labels 4-byte) and m is a multiple of 4: four neighbouring columns per
+    // thread and step, a quarter of the load instructions
+    if (vec4) {
+        for (long long j = 4ll * tid; j < m; j += 4 * PREP_THREADS) {
+            const float4 w4 = *(const float4 *)(Wr + j), s4 = *(const float4 *)(Sr + j);
+            const float4 a4 = alpha ? *(const float4 *)(alpha + j) : make_float4(1.f, 1.f, 1.f, 1.f);
+            const uint32_t l4 = *(const uint32_t *)(Lr + j);
+            add_element(w4.x, s4.x, a4.x, (int)(l4 & 15u));
+            add_element(w4.y, s4.y, a4.y, (int)((l4 >> 8) & 15u));
+            add_element(w4.z, s4.z, a4.z, (int)((l4 >> 16) & 15u));
+            add_element(w4.w, s4.w, a4.w, (int)((l4 >> 24) & 15u));
+        }
+    } else {
+        for (long long j = tid; j < m; j += PREP_THREADS) add_element(Wr[j], Sr[j], alpha ? alpha[j] : 1.0f, Lr[j] & 15);
     }
     __syncthreads();
     if (tid < 16) {
@@ -106,6 +119,25 @@ __global__ void __launch_bounds__(PREP_THREADS) row_prep_kernel(const float *W, 
     }
     __syncthreads();
     // dW as float32 for dwh_gemm_kernel, or as three bfloat16 pieces per value for dwh_gemm3_kernel
+    if (vec4 && dWp) {
+        for (long long j = 4ll * tid; j < m; j += 4 * PREP_THREADS) {
+            const float4 w4 = *(const float4 *)(Wr + j);
+            const float4 a4 = alpha ? *(const float4 *)(alpha + j) : make_float4(1.f, 1.f, 1.f, 1.f);
+            const uint32_t l4 = *(const uint32_t *)(Lr + j);
+            const float wv[4] = {w4.x, w4.y, w4.z, w4.w}, av[4] = {a4.x, a4.y, a4.z, a4.w};
+            uint32_t pc[3][4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float d = (float)((double)wv[e] - (double)av[e] * csh[(l4 >> (8 * e)) & 15u]);
+                split3(d, pc[0][e], pc[1][e], pc[2][e]);
+            }
+            uint16_t *o = dWp + plane_index(row, m, j);       // four neighbouring k stay inside one block of 32
+#pragma unroll
+            for (int q = 0; q < 3; ++q)
+                *(uint2 *)(o + 32 * q) = make_uint2(pc[q][0] | (pc[q][1] << 16), pc[q][2] | (pc[q][3] << 16));
+        }
+        return;
+    }
     for (long long j = tid; j < m; j += PREP_THREADS) {
         const double a = alpha ? (double)alpha[j] : 1.0;
         const float d = (float)((double)Wr[j] - a * csh[Lr[j] & 15]);
@@ -434,11 +466,11 @@ static void launch_loss_finish(hipStream_t stream, double *partial, int ntile, l
 constexpr int GRAD_NC = 16;
 
 template <bool REG>
-__global__ void __launch_bounds__(PREP_THREADS) grad_rows_kernel(const float *W, const float *S, const float *alpha,
+__global__ void __launch_bounds__(PREP_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) grad_rows_kernel(const float *W, const float *S, const float *alpha,
                                                                  long long n, long long m, long long ld,
                                                                  const uint8_t *labels, const float *P,
                                                                  const double *cent, const double *Den,
-                                                                 double *gpart) {
+                                                                 double *gpart, bool vec4) {
     __shared__ double binQ[BIN_SETS][16];
     __shared__ double rsh[16], csh[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -446,10 +478,16 @@ __global__ void __launch_bounds__(PREP_THREADS) grad_rows_kernel(const float *W,
     double *gp = gpart + (long long)blockIdx.x * m;
     double gacc[GRAD_NC];
     float al[GRAD_NC];
+    // The columns of a thread (REG): tid, tid + 256, ... -- or, when the rows can be read 16 bytes at a time (vec4),
+    // four groups of four neighbouring columns 4 (tid + 256 q) .. + 3: a quarter of the load instructions, and a
+    // row then arrives in a third of the time.
+    auto colof = [&](int c) -> long long {
+        return vec4 ? 4ll * (tid + (long long)(c >> 2) * PREP_THREADS) + (c & 3) : tid + (long long)c * PREP_THREADS;
+    };
     if (REG) {
 #pragma unroll
         for (int c = 0; c < GRAD_NC; ++c) {
-            const long long l = tid + (long long)c * PREP_THREADS;
+            const long long l = colof(c);
             gacc[c] = 0.0;
             al[c] = l < m ? alpha[l] : 0.0f;
         }
@@ -462,31 +500,58 @@ __global__ void __launch_bounds__(PREP_THREADS) grad_rows_kernel(const float *W,
         const uint8_t *Lr = labels + row * m;
         const float *Wr = W + row * ld, *Sr = S + row * ld;
         (&binQ[0][0])[tid] = 0.0;
+        // the row's cluster masses and centroids are requested now by the 16 threads that need them between the
+        // barriers below, where every other thread waits for them
+        double den_k = 0.0, cen_k = 0.0;
+        if (tid < 16) {
+            den_k = Den[row * 16 + tid];
+            cen_k = cent[row * 16 + tid];
+        }
         __syncthreads();      // bins cleared; the previous row's rsh/csh are no longer read
         float pv[GRAD_NC], wv[GRAD_NC], sv[GRAD_NC];
         int lv[GRAD_NC];
         if (REG) {
+            if (vec4) {
 #pragma unroll
-            for (int c = 0; c < GRAD_NC; ++c) {
-                const long long l = tid + (long long)c * PREP_THREADS;
-                const bool in = l < m;
-                pv[c] = in ? Pr[l] : 0.0f;
-                lv[c] = in ? (Lr[l] & 15) : 0;
-                wv[c] = in ? Wr[l] : 0.0f;
-                sv[c] = in ? Sr[l] : 0.0f;
+                for (int q = 0; q < GRAD_NC / 4; ++q) {
+                    const long long l = colof(4 * q);
+                    float4 p4 = make_float4(0.f, 0.f, 0.f, 0.f), w4 = p4, s4 = p4;
+                    uint32_t l4 = 0u;
+                    if (l < m) {          // m is a multiple of 4 here: the four columns are inside together
+                        p4 = *(const float4 *)(Pr + l);
+                        w4 = *(const float4 *)(Wr + l);
+                        s4 = *(const float4 *)(Sr + l);
+                        l4 = *(const uint32_t *)(Lr + l);
+                    }
+                    pv[4 * q] = p4.x; pv[4 * q + 1] = p4.y; pv[4 * q + 2] = p4.z; pv[4 * q + 3] = p4.w;
+                    wv[4 * q] = w4.x; wv[4 * q + 1] = w4.y; wv[4 * q + 2] = w4.z; wv[4 * q + 3] = w4.w;
+                    sv[4 * q] = s4.x; sv[4 * q + 1] = s4.y; sv[4 * q + 2] = s4.z; sv[4 * q + 3] = s4.w;
+                    lv[4 * q] = (int)(l4 & 15u); lv[4 * q + 1] = (int)((l4 >> 8) & 15u);
+                    lv[4 * q + 2] = (int)((l4 >> 16) & 15u); lv[4 * q + 3] = (int)((l4 >> 24) & 15u);
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < GRAD_NC; ++c) {
+                    const long long l = colof(c);
+                    const bool in = l < m;
+                    pv[c] = in ? Pr[l] : 0.0f;
+                    lv[c] = in ? (Lr[l] & 15) : 0;
+                    wv[c] = in ? Wr[l] : 0.0f;
+                    sv[c] = in ? Sr[l] : 0.0f;
+                }
             }
 #pragma unroll
             for (int c = 0; c < GRAD_NC; ++c)
-                if (tid + (long long)c * PREP_THREADS < m) atomicAdd(&myQ[lv[c]], (double)pv[c] * (double)al[c]);
+                if (colof(c) < m) atomicAdd(&myQ[lv[c]], (double)pv[c] * (double)al[c]);
         } else {
             for (long long j = tid; j < m; j += PREP_THREADS)
                 atomicAdd(&myQ[Lr[j] & 15], (double)Pr[j] * (double)alpha[j]);
         }
         __syncthreads();
         if (tid < 16) {
-            const double q = bin_total(binQ, tid), d = Den[row * 16 + tid];
+            const double q = bin_total(binQ, tid), d = den_k;
             rsh[tid] = d > 0.0 ? q / d : 0.0;
-            csh[tid] = cent[row * 16 + tid];
+            csh[tid] = cen_k;
         }
         __syncthreads();
         if (REG) {
@@ -508,7 +573,7 @@ __global__ void __launch_bounds__(PREP_THREADS) grad_rows_kernel(const float *W,
     if (REG) {
 #pragma unroll
         for (int c = 0; c < GRAD_NC; ++c) {
-            const long long l = tid + (long long)c * PREP_THREADS;
+            const long long l = colof(c);
             if (l < m) gp[l] = gacc[c];
         }
     }
@@ -615,6 +680,11 @@ skim_status launch_contraction(skim_ctx *ctx, const LossWs &w, const float *H, i
     return SKIM_OK;
 }
 
+// rows of W and S start 16-byte aligned, alpha is, and the labels of a row start 4-byte aligned (m is a multiple of 16)
+bool rows_vec4(const float *W, const float *S, const float *alpha, const uint8_t *labels, int64_t ld) {
+    return (ld % 4) == 0 && (((uintptr_t)W | (uintptr_t)S | (uintptr_t)alpha) & 15) == 0 && ((uintptr_t)labels & 3) == 0;
+}
+
 skim_status check_shape(skim_ctx *ctx, int64_t n, int64_t m, int64_t ld) {
     if (n < 1 || n > 0x7fffffff || m < BK || m > 0x7fffffff || ld < m || (m % BK) != 0)
         SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "layer loss needs n >= 1, m a multiple of %d, ld >= m (n=%lld m=%lld ld=%lld)", BK,
@@ -642,7 +712,8 @@ skim_status skim_layer_loss_strided(skim_ctx *ctx, const float *W, const float *
     LossWs w;
     if ((st = carve(ctx, n, m, false, w)) != SKIM_OK) return st;
     hipLaunchKernelGGL(row_prep_kernel, dim3((unsigned)n), dim3(PREP_THREADS), 0, ctx->stream, W, S, alpha, (long long)m,
-                       (long long)ld, labels, w.cent, w.Den, w.dW, w.dWp, kept, (long long)kept_stride, kept_n);
+                       (long long)ld, labels, w.cent, w.Den, w.dW, w.dWp, kept, (long long)kept_stride, kept_n,
+                       rows_vec4(W, S, alpha, labels, ld));
     if ((st = launch_contraction(ctx, w, H, n, m, false, false)) != SKIM_OK) return st;
     launch_loss_finish(ctx->stream, w.partial, w.ntile, (long long)n, loss, row_loss, (long long)row_stride);
     SKIM_HIP(ctx, hipGetLastError());
@@ -676,17 +747,20 @@ skim_status scale_step_impl(skim_ctx *ctx, const float *W, const float *S, const
     LossWs w;
     if ((st = carve(ctx, n, m, true, w)) != SKIM_OK) return st;
     hipLaunchKernelGGL(row_prep_kernel, dim3((unsigned)n), dim3(PREP_THREADS), 0, ctx->stream, W, S, (const float *)alpha,
-                       (long long)m, (long long)ld, labels, w.cent, w.Den, w.dW, w.dWp, (const double *)nullptr, 0ll, 0);
+                       (long long)m, (long long)ld, labels, w.cent, w.Den, w.dW, w.dWp, (const double *)nullptr, 0ll, 0,
+                       rows_vec4(W, S, alpha, labels, ld));
     if ((st = launch_contraction(ctx, w, H, n, m, true, h_ready)) != SKIM_OK) return st;
     launch_loss_finish(ctx->stream, w.partial, w.ntile, (long long)n, loss_before, (double *)nullptr, 1ll);
+    // rows of W, S, P start 16-byte aligned and the labels of a row 4-byte aligned (m is a multiple of 16)
+    const bool vec4 = rows_vec4(W, S, alpha, labels, ld) && ((uintptr_t)w.P & 15) == 0;
     if (m <= (int64_t)GRAD_NC * PREP_THREADS)
         hipLaunchKernelGGL(grad_rows_kernel<true>, dim3(w.nstrip), dim3(PREP_THREADS), 0, ctx->stream, W, S,
                            (const float *)alpha, (long long)n, (long long)m, (long long)ld, labels, w.P, w.cent, w.Den,
-                           w.gpart);
+                           w.gpart, vec4);
     else
         hipLaunchKernelGGL(grad_rows_kernel<false>, dim3(w.nstrip), dim3(PREP_THREADS), 0, ctx->stream, W, S,
                            (const float *)alpha, (long long)n, (long long)m, (long long)ld, labels, w.P, w.cent, w.Den,
-                           w.gpart);
+                           w.gpart, false);
     const double lr = (double)opts->lr0 * pow((double)opts->decay, (double)((t - 1) / opts->decay_every));
     const double bc1 = 1.0 - pow((double)opts->beta1, (double)t), bc2 = 1.0 - pow((double)opts->beta2, (double)t);
     hipLaunchKernelGGL(adam_kernel, dim3((unsigned)((m + ADAM_COLS - 1) / ADAM_COLS)), dim3(ADAM_COLS * ADAM_GROUPS), 0, ctx->stream, w.gpart, w.nstrip,
