@@ -32,8 +32,8 @@ __device__ __forceinline__ void split3(float x, uint32_t &p1, uint32_t &p2, uint
     r -= bf16_f32(p2);                // exact; at most 8 significant bits are left
     p3 = bf16_rn(r);
 }
-__device__ __forceinline__ size_t plane_index(long long row, long long m, long long k) {
-    return (size_t)row * 3 * (size_t)m + (size_t)(k >> 5) * 96 + (size_t)(k & 31);     // piece p at + 32 p
+__device__ __forceinline__ size_t plane_index(long long row, long long rows, long long k) {
+    return ((size_t)(k >> 5) * (size_t)rows + (size_t)row) * 96 + (size_t)(k & 31);     // piece p at + 32 p
 }
 
 
@@ -76,7 +76,7 @@ __global__ void __launch_bounds__(PREP_THREADS) row_prep_kernel(const float *W, 
                                                                 bool vec4) {
     __shared__ double binD[BIN_SETS][16], binN[BIN_SETS][16];
     __shared__ double csh[16];
-    const long long row = blockIdx.x;
+    const long long row = blockIdx.x, nrows = gridDim.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *Wr = W + row * ld, *Sr = S + row * ld;
     const uint8_t *Lr = labels + row * m;
@@ -131,7 +131,7 @@ __global__ void __launch_bounds__(PREP_THREADS) row_prep_kernel(const float *W, 
                 const float d = (float)((double)wv[e] - (double)av[e] * csh[(l4 >> (8 * e)) & 15u]);
                 split3(d, pc[0][e], pc[1][e], pc[2][e]);
             }
-            uint16_t *o = dWp + plane_index(row, m, j);       // four neighbouring k stay inside one block of 32
+            uint16_t *o = dWp + plane_index(row, nrows, j);   // four neighbouring k stay inside one block of 32
 #pragma unroll
             for (int q = 0; q < 3; ++q)
                 *(uint2 *)(o + 32 * q) = make_uint2(pc[q][0] | (pc[q][1] << 16), pc[q][2] | (pc[q][3] << 16));
@@ -144,7 +144,7 @@ __global__ void __launch_bounds__(PREP_THREADS) row_prep_kernel(const float *W, 
         if (dWp) {
             uint32_t p1, p2, p3;
             split3(d, p1, p2, p3);
-            uint16_t *o = dWp + plane_index(row, m, j);
+            uint16_t *o = dWp + plane_index(row, nrows, j);
             o[0] = (uint16_t)p1;
             o[32] = (uint16_t)p2;
             o[64] = (uint16_t)p3;
@@ -268,8 +268,10 @@ __global__ void __launch_bounds__(GEMM_THREADS) __attribute__((amdgpu_waves_per_
 // products with piece indices i + j <= 4 carry everything down to 2^-24 of |x y| -- the size of float32's own
 // rounding -- and v_mfma_f32_32x32x16_bf16 does one of them for 16 k in half the time v_mfma_f32_32x32x2_f32
 // needs for 2 k: 6 x 32 clocks against 512 per 16 k.  Accumulation is float32 in the matrix core either way.
-// Layout of a split matrix ("planes"): row r, for every block of 32 k: [piece 1 (32) | piece 2 (32) | piece 3 (32)]
-// as 192 contiguous bytes, 3 m bfloat16 per row; a 32-k step of a row is then one contiguous read.
+// Layout of a split matrix ("planes"): for every block of 32 k, row after row, [piece 1 (32) | piece 2 (32) |
+// piece 3 (32)] as 192 contiguous bytes: the rows of a tile for one 32-k step are one contiguous region of memory
+// (64 lanes of a load instruction read 1024 consecutive bytes; with the blocks of a row side by side instead, an
+// instruction read 192 bytes of each of six rows and the kernel sat at the rate the memory system serves that).
 // H (m x m float32, symmetric, m % 32 == 0) -> its planes, row j of the planes = row j of H = column j of H.
 __global__ void __launch_bounds__(256) split_rows_kernel(const float *__restrict__ H, long long rows, long long m,
                                                          uint16_t *__restrict__ Hp) {
@@ -282,7 +284,7 @@ __global__ void __launch_bounds__(256) split_rows_kernel(const float *__restrict
     uint32_t p[3][8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) split3(x[e], p[0][e], p[1][e], p[2][e]);
-    uint16_t *dst = Hp + plane_index(j, m, k);
+    uint16_t *dst = Hp + plane_index(j, rows, k);
 #pragma unroll
     for (int q = 0; q < 3; ++q)
         *(uint4 *)(dst + 32 * q) = make_uint4(p[q][0] | (p[q][1] << 16), p[q][2] | (p[q][3] << 16), p[q][4] | (p[q][5] << 16),
@@ -321,14 +323,17 @@ dwh_gemm3_kernel(const uint16_t *__restrict__ Ap, const uint16_t *__restrict__ H
         const bool isa = trow < G3_BM;
         const long long grow = isa ? (long long)row0 + trow : (long long)col0 + (trow - G3_BM);
         ok[q] = grow < (isa ? (long long)n : (long long)m);
-        src[q] = (isa ? Ap : Hp) + (size_t)(ok[q] ? grow : 0) * 3 * (size_t)m + 8 * part;
+        src[q] = (isa ? Ap : Hp) + (size_t)(ok[q] ? grow : 0) * 96 + 8 * part;
         dst[q] = (uint32_t)(trow * G3_PITCH + 8 * part) * 2u;
     }
+    // (pieces 0 .. 3071 of a step are rows of dW, the rest rows of H: q < 6 is all dW, q = 6 .. 8 all H)
+    static_assert(6 * G3_THREADS == G3_BM * 12, "the dW rows of a step end on a whole pass of the workgroup");
+    const size_t step_a = (size_t)n * 96, step_h = (size_t)m * 96;      // from one 32-k block to the next
     uint4 sg[G3_CHUNKS];
     auto load_step = [&](int kt) {
 #pragma unroll
         for (int q = 0; q < G3_CHUNKS; ++q) {
-            const uint4 v = *(const uint4 *)(src[q] + (size_t)kt * 96);
+            const uint4 v = *(const uint4 *)(src[q] + (size_t)kt * (q < 6 ? step_a : step_h));
             sg[q] = ok[q] ? v : make_uint4(0u, 0u, 0u, 0u);
         }
     };
@@ -380,10 +385,9 @@ dwh_gemm3_kernel(const uint16_t *__restrict__ Ap, const uint16_t *__restrict__ H
                     acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][x], b[0][y], acc[x][y], 0, 0, 0);
                     acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][x], b[0][y], acc[x][y], 0, 0, 0);
                 }
-            // the next step's rows go to the other buffer between the MFMAs (past the end: a repeat, never read)
-            if (ks == 0) store_step(buf ^ 1, 0, 5);
-            else store_step(buf ^ 1, 5, G3_CHUNKS);
         }
+        // the next step's rows, requested a whole step ago, go to the other buffer (past the end: a repeat, never read)
+        store_step(buf ^ 1, 0, G3_CHUNKS);
         load_step(min(kt + 2, nk - 1));
         __syncthreads();
     }
@@ -403,7 +407,7 @@ dwh_gemm3_kernel(const uint16_t *__restrict__ Ap, const uint16_t *__restrict__ H
                 if (r < n && c < m) {
                     const float p = acc[i][j][e];
                     if (STORE_P) P[(long long)r * m + c] = p;
-                    const uint16_t *ap = Ap + plane_index(r, m, c);
+                    const uint16_t *ap = Ap + plane_index(r, n, c);
                     const float dw = (bf16_f32(ap[0]) + bf16_f32(ap[32])) + bf16_f32(ap[64]);     // exact
                     t += (double)p * (double)dw;
                 }
