@@ -39,7 +39,10 @@ def make_case(seed, n, m, K, N=None, with_alpha=True):
     return W, S, labels, H, al
 
 
-@pytest.mark.parametrize("n,m,K", [(1, 16, 2), (37, 48, 4), (130, 144, 8), (257, 272, 16), (128, 512, 16), (300, 1024, 8)])
+# (m a multiple of 32 from 128 up takes the contraction on the bf16 matrix cores, 256 x 128 tiles: 160 and 416 columns
+# leave its last column tile part empty, 70, 260 and 300 rows its last row tile)
+@pytest.mark.parametrize("n,m,K", [(1, 16, 2), (37, 48, 4), (130, 144, 8), (257, 272, 16), (128, 512, 16), (300, 1024, 8),
+                                   (70, 160, 8), (260, 416, 16)])
 @pytest.mark.parametrize("with_alpha", [False, True])
 def test_layer_loss_matches_oracle(ctx, n, m, K, with_alpha):
     W, S, labels, H, al = make_case(n + m, n, m, K, with_alpha=with_alpha)
@@ -66,7 +69,7 @@ def test_layer_loss_identity_and_diagonal_hessian(ctx):
     np.testing.assert_allclose(out["row_loss"].cpu().numpy(), (h.astype(np.float64)[None, :] * dWd ** 2).sum(1), rtol=RTOL)
 
 
-@pytest.mark.parametrize("n,m,K", [(5, 32, 4), (40, 144, 8), (130, 512, 16)])
+@pytest.mark.parametrize("n,m,K", [(5, 32, 4), (40, 144, 8), (130, 512, 16), (33, 160, 8)])
 @pytest.mark.parametrize("t_step", [1, 41])
 def test_scale_step_matches_oracle(ctx, gpu_lib, n, m, K, t_step):
     W, S, labels, H, al = make_case(100 + n, n, m, K)
