@@ -1576,14 +1576,15 @@ lloyd_iter_kernel(ClusterParams prm, long long nrows, LevelMap LM) {
         }
         const bool searching = !done && (p > 0) && !dup;
         const bool tie_lo = replo < rep;  // equal distances go to the lower cluster index
-        // |x - vlo| < |x - v|, or <= when the lower cluster wins ties: the difference of the two
-        // distances is zero exactly when they are equal, and no double lies between zero and the
-        // smallest subnormal, so "<= 0" is "< smallest subnormal"
-        const double thr = tie_lo ? __longlong_as_double(1ll) : 0.0;
-        auto nearer_lo = [&](float xf) -> bool {
+        // |x - vlo| < |x - v|, or <= when the lower cluster wins ties.  One strict comparison serves both: with the
+        // two centroids swapped, "<=" is the negation of "<" (a <= b is !(b < a)), so a lane that gives ties to the
+        // lower cluster compares the other way round and flips the answer.
+        const double c1 = tie_lo ? v : vlo, c2 = tie_lo ? vlo : v;
+        auto nearer_raw = [&](float xf) -> bool {
             const double x = (double)xf;
-            return (fabs(x - vlo) - fabs(x - v)) < thr;
+            return fabs(x - c1) < fabs(x - c2);
         };
+        auto nearer_lo = [&](float xf) -> bool { return nearer_raw(xf) != tie_lo; };
 
         // ---- chunk of the boundary: cnt = number of chunks whose first key is nearer to the lower
         // centroid (a prefix of the chunks); invariant lo <= cnt <= hi -----------------------------
@@ -1679,17 +1680,19 @@ lloyd_iter_kernel(ClusterParams prm, long long nrows, LevelMap LM) {
         };
         if (WAVES <= 2) load_pieces();
 
-        int tc = 0;
+        int tc = 0;         // (counted with the raw comparison and turned round once for the lanes that flip it)
         if (RAGGED) {
             const int nvalid = m - rbase;   // keys past the end of the row are not this row's
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 if (j >= nvalid) el[j] = NEUTRAL_KEY;
-                tc += (j < nvalid && nearer_lo(elem_w(el[j]))) ? 1 : 0;
+                tc += (j < nvalid && nearer_raw(elem_w(el[j]))) ? 1 : 0;
             }
+            if (tie_lo) tc = min(max(nvalid, 0), 16) - tc;
         } else {
 #pragma unroll
-            for (int j = 0; j < 16; ++j) tc += nearer_lo(elem_w(el[j])) ? 1 : 0;
+            for (int j = 0; j < 16; ++j) tc += nearer_raw(elem_w(el[j])) ? 1 : 0;
+            if (tie_lo) tc = 16 - tc;
         }
         if (cl < 0) tc = 0;
         Bcur = (searching && cl >= 0) ? rbase + tc : 0;  // p == 0 or no chunk below the boundary: 0
