@@ -67,6 +67,7 @@ struct ClusterParams {
     u64 *keys_seg;
     int *segmass;         // per segment of a long row: nonzero when it holds sensitivity mass
     long long nwork;      // rows x segments: the units of work sort_kernel's workgroups share out
+    int *work_counters;   // [0] units handed out beyond every workgroup's first two, [1] workgroups done (both zero at launch)
     int *vflag;           // validation result (one word of scratch)
     // bucket path of sort_kernel: value bins per thread (0: always the bitonic network) and the byte
     // offsets of its tables inside the dynamic LDS
@@ -316,16 +317,23 @@ __device__ __forceinline__ int quad_sum(int x) {
 //   * every thread sorts the 16 slots [16t, 16t+16) in registers (Batcher's odd-even merge sort,
 //     63 compare-exchanges), which orders every bin that lies inside one such window;
 //   * a bin that straddles a multiple of 16 has at most 8 keys on either side when no bin holds
-//     more than 8 keys, so one 8+8 merge of the upper half of window t with the lower half of
+//     more than 9 keys, so one 8+8 merge of the upper half of window t with the lower half of
 //     window t+1 (25 compare-exchanges) finishes the row.
 // The bin map has two levels so that it adapts to the row: a coarse histogram over COARSE_N equal
 // intervals of [min, max], then every coarse interval is cut into a number of equal bins
 // proportional to its count (a piecewise linear estimate of the distribution function).  Any
-// monotone map gives a correct sort; the map only decides how full the bins get.  A row in which
-// some bin holds more than 8 keys (heavy duplicates, wild outliers, a constant row) takes the
+// monotone map gives a correct sort; the map only decides how full the bins get.
+//   * A row in which some bin holds 10 to 17 keys (a few rows in a thousand: the map is an estimate) gets a third
+//     pass, an 8+8 merge of the two halves of every window: a bin of at most 17 keys touches at most three
+//     aligned blocks of 8 slots, and block merges over the pairs (2i, 2i+1), (2i+1, 2i+2), (2i, 2i+1) carry every
+//     key across the two block borders it may have to cross, in either direction.
+// A row in which some bin holds more than 17 keys (heavy duplicates, wild outliers, a constant row) takes the
 // bitonic network instead: same result, key for key.
 // ---------------------------------------------------------------------------------------------
-constexpr int BIN_MAX_KEYS = 8;
+// (a bin of 9 keys that straddles a multiple of 16 still has at most 8 on either side, one of 10 may have 9;
+// likewise 17 for three passes)
+constexpr int BIN_MAX_KEYS = 9;      // no bin above this: two passes
+constexpr int BIN_MAX_KEYS3 = 17;    // no bin above this: three passes
 
 // position of a weight on the coarse axis; single-precision operations that the compiler may not fuse,
 // so that the two places that evaluate it agree bit for bit
@@ -485,7 +493,7 @@ __device__ __forceinline__ void write_bin_table(float2 *table, int lane, const f
 // swz(r), by the bucket path.  map: see BinMap; when map.have is false, map.lo / map.scale must hold the axis of
 // this unit (least weight, COARSE_N / range) and the coarse counters must be zero (with a barrier between
 // clearing them and this call).  Returns false, with nothing of value in LDS and map.have false, when some bin
-// took more than BIN_MAX_KEYS keys; all threads of the workgroup return the same.  Contains workgroup
+// took more than BIN_MAX_KEYS3 keys; all threads of the workgroup return the same.  Contains workgroup
 // barriers: every thread must call it.  wave_mass: whether a key of this wavefront carries sensitivity mass;
 // anymass (out): whether any key of the unit does; a unit without mass is scattered with unit weights (single
 // segment rows only).  prefetch(g), g = 1, 2, 3: issues part g of the loads of the next unit.  The parts are
@@ -557,7 +565,7 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
                 // bind while the table is consistent; it keeps the index inside the counters)
                 const float x = fminf(fmaxf(coarse_pos(bin_weight<SPREAD>(key[k], map, stab), lo, scale), 0.0f), (float)COARSE_N - 0.0001f);
                 // (a carried map may promise clear low bits that this unit does not have: it then sorts by the network)
-                if (SPREAD && ((uint32_t)(key[k] >> 32) & map.lowmask)) smax = (uint32_t)BIN_MAX_KEYS;
+                if (SPREAD && ((uint32_t)(key[k] >> 32) & map.lowmask)) smax = (uint32_t)BIN_MAX_KEYS3;
                 const uint32_t cb = (uint32_t)(int)x;
                 const float fr = __builtin_amdgcn_fractf(x);
                 const float2 tb = table[cb];
@@ -576,6 +584,7 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
     prefetch(1);
     __syncthreads();
     // ---- first rank of every bin: exclusive scan of the counters, written over them (16 bits each)
+    bool third_pass = false;      // (the same in every thread)
     {
         const int nq = bpt >> 3;                       // 16-byte pieces of this thread's block
         uint4 *mine = (uint4 *)(hist + tid * hstride);
@@ -590,8 +599,10 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
         }
         const uint32_t inc = wave_scan_incl(run);
         const bool wave_over = __ballot(smax >= (uint32_t)BIN_MAX_KEYS) != 0;
-        // one word per wavefront: keys up to and including this wavefront's bins << 2 | overflow << 1 | mass
-        if (lane == 63) wtot[wave] = (inc << 2) | (wave_over ? 2u : 0u) | (wave_mass ? 1u : 0u);
+        const bool wave_over3 = __ballot(smax >= (uint32_t)BIN_MAX_KEYS3) != 0;
+        // one word per wavefront: keys up to and including this wavefront's bins << 3 | a bin too full for three
+        // passes << 2 | a bin too full for two << 1 | mass
+        if (lane == 63) wtot[wave] = (inc << 3) | (wave_over3 ? 4u : 0u) | (wave_over ? 2u : 0u) | (wave_mass ? 1u : 0u);
         __syncthreads();
         uint32_t below = 0, flags = 0;
         {
@@ -603,16 +614,17 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     if (4 * q + i < nw) flags |= e[i];
-                    if (4 * q + i < wave) below += e[i] >> 2;
+                    if (4 * q + i < wave) below += e[i] >> 3;
                 }
             }
         }
         anymass = (int)(flags & 1u);
-        // a bin with more than BIN_MAX_KEYS keys anywhere in the unit: the caller sorts by the network instead
-        if (flags & 2u) {
+        // a bin with more than BIN_MAX_KEYS3 keys anywhere in the unit: the caller sorts by the network instead
+        if (flags & 4u) {
             map.have = false;
             return false;
         }
+        third_pass = (flags & 2u) != 0u;
         // the counters are read once more (cheaper than carrying them in registers across the barrier)
         uint32_t at = inc - run + below;
         auto step = [&](uint32_t c) -> uint32_t {
@@ -737,6 +749,19 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
         }
     }
     __syncthreads();
+    if (__builtin_expect(third_pass, 0)) {
+        // some bin holds 10 to 17 keys: both halves of every window are in order now, merge them
+        if (p0 < m) {
+            double *win = lds + swz((uint32_t)p0);
+#pragma unroll
+            for (int r = 0; r < EPT; ++r) v[r] = (p0 + r < m) ? win[r] : pad;
+            merge8x8(v);
+#pragma unroll
+            for (int r = 0; r < EPT; ++r)
+                if (p0 + r < m) win[r] = v[r];
+        }
+        __syncthreads();
+    }
     map.have = true;
     return true;
 }
@@ -825,7 +850,19 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     map.scale = 0.0f;
     map.lowmask = 0u;
     map.sbm = 0u;
-    for (long long work = blockIdx.x; work < prm.nwork; work += gridDim.x) {
+    // Units of work: a workgroup's first two are blockIdx.x and blockIdx.x + gridDim.x; every further one is
+    // claimed from a counter in global memory, one unit ahead of the prefetch (the claim for the unit after next
+    // is issued while the current unit is sorted, and passes through one LDS word at a barrier the sort has
+    // anyway).  A unit that has to take the bitonic network costs about three units of the bucket path: with
+    // fixed shares the workgroups that meet such units would finish last and the kernel with them.
+    __shared__ int next_slot[2];   // the answers of consecutive units alternate between the two words
+    const int nwork = (int)prm.nwork;
+    if (tid0 == 0) next_slot[0] = (int)min((long long)blockIdx.x + gridDim.x, prm.nwork);
+    __syncthreads();
+    int next = 0, par = 0;
+    for (int work = (int)blockIdx.x; work < nwork; work = next, par ^= 1) {
+    // the unit that is fetched while this one is sorted: the answer to the previous unit's claim
+    next = prm.bk_bpt > 0 ? __builtin_amdgcn_readfirstlane(next_slot[par]) : (int)min((long long)work + gridDim.x, prm.nwork);
     // the thread index is made opaque per unit: per-thread addresses are recomputed where they are
     // used instead of being hoisted out of this loop and held in registers through the sort
     int tid = tid0;
@@ -834,7 +871,7 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     const int col0 = prm.nseg > 1 ? (int)(work & 1) * prm.seglen : 0;   // first column of this segment
     const int m = min(prm.m - col0, prm.seglen);                     // keys sorted by this workgroup
     const float *alpha = prm.alpha ? prm.alpha + col0 : nullptr;
-    const bool more = work + gridDim.x < prm.nwork;
+    const bool more = next < nwork;
     const bool buckets = prm.bk_bpt > 0;
     const Slots<VEC> sm(m, nth, tid);
 
@@ -844,8 +881,24 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     float wlo = INFINITY, whi = -INFINITY;
     build_keys<NS, VEC>(pw, ps, alpha, tid, nth, m, key, mass, wlo, whi);
     // (the bitonic network needs the registers: without the bucket path the next unit is fetched after the sort)
-    auto prefetch = [&](int part) { fetch_unit<NS, VEC>(prm, more ? work + gridDim.x : work, tid, nth, pw, ps, more, part); };
-    if (buckets) prefetch(0);
+    // the claim for the unit after next: thread 0 asks, and puts the answer into the other word of next_slot ahead
+    // of one of the unit's barriers; everybody reads it at the start of the next unit (this unit's word is
+    // written again two units on, behind barriers every reader has passed by then)
+    unsigned claim = 0u;
+    auto claim_next = [&]() {
+        if (more && tid == 0) claim = (unsigned)atomicAdd(prm.work_counters, 1);
+    };
+    auto publish = [&]() {
+        if (tid == 0) next_slot[par ^ 1] = more ? (int)min(2ll * gridDim.x + (long long)claim, (long long)nwork) : nwork;
+    };
+    auto prefetch = [&](int part) {
+        fetch_unit<NS, VEC>(prm, more ? next : work, tid, nth, pw, ps, more, part);
+        if (part == 1) publish();
+    };
+    if (buckets) {
+        claim_next();
+        prefetch(0);
+    }
     int anymass = 1;
     bool sorted_ok = false;
     if (buckets) {
@@ -961,6 +1014,7 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
             map.scale = (float)COARSE_N / (hi - lo) * 0.99999904632568359375f;
         }
         if (usable) sorted_ok = bucket_sort<NS, VEC>(smem, prm, key, tid, nth, m, map, wave_mass, anymass, prefetch);
+        else publish();
     } else {
         anymass = __syncthreads_or((int)mass);
     }
@@ -1003,7 +1057,7 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
                     break;
             }
         }
-        fetch_unit<NS, VEC>(prm, more ? work + gridDim.x : work, tid, nth, pw, ps, more);
+        fetch_unit<NS, VEC>(prm, more ? next : work, tid, nth, pw, ps, more);
     }
 
     if (prm.nseg > 1) {
@@ -1052,6 +1106,15 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     // lie beyond that region, and passes several barriers before its scatter; its bitonic branch has a barrier
     // of its own.  Without the bucket path the refill is immediate.
     if (!buckets) __syncthreads();
+    }
+    // the last workgroup to get here leaves both counters at zero for the next launch (every claim of every
+    // workgroup has been answered by then: a workgroup uses the answers before it leaves its loop)
+    if (tid0 == 0) {
+        const int done = atomicAdd(prm.work_counters + 1, 1);
+        if (done == (int)gridDim.x - 1) {
+            atomicExch(prm.work_counters, 0);
+            atomicExch(prm.work_counters + 1, 0);
+        }
     }
 }
 
@@ -2474,6 +2537,7 @@ skim_status launch_cluster(skim_ctx *ctx, ClusterParams &prm, int64_t n, bool so
     if (n == 0) return SKIM_OK;
     if ((int64_t)n * prm.nseg > 0x7fffffff) SKIM_FAIL(ctx, SKIM_ERR_SHAPE, "too many rows");
     prm.nwork = (long long)n * prm.nseg;
+    prm.work_counters = ctx->sort_counters;
     // as many workgroups as the device holds at once (LDS and thread limits), each looping over its units
     int per_cu = (int)(ctx->lds_limit / (int64_t)(lds + 256));   // (+ the kernel's small static LDS)
     if (per_cu > 2048 / threads) per_cu = 2048 / threads;

@@ -24,6 +24,8 @@ struct skim_ctx {
     int greedy_lds_enabled, xtx_lds_enabled, gemm3_lds_enabled;   // the larger dynamic-LDS limit of these kernels has been set through this context
     int validate;        // check W, S, alpha of the clustering calls for values the method is not defined on
     void *pack_scratch;  // this device's address of the static scratch of skim_pack_static
+    int *sort_counters;  // device memory owned by the context: [0] units of work handed out by the running sort_kernel, [1] its workgroups
+                         // that are done; both are zero between launches (the last workgroup to finish clears them)
 };
 
 #define SKIM_FAIL(ctx, code, ...)                                   \

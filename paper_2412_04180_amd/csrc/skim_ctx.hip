@@ -63,8 +63,19 @@ extern "C" skim_status skim_create(skim_ctx **out, int device, void *hip_stream)
     c->gemm3_lds_enabled = 0;
     c->validate = 0;
     c->pack_scratch = nullptr;
+    c->sort_counters = nullptr;
+    e = hipMalloc((void **)&c->sort_counters, 256);
+    if (e == hipSuccess) e = hipMemset(c->sort_counters, 0, 256);
+    if (e == hipSuccess) e = hipDeviceSynchronize();   // the clear is complete before any stream of the caller's uses the context
+    if (e != hipSuccess) {
+        snprintf(g_create_err, sizeof(g_create_err), "skim_create: the sort's work counters: %s", hipGetErrorString(e));
+        if (c->sort_counters) (void)hipFree(c->sort_counters);
+        delete c;
+        return SKIM_ERR_HIP;
+    }
     if (skim_pack_static_setup(c) != SKIM_OK) {
         snprintf(g_create_err, sizeof(g_create_err), "skim_create: %s", c->err);
+        (void)hipFree(c->sort_counters);
         delete c;
         return SKIM_ERR_HIP;
     }
@@ -76,6 +87,7 @@ extern "C" skim_status skim_destroy(skim_ctx *ctx) {
     if (!ctx) return SKIM_ERR_ARG;
     for (int i = 0; i < 3; ++i)
         if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
+    if (ctx->sort_counters) (void)hipFree(ctx->sort_counters);
     delete ctx;
     return SKIM_OK;
 }
