@@ -8,9 +8,12 @@
  * General rules
  *   - Plain C types only.  "dev" = pointer to device (HBM) memory of the
  *     context's GPU, "host" = pointer to host memory.
- *   - The caller owns every buffer.  The library allocates no device memory:
- *     scratch comes from the workspace the caller registers.  It keeps no
- *     pointer after a call returns, except the registered workspace.
+ *   - The caller owns every buffer.  The calls allocate no device memory:
+ *     scratch comes from the workspace the caller registers (skim_create alone
+ *     allocates 256 bytes that the context keeps until skim_destroy: the
+ *     counters from which the row sort's workgroups take their rows).  The
+ *     library keeps no pointer after a call returns, except the registered
+ *     workspace.
  *   - Device calls enqueue work on the context's HIP stream and return without
  *     synchronising; results (including scalars) land in device memory.
  *     skim_greedy_allocate is synchronous host code.
@@ -67,7 +70,9 @@ typedef struct {
 
 /* Create a context on GPU `device` that enqueues on `hip_stream` (a
  * hipStream_t passed as void*, NULL = the default stream).  Fails with
- * SKIM_ERR_HIP when the device is not a usable gfx950 GPU. */
+ * SKIM_ERR_HIP when the device is not a usable gfx950 GPU.  Allocates the
+ * context's 256 bytes of device memory and synchronises the device once;
+ * not for use under stream capture. */
 skim_status skim_create(skim_ctx **out, int device, void *hip_stream);
 skim_status skim_destroy(skim_ctx *ctx);
 /* Text of the last error on this context (ctx-owned, valid until the next
