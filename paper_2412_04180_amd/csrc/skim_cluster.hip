@@ -810,9 +810,7 @@ __device__ __forceinline__ void fetch_unit(const ClusterParams &prm, long long w
 // Scaling and key encoding of the values a thread fetched (column tid + k * nth in slot k; padding beyond m).
 template <int NS, bool VEC>
 __device__ __forceinline__ void build_keys(const float (&pw)[NS], const float (&ps)[NS], const float *alpha, int tid,
-                                           int nth, int m, u64 (&key)[NS], bool &mass, float &wlo, float &whi) {
-    wlo = INFINITY;
-    whi = -INFINITY;
+                                           int nth, int m, u64 (&key)[NS], bool &mass) {
     const Slots<VEC> sm(m, nth, tid);
 #pragma unroll
     for (int k = 0; k < NS; ++k) {
@@ -822,8 +820,6 @@ __device__ __forceinline__ void build_keys(const float (&pw)[NS], const float (&
             scaled_pair(pw[k], ps[k], alpha, sm.col(k), wt, st);
             key[k] = make_key(wt, st);
             mass = mass || (st != 0.0f);
-            wlo = fminf(wlo, wt);
-            whi = fmaxf(whi, wt);
         }
     }
 }
@@ -875,11 +871,10 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     const bool buckets = prm.bk_bpt > 0;
     const Slots<VEC> sm(m, nth, tid);
 
-    // keys in registers; least and largest weight, and whether the unit holds any sensitivity mass
+    // keys in registers, and whether the unit holds any sensitivity mass
     u64 key[NS];
     bool mass = false;
-    float wlo = INFINITY, whi = -INFINITY;
-    build_keys<NS, VEC>(pw, ps, alpha, tid, nth, m, key, mass, wlo, whi);
+    build_keys<NS, VEC>(pw, ps, alpha, tid, nth, m, key, mass);
     // (the bitonic network needs the registers: without the bucket path the next unit is fetched after the sort)
     // the claim for the unit after next: thread 0 asks, and puts the answer into the other word of next_slot ahead
     // of one of the unit's barriers; everybody reads it at the start of the next unit (this unit's word is
@@ -902,23 +897,33 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
     int anymass = 1;
     bool sorted_ok = false;
     if (buckets) {
-        // per wavefront: least and largest weight and the mass flag, for whoever needs them after a barrier
-        float *wmin = (float *)(smem + prm.bk_misc_off + BK_WMIN), *wmax = (float *)(smem + prm.bk_misc_off + BK_WMAX);
-        uint32_t *wmass = (uint32_t *)(smem + prm.bk_misc_off + BK_WMASS);
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) {
-            wlo = fminf(wlo, __shfl_xor(wlo, o, 64));
-            whi = fmaxf(whi, __shfl_xor(whi, o, 64));
-        }
         const bool wave_mass = __ballot(mass) != 0;
-        if ((tid & 63) == 0) {
-            wmin[tid >> 6] = wlo;
-            wmax[tid >> 6] = whi;
-            wmass[tid >> 6] = wave_mass ? 1u : 0u;
-        }
         bool usable = true;
         if (__builtin_expect(!map.have, 0)) {
-            // no map carried over: the axis is this unit's own range
+            // no map carried over: the axis is this unit's own range.  Per wavefront: least and largest weight and
+            // the mass flag, for everybody after the barrier below
+            float *wmin = (float *)(smem + prm.bk_misc_off + BK_WMIN), *wmax = (float *)(smem + prm.bk_misc_off + BK_WMAX);
+            uint32_t *wmass = (uint32_t *)(smem + prm.bk_misc_off + BK_WMASS);
+            {
+                float wlo = INFINITY, whi = -INFINITY;
+#pragma unroll
+                for (int k = 0; k < NS; ++k) {
+                    if (sm.has(k)) {
+                        wlo = fminf(wlo, elem_w(key[k]));
+                        whi = fmaxf(whi, elem_w(key[k]));
+                    }
+                }
+#pragma unroll
+                for (int o = 32; o >= 1; o >>= 1) {
+                    wlo = fminf(wlo, __shfl_xor(wlo, o, 64));
+                    whi = fmaxf(whi, __shfl_xor(whi, o, 64));
+                }
+                if ((tid & 63) == 0) {
+                    wmin[tid >> 6] = wlo;
+                    wmax[tid >> 6] = whi;
+                    wmass[tid >> 6] = wave_mass ? 1u : 0u;
+                }
+            }
             uint32_t *cc = (uint32_t *)(smem + prm.bk_coarse_off);
             for (int i = tid; i < COARSE_N * 4; i += nth) cc[i] = 0u;
             // which bits any weight of the unit has set, and the typical exponent of s (sum and count of the
@@ -1028,8 +1033,7 @@ __global__ void __launch_bounds__(1024) sort_kernel(ClusterParams prm) {
             __syncthreads();
             fetch_unit<NS, VEC>(prm, work, tid, nth, pw, ps);
             bool mass2 = false;
-            float lo2, hi2;
-            build_keys<NS, VEC>(pw, ps, alpha, tid, nth, m, key, mass2, lo2, hi2);
+            build_keys<NS, VEC>(pw, ps, alpha, tid, nth, m, key, mass2);
         }
         if (!anymass && prm.nseg == 1) {
             // no sensitivity mass in this row: cluster with unit weights
