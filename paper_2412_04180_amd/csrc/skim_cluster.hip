@@ -516,8 +516,8 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
     const float lo = map.lo, scale = map.scale;
     // half-word (16-bit counter, later first rank) of a bin inside hist
     auto bin_halfword = [&](uint32_t fb) -> uint32_t {
-        const uint32_t wd = (fb >> 1) + (prm.bk_pad ? (fb >> prm.bk_lgbpt) << 2 : 0u);
-        return (wd << 1) | (fb & 1u);
+        // (word = fb / 2 + 4 spare words per block of bk_bpt bins, half-word = 2 * word + fb % 2)
+        return fb + (prm.bk_pad ? (fb >> prm.bk_lgbpt) << 3 : 0u);
     };
     if (__builtin_expect(!map.have, 0)) {
         // ---- coarse histogram of the unit's keys (a sample of every fourth key was tried: its table overflowed a
@@ -554,6 +554,42 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
     const bool padded = prm.bk_pad != 0;
     auto count_keys = [&](auto spread) {
         constexpr bool SPREAD = decltype(spread)::value;
+        if (sm.has(NS - 1)) {
+            // every slot of this thread holds a key (all threads of a full wavefront): the same steps as below,
+            // but half the slots at a time and step by step, so that the LDS reads of a batch are in flight
+            // together and then its atomics (key by key, every LDS access waits for the one before it)
+            constexpr int HB = NS / 2;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                float fr[HB];
+                uint32_t cb[HB];
+#pragma unroll
+                for (int i = 0; i < HB; ++i) {
+                    const int k = h * HB + i;
+                    const float x = fminf(fmaxf(coarse_pos(bin_weight<SPREAD>(key[k], map, stab), lo, scale), 0.0f), (float)COARSE_N - 0.0001f);
+                    if (SPREAD && ((uint32_t)(key[k] >> 32) & map.lowmask)) smax = (uint32_t)BIN_MAX_KEYS3;
+                    cb[i] = (uint32_t)(int)x;
+                    fr[i] = __builtin_amdgcn_fractf(x);
+                }
+                float2 tb[HB];
+#pragma unroll
+                for (int i = 0; i < HB; ++i) tb[i] = table[cb[i]];
+                uint32_t hw[HB], old[HB];
+#pragma unroll
+                for (int i = 0; i < HB; ++i) {
+                    const uint32_t fb = min((uint32_t)fmaf(fr[i], tb[i].y, tb[i].x), (uint32_t)(nbins - 1));
+                    hw[i] = padded ? bin_halfword(fb) : fb;
+                    old[i] = atomicAdd(&hist[hw[i] >> 1], 1u << ((hw[i] & 1u) << 4));
+                }
+#pragma unroll
+                for (int i = 0; i < HB; ++i) {
+                    const uint32_t slot = (old[i] >> ((hw[i] & 1u) << 4)) & 0xFFFFu;
+                    smax = max(smax, slot);
+                    fbs[h * HB + i] = hw[i] | (slot << 16);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int k = 0; k < NS; ++k) {
             fbs[k] = 0u;
@@ -652,7 +688,17 @@ __device__ __forceinline__ bool bucket_sort(unsigned char *smem, const ClusterPa
     double *lds = (double *)smem;
     const unsigned short *first = (const unsigned short *)hist;
     const bool unit_weights = !anymass && prm.nseg == 1;
-    if (!unit_weights) {
+    if (!unit_weights && sm.has(NS - 1)) {
+        // every slot holds a key: all first ranks are read before the first key is stored
+        uint32_t pos[NS];
+#pragma unroll
+        for (int k = 0; k < NS; ++k) pos[k] = first[fbs[k] & 0xFFFFu];
+#pragma unroll
+        for (int k = 0; k < NS; ++k) {
+            const uint32_t at = min(pos[k] + (fbs[k] >> 16), (uint32_t)(m - 1));
+            lds[swz(at)] = __longlong_as_double((long long)key[k]);
+        }
+    } else if (!unit_weights) {
 #pragma unroll
         for (int k = 0; k < NS; ++k) {
             if (sm.has(k)) {
