@@ -216,13 +216,15 @@ def test_many_rows_of_repeated_values_take_the_network_row_after_row(ctx):
     assert np.array_equal(alone["centroids_all"].cpu().numpy(), ca)
 
 
+@pytest.mark.parametrize("where", ["start", "middle", "end"])
 @pytest.mark.parametrize("m", [1000, 4096, 11008])
-def test_rows_with_one_value_9_to_20_times_over(ctx, m):
+def test_rows_with_one_value_9_to_20_times_over(ctx, m, where):
     """Smooth rows in which one value occurs k times, k = 9 .. 20, starting at every alignment to the sort's
-    16-slot windows (the rank of the repeated value moves from row to row): the value's bin holds k keys, more than
+    16-slot windows (the rank of the repeated value moves from row to row; at either end of the row or in the
+    middle): the value's bin holds k keys, more than
     the two register passes of the bucket path put in order (9 they still do).  Up to 17 the third pass finishes the row, beyond
     that the network does; either way the table must be the oracle's."""
-    rng = np.random.default_rng(4100 + m)
+    rng = np.random.default_rng(4100 + m + len(where))
     ks = list(range(9, 21))
     n = len(ks) * 16
     W = (rng.standard_normal((n, m)) * 0.02).astype(np.float32)
@@ -230,7 +232,9 @@ def test_rows_with_one_value_9_to_20_times_over(ctx, m):
     for i in range(n):
         k = ks[i // 16]
         order = np.argsort(W[i], kind="stable")
-        r = (m // 3) + (i % 16)                      # rank at which the run of equal values starts
+        # rank at which the run of equal values starts: at the least weights of the row, in the middle, or so that
+        # the run ends within the last 16 ranks (the last, possibly part-filled, window of the sort)
+        r = {"start": i % 16, "middle": (m // 3) + (i % 16), "end": m - k - (i % 16)}[where]
         cols = order[r:r + k]
         W[i, cols] = W[i, order[r]]
     ref, out, excused = check_table(ctx, W, S)
